@@ -1,0 +1,216 @@
+"""Pins of the stage-level oracle: finite differences through whole layers (dense with all seven LoRA
+adapters and QK-norm; MoE), stage composition, and the paper's printed accounting values."""
+import os
+
+import numpy as np
+
+import synth
+from oracle import StageConfig, accounting, stage
+from oracle import layers as L
+
+RNG = np.random.default_rng(99)
+
+
+def tiny_cfg(**kw):
+    base = dict(n_layers=2, hidden=16, n_q_heads=4, n_kv_heads=2, head_dim=4, ffn=24, vocab=32,
+                rope_base=100.0, rms_eps=1e-6, qk_norm=True, lora_rank=2, lora_scale=0.8,
+                lora_targets=synth.LORA_ORDER, train_base=True)
+    base.update(kw)
+    return StageConfig(**base)
+
+
+def draw_layer(cfg, scale=0.4):
+    h, d, m = cfg.hidden, cfg.head_dim, cfg.ffn
+    qd, kd, E, r = cfg.qd, cfg.kd, cfg.n_experts, cfg.lora_rank
+    n = lambda *s: RNG.standard_normal(s) * scale
+    p = {"g1": 1 + n(h), "g2": 1 + n(h), "gq": 1 + n(d), "gk": 1 + n(d),
+         "Wq": n(qd, h), "Wk": n(kd, h), "Wv": n(kd, h), "Wo": n(h, qd)}
+    if E:
+        p.update(Wg=n(E, m, h), Wu=n(E, m, h), Wd=n(E, h, m))
+    else:
+        p.update(Wg=n(m, h), Wu=n(m, h), Wd=n(h, m))
+    dims = {"q": (qd, h), "k": (kd, h), "v": (kd, h), "o": (h, qd), "gate": (m, h), "up": (m, h), "down": (h, m)}
+    p["lora"] = {nm: (n(r, dims[nm][1]), n(dims[nm][0], r)) for nm in cfg.lora_targets} if r else {}
+    return p
+
+
+def fd_param(f, arr, an, n_probe=6, eps=1e-6, tol=5e-6):
+    flat, anf = arr.reshape(-1), np.asarray(an).reshape(-1)
+    scale = max(np.max(np.abs(anf)), 1e-12)
+    for i in RNG.choice(flat.size, size=min(n_probe, flat.size), replace=False):
+        old = flat[i]
+        flat[i] = old + eps
+        fp = f()
+        flat[i] = old - eps
+        fm = f()
+        flat[i] = old
+        assert abs((fp - fm) / (2 * eps) - anf[i]) <= tol * scale + 1e-9, (i, (fp - fm) / (2 * eps), anf[i])
+
+
+def test_dense_stage_backward_matches_finite_differences():
+    cfg = tiny_cfg()
+    batch, seq = 2, 4
+    T = batch * seq
+    params = [draw_layer(cfg) for _ in range(cfg.n_layers)]
+    x = RNG.standard_normal((T, cfg.hidden))
+    dy = RNG.standard_normal((T, cfg.hidden))
+    out, dx, grads = stage.stage_fwd_bwd(x, dy, params, cfg, batch, seq)
+    f = lambda: float(np.sum(dy * stage.stage_fwd(x, params, cfg, batch, seq)[0]))
+    fd_param(f, x, dx, n_probe=10)
+    for li, p in enumerate(params):
+        for name in ("g1", "g2", "gq", "gk", "Wq", "Wk", "Wv", "Wo", "Wg", "Wu", "Wd"):
+            fd_param(f, p[name], grads[li][name])
+        for nm in cfg.lora_targets:
+            fd_param(f, p["lora"][nm][0], grads[li]["lora"][nm][0], n_probe=4)
+            fd_param(f, p["lora"][nm][1], grads[li]["lora"][nm][1], n_probe=4)
+
+
+def test_moe_layer_backward_matches_finite_differences():
+    cfg = tiny_cfg(n_layers=1, n_experts=5, top_k=2, ffn=6, lora_targets=("q", "k", "v", "o"))
+    batch, seq = 1, 5
+    T = batch * seq
+    params = [draw_layer(cfg)]
+    x = RNG.standard_normal((T, cfg.hidden))
+    dy = RNG.standard_normal((T, cfg.hidden))
+    rl = [RNG.standard_normal((T, 5)) * 2.0]
+    out, dx, grads = stage.stage_fwd_bwd(x, dy, params, cfg, batch, seq, rl)
+    f = lambda: float(np.sum(dy * stage.stage_fwd(x, params, cfg, batch, seq, rl)[0]))
+    fd_param(f, x, dx, n_probe=10)
+    fd_param(f, rl[0], grads[0]["router_logits"], n_probe=12)
+    for name in ("Wg", "Wu", "Wd", "Wo", "g2"):
+        fd_param(f, params[0][name], grads[0][name])
+
+
+def test_frozen_base_returns_no_base_weight_grads_but_same_dx():
+    cfg_t = tiny_cfg()
+    cfg_f = tiny_cfg(train_base=False)
+    batch, seq = 1, 6
+    params = [draw_layer(cfg_t) for _ in range(2)]
+    x = RNG.standard_normal((6, cfg_t.hidden))
+    dy = RNG.standard_normal((6, cfg_t.hidden))
+    _, dx_t, g_t = stage.stage_fwd_bwd(x, dy, params, cfg_t, batch, seq)
+    _, dx_f, g_f = stage.stage_fwd_bwd(x, dy, params, cfg_f, batch, seq)
+    np.testing.assert_array_equal(dx_t, dx_f)
+    assert "Wq" in g_t[0] and "Wq" not in g_f[0]
+    np.testing.assert_array_equal(g_t[1]["lora"]["down"][0], g_f[1]["lora"]["down"][0])
+
+
+def test_stage_is_chain_of_single_layer_stages():
+    cfg = tiny_cfg(n_layers=3, lora_rank=0, lora_targets=())
+    batch, seq = 1, 5
+    params = [draw_layer(cfg) for _ in range(3)]
+    x = RNG.standard_normal((5, cfg.hidden))
+    dy = RNG.standard_normal((5, cfg.hidden))
+    out, dx, grads = stage.stage_fwd_bwd(x, dy, params, cfg, batch, seq)
+    # forward: three one-layer stages, keeping each boundary
+    xs = [x]
+    for p in params:
+        xs.append(stage.stage_fwd(xs[-1], [p], cfg, batch, seq)[0])
+    np.testing.assert_allclose(out, xs[-1], rtol=1e-13)
+    out_f, layer_inputs = stage.stage_fwd(x, params, cfg, batch, seq)
+    for li in range(3):
+        np.testing.assert_allclose(layer_inputs[li], xs[li], rtol=1e-13)
+    # backward: each one-layer backward stage recomputes from its stored input
+    d = dy
+    for li in reversed(range(3)):
+        _, d, g = stage.stage_fwd_bwd(xs[li], d, [params[li]], cfg, batch, seq)
+        np.testing.assert_allclose(g[0]["Wd"], grads[li]["Wd"], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(d, dx, rtol=1e-11, atol=1e-13)
+
+
+def test_batch_entries_are_independent_sequences():
+    cfg = tiny_cfg(n_layers=1, lora_rank=0, lora_targets=())
+    p = [draw_layer(cfg)]
+    x = RNG.standard_normal((8, cfg.hidden))
+    both, _ = stage.stage_fwd(x, p, cfg, 2, 4)
+    first, _ = stage.stage_fwd(x[:4], p, cfg, 1, 4)
+    second, _ = stage.stage_fwd(x[4:], p, cfg, 1, 4)
+    np.testing.assert_allclose(both, np.concatenate([first, second]), rtol=1e-13)
+
+
+def test_head_chain_gradient_flows_into_stage():
+    """loss(head(stage(x))) differentiated end to end equals FD of the composed scalar."""
+    cfg = tiny_cfg(n_layers=1)
+    batch, seq = 1, 6
+    params = [draw_layer(cfg)]
+    head = {"gf": 1 + 0.3 * RNG.standard_normal(cfg.hidden), "Wv": RNG.standard_normal((cfg.vocab, cfg.hidden))}
+    x = RNG.standard_normal((6, cfg.hidden))
+    labels = np.array([3, 1, -100, 31, 0, 7], dtype=np.int32)
+
+    def f():
+        o, _ = stage.stage_fwd(x, params, cfg, batch, seq)
+        return float(stage.head_fwd_bwd(o, head, labels, cfg, want_dW=False)[0])
+
+    o, _ = stage.stage_fwd(x, params, cfg, batch, seq)
+    loss, dxo, gh = stage.head_fwd_bwd(o, head, labels, cfg)
+    _, dx, grads = stage.stage_fwd_bwd(x, dxo, params, cfg, batch, seq)
+    fd_param(f, x, dx, n_probe=10)
+    fd_param(f, params[0]["Wq"], grads[0]["Wq"])
+    fd_param(f, head["Wv"], gh["Wv"])
+    fd_param(f, head["gf"], gh["gf"])
+
+
+# ----------------------------------------------------------------------------- paper's printed values
+def golden():
+    vals = {}
+    path = os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            vals[k.strip()] = float(v)
+    return vals
+
+
+def test_activation_bytes_worked_example():
+    g = golden()
+    per_layer = accounting.activation_bytes_per_layer(s=16384, b=1, h=4096, m=14336, a=32, k=8)
+    total_gib = 32 * per_layer / 2 ** 30
+    assert round(total_gib) == g["act_total_gib_llama31_8b_16k"]
+    assert accounting.checkpoint_bytes_per_layer(16384, 1, 4096) == 2 * 16384 * 4096
+
+
+def test_operational_intensity_crossings():
+    g = golden()
+    ridge = 330e12 / 32e9
+    assert abs(ridge - g["ridge_4090_flop_per_byte"]) < 1e-6
+    qwen17 = dict(h=2048, m=6144, a=16, k=8)
+    # dense: below the 4090 ridge at B=4, above at the paper's B=8 (s=2048)
+    assert accounting.oi_fwd(2048, 4, **qwen17) < ridge < accounting.oi_fwd(2048, int(g["dense_crossing_batch"]), **qwen17)
+    # MoE (Qwen3-235B row): crosses somewhere below B=100
+    q235 = dict(h=4096, m=1536, a=64, k=4, e_act=8, e=128)
+    bs = [b for b in range(1, 101) if accounting.oi_fwd(2048, b, **q235) > ridge]
+    assert bs and 8 < bs[0] < g["moe_crossing_batch_upper"]
+    # had the attention term been linear in s (as printed), the dense model would still be below the ridge at B=8
+    lin = lambda b: (accounting.fwd_flops(2048, b, **qwen17) - 4.0 * 2048 * 2048 * b * 2048 + 4.0 * 2048 * b * b * 2048) \
+        / accounting.fwd_upload_bytes(2048, b, **qwen17)
+    assert lin(8) < ridge
+
+
+def test_bwd_flops_and_bubble_ratio():
+    g = golden()
+    f = accounting.fwd_flops(2048, 4, 2048, 6144, 16, 8)
+    assert accounting.bwd_flops(2048, 4, 2048, 6144, 16, 8) == g["bwd_over_fwd_flops"] * f
+    assert abs(accounting.bubble_ratio_roundpipe(8, 16, 13) - 56.0 / (16 * 13 + 56)) < 1e-15
+
+
+# ----------------------------------------------------------------------------- seeded inputs
+def test_synth_bf16_rounding_is_rne_and_idempotent():
+    x = np.array([1.0, 1.00390625, 1.01171875, -3.1415927, 65504.0, 1e-40], dtype=np.float32)
+    r = synth.bf16_round(x)
+    # 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even mantissa (1.0); 1 + 3*2^-8 ties to 1 + 2^-6
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == np.float32(1.015625)
+    np.testing.assert_array_equal(synth.bf16_round(r), r)
+    assert np.all((r.view(np.uint32) & 0xFFFF) == 0)
+    np.testing.assert_array_equal(synth.bits_to_f32(synth.bf16_bits(r)), r)
+
+
+def test_synth_workload_is_deterministic_and_labels_shifted():
+    c = synth.CONFIGS["C1"]
+    w1 = synth.make_workload(c, synth.config_seed("C1"))
+    w2 = synth.make_workload(c, synth.config_seed("C1"))
+    np.testing.assert_array_equal(w1["x"], w2["x"])
+    np.testing.assert_array_equal(w1["layers"][1]["Wd"], w2["layers"][1]["Wd"])
+    assert w1["labels"][-1] == -100 and w1["labels"].shape == (128,)
+    assert set(w1["layers"][0]["lora"]) == {"q", "v"}
+    assert w1["head"]["Wv"].shape == (4096, 256)
