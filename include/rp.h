@@ -1,0 +1,179 @@
+/*
+ * rp.h -- C ABI of the RoundPipe worker hot path on one MI355X (gfx950).
+ *
+ * A worker in the paper's computation-dispatch scheme is stateless: it is handed one pipeline
+ * stage's weights (streamed from pinned host memory) and an activation, runs the stage and hands
+ * the result back (Sec. 3.1; Sec. 4.1, "GPU worker"; Sec. 4.2, parameter-upload stream).  A
+ * forward stage runs a contiguous range of decoder layers; a backward stage re-runs that forward
+ * from the stored stage input keeping the internals, then back-propagates, accumulating weight
+ * gradients in place (Sec. 3.2 "asymmetric stage splitting"; Sec. 4.1.1; App. C.3).  The LM head
+ * with its loss is the oversized last stage and returns a scalar loss (Sec. 2.3, Sec. 4.1.1).
+ *
+ * General rules
+ *  - Plain C99 types only.  Pointers marked [dev] are device pointers, [host] are host pointers,
+ *    [pinned] are page-locked host pointers.  The caller owns every buffer; the library allocates
+ *    no device memory and keeps only the configuration, HIP events and slot bookkeeping in rp_ctx.
+ *  - All tensors are row-major and token-major: an activation is [T, features], T = batch*seq,
+ *    sequences of one batch entry are contiguous.  bf16 unless stated.  Feature sizes (hidden,
+ *    heads*head_dim, ffn, vocab, lora_rank) must be multiples of 8; T must be a multiple of 8.
+ *  - Every call only enqueues work (compute calls on the compute stream given at creation, uploads
+ *    on the copy stream) and returns; no call synchronises the device.  Ordering between an upload
+ *    and the stage that uses the slot, and between a stage and the next upload into the same slot,
+ *    is enforced on the device with events.
+ *  - Return value: RP_OK or an error code; rp_last_error() gives a message.  Argument errors are
+ *    detected before anything is enqueued, so a failed call has no side effects.
+ *  - A ctx is used from one thread at a time.
+ */
+#ifndef RP_H
+#define RP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#ifndef RP_API
+#define RP_API __attribute__((visibility("default")))
+#endif
+
+typedef struct rp_ctx rp_ctx;
+
+typedef enum {
+  RP_OK = 0,
+  RP_EINVAL = 1,       /* NULL pointer, bad size, bad id */
+  RP_ENOMEM = 2,       /* workspace or slot too small */
+  RP_EHIP = 3,         /* a HIP runtime call failed */
+  RP_ESTATE = 4,       /* slot never uploaded / bound */
+  RP_EUNSUPPORTED = 5  /* shape the kernels do not cover */
+} rp_status;
+
+/* lora_mask bits, in the order the adapters appear in the weight blob */
+enum { RP_LORA_Q = 1, RP_LORA_K = 2, RP_LORA_V = 4, RP_LORA_O = 8, RP_LORA_GATE = 16, RP_LORA_UP = 32, RP_LORA_DOWN = 64 };
+
+#define RP_MAX_SLOTS 4
+#define RP_IGNORE_INDEX (-100)
+
+/* One stage's shape.  Plain data; struct_size = sizeof(rp_stage_cfg) guards against layout drift. */
+typedef struct {
+  uint32_t struct_size;
+  int32_t n_layers;    /* decoder layers in the stage; 0 = head-only stage */
+  int32_t hidden;      /* h */
+  int32_t n_q_heads;   /* a */
+  int32_t n_kv_heads;  /* k; a % k == 0 */
+  int32_t head_dim;    /* d in {64, 128} */
+  int32_t ffn;         /* m (per expert for MoE) */
+  int32_t vocab;       /* V; 0 = stage has no LM head */
+  int32_t n_experts;   /* E; 0 = dense FFN */
+  int32_t top_k;       /* E_act */
+  float rope_base;     /* theta base, e.g. 1e6 */
+  float rms_eps;       /* e.g. 1e-6 */
+  int32_t qk_norm;     /* 1: per-head RMSNorm on q and k before RoPE */
+  int32_t lora_rank;   /* r; 0 = no adapters */
+  float lora_scale;    /* s in y = x W^T + s (x A^T) B^T */
+  uint32_t lora_mask;  /* RP_LORA_* bits */
+  int32_t train_base;  /* 1: base weights and norm gains receive fp32 gradients; 0: frozen */
+} rp_stage_cfg;
+
+/* Tensor ids inside one layer's chunk of the weight blob (and of the gradient blob). */
+typedef enum {
+  RP_T_G1 = 0,   /* [h]                 input RMSNorm gain */
+  RP_T_WQKV,     /* [a*d + 2*k*d, h]    rows: q heads, then k heads, then v heads */
+  RP_T_GQ,       /* [d]                 per-head q norm gain (present only with qk_norm) */
+  RP_T_GK,       /* [d] */
+  RP_T_WO,       /* [h, a*d] */
+  RP_T_G2,       /* [h]                 post-attention RMSNorm gain */
+  RP_T_WGU,      /* dense [2m, h]: gate rows then up rows;  MoE [E, 2m, h] */
+  RP_T_WD,       /* dense [h, m];  MoE [E, h, m] */
+  RP_T_LA_Q, RP_T_LA_K, RP_T_LA_V,          /* LoRA A [r, h]  (enabled ones are adjacent)      */
+  RP_T_LB_Q, RP_T_LB_K, RP_T_LB_V,          /* LoRA B [a*d, r], [k*d, r], [k*d, r]             */
+  RP_T_LA_O, RP_T_LB_O,                     /* [r, a*d], [h, r]                                */
+  RP_T_LA_GATE, RP_T_LA_UP,                 /* [r, h]                                          */
+  RP_T_LB_GATE, RP_T_LB_UP,                 /* [m, r]                                          */
+  RP_T_LA_DOWN, RP_T_LB_DOWN,               /* [r, m], [h, r]                                  */
+  RP_T_GF,       /* head chunk: final RMSNorm gain [h] */
+  RP_T_WV,       /* head chunk: LM head [V, h] */
+  RP_T_COUNT
+} rp_tensor_id;
+
+/* ---- context ------------------------------------------------------------------------------- */
+
+/* Creates a context for one stage shape on `device`.  compute_stream / copy_stream are hipStream_t
+ * handles owned by the caller (both non-NULL, default priority).  Creates the per-slot, per-layer
+ * events.  Errors: RP_EINVAL (NULL, struct_size mismatch), RP_EUNSUPPORTED (shape), RP_EHIP. */
+RP_API rp_status rp_ctx_create(rp_ctx** out, int device, void* compute_stream, void* copy_stream, const rp_stage_cfg* cfg);
+
+/* Destroys events and frees the context.  The caller must have synchronised both streams. */
+RP_API rp_status rp_ctx_destroy(rp_ctx* ctx);
+
+/* Message of the last failed call on this ctx (NULL ctx: last failed ctx-less call). Valid until the next call. */
+RP_API const char* rp_last_error(const rp_ctx* ctx);
+
+/* ---- sizes and layouts (pure host functions, no HIP calls) ------------------------------------ */
+
+/* weight_blob_bytes: size of the packed stage weights (host blob == device slot, same layout);
+ * grad_blob_bytes: size of the fp32 gradient blob; workspace_bytes: device scratch a stage call or a
+ * head call needs for (batch, seq).  Any output pointer may be NULL. */
+RP_API rp_status rp_query_sizes(const rp_stage_cfg* cfg, int batch, int seq, size_t* weight_blob_bytes,
+                         size_t* grad_blob_bytes, size_t* workspace_bytes);
+
+/* Byte offset and element count of tensor `id` of layer `layer` (layer == n_layers addresses the head
+ * chunk) inside the weight blob (bf16 elements).  n_elems == 0 when the tensor is absent. */
+RP_API rp_status rp_weight_layout(const rp_stage_cfg* cfg, int layer, int id, size_t* byte_offset, size_t* n_elems);
+
+/* Same for the fp32 gradient blob.  Base tensors and gains are present only with train_base. */
+RP_API rp_status rp_grad_layout(const rp_stage_cfg* cfg, int layer, int id, size_t* byte_offset, size_t* n_elems);
+
+/* Byte range [begin, end) of layer `layer`'s chunk in the weight blob (the unit of upload and of event gating). */
+RP_API rp_status rp_weight_chunk(const rp_stage_cfg* cfg, int layer, size_t* begin, size_t* end);
+
+/* ---- the four calls of the hot path ------------------------------------------------------------ */
+
+/* Weight streaming (Sec. 4.2, parameter-upload stream).  Copies the packed stage weights from pinned host
+ * memory into the caller-owned device slot, one hipMemcpyAsync per layer chunk on the copy stream, recording
+ * one event per chunk so that layer l can start as soon as its own bytes have landed.  Before copying, the copy
+ * stream waits for the last stage call that read this slot.  bytes must equal weight_blob_bytes.
+ * host_blob [pinned], dev_slot [dev].  Errors: RP_EINVAL, RP_EHIP. */
+RP_API rp_status rp_stage_upload_weights(rp_ctx* ctx, int slot_id, void* dev_slot, const void* host_blob, size_t bytes);
+
+/* Marks a device blob that already holds packed weights (written on the compute stream or before it) as slot
+ * `slot_id` without copying; later stage calls on the slot wait for nothing. */
+RP_API rp_status rp_stage_bind_weights(rp_ctx* ctx, int slot_id, void* dev_slot, size_t bytes);
+
+/* Forward stage (Sec. 3.2): x_out = layers(x_in).  x_in, x_out [dev] bf16 [T, h] (may not alias).
+ * layer_inputs_out [host array of n_layers dev pointers, or NULL]: entry l, when non-NULL, receives a copy of the
+ * input of layer l (the activation checkpoint kept under full recomputation, Sec. 2.1.1).
+ * router_logits [dev] fp32 [n_layers, T, E] for MoE stages, else NULL.
+ * Waits on the slot's per-layer upload events.  workspace [dev], at least workspace_bytes of rp_query_sizes.
+ * Errors: RP_EINVAL, RP_ENOMEM (workspace), RP_ESTATE (slot not uploaded), RP_EHIP. */
+RP_API rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_out, void* const* layer_inputs_out,
+                           const float* router_logits, int batch, int seq, void* workspace, size_t workspace_bytes);
+
+/* Backward stage with recomputation (Sec. 3.2; App. C.3): from the stored stage input x_in the forward is re-run
+ * keeping the internals in the workspace, then the backward runs in reverse layer order.
+ * dy [dev] bf16 [T, h]: gradient of the stage output;  dx [dev] bf16 [T, h]: overwritten with the gradient of x_in;
+ * x_out [dev] bf16 [T, h] or NULL: receives the recomputed stage output (the fused forward+backward stage of the
+ * last layers uses it);  grads [dev]: fp32 gradient blob, ACCUMULATED (+=) -- the in-place accumulation over
+ * micro-batches of Sec. 4.1.1;  router_logits / d_router_logits [dev] fp32 [n_layers, T, E] (MoE only; the
+ * latter is overwritten).  Errors as rp_stage_forward. */
+RP_API rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, const void* x_in, const void* dy, void* dx, void* x_out,
+                            void* grads, const float* router_logits, float* d_router_logits, int batch, int seq,
+                            void* workspace, size_t workspace_bytes);
+
+/* LM head fused with the mean cross-entropy, forward and backward in one call (the oversized last stage, Sec. 2.3;
+ * returns a scalar loss, Sec. 4.1.1).  xf = rmsnorm(x; gf); Z = xf Wv^T is produced tile by tile and reduced on
+ * the fly, never stored at [T, V];  loss = mean over rows with label != RP_IGNORE_INDEX of (logsumexp Z_t - Z[t, y_t]);
+ * dZ = grad_scale (softmax - onehot) / N_valid.
+ * x [dev] bf16 [T, h]; labels [dev] int32 [T]; loss_out [dev] one fp32; dx [dev] bf16 [T, h] overwritten;
+ * grads [dev]: the stage's fp32 gradient blob (the one rp_stage_backward takes); its head chunk {gf [h], Wv [V, h]}
+ * is accumulated when train_base is set; NULL = frozen head.  Uses the head chunk (layer index n_layers) of the
+ * slot.  Errors as rp_stage_forward. */
+RP_API rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const int32_t* labels, float* loss_out,
+                               void* dx, void* grads, float grad_scale, int batch, int seq, void* workspace,
+                               size_t workspace_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RP_H */

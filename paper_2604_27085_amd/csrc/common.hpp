@@ -1,0 +1,61 @@
+// Shared device/host helpers for the gfx950 kernels (wave64, bf16 MFMA).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define RP_DEV __device__ __forceinline__
+
+static RP_DEV float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+static RP_DEV float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+static RP_DEV float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// round-to-nearest-even float -> bf16 bit pattern
+static RP_DEV uint32_t f32_to_bf16_bits(float f) {
+  bf16 h = (bf16)f;
+  return (uint32_t)__builtin_bit_cast(unsigned short, h);
+}
+static RP_DEV uint32_t pack_bf16x2(float lo, float hi) { return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16); }
+
+// 8x8 transpose of bf16 held as 8 uint4 rows (row r = 8 consecutive columns) -> 8 uint4 (entry c = column c, rows 0..7)
+static RP_DEV void transpose8x8_bf16(const uint4 (&in)[8], uint4 (&out)[8]) {
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(in);  // w[r*4 + j] holds columns 2j (lo), 2j+1 (hi) of row r
+  uint32_t* o = reinterpret_cast<uint32_t*>(out);             // o[c*4 + j] holds rows 2j (lo), 2j+1 (hi) of column c
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {      // column pair (2j, 2j+1)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {    // row pair (2i, 2i+1)
+      uint32_t a = w[(2 * i) * 4 + j], b = w[(2 * i + 1) * 4 + j];
+      o[(2 * j) * 4 + i] = (a & 0xffffu) | (b << 16);
+      o[(2 * j + 1) * 4 + i] = (a >> 16) | (b & 0xffff0000u);
+    }
+  }
+}
+
+static RP_DEV f32x16 mfma32(const uint4& a, const uint4& b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+static RP_DEV float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+static RP_DEV float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Blocks are handed to the 8 XCDs round-robin; remap so that consecutive logical ids share an XCD (and its L2).
+static RP_DEV int xcd_remap(int pid, int nblk) {
+  const int q = nblk >> 3, r = nblk & 7;
+  const int xcd = pid & 7, local = pid >> 3;
+  return xcd * q + (xcd < r ? xcd : r) + local;
+}

@@ -1,0 +1,454 @@
+// Memory-bound kernels of the decoder layer: RMSNorm, per-head QK-norm + RoPE, SwiGLU, small utilities.
+// All of them move 16 bytes per lane per access, keep their arithmetic in fp32 and are bounded by HBM bandwidth.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace {
+
+RP_DEV void unpack8(const uint4& u, float (&f)[8]) {
+  f[0] = bf16_lo(u.x); f[1] = bf16_hi(u.x); f[2] = bf16_lo(u.y); f[3] = bf16_hi(u.y);
+  f[4] = bf16_lo(u.z); f[5] = bf16_hi(u.z); f[6] = bf16_lo(u.w); f[7] = bf16_hi(u.w);
+}
+RP_DEV uint4 pack8(const float (&f)[8]) {
+  return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+}
+
+// ------------------------------------------------------------------------------------------------ RMSNorm forward
+// One wave per row, the row lives in registers between the sum of squares and the scaling.  MAXC = 16-byte chunks
+// per lane (h <= 512*MAXC).
+template <int MAXC>
+__global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const bf16* __restrict__ x, const bf16* __restrict__ g,
+                                                          bf16* __restrict__ y, float* __restrict__ rstd_out, int T,
+                                                          int h, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const int nch = h >> 3;
+  const uint4* xr = reinterpret_cast<const uint4*>(x + (long)row * h);
+  uint4 v[MAXC];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    const int c = lane + 64 * i;
+    v[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (c < nch) {
+      v[i] = xr[c];
+      float f[8];
+      unpack8(v[i], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+    }
+  }
+  ss = wave_sum(ss);
+  const float rstd = 1.0f / sqrtf(ss / (float)h + eps);
+  if (lane == 0 && rstd_out) rstd_out[row] = rstd;
+  const uint4* gr = reinterpret_cast<const uint4*>(g);
+  uint4* yr = reinterpret_cast<uint4*>(y + (long)row * h);
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+      float f[8], gg[8];
+      unpack8(v[i], f);
+      unpack8(gr[c], gg);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * gg[e];
+      yr[c] = pack8(f);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ RMSNorm backward
+// dx = rstd*(dy*g) - rstd^3/h * x * sum_j(dy_j g_j x_j)  (+ dres, the gradient arriving over the residual branch);
+// dg += sum_t dy_t * x_t * rstd_t, accumulated per lane over the rows a wave visits, then added atomically.
+template <int MAXC, typename DyT>
+__global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict__ dy, const bf16* __restrict__ x,
+                                                          const bf16* __restrict__ g, const float* __restrict__ rstd_in,
+                                                          const bf16* __restrict__ dres, bf16* __restrict__ dx,
+                                                          float* __restrict__ dg, int T, int h) {
+  const int lane = threadIdx.x & 63;
+  const int wave_id = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int nwaves = gridDim.x * 4;
+  const int nch = h >> 3;
+  const uint4* gr = reinterpret_cast<const uint4*>(g);
+  float dgacc[MAXC][8];
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dgacc[i][e] = 0.f;
+
+  for (int row = wave_id; row < T; row += nwaves) {
+    const float rstd = rstd_in[row];
+    const uint4* xr = reinterpret_cast<const uint4*>(x + (long)row * h);
+    float dyv[MAXC][8];
+    uint4 xv[MAXC];
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      const int c = lane + 64 * i;
+      xv[i] = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dyv[i][e] = 0.f;
+      if (c < nch) {
+        xv[i] = xr[c];
+        if constexpr (sizeof(DyT) == 4) {
+          const float4* dr = reinterpret_cast<const float4*>(dy + (long)row * h) + 2 * c;
+          const float4 a = dr[0], b = dr[1];
+          dyv[i][0] = a.x; dyv[i][1] = a.y; dyv[i][2] = a.z; dyv[i][3] = a.w;
+          dyv[i][4] = b.x; dyv[i][5] = b.y; dyv[i][6] = b.z; dyv[i][7] = b.w;
+        } else {
+          unpack8(reinterpret_cast<const uint4*>(dy + (long)row * h)[c], dyv[i]);
+        }
+        float xf[8], gg[8];
+        unpack8(xv[i], xf);
+        unpack8(gr[c], gg);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          dot += dyv[i][e] * gg[e] * xf[e];
+          dgacc[i][e] += dyv[i][e] * xf[e] * rstd;
+        }
+      }
+    }
+    dot = wave_sum(dot);
+    const float k2 = rstd * rstd * rstd * dot / (float)h;
+    uint4* dxr = reinterpret_cast<uint4*>(dx + (long)row * h);
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+        float xf[8], gg[8], o[8];
+        unpack8(xv[i], xf);
+        unpack8(gr[c], gg);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = rstd * dyv[i][e] * gg[e] - k2 * xf[e];
+        if (dres) {
+          float rr[8];
+          unpack8(reinterpret_cast<const uint4*>(dres + (long)row * h)[c], rr);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] += rr[e];
+        }
+        dxr[c] = pack8(o);
+      }
+    }
+  }
+  if (dg) {
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) atomicAdd(dg + c * 8 + e, dgacc[i][e]);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ RoPE table
+// cs[p][i] = (cos, sin)(p * base^(-2i/d)), evaluated in double so that long sequences keep full fp32 accuracy.
+__global__ void rope_table_kernel(float2* __restrict__ cs, int seq, int half, double log2_base) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= seq * half) return;
+  const int p = idx / half, i = idx - p * half;
+  const double theta = exp2(-(double)i / (double)half * log2_base);
+  const double phi = (double)p * theta;
+  double s, c;
+  sincos(phi, &s, &c);
+  cs[idx] = make_float2((float)c, (float)s);
+}
+
+// ------------------------------------------------------------------------------------------------ QK-norm + RoPE
+// One wave per token.  A head vector of D elements is spread over D/8 lanes (8 elements each); the rotation partner
+// (i, i + D/2) sits D/16 lanes away.  Heads 0..a-1 are query heads, a..a+k-1 key heads, both read from the fused
+// projection output (row stride ld_in) and written to dense [T, a, D] / [T, k, D] buffers.
+template <int D, bool BWD>
+__global__ void __launch_bounds__(256) qknorm_rope_kernel(const bf16* __restrict__ in_q, const bf16* __restrict__ in_k,
+                                                          long ld_in_q, long ld_in_k, bf16* __restrict__ out_q,
+                                                          bf16* __restrict__ out_k, long ld_out_q, long ld_out_k,
+                                                          const bf16* __restrict__ gq, const bf16* __restrict__ gk,
+                                                          float* __restrict__ rstd_q, float* __restrict__ rstd_k,
+                                                          const bf16* __restrict__ raw_q, const bf16* __restrict__ raw_k,
+                                                          long ld_raw, float* __restrict__ dgq, float* __restrict__ dgk,
+                                                          const float2* __restrict__ cs, int T, int seq, int a, int k,
+                                                          int use_norm, float eps) {
+  constexpr int LPH = D / 8;          // lanes per head
+  constexpr int HPW = 64 / LPH;       // heads per wave pass
+  const int lane = threadIdx.x & 63;
+  const int sub = lane % LPH, hsel = lane / LPH;
+  const int wave_id = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int nwaves = gridDim.x * 4;
+  const bool first_half = sub < LPH / 2;
+  float gqv[8], gkv[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { gqv[e] = 1.f; gkv[e] = 1.f; }
+  if (use_norm) {
+    unpack8(reinterpret_cast<const uint4*>(gq)[sub], gqv);
+    unpack8(reinterpret_cast<const uint4*>(gk)[sub], gkv);
+  }
+  float dgq_acc[8], dgk_acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { dgq_acc[e] = 0.f; dgk_acc[e] = 0.f; }
+
+  for (int t = wave_id; t < T; t += nwaves) {
+    const int pos = t % seq;
+    float c8[8], s8[8];
+    {
+      const float2* row = cs + (long)pos * (D / 2) + (sub % (LPH / 2)) * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float2 v = row[e]; c8[e] = v.x; s8[e] = v.y; }
+    }
+    for (int h0 = 0; h0 < a + k; h0 += HPW) {
+      const int head = h0 + hsel;
+      const bool ok = head < a + k;
+      const bool isq = head < a;
+      const int hh = isq ? head : head - a;
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = 0.f;
+      if (ok) {
+        const bf16* src = isq ? in_q + (long)t * ld_in_q + hh * D : in_k + (long)t * ld_in_k + hh * D;
+        unpack8(reinterpret_cast<const uint4*>(src)[sub], f);
+      }
+      if constexpr (!BWD) {
+        if (use_norm) {
+          float ss = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+#pragma unroll
+          for (int o = LPH / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+          const float rstd = 1.0f / sqrtf(ss / (float)D + eps);
+          if (ok && sub == 0) {
+            if (isq) rstd_q[(long)t * a + hh] = rstd; else rstd_k[(long)t * k + hh] = rstd;
+          }
+#pragma unroll
+          for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * (isq ? gqv[e] : gkv[e]);
+        }
+        float o8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float partner = __shfl_xor(f[e], LPH / 2, 64);
+          o8[e] = first_half ? (f[e] * c8[e] - partner * s8[e]) : (f[e] * c8[e] + partner * s8[e]);
+        }
+        if (ok) {
+          bf16* dst = isq ? out_q + (long)t * ld_out_q + hh * D : out_k + (long)t * ld_out_k + hh * D;
+          reinterpret_cast<uint4*>(dst)[sub] = pack8(o8);
+        }
+      } else {
+        // inverse rotation of the incoming gradient
+        float gr[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float partner = __shfl_xor(f[e], LPH / 2, 64);
+          gr[e] = first_half ? (f[e] * c8[e] + partner * s8[e]) : (f[e] * c8[e] - partner * s8[e]);
+        }
+        if (use_norm) {
+          float xr[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) xr[e] = 0.f;
+          float rstd = 0.f;
+          if (ok) {
+            const bf16* rsrc = (isq ? raw_q : raw_k) + (long)t * ld_raw + hh * D;
+            unpack8(reinterpret_cast<const uint4*>(rsrc)[sub], xr);
+            rstd = isq ? rstd_q[(long)t * a + hh] : rstd_k[(long)t * k + hh];
+          }
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float gg = isq ? gqv[e] : gkv[e];
+            dot += gr[e] * gg * xr[e];
+            if (isq) dgq_acc[e] += gr[e] * xr[e] * rstd; else dgk_acc[e] += gr[e] * xr[e] * rstd;
+          }
+#pragma unroll
+          for (int o = LPH / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+          const float k2 = rstd * rstd * rstd * dot / (float)D;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) gr[e] = rstd * gr[e] * (isq ? gqv[e] : gkv[e]) - k2 * xr[e];
+        }
+        if (ok) {
+          bf16* dst = isq ? out_q + (long)t * ld_out_q + hh * D : out_k + (long)t * ld_out_k + hh * D;
+          reinterpret_cast<uint4*>(dst)[sub] = pack8(gr);
+        }
+      }
+    }
+  }
+  if constexpr (BWD) {
+    if (use_norm && dgq) {
+      // lanes with the same `sub` hold partial sums for the same 8 gain entries
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float vq = dgq_acc[e], vk = dgk_acc[e];
+#pragma unroll
+        for (int o = LPH; o < 64; o <<= 1) { vq += __shfl_xor(vq, o, 64); vk += __shfl_xor(vk, o, 64); }
+        if (hsel == 0) { atomicAdd(dgq + sub * 8 + e, vq); atomicAdd(dgk + sub * 8 + e, vk); }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ SwiGLU
+__global__ void __launch_bounds__(256) swiglu_fwd_kernel(const bf16* __restrict__ gu, bf16* __restrict__ act, long T,
+                                                         int m) {
+  const int mc = m >> 3;
+  const long total = T * mc;
+  for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long)gridDim.x * blockDim.x) {
+    const long row = idx / mc;
+    const int c = (int)(idx - row * mc);
+    const uint4* r = reinterpret_cast<const uint4*>(gu + row * 2 * m);
+    float g[8], u[8], o[8];
+    unpack8(r[c], g);
+    unpack8(r[mc + c], u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.f + __expf(-g[e])) * u[e];
+    reinterpret_cast<uint4*>(act + row * m)[c] = pack8(o);
+  }
+}
+
+__global__ void __launch_bounds__(256) swiglu_bwd_kernel(const bf16* __restrict__ dact, const bf16* __restrict__ gu,
+                                                         bf16* __restrict__ dgu, long T, int m) {
+  const int mc = m >> 3;
+  const long total = T * mc;
+  for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long)gridDim.x * blockDim.x) {
+    const long row = idx / mc;
+    const int c = (int)(idx - row * mc);
+    const uint4* r = reinterpret_cast<const uint4*>(gu + row * 2 * m);
+    float g[8], u[8], d[8], dg[8], du[8];
+    unpack8(r[c], g);
+    unpack8(r[mc + c], u);
+    unpack8(reinterpret_cast<const uint4*>(dact + row * m)[c], d);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float sg = 1.f / (1.f + __expf(-g[e]));
+      dg[e] = d[e] * u[e] * sg * (1.f + g[e] * (1.f - sg));
+      du[e] = d[e] * g[e] * sg;
+    }
+    uint4* o = reinterpret_cast<uint4*>(dgu + row * 2 * m);
+    o[c] = pack8(dg);
+    o[mc + c] = pack8(du);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ utilities
+__global__ void fill_u32_kernel(uint32_t* __restrict__ p, long n, uint32_t v) {
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) p[i] = v;
+}
+
+__global__ void copy16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long n) {
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+__global__ void cast_f32_bf16_kernel(const float* __restrict__ src, bf16* __restrict__ dst, long n8) {
+  for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (long)gridDim.x * blockDim.x) {
+    const float4 a = reinterpret_cast<const float4*>(src)[2 * i], b = reinterpret_cast<const float4*>(src)[2 * i + 1];
+    const float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    reinterpret_cast<uint4*>(dst)[i] = pack8(f);
+  }
+}
+
+// Block-diagonal LoRA B for a fused projection: out[n, seg.col0 + c] = src_seg[n - seg.row0, c] inside a segment, 0 elsewhere.
+__global__ void lora_blockdiag_kernel(bf16* __restrict__ out, int N, int ncols, LoraSegs segs, int r) {
+  const long total = (long)N * ncols;
+  for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long)gridDim.x * blockDim.x) {
+    const int n = (int)(idx / ncols), c = (int)(idx - (long)n * ncols);
+    bf16 v = (bf16)0.f;
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+      if (segs.src[s] && n >= segs.row0[s] && n < segs.row1[s] && c >= segs.col0[s] && c < segs.col0[s] + r)
+        v = reinterpret_cast<const bf16*>(segs.src[s])[(long)(n - segs.row0[s]) * r + (c - segs.col0[s])];
+    }
+    out[idx] = v;
+  }
+}
+
+int grid_for(long n, int block = 256, int cap = 256 * 16) {
+  long g = (n + block - 1) / block;
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return (int)g;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------ launchers
+hipError_t k_rmsnorm_fwd(hipStream_t st, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps) {
+  const int grid = (T + 3) / 4;
+  if (grid == 0) return hipSuccess;
+  if (h <= 2048)
+    hipLaunchKernelGGL((rmsnorm_fwd_kernel<4>), dim3(grid), dim3(256), 0, st, (const bf16*)x, (const bf16*)g, (bf16*)y, rstd, T, h, eps);
+  else
+    hipLaunchKernelGGL((rmsnorm_fwd_kernel<16>), dim3(grid), dim3(256), 0, st, (const bf16*)x, (const bf16*)g, (bf16*)y, rstd, T, h, eps);
+  return hipGetLastError();
+}
+
+hipError_t k_rmsnorm_bwd(hipStream_t st, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
+                         const void* dres, void* dx, float* dg, int T, int h) {
+  if (T == 0) return hipSuccess;
+  int grid = (T + 3) / 4;
+  if (grid > 512) grid = 512;
+#define RP_LAUNCH_RB(MAXC, DT) \
+  hipLaunchKernelGGL((rmsnorm_bwd_kernel<MAXC, DT>), dim3(grid), dim3(256), 0, st, (const DT*)dy, (const bf16*)x, \
+                     (const bf16*)g, rstd, (const bf16*)dres, (bf16*)dx, dg, T, h)
+  if (h <= 2048) { if (dy_is_f32) RP_LAUNCH_RB(4, float); else RP_LAUNCH_RB(4, bf16); }
+  else { if (dy_is_f32) RP_LAUNCH_RB(16, float); else RP_LAUNCH_RB(16, bf16); }
+#undef RP_LAUNCH_RB
+  return hipGetLastError();
+}
+
+hipError_t k_rope_table(hipStream_t st, float2* cs, int seq, int d, float base) {
+  const int n = seq * (d / 2);
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cs, seq, d / 2, log2((double)base));
+  return hipGetLastError();
+}
+
+hipError_t k_qknorm_rope(hipStream_t st, int bwd, int d, const void* in_q, const void* in_k, long ld_in_q, long ld_in_k,
+                         void* out_q, void* out_k, long ld_out_q, long ld_out_k, const void* gq, const void* gk,
+                         float* rstd_q, float* rstd_k, const void* raw_q, const void* raw_k, long ld_raw, float* dgq,
+                         float* dgk, const float2* cs, int T, int seq, int a, int k, int use_norm, float eps) {
+  if (T == 0) return hipSuccess;
+  int grid = (T + 3) / 4;
+  if (bwd && grid > 1024) grid = 1024;
+#define RP_LAUNCH_QR(D, B) \
+  hipLaunchKernelGGL((qknorm_rope_kernel<D, B>), dim3(grid), dim3(256), 0, st, (const bf16*)in_q, (const bf16*)in_k, \
+                     ld_in_q, ld_in_k, (bf16*)out_q, (bf16*)out_k, ld_out_q, ld_out_k, (const bf16*)gq, (const bf16*)gk, \
+                     rstd_q, rstd_k, (const bf16*)raw_q, (const bf16*)raw_k, ld_raw, dgq, dgk, cs, T, seq, a, k, use_norm, eps)
+  if (d == 128) { if (bwd) RP_LAUNCH_QR(128, true); else RP_LAUNCH_QR(128, false); }
+  else if (d == 64) { if (bwd) RP_LAUNCH_QR(64, true); else RP_LAUNCH_QR(64, false); }
+  else return hipErrorInvalidValue;
+#undef RP_LAUNCH_QR
+  return hipGetLastError();
+}
+
+hipError_t k_swiglu_fwd(hipStream_t st, const void* gu, void* act, long T, int m) {
+  if (T == 0) return hipSuccess;
+  hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(grid_for(T * (m / 8))), dim3(256), 0, st, (const bf16*)gu, (bf16*)act, T, m);
+  return hipGetLastError();
+}
+
+hipError_t k_swiglu_bwd(hipStream_t st, const void* dact, const void* gu, void* dgu, long T, int m) {
+  if (T == 0) return hipSuccess;
+  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(grid_for(T * (m / 8))), dim3(256), 0, st, (const bf16*)dact, (const bf16*)gu, (bf16*)dgu, T, m);
+  return hipGetLastError();
+}
+
+hipError_t k_fill_u32(hipStream_t st, void* p, long n_words, uint32_t v) {
+  if (n_words == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(n_words)), dim3(256), 0, st, (uint32_t*)p, n_words, v);
+  return hipGetLastError();
+}
+
+hipError_t k_copy16(hipStream_t st, const void* src, void* dst, long bytes) {
+  if (bytes == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy16_kernel, dim3(grid_for(bytes / 16)), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, bytes / 16);
+  return hipGetLastError();
+}
+
+hipError_t k_cast_f32_bf16(hipStream_t st, const float* src, void* dst, long n) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(cast_f32_bf16_kernel, dim3(grid_for(n / 8)), dim3(256), 0, st, src, (bf16*)dst, n / 8);
+  return hipGetLastError();
+}
+
+hipError_t k_lora_blockdiag(hipStream_t st, void* out, int N, int ncols, const LoraSegs& segs, int r) {
+  if ((long)N * ncols == 0) return hipSuccess;
+  hipLaunchKernelGGL(lora_blockdiag_kernel, dim3(grid_for((long)N * ncols)), dim3(256), 0, st, (bf16*)out, N, ncols, segs, r);
+  return hipGetLastError();
+}

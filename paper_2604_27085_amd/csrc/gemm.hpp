@@ -1,0 +1,43 @@
+// Host-side interface of the bf16 MFMA GEMM family.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// Operand layouts.  "Reduction-contiguous" operands are read as they are; the others are transposed on their way
+// into LDS.
+//   NT: C[M,N] = A[M,K] * B[N,K]^T      (forward of a linear layer: activations x weights)
+//   NN: C[M,N] = A[M,K] * B[K,N]        (activation gradient: dY x W)
+//   TN: C[M,N] = A[K,M]^T * B[K,N]      (weight gradient: dY^T x X)
+enum { GEMM_NT = 0, GEMM_NN = 1, GEMM_TN = 2 };
+
+enum {
+  EPI_BF16 = 0,      // C bf16 = alpha*acc (+ R)
+  EPI_F32 = 1,       // C fp32 = alpha*acc (+ C if beta)
+  EPI_F32_ATOMIC = 2,// C fp32 atomically += alpha*acc
+  EPI_CE_STATS = 3,  // rows = vocab, cols = tokens: per-column (max, sum exp) partials + label logit
+  EPI_CE_DZ = 4      // C bf16 [rows, cols] = (exp(acc - lse[col]) - (row == label[col])) * coef[col]
+};
+
+struct GemmArgs {
+  const void* A; const void* B;
+  long lda, ldb;
+  int M, N, K;
+  // optional second operand pair appended to the reduction (LoRA up-projection fused into the base GEMM)
+  const void* A2; const void* B2;
+  long lda2, ldb2;
+  int K2;
+  void* C; long ldc;
+  const void* R; long ldr;     // optional bf16 residual added in the epilogue (EPI_BF16)
+  float alpha; int beta;
+  int epi;
+  // cross-entropy epilogues
+  const int* labels; float* zlab; float2* part; long part_ld; const float* lse; const float* coef;
+  int row_offset;              // global vocab index of row 0 of A
+  int part_row0;               // first partial row this launch writes (2 per M tile)
+};
+
+// Enqueues one GEMM.  Returns hipSuccess or the launch error.  tile_hint: 0 = choose automatically.
+hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a, int tile_hint = 0);
+// Number of partial rows an EPI_CE_STATS launch with M vocab rows writes for tile choice made by gemm_launch.
+int gemm_ce_stats_partials(int M);
+void gemm_zero_args(GemmArgs& a);

@@ -1,0 +1,46 @@
+// Launchers of the non-GEMM kernels.  Every function only enqueues on `st` and returns the launch status.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+struct LoraSegs {           // up to three row segments of a fused projection, each with its own LoRA B [rows, r]
+  const void* src[3];
+  int row0[3], row1[3], col0[3];
+};
+
+// y = x * rstd * g, rstd[T] saved (may be NULL).  x, y bf16 [T, h]; g bf16 [h].
+hipError_t k_rmsnorm_fwd(hipStream_t st, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps);
+// dx = rmsnorm backward (+ dres if non-NULL); dg (fp32 [h], may be NULL) accumulated atomically.  dy bf16 or fp32.
+hipError_t k_rmsnorm_bwd(hipStream_t st, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
+                         const void* dres, void* dx, float* dg, int T, int h);
+// cs[seq][d/2] = (cos, sin)(pos * base^(-2i/d))
+hipError_t k_rope_table(hipStream_t st, float2* cs, int seq, int d, float base);
+// forward: (optional per-head RMSNorm) then RoPE on q heads and k heads.  backward: the transpose.
+hipError_t k_qknorm_rope(hipStream_t st, int bwd, int d, const void* in_q, const void* in_k, long ld_in_q, long ld_in_k,
+                         void* out_q, void* out_k, long ld_out_q, long ld_out_k, const void* gq, const void* gk,
+                         float* rstd_q, float* rstd_k, const void* raw_q, const void* raw_k, long ld_raw, float* dgq,
+                         float* dgk, const float2* cs, int T, int seq, int a, int k, int use_norm, float eps);
+// act[T, m] = silu(gu[:, :m]) * gu[:, m:]
+hipError_t k_swiglu_fwd(hipStream_t st, const void* gu, void* act, long T, int m);
+hipError_t k_swiglu_bwd(hipStream_t st, const void* dact, const void* gu, void* dgu, long T, int m);
+hipError_t k_fill_u32(hipStream_t st, void* p, long n_words, uint32_t v);
+hipError_t k_copy16(hipStream_t st, const void* src, void* dst, long bytes);
+hipError_t k_cast_f32_bf16(hipStream_t st, const float* src, void* dst, long n);
+hipError_t k_lora_blockdiag(hipStream_t st, void* out, int N, int ncols, const LoraSegs& segs, int r);
+
+// Causal GQA attention, flash style.  q [T, a, d] (row stride ldq elements), k, v [T, kh, d] (ldk, ldv), o [T, a, d]
+// (ldo); lse fp32 [batch, a, seq].  T = batch*seq; sequences are independent.
+hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* v, void* o, float* lse, long ldq,
+                      long ldk, long ldv, long ldo, int batch, int seq, int a, int kh, int d);
+// delta[batch, a, seq] = rowsum(dO * O)
+hipError_t k_attn_delta(hipStream_t st, const void* o, const void* dout, float* delta, long ldo, long lddo, int batch,
+                        int seq, int a, int d);
+// dq [T, a, d] (lddq), dk, dv [T, kh, d] (lddk, lddv), summed over the query heads of each group.
+hipError_t k_attn_bwd(hipStream_t st, const void* q, const void* k, const void* v, const void* dout, const float* lse,
+                      const float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv, long lddo, long lddq,
+                      long lddk, long lddv, int batch, int seq, int a, int kh, int d);
+
+// Cross-entropy helpers.  part [P, T] (max, sumexp) partials -> lse[T]; then loss / coef from lse, label logits, labels.
+hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, float* lse, int T);
+hipError_t k_ce_finalize(hipStream_t st, const float* lse, const float* zlab, const int* labels, float grad_scale,
+                         float* coef, float* loss_out, int T);

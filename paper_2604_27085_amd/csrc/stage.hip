@@ -1,0 +1,604 @@
+// Stage executor and C ABI: weight upload with per-layer events, forward stage, backward stage with recomputation,
+// LM head fused with cross-entropy.  Host code only enqueues kernels; nothing here synchronises the device.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <new>
+
+#include "../../include/rp.h"
+#include "../../include/rp_ops.h"
+#include "gemm.hpp"
+#include "kernels.hpp"
+#include "layout.hpp"
+
+using namespace rp;
+
+namespace {
+
+typedef unsigned short bf16_t;   // host code never does bf16 arithmetic; this is only for pointer stepping
+
+struct Slot {
+  void* dev = nullptr;
+  size_t bytes = 0;
+  bool valid = false;     // uploaded or bound
+  bool gated = false;     // stage calls must wait on the per-chunk events
+  bool used = false;      // a stage call has read the slot since the last upload
+  hipEvent_t* ev = nullptr;   // n_layers + 1 events
+  hipEvent_t free_ev = nullptr;
+};
+
+char g_err[512];
+
+}  // namespace
+
+struct rp_ctx {
+  rp_stage_cfg cfg;
+  int device;
+  hipStream_t compute, copy;
+  Slot slots[RP_MAX_SLOTS];
+  BlobLayout wl, gl;
+  char err[512];
+};
+
+namespace {
+
+rp_status fail(rp_ctx* ctx, rp_status code, const char* fmt, ...) {
+  char* dst = ctx ? ctx->err : g_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 512, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                              \
+  do {                                                                                                  \
+    hipError_t e_ = (expr);                                                                             \
+    if (e_ != hipSuccess) return fail(ctx, RP_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));      \
+  } while (0)
+
+rp_status validate_cfg(const rp_stage_cfg* c, rp_ctx* ctx) {
+  if (!c) return fail(ctx, RP_EINVAL, "cfg is NULL");
+  if (c->struct_size != sizeof(rp_stage_cfg)) return fail(ctx, RP_EINVAL, "cfg.struct_size %u != %zu", c->struct_size, sizeof(rp_stage_cfg));
+  if (c->n_layers < 0 || c->vocab < 0 || (c->n_layers == 0 && c->vocab == 0)) return fail(ctx, RP_EINVAL, "stage has neither layers nor a head");
+  if (c->hidden <= 0 || c->hidden % 8 || c->hidden > 8192) return fail(ctx, RP_EUNSUPPORTED, "hidden must be a multiple of 8 in (0, 8192]");
+  if (c->vocab % 8) return fail(ctx, RP_EUNSUPPORTED, "vocab must be a multiple of 8");
+  if (c->n_layers > 0) {
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(ctx, RP_EUNSUPPORTED, "head_dim must be 64 or 128");
+    if (c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads) return fail(ctx, RP_EINVAL, "n_q_heads must be a positive multiple of n_kv_heads");
+    if (c->ffn <= 0 || c->ffn % 8) return fail(ctx, RP_EUNSUPPORTED, "ffn must be a positive multiple of 8");
+    if (c->lora_rank < 0 || c->lora_rank % 8 || c->lora_rank > 64) return fail(ctx, RP_EUNSUPPORTED, "lora_rank must be a multiple of 8, at most 64");
+    if (c->lora_mask >> 7) return fail(ctx, RP_EINVAL, "lora_mask has unknown bits");
+    if (c->n_experts < 0 || c->top_k < 0 || (c->n_experts > 0 && (c->top_k <= 0 || c->top_k > c->n_experts))) return fail(ctx, RP_EINVAL, "bad n_experts/top_k");
+    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 1.f)) return fail(ctx, RP_EINVAL, "bad rms_eps / rope_base");
+  }
+  return RP_OK;
+}
+
+rp_status validate_shape(rp_ctx* ctx, int batch, int seq) {
+  if (batch <= 0 || seq <= 0) return fail(ctx, RP_EINVAL, "batch and seq must be positive");
+  if (((long)batch * seq) % 8) return fail(ctx, RP_EUNSUPPORTED, "batch*seq must be a multiple of 8");
+  if ((long)batch * seq > (1L << 24)) return fail(ctx, RP_EUNSUPPORTED, "batch*seq too large");
+  return RP_OK;
+}
+
+// ---- pointers into one layer's chunk ------------------------------------------------------------------------------
+struct LayerW {
+  const char* base;
+  const BlobLayout* L;
+  const bf16_t* t(int id) const { return L->elems[id] ? reinterpret_cast<const bf16_t*>(base + L->off[id]) : nullptr; }
+};
+struct LayerG {
+  char* base;   // may be NULL (no gradient blob)
+  const BlobLayout* L;
+  float* t(int id) const { return (base && L->elems[id]) ? reinterpret_cast<float*>(base + L->off[id]) : nullptr; }
+};
+
+struct Exec {
+  rp_ctx* ctx;
+  hipStream_t st;
+  Dims D;
+  int batch, seq;
+  long T;
+  char* ws;
+  Plan P;
+  hipError_t err = hipSuccess;
+  const char* where = "";
+
+  void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
+  template <typename Tp> Tp* at(size_t off) const { return reinterpret_cast<Tp*>(ws + off); }
+
+  // C[M,N] (bf16) = alpha * A * op(B) (+ second pair) (+ R)
+  void gemm_bf16(int layout, const void* A, long lda, const void* B, long ldb, void* C, long ldc, int M, int N, int K,
+                 float alpha = 1.f, const void* A2 = nullptr, long lda2 = 0, const void* B2 = nullptr, long ldb2 = 0,
+                 int K2 = 0, const void* R = nullptr, long ldr = 0) {
+    GemmArgs g; gemm_zero_args(g);
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
+    g.A2 = A2; g.lda2 = lda2; g.B2 = B2; g.ldb2 = ldb2; g.K2 = K2; g.R = R; g.ldr = ldr; g.epi = EPI_BF16;
+    chk(gemm_launch(st, layout, g), "gemm_bf16");
+  }
+  // C[M,N] (fp32) (+)= A^T * B : weight-gradient form, reduction over the rows of A and B
+  void gemm_wgrad(const void* A, long lda, const void* B, long ldb, float* C, long ldc, int M, int N, int K) {
+    if (!C) return;
+    GemmArgs g; gemm_zero_args(g);
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.beta = 1; g.epi = EPI_F32;
+    chk(gemm_launch(st, GEMM_TN, g), "gemm_wgrad");
+  }
+};
+
+// Which LoRA adapters feed a fused projection: ids of A/B tensors, row ranges in the fused output.
+struct FusedLora {
+  int n = 0;               // adapted projections
+  int a_id[3], b_id[3], row0[3], row1[3];
+};
+
+FusedLora fused_qkv(const Dims& D) {
+  FusedLora f;
+  const int a_ids[3] = {RP_T_LA_Q, RP_T_LA_K, RP_T_LA_V}, b_ids[3] = {RP_T_LB_Q, RP_T_LB_K, RP_T_LB_V};
+  const int r0[3] = {0, D.qd, D.qd + D.kd}, r1[3] = {D.qd, D.qd + D.kd, D.n1};
+  for (int i = 0; i < 3; ++i)
+    if (D.lora[i]) { f.a_id[f.n] = a_ids[i]; f.b_id[f.n] = b_ids[i]; f.row0[f.n] = r0[i]; f.row1[f.n] = r1[i]; ++f.n; }
+  return f;
+}
+FusedLora fused_gu(const Dims& D) {
+  FusedLora f;
+  const int a_ids[2] = {RP_T_LA_GATE, RP_T_LA_UP}, b_ids[2] = {RP_T_LB_GATE, RP_T_LB_UP};
+  const int r0[2] = {0, D.m}, r1[2] = {D.m, 2 * D.m};
+  for (int i = 0; i < 2; ++i)
+    if (D.lora[4 + i]) { f.a_id[f.n] = a_ids[i]; f.b_id[f.n] = b_ids[i]; f.row0[f.n] = r0[i]; f.row1[f.n] = r1[i]; ++f.n; }
+  return f;
+}
+FusedLora fused_single(bool on, int a_id, int b_id, int rows) {
+  FusedLora f;
+  if (on) { f.n = 1; f.a_id[0] = a_id; f.b_id[0] = b_id; f.row0[0] = 0; f.row1[0] = rows; }
+  return f;
+}
+
+// Builds the block-diagonal B [N, n*r] of a fused projection in the workspace; returns it (or the plain B when n == 1).
+const void* lora_b_matrix(Exec& X, const LayerW& W, const FusedLora& f, int N, size_t bd_off) {
+  if (f.n == 0) return nullptr;
+  if (f.n == 1 && f.row0[0] == 0 && f.row1[0] == N) return W.t(f.b_id[0]);
+  LoraSegs s{};
+  for (int i = 0; i < f.n; ++i) { s.src[i] = W.t(f.b_id[i]); s.row0[i] = f.row0[i]; s.row1[i] = f.row1[i]; s.col0[i] = i * X.D.r; }
+  X.chk(k_lora_blockdiag(X.st, X.at<void>(bd_off), N, f.n * X.D.r, s, X.D.r), "lora_blockdiag");
+  return X.at<void>(bd_off);
+}
+
+// Y[T,N] = X W^T (+ LoRA) (+ R).  u_buf receives U = s * X A^T (kept for the backward).
+void linear_fwd(Exec& X, const LayerW& W, int w_id, const FusedLora& f, size_t bd_off, const void* x, int K, void* y,
+                int N, void* u_buf, const void* R) {
+  const int nr = f.n * X.D.r;
+  const void* Bm = nullptr;
+  if (f.n) {
+    Bm = lora_b_matrix(X, W, f, N, bd_off);
+    X.gemm_bf16(GEMM_NT, x, K, W.t(f.a_id[0]), K, u_buf, nr, (int)X.T, nr, K, X.ctx->cfg.lora_scale);
+  }
+  X.gemm_bf16(GEMM_NT, x, K, W.t(w_id), K, y, N, (int)X.T, N, K, 1.f, f.n ? u_buf : nullptr, nr, Bm, nr, f.n ? nr : 0, R, N);
+}
+
+// dX[T,K] = dY W (+ LoRA);  dW += dY^T X;  LoRA gradients.  u_buf = U saved by the forward, ud = scratch [T, n*r].
+void linear_bwd(Exec& X, const LayerW& W, const LayerG& G, int w_id, const FusedLora& f, size_t bd_off, const void* dy,
+                int N, const void* x, int K, void* dx, const void* u_buf) {
+  const int nr = f.n * X.D.r;
+  void* ud = X.at<void>(X.P.ud);
+  const void* Bm = nullptr;
+  if (f.n) {
+    Bm = lora_b_matrix(X, W, f, N, bd_off);
+    X.gemm_bf16(GEMM_NN, dy, N, Bm, nr, ud, nr, (int)X.T, nr, N, X.ctx->cfg.lora_scale);
+  }
+  X.gemm_bf16(GEMM_NN, dy, N, W.t(w_id), K, dx, K, (int)X.T, K, N, 1.f, f.n ? ud : nullptr, nr, f.n ? W.t(f.a_id[0]) : nullptr,
+              K, f.n ? nr : 0);
+  X.gemm_wgrad(dy, N, x, K, G.t(w_id), K, N, K, (int)X.T);
+  if (f.n) {
+    // the adapted A matrices are adjacent in both blobs, so one product fills all of them
+    X.gemm_wgrad(ud, nr, x, K, G.t(f.a_id[0]), K, nr, K, (int)X.T);
+    for (int i = 0; i < f.n; ++i)
+      X.gemm_wgrad(reinterpret_cast<const bf16_t*>(dy) + f.row0[i], N, reinterpret_cast<const bf16_t*>(u_buf) + i * X.D.r, nr,
+                   G.t(f.b_id[i]), X.D.r, f.row1[i] - f.row0[i], X.D.r, (int)X.T);
+  }
+}
+
+void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z) {
+  const Dims& D = X.D;
+  const LayerBuf& b = X.P.lb;
+  const rp_stage_cfg& c = X.ctx->cfg;
+  const int T = (int)X.T;
+  auto S = [&](size_t off) { return reinterpret_cast<void*>(set + off); };
+  bf16_t* qkv = reinterpret_cast<bf16_t*>(S(b.qkv));
+
+  X.chk(k_rmsnorm_fwd(X.st, x, W.t(RP_T_G1), S(b.n1), (float*)S(b.rstd1), T, D.h, c.rms_eps), "rmsnorm1");
+  linear_fwd(X, W, RP_T_WQKV, fused_qkv(D), X.P.bd1, S(b.n1), D.h, qkv, D.n1, S(b.u1), nullptr);
+  X.chk(k_qknorm_rope(X.st, 0, D.d, qkv, qkv + D.qd, D.n1, D.n1, S(b.qr), S(b.kr), D.qd, D.kd, W.t(RP_T_GQ), W.t(RP_T_GK),
+                      (float*)S(b.rstd_q), (float*)S(b.rstd_k), nullptr, nullptr, 0, nullptr, nullptr,
+                      X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps), "qknorm_rope");
+  X.chk(k_attn_fwd(X.st, S(b.qr), S(b.kr), qkv + D.qd + D.kd, S(b.o), (float*)S(b.lse), D.qd, D.kd, D.n1, D.qd, X.batch,
+                   X.seq, D.a, D.kh, D.d), "attn_fwd");
+  linear_fwd(X, W, RP_T_WO, fused_single(D.lora[3], RP_T_LA_O, RP_T_LB_O, D.h), 0, S(b.o), D.qd, S(b.y), D.h, S(b.u2), x);
+  X.chk(k_rmsnorm_fwd(X.st, S(b.y), W.t(RP_T_G2), S(b.n2), (float*)S(b.rstd2), T, D.h, c.rms_eps), "rmsnorm2");
+  linear_fwd(X, W, RP_T_WGU, fused_gu(D), X.P.bd3, S(b.n2), D.h, S(b.gu), 2 * D.m, S(b.u3), nullptr);
+  X.chk(k_swiglu_fwd(X.st, S(b.gu), S(b.act), T, D.m), "swiglu");
+  linear_fwd(X, W, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, S(b.act), D.m, z, D.h, S(b.u4), S(b.y));
+}
+
+// dz: gradient of the layer output; dx_out receives the gradient of the layer input x.
+void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const void* x, const void* dz, void* dx_out) {
+  const Dims& D = X.D;
+  const LayerBuf& b = X.P.lb;
+  const rp_stage_cfg& c = X.ctx->cfg;
+  const int T = (int)X.T;
+  auto S = [&](size_t off) { return reinterpret_cast<void*>(set + off); };
+  bf16_t* qkv = reinterpret_cast<bf16_t*>(S(b.qkv));
+  bf16_t* dqkv = X.at<bf16_t>(X.P.dqkv);
+  void* dy = X.at<void>(X.P.tA);
+
+  // z = y + down(act)
+  linear_bwd(X, W, G, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, dz, D.h, S(b.act), D.m,
+             X.at<void>(X.P.dact), S(b.u4));
+  X.chk(k_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), X.at<void>(X.P.dgu), T, D.m), "swiglu_bwd");
+  linear_bwd(X, W, G, RP_T_WGU, fused_gu(D), X.P.bd3, X.at<void>(X.P.dgu), 2 * D.m, S(b.n2), D.h, X.at<void>(X.P.dn), S(b.u3));
+  X.chk(k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, S(b.y), W.t(RP_T_G2), (const float*)S(b.rstd2), dz, dy, G.t(RP_T_G2), T, D.h), "rmsnorm2_bwd");
+  // y = x + o_proj(o)
+  linear_bwd(X, W, G, RP_T_WO, fused_single(D.lora[3], RP_T_LA_O, RP_T_LB_O, D.h), 0, dy, D.h, S(b.o), D.qd,
+             X.at<void>(X.P.dout), S(b.u2));
+  X.chk(k_attn_delta(X.st, S(b.o), X.at<void>(X.P.dout), X.at<float>(X.P.delta), D.qd, D.qd, X.batch, X.seq, D.a, D.d), "attn_delta");
+  X.chk(k_attn_bwd(X.st, S(b.qr), S(b.kr), qkv + D.qd + D.kd, X.at<void>(X.P.dout), (const float*)S(b.lse),
+                   X.at<float>(X.P.delta), X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), dqkv + D.qd + D.kd, D.qd, D.kd, D.n1, D.qd,
+                   D.qd, D.kd, D.n1, X.batch, X.seq, D.a, D.kh, D.d), "attn_bwd");
+  X.chk(k_qknorm_rope(X.st, 1, D.d, X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), D.qd, D.kd, dqkv, dqkv + D.qd, D.n1, D.n1,
+                      W.t(RP_T_GQ), W.t(RP_T_GK), (float*)S(b.rstd_q), (float*)S(b.rstd_k), qkv, qkv + D.qd, D.n1,
+                      G.t(RP_T_GQ), G.t(RP_T_GK), X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps), "qknorm_rope_bwd");
+  linear_bwd(X, W, G, RP_T_WQKV, fused_qkv(D), X.P.bd1, dqkv, D.n1, S(b.n1), D.h, X.at<void>(X.P.dn), S(b.u1));
+  X.chk(k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, x, W.t(RP_T_G1), (const float*)S(b.rstd1), dy, dx_out, G.t(RP_T_G1), T, D.h), "rmsnorm1_bwd");
+}
+
+rp_status check_call(rp_ctx* ctx, int slot_id, int batch, int seq, const void* ws, size_t ws_bytes, size_t need) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (slot_id < 0 || slot_id >= RP_MAX_SLOTS) return fail(ctx, RP_EINVAL, "slot_id %d out of range", slot_id);
+  rp_status s = validate_shape(ctx, batch, seq);
+  if (s != RP_OK) return s;
+  if (!ctx->slots[slot_id].valid) return fail(ctx, RP_ESTATE, "slot %d holds no weights (upload or bind first)", slot_id);
+  if (!ws) return fail(ctx, RP_EINVAL, "workspace is NULL");
+  if (ws_bytes < need) return fail(ctx, RP_ENOMEM, "workspace too small: %zu < %zu", ws_bytes, need);
+  if (reinterpret_cast<uintptr_t>(ws) % 256) return fail(ctx, RP_EINVAL, "workspace must be 256-byte aligned");
+  return RP_OK;
+}
+
+rp_status wait_chunk(rp_ctx* ctx, Slot& sl, int chunk) {
+  if (sl.gated) HIP_TRY(ctx, hipStreamWaitEvent(ctx->compute, sl.ev[chunk], 0));
+  return RP_OK;
+}
+
+rp_status finish_call(rp_ctx* ctx, Slot& sl, Exec& X) {
+  if (X.err != hipSuccess) return fail(ctx, RP_EHIP, "%s: %s", X.where, hipGetErrorString(X.err));
+  HIP_TRY(ctx, hipEventRecord(sl.free_ev, ctx->compute));
+  sl.used = true;
+  return RP_OK;
+}
+
+}  // namespace
+
+// ==================================================================================================== C ABI
+extern "C" {
+
+const char* rp_last_error(const rp_ctx* ctx) { return ctx ? ctx->err : g_err; }
+
+rp_status rp_query_sizes(const rp_stage_cfg* cfg, int batch, int seq, size_t* weight_blob_bytes, size_t* grad_blob_bytes,
+                         size_t* workspace_bytes_out) {
+  rp_status s = validate_cfg(cfg, nullptr);
+  if (s != RP_OK) return s;
+  if (weight_blob_bytes) *weight_blob_bytes = blob_layout(*cfg, false).total;
+  if (grad_blob_bytes) *grad_blob_bytes = blob_layout(*cfg, true).total;
+  if (workspace_bytes_out) {
+    s = validate_shape(nullptr, batch, seq);
+    if (s != RP_OK) return s;
+    *workspace_bytes_out = workspace_bytes(make_plan(*cfg, batch, seq), *cfg);
+  }
+  return RP_OK;
+}
+
+static rp_status layout_query(const rp_stage_cfg* cfg, bool grads, int layer, int id, size_t* off, size_t* n) {
+  rp_status s = validate_cfg(cfg, nullptr);
+  if (s != RP_OK) return s;
+  if (id < 0 || id >= RP_T_COUNT || layer < 0 || layer > cfg->n_layers) return fail(nullptr, RP_EINVAL, "bad layer/tensor id");
+  const BlobLayout B = blob_layout(*cfg, grads);
+  const bool head = is_head_tensor(id);
+  if (head != (layer == cfg->n_layers)) { if (off) *off = 0; if (n) *n = 0; return RP_OK; }
+  if (off) *off = (head ? B.layer_bytes * (size_t)cfg->n_layers : B.layer_bytes * (size_t)layer) + B.off[id];
+  if (n) *n = B.elems[id];
+  return RP_OK;
+}
+rp_status rp_weight_layout(const rp_stage_cfg* cfg, int layer, int id, size_t* off, size_t* n) { return layout_query(cfg, false, layer, id, off, n); }
+rp_status rp_grad_layout(const rp_stage_cfg* cfg, int layer, int id, size_t* off, size_t* n) { return layout_query(cfg, true, layer, id, off, n); }
+
+rp_status rp_weight_chunk(const rp_stage_cfg* cfg, int layer, size_t* begin, size_t* end) {
+  rp_status s = validate_cfg(cfg, nullptr);
+  if (s != RP_OK) return s;
+  if (layer < 0 || layer > cfg->n_layers) return fail(nullptr, RP_EINVAL, "bad layer");
+  const BlobLayout B = blob_layout(*cfg, false);
+  const size_t b0 = B.layer_bytes * (size_t)layer;
+  if (begin) *begin = b0;
+  if (end) *end = layer == cfg->n_layers ? b0 + B.head_bytes : b0 + B.layer_bytes;
+  return RP_OK;
+}
+
+rp_status rp_ctx_create(rp_ctx** out, int device, void* compute_stream, void* copy_stream, const rp_stage_cfg* cfg) {
+  if (!out) return fail(nullptr, RP_EINVAL, "out is NULL");
+  *out = nullptr;
+  rp_status s = validate_cfg(cfg, nullptr);
+  if (s != RP_OK) return s;
+  if (!compute_stream || !copy_stream) return fail(nullptr, RP_EINVAL, "both streams must be non-NULL");
+  HIP_TRY(nullptr, hipSetDevice(device));
+  rp_ctx* c = new (std::nothrow) rp_ctx();
+  if (!c) return fail(nullptr, RP_ENOMEM, "out of host memory");
+  c->cfg = *cfg; c->device = device;
+  c->compute = reinterpret_cast<hipStream_t>(compute_stream);
+  c->copy = reinterpret_cast<hipStream_t>(copy_stream);
+  c->wl = blob_layout(*cfg, false);
+  c->gl = blob_layout(*cfg, true);
+  c->err[0] = 0;
+  const int nev = cfg->n_layers + 1;
+  for (int i = 0; i < RP_MAX_SLOTS; ++i) {
+    c->slots[i].ev = new (std::nothrow) hipEvent_t[nev]();
+    if (!c->slots[i].ev) { rp_ctx_destroy(c); return fail(nullptr, RP_ENOMEM, "out of host memory"); }
+    for (int j = 0; j < nev; ++j)
+      if (hipEventCreateWithFlags(&c->slots[i].ev[j], hipEventDisableTiming) != hipSuccess) { rp_ctx_destroy(c); return fail(nullptr, RP_EHIP, "hipEventCreate failed"); }
+    if (hipEventCreateWithFlags(&c->slots[i].free_ev, hipEventDisableTiming) != hipSuccess) { rp_ctx_destroy(c); return fail(nullptr, RP_EHIP, "hipEventCreate failed"); }
+  }
+  *out = c;
+  return RP_OK;
+}
+
+rp_status rp_ctx_destroy(rp_ctx* c) {
+  if (!c) return RP_OK;
+  for (int i = 0; i < RP_MAX_SLOTS; ++i) {
+    if (c->slots[i].ev) {
+      for (int j = 0; j <= c->cfg.n_layers; ++j) if (c->slots[i].ev[j]) (void)hipEventDestroy(c->slots[i].ev[j]);
+      delete[] c->slots[i].ev;
+    }
+    if (c->slots[i].free_ev) (void)hipEventDestroy(c->slots[i].free_ev);
+  }
+  delete c;
+  return RP_OK;
+}
+
+rp_status rp_stage_upload_weights(rp_ctx* ctx, int slot_id, void* dev_slot, const void* host_blob, size_t bytes) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (slot_id < 0 || slot_id >= RP_MAX_SLOTS) return fail(ctx, RP_EINVAL, "slot_id %d out of range", slot_id);
+  if (!dev_slot || !host_blob) return fail(ctx, RP_EINVAL, "NULL buffer");
+  if (bytes != ctx->wl.total) return fail(ctx, RP_EINVAL, "bytes %zu != weight blob size %zu", bytes, ctx->wl.total);
+  if (reinterpret_cast<uintptr_t>(dev_slot) % 256) return fail(ctx, RP_EINVAL, "dev_slot must be 256-byte aligned");
+  Slot& sl = ctx->slots[slot_id];
+  if (sl.used) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, sl.free_ev, 0));
+  const int L = ctx->cfg.n_layers;
+  for (int l = 0; l <= L; ++l) {
+    const size_t b0 = ctx->wl.layer_bytes * (size_t)l;
+    const size_t n = l == L ? ctx->wl.head_bytes : ctx->wl.layer_bytes;
+    if (n) HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(dev_slot) + b0, static_cast<const char*>(host_blob) + b0, n, hipMemcpyHostToDevice, ctx->copy));
+    HIP_TRY(ctx, hipEventRecord(sl.ev[l], ctx->copy));
+  }
+  sl.dev = dev_slot; sl.bytes = bytes; sl.valid = true; sl.gated = true; sl.used = false;
+  return RP_OK;
+}
+
+rp_status rp_stage_bind_weights(rp_ctx* ctx, int slot_id, void* dev_slot, size_t bytes) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (slot_id < 0 || slot_id >= RP_MAX_SLOTS) return fail(ctx, RP_EINVAL, "slot_id %d out of range", slot_id);
+  if (!dev_slot) return fail(ctx, RP_EINVAL, "NULL buffer");
+  if (bytes != ctx->wl.total) return fail(ctx, RP_EINVAL, "bytes %zu != weight blob size %zu", bytes, ctx->wl.total);
+  if (reinterpret_cast<uintptr_t>(dev_slot) % 256) return fail(ctx, RP_EINVAL, "dev_slot must be 256-byte aligned");
+  Slot& sl = ctx->slots[slot_id];
+  sl.dev = dev_slot; sl.bytes = bytes; sl.valid = true; sl.gated = false; sl.used = false;
+  return RP_OK;
+}
+
+rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_out, void* const* layer_inputs_out,
+                           const float* router_logits, int batch, int seq, void* workspace, size_t workspace_bytes_in) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (ctx->cfg.n_layers == 0) return fail(ctx, RP_EINVAL, "stage has no decoder layers");
+  if (ctx->cfg.n_experts > 0) return fail(ctx, RP_EUNSUPPORTED, "MoE stages are not implemented");
+  (void)router_logits;
+  const Plan P = make_plan(ctx->cfg, batch > 0 ? batch : 1, seq > 0 ? seq : 8);
+  rp_status s = check_call(ctx, slot_id, batch, seq, workspace, workspace_bytes_in, P.fwd_bytes);
+  if (s != RP_OK) return s;
+  if (!x_in || !x_out || x_in == x_out) return fail(ctx, RP_EINVAL, "x_in / x_out must be distinct non-NULL buffers");
+  Slot& sl = ctx->slots[slot_id];
+  Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
+  const int L = ctx->cfg.n_layers;
+  const size_t act_bytes = (size_t)X.T * X.D.h * 2;
+  X.chk(k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base), "rope_table");
+  char* set = X.ws + P.layer0;
+  void* pp[2] = {set + P.lb.z, X.ws + P.layer0 + P.layer_stride};
+  const void* x = x_in;
+  for (int l = 0; l < L; ++l) {
+    s = wait_chunk(ctx, sl, l);
+    if (s != RP_OK) return s;
+    if (layer_inputs_out && layer_inputs_out[l] && layer_inputs_out[l] != x) X.chk(k_copy16(X.st, x, layer_inputs_out[l], (long)act_bytes), "checkpoint copy");
+    void* z = (l == L - 1) ? x_out : pp[l & 1];
+    const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
+    layer_forward(X, W, set, x, z);
+    x = z;
+  }
+  return finish_call(ctx, sl, X);
+}
+
+rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, const void* x_in, const void* dy, void* dx, void* x_out, void* grads,
+                            const float* router_logits, float* d_router_logits, int batch, int seq, void* workspace,
+                            size_t workspace_bytes_in) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (ctx->cfg.n_layers == 0) return fail(ctx, RP_EINVAL, "stage has no decoder layers");
+  if (ctx->cfg.n_experts > 0) return fail(ctx, RP_EUNSUPPORTED, "MoE stages are not implemented");
+  (void)router_logits; (void)d_router_logits;
+  const Plan P = make_plan(ctx->cfg, batch > 0 ? batch : 1, seq > 0 ? seq : 8);
+  rp_status s = check_call(ctx, slot_id, batch, seq, workspace, workspace_bytes_in, P.bwd_bytes);
+  if (s != RP_OK) return s;
+  if (!x_in || !dy || !dx) return fail(ctx, RP_EINVAL, "x_in, dy and dx must be non-NULL");
+  if (dx == x_in || dx == dy) return fail(ctx, RP_EINVAL, "dx must not alias x_in or dy");
+  if (!grads && ctx->gl.total > 0) return fail(ctx, RP_EINVAL, "grads is NULL but the stage has trainable tensors");
+  Slot& sl = ctx->slots[slot_id];
+  Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
+  const int L = ctx->cfg.n_layers;
+  const size_t act_bytes = (size_t)X.T * X.D.h * 2;
+  X.chk(k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base), "rope_table");
+  auto set_of = [&](int l) { return X.ws + P.layer0 + P.layer_stride * (size_t)l; };
+  // recomputation: forward over the stage keeping every layer's internals
+  const void* x = x_in;
+  for (int l = 0; l < L; ++l) {
+    s = wait_chunk(ctx, sl, l);
+    if (s != RP_OK) return s;
+    const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
+    void* z = set_of(l) + P.lb.z;
+    layer_forward(X, W, set_of(l), x, z);
+    x = z;
+  }
+  if (x_out) X.chk(k_copy16(X.st, x, x_out, (long)act_bytes), "x_out copy");
+  // backward in reverse layer order
+  const void* dz = dy;
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
+    const LayerG G{grads ? static_cast<char*>(grads) + ctx->gl.layer_bytes * (size_t)l : nullptr, &ctx->gl};
+    const void* xl = l == 0 ? x_in : set_of(l - 1) + P.lb.z;
+    void* dxl = l == 0 ? dx : X.at<void>(P.tB);
+    layer_backward(X, W, G, set_of(l), xl, dz, dxl);
+    dz = dxl;
+  }
+  return finish_call(ctx, sl, X);
+}
+
+rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const int32_t* labels, float* loss_out, void* dx,
+                               void* grads, float grad_scale, int batch, int seq, void* workspace, size_t workspace_bytes_in) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (ctx->cfg.vocab == 0) return fail(ctx, RP_EINVAL, "stage has no LM head");
+  const Plan P = make_plan(ctx->cfg, batch > 0 ? batch : 1, seq > 0 ? seq : 8);
+  rp_status s = check_call(ctx, slot_id, batch, seq, workspace, workspace_bytes_in, P.head_bytes);
+  if (s != RP_OK) return s;
+  if (!x || !labels || !loss_out || !dx) return fail(ctx, RP_EINVAL, "x, labels, loss_out and dx must be non-NULL");
+  if (dx == x) return fail(ctx, RP_EINVAL, "dx must not alias x");
+  Slot& sl = ctx->slots[slot_id];
+  Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
+  const Dims& D = X.D;
+  const int T = (int)X.T, L = ctx->cfg.n_layers;
+  s = wait_chunk(ctx, sl, L);
+  if (s != RP_OK) return s;
+  const char* hb = static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)L;
+  const LayerW W{hb, &ctx->wl};
+  const bool train = grads && ctx->cfg.train_base;
+  const LayerG G{train ? static_cast<char*>(grads) + ctx->gl.layer_bytes * (size_t)L : nullptr, &ctx->gl};
+  const bf16_t* Wv = W.t(RP_T_WV);
+
+  X.chk(k_rmsnorm_fwd(X.st, x, W.t(RP_T_GF), X.at<void>(P.h_xf), X.at<float>(P.h_rstd), T, D.h, ctx->cfg.rms_eps), "final norm");
+  X.chk(k_fill_u32(X.st, X.at<void>(P.h_zlab), T, 0u), "zlab fill");
+  {  // sweep 1: logits tile by tile, reduced to per-token (max, sum exp) partials; nothing of size T x V is stored
+    GemmArgs g; gemm_zero_args(g);
+    g.A = Wv; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = D.V; g.N = T; g.K = D.h; g.epi = EPI_CE_STATS;
+    g.labels = labels; g.zlab = X.at<float>(P.h_zlab); g.part = X.at<float2>(P.h_part); g.part_ld = T;
+    X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head sweep 1");
+  }
+  X.chk(k_ce_lse(X.st, X.at<float2>(P.h_part), P.head_parts, T, X.at<float>(P.h_lse), T), "ce lse");
+  X.chk(k_ce_finalize(X.st, X.at<float>(P.h_lse), X.at<float>(P.h_zlab), labels, grad_scale, X.at<float>(P.h_coef), loss_out, T), "ce finalize");
+  // sweep 2: per vocabulary chunk recompute the logits, turn them into dZ^T (bf16), and feed dX and dW
+  for (int v0 = 0, ci = 0; v0 < D.V; v0 += P.head_chunk, ++ci) {
+    const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
+    const bf16_t* Wc = Wv + (size_t)v0 * D.h;
+    GemmArgs g; gemm_zero_args(g);
+    g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h; g.epi = EPI_CE_DZ;
+    g.C = X.at<void>(P.h_dzt); g.ldc = T; g.labels = labels; g.lse = X.at<float>(P.h_lse); g.coef = X.at<float>(P.h_coef);
+    g.row_offset = v0;
+    X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head sweep 2");
+    GemmArgs d; gemm_zero_args(d);   // dXf[T, h] (+)= dZ^T^T . W_c   (reduction over the chunk's vocabulary rows)
+    d.A = X.at<void>(P.h_dzt); d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = X.at<void>(P.h_dxacc);
+    d.ldc = D.h; d.beta = ci > 0; d.epi = EPI_F32;
+    X.chk(gemm_launch(X.st, GEMM_TN, d), "lm head dX");
+    if (G.t(RP_T_WV)) {
+      GemmArgs w; gemm_zero_args(w);  // dW_c[vc, h] += dZ^T . xf
+      w.A = X.at<void>(P.h_dzt); w.lda = T; w.B = X.at<void>(P.h_xf); w.ldb = D.h; w.M = vc; w.N = D.h; w.K = T;
+      w.C = G.t(RP_T_WV) + (size_t)v0 * D.h; w.ldc = D.h; w.beta = 1; w.epi = EPI_F32;
+      X.chk(gemm_launch(X.st, GEMM_NN, w), "lm head dW");
+    }
+  }
+  X.chk(k_rmsnorm_bwd(X.st, X.at<void>(P.h_dxacc), 1, x, W.t(RP_T_GF), X.at<float>(P.h_rstd), nullptr, dx, G.t(RP_T_GF), T, D.h), "final norm bwd");
+  return finish_call(ctx, sl, X);
+}
+
+// ---- kernel-level entry points (unit parity tests) ----------------------------------------------------------------
+#define OP_RET(e) return ((e) == hipSuccess ? RP_OK : fail(nullptr, RP_EHIP, "%s", hipGetErrorString(e)))
+
+rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const void* B, void* C, int M, int N, int K,
+                     long lda, long ldb, long ldc, float alpha, int beta, const void* A2, const void* B2, int K2, long lda2,
+                     long ldb2, const void* R, long ldr, int tile) {
+  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 4)
+    return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad arguments");
+  if ((layout != GEMM_NT) && (N % 8 || (layout == GEMM_TN && M % 8))) return fail(nullptr, RP_EINVAL, "rp_op_gemm: transposed operands need multiples of 8");
+  GemmArgs g; gemm_zero_args(g);
+  g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.alpha = alpha; g.beta = beta;
+  g.A2 = A2; g.B2 = B2; g.K2 = (A2 && B2) ? K2 : 0; g.lda2 = lda2; g.ldb2 = ldb2; g.R = R; g.ldr = ldr;
+  g.epi = out_f32 == 2 ? EPI_F32_ATOMIC : (out_f32 ? EPI_F32 : EPI_BF16);
+  hipError_t e = gemm_launch(reinterpret_cast<hipStream_t>(stream), layout, g, tile);
+  OP_RET(e);
+}
+
+rp_status rp_op_rmsnorm_fwd(void* stream, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps) {
+  if (!x || !g || !y || h % 8 || h > 8192) return fail(nullptr, RP_EINVAL, "rp_op_rmsnorm_fwd: bad arguments");
+  hipError_t e = k_rmsnorm_fwd(reinterpret_cast<hipStream_t>(stream), x, g, y, rstd, T, h, eps);
+  OP_RET(e);
+}
+
+rp_status rp_op_rmsnorm_bwd(void* stream, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
+                            const void* dres, void* dx, float* dg, int T, int h) {
+  if (!dy || !x || !g || !rstd || !dx || h % 8 || h > 8192) return fail(nullptr, RP_EINVAL, "rp_op_rmsnorm_bwd: bad arguments");
+  hipError_t e = k_rmsnorm_bwd(reinterpret_cast<hipStream_t>(stream), dy, dy_is_f32, x, g, rstd, dres, dx, dg, T, h);
+  OP_RET(e);
+}
+
+rp_status rp_op_rope_table(void* stream, void* cs, int seq, int d, float base) {
+  if (!cs || (d != 64 && d != 128)) return fail(nullptr, RP_EINVAL, "rp_op_rope_table: bad arguments");
+  hipError_t e = k_rope_table(reinterpret_cast<hipStream_t>(stream), static_cast<float2*>(cs), seq, d, base);
+  OP_RET(e);
+}
+
+rp_status rp_op_qknorm_rope(void* stream, int bwd, int d, const void* in_q, const void* in_k, long ld_in_q, long ld_in_k,
+                            void* out_q, void* out_k, long ld_out_q, long ld_out_k, const void* gq, const void* gk, float* rstd_q,
+                            float* rstd_k, const void* raw_q, const void* raw_k, long ld_raw, float* dgq, float* dgk,
+                            const void* cs, int T, int seq, int a, int k, int use_norm, float eps) {
+  if (!in_q || !in_k || !out_q || !out_k || !cs || (d != 64 && d != 128)) return fail(nullptr, RP_EINVAL, "rp_op_qknorm_rope: bad arguments");
+  if (use_norm && (!gq || !gk || !rstd_q || !rstd_k || (bwd && (!raw_q || !raw_k)))) return fail(nullptr, RP_EINVAL, "rp_op_qknorm_rope: norm buffers missing");
+  hipError_t e = k_qknorm_rope(reinterpret_cast<hipStream_t>(stream), bwd, d, in_q, in_k, ld_in_q, ld_in_k, out_q, out_k, ld_out_q,
+                               ld_out_k, gq, gk, rstd_q, rstd_k, raw_q, raw_k, ld_raw, dgq, dgk, static_cast<const float2*>(cs), T,
+                               seq, a, k, use_norm, eps);
+  OP_RET(e);
+}
+
+rp_status rp_op_swiglu_fwd(void* stream, const void* gu, void* act, long T, int m) {
+  if (!gu || !act || m % 8) return fail(nullptr, RP_EINVAL, "rp_op_swiglu_fwd: bad arguments");
+  hipError_t e = k_swiglu_fwd(reinterpret_cast<hipStream_t>(stream), gu, act, T, m);
+  OP_RET(e);
+}
+
+rp_status rp_op_swiglu_bwd(void* stream, const void* dact, const void* gu, void* dgu, long T, int m) {
+  if (!dact || !gu || !dgu || m % 8) return fail(nullptr, RP_EINVAL, "rp_op_swiglu_bwd: bad arguments");
+  hipError_t e = k_swiglu_bwd(reinterpret_cast<hipStream_t>(stream), dact, gu, dgu, T, m);
+  OP_RET(e);
+}
+
+rp_status rp_op_attn_fwd(void* stream, const void* q, const void* k, const void* v, void* o, float* lse, long ldq, long ldk,
+                         long ldv, long ldo, int batch, int seq, int a, int kh, int d) {
+  if (!q || !k || !v || !o || !lse || (d != 64 && d != 128) || a <= 0 || kh <= 0 || a % kh || ldq % 8 || ldk % 8 || ldv % 8 || ldo % 8)
+    return fail(nullptr, RP_EINVAL, "rp_op_attn_fwd: bad arguments");
+  hipError_t e = k_attn_fwd(reinterpret_cast<hipStream_t>(stream), q, k, v, o, lse, ldq, ldk, ldv, ldo, batch, seq, a, kh, d);
+  OP_RET(e);
+}
+
+rp_status rp_op_attn_bwd(void* stream, const void* q, const void* k, const void* v, const void* o, const void* dout,
+                         const float* lse, float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv, long ldo,
+                         long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh, int d) {
+  if (!q || !k || !v || !o || !dout || !lse || !delta || !dq || !dk || !dv || (d != 64 && d != 128) || a <= 0 || kh <= 0 || a % kh)
+    return fail(nullptr, RP_EINVAL, "rp_op_attn_bwd: bad arguments");
+  if (ldq % 8 || ldk % 8 || ldv % 8 || ldo % 8 || lddo % 8 || lddq % 8 || lddk % 8 || lddv % 8) return fail(nullptr, RP_EINVAL, "rp_op_attn_bwd: strides must be multiples of 8");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e = k_attn_delta(st, o, dout, delta, ldo, lddo, batch, seq, a, d);
+  if (e == hipSuccess) e = k_attn_bwd(st, q, k, v, dout, lse, delta, dq, dk, dv, ldq, ldk, ldv, lddo, lddq, lddk, lddv, batch, seq, a, kh, d);
+  OP_RET(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+"""Shared helpers of the GPU parity tests: run one workload through the oracle and through the HIP library."""
+import numpy as np
+
+from oracle import StageConfig, stage
+
+
+def oracle_cfg(c):
+    return StageConfig(n_layers=c["n_layers"], hidden=c["hidden"], n_q_heads=c["n_q_heads"], n_kv_heads=c["n_kv_heads"],
+                       head_dim=c["head_dim"], ffn=c["ffn"], vocab=c["vocab"], n_experts=c["n_experts"], top_k=c["top_k"],
+                       rope_base=c.get("rope_base", 1.0e6), rms_eps=c.get("rms_eps", 1.0e-6), qk_norm=bool(c.get("qk_norm", 1)),
+                       lora_rank=c["lora_rank"], lora_scale=c.get("lora_scale", 1.0), lora_targets=tuple(c["lora"]),
+                       train_base=bool(c["train_base"]))
+
+
+def cast_tree(obj, dtype):
+    if isinstance(obj, dict):
+        return {k: cast_tree(v, dtype) for k, v in obj.items()}
+    if isinstance(obj, (list, tuple)):
+        return type(obj)(cast_tree(v, dtype) for v in obj)
+    if isinstance(obj, np.ndarray) and obj.dtype.kind == "f":
+        return obj.astype(dtype)
+    return obj
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def oracle_chain(c, wl, dtype=np.float64, grad_scale=1.0):
+    """stage forward -> (head loss, dx) -> stage backward; without a head, dy comes from the workload."""
+    cfg = oracle_cfg(c)
+    layers = cast_tree(wl["layers"], dtype)
+    x = wl["x"].astype(dtype)
+    res = {}
+    if wl["head"] is not None:
+        out, _ = stage.stage_fwd(x, layers, cfg, c["batch"], c["seq"])
+        loss, dy, gh = stage.head_fwd_bwd(out, cast_tree(wl["head"], dtype), wl["labels"], cfg, grad_scale,
+                                          want_dW=cfg.train_base)
+        res.update(loss=float(loss), head_dx=dy, head_grads=gh)
+    else:
+        dy = wl["dy"].astype(dtype)
+    if c["n_layers"] > 0:
+        out, dx, grads = stage.stage_fwd_bwd(x, dy, layers, cfg, c["batch"], c["seq"])
+        res.update(out=out, dx=dx, grads=grads)
+    return res
+
+
+def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True):
+    import torch
+    cfg = harness.cfg_from_dict(c, with_head=wl["head"] is not None)
+    R = harness.StageRunner(cfg, c["batch"], c["seq"])
+    try:
+        host = R.pinned_blob(wl["layers"], wl["head"])
+        if use_upload:
+            R.upload(host)
+        else:
+            R.slots[0].copy_(host)
+            torch.cuda.synchronize()
+            R.bind()
+        x = harness.bf16_tensor(wl["x"], R.device)
+        torch.cuda.synchronize()
+        res = {}
+        if wl["head"] is not None:
+            labels = torch.from_numpy(wl["labels"]).to(R.device)
+            torch.cuda.synchronize()
+            if c["n_layers"] > 0:
+                out = R.forward(x)
+            else:
+                out = x
+            loss, dy = R.head(out, labels, grad_scale, train=bool(c["train_base"]))
+            R.sync()
+            res.update(loss=float(loss.item()), head_dx=harness.to_f32(dy))
+        else:
+            dy = harness.bf16_tensor(wl["dy"], R.device)
+            torch.cuda.synchronize()
+        if c["n_layers"] > 0:
+            out2, dx = R.backward(x, dy)
+            R.sync()
+            res.update(out=harness.to_f32(out2), dx=harness.to_f32(dx))
+        R.sync()
+        layer_g, head_g = harness.unpack_grads(cfg, R.grads)
+        res.update(grads=layer_g, head_grads=head_g)
+        return res
+    finally:
+        R.close()
+
+
+def compare_chain(ref, got, c, tol=2e-2, loss_tol=1e-4, report=None):
+    """Asserts the task's bounds: rel-L2 <= tol on outputs and every gradient tensor, |dloss|/|loss| <= loss_tol."""
+    errs = {}
+    if "loss" in ref:
+        errs["loss"] = abs(got["loss"] - ref["loss"]) / abs(ref["loss"])
+        errs["head_dx"] = rel_l2(got["head_dx"], ref["head_dx"])
+        for k, v in ref["head_grads"].items():
+            if k in got["head_grads"] and got["head_grads"][k] is not None:
+                errs["head." + k] = rel_l2(got["head_grads"][k], v)
+    if "out" in ref:
+        errs["out"] = rel_l2(got["out"], ref["out"])
+        errs["dx"] = rel_l2(got["dx"], ref["dx"])
+        for li, g in enumerate(ref["grads"]):
+            gg = got["grads"][li]
+            for k, v in g.items():
+                if k == "lora":
+                    for nm, (dA, dB) in v.items():
+                        errs["L%d.lora.%s.A" % (li, nm)] = rel_l2(gg["lora"][nm][0], dA)
+                        errs["L%d.lora.%s.B" % (li, nm)] = rel_l2(gg["lora"][nm][1], dB)
+                elif k in gg and gg[k] is not None:
+                    errs["L%d.%s" % (li, k)] = rel_l2(gg[k], v)
+    if report is not None:
+        report.update(errs)
+    bad = {k: v for k, v in errs.items() if v > (loss_tol if k == "loss" else tol) or not np.isfinite(v)}
+    assert not bad, "parity violations: %s\nall: %s" % (bad, errs)
+    return errs

@@ -1,0 +1,248 @@
+"""Kernel-by-kernel parity of the HIP library (through its C ABI) against the CPU oracle, on seeded inputs at sizes that
+span several tiles and a ragged tail.  Tolerance: relative L2 error <= 2e-2 for bf16 results (the bound the task
+states), much tighter where the result is fp32."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import layers as L
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def rp():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2604_27085_amd import binding, harness
+    return binding, harness
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def rnd(rng, shape, std=1.0):
+    return synth.bf16_round(rng.standard_normal(shape, dtype=np.float32) * np.float32(std))
+
+
+def dev(h, arr):
+    return h.bf16_tensor(arr, "cuda:0")
+
+
+def stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+# ----------------------------------------------------------------------------------------------- GEMM
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("layout", [0, 1, 2])
+def test_gemm_layouts_ragged(rp, layout, tile):
+    B, H = rp
+    rng = np.random.default_rng(100 + layout * 10 + tile)
+    M, N, K = 328, 264, 200          # ragged against every tile size, K not a multiple of 64
+    a = rnd(rng, (M, K))
+    b = rnd(rng, (N, K))
+    ref = a.astype(np.float64) @ b.astype(np.float64).T
+    if layout == 0:
+        A, Bm, lda, ldb = dev(H, a), dev(H, b), K, K
+    elif layout == 1:
+        A, Bm, lda, ldb = dev(H, a), dev(H, np.ascontiguousarray(b.T)), K, N
+    else:
+        A, Bm, lda, ldb = dev(H, np.ascontiguousarray(a.T)), dev(H, np.ascontiguousarray(b.T)), M, N
+    Cm = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
+    B.rp_op_gemm(stream(), layout, 0, A, Bm, Cm, M, N, K, lda, ldb, N, tile=tile)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(Cm), ref) < 4e-3
+    # fp32 output, accumulate on top of an existing value, alpha
+    C32 = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda:0")
+    B.rp_op_gemm(stream(), layout, 1, A, Bm, C32, M, N, K, lda, ldb, N, alpha=0.25, beta=1, tile=tile)
+    torch.cuda.synchronize()
+    assert rel_l2(C32.cpu().numpy(), 0.25 * ref + 0.5) < 1e-5
+
+
+def test_gemm_second_pair_residual_and_atomic(rp):
+    B, H = rp
+    rng = np.random.default_rng(7)
+    M, N, K, K2 = 520, 392, 328, 24
+    x, w = rnd(rng, (M, K)), rnd(rng, (N, K), 0.05)
+    u, bl = rnd(rng, (M, K2)), rnd(rng, (N, K2), 0.1)
+    res = rnd(rng, (M, N))
+    ref = x.astype(np.float64) @ w.T.astype(np.float64) + u.astype(np.float64) @ bl.T.astype(np.float64) + res
+    Cm = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
+    B.rp_op_gemm(stream(), 0, 0, dev(H, x), dev(H, w), Cm, M, N, K, K, K, N, A2=dev(H, u), B2=dev(H, bl), K2=K2, lda2=K2,
+                 ldb2=K2, R=dev(H, res), ldr=N)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(Cm), ref) < 4e-3
+    # NN with a second pair (activation gradient of a LoRA linear): dx = dy W + ud A
+    dy, ud, a_l = rnd(rng, (M, N)), rnd(rng, (M, K2)), rnd(rng, (K2, K), 0.1)
+    ref2 = dy.astype(np.float64) @ w.astype(np.float64) + ud.astype(np.float64) @ a_l.astype(np.float64)
+    C2 = torch.zeros((M, K), dtype=torch.bfloat16, device="cuda:0")
+    B.rp_op_gemm(stream(), 1, 0, dev(H, dy), dev(H, w), C2, M, K, N, N, K, K, A2=dev(H, ud), B2=dev(H, a_l), K2=K2,
+                 lda2=K2, ldb2=K)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(C2), ref2) < 4e-3
+    # atomic accumulation, skinny output (LoRA gradient shape): dB[N, r] += dy^T u
+    C3 = torch.ones((N, K2), dtype=torch.float32, device="cuda:0")
+    B.rp_op_gemm(stream(), 2, 2, dev(H, dy), dev(H, u), C3, N, K2, M, N, K2, K2)
+    torch.cuda.synchronize()
+    assert rel_l2(C3.cpu().numpy(), dy.T.astype(np.float64) @ u.astype(np.float64) + 1.0) < 1e-5
+
+
+def test_gemm_submatrix_views_and_tiny(rp):
+    B, H = rp
+    rng = np.random.default_rng(8)
+    T, N, r = 72, 96, 8
+    dy, u = rnd(rng, (T, N)), rnd(rng, (T, 3 * r))
+    # dB_k[32, r] += dy[:, 40:72]^T u[:, r:2r]  via pointer offsets and leading dimensions
+    dyt, ut = dev(H, dy), dev(H, u)
+    out = torch.zeros((32, r), dtype=torch.float32, device="cuda:0")
+    B.rp_op_gemm(stream(), 2, 1, dyt.data_ptr() + 40 * 2, ut.data_ptr() + r * 2, out, 32, r, T, N, 3 * r, r, beta=1)
+    torch.cuda.synchronize()
+    ref = dy[:, 40:72].T.astype(np.float64) @ u[:, r:2 * r].astype(np.float64)
+    assert rel_l2(out.cpu().numpy(), ref) < 1e-5
+    # empty problem is a no-op
+    B.rp_op_gemm(stream(), 0, 0, dyt, ut, out, 0, 8, 8, 8, 8, 8)
+    torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------------------- RMSNorm
+@pytest.mark.parametrize("T,h", [(37, 256), (130, 2048), (21, 5120)])
+def test_rmsnorm_fwd_bwd(rp, T, h):
+    B, H = rp
+    rng = np.random.default_rng(T + h)
+    x, g, dy, dres = rnd(rng, (T, h)), synth.bf16_round(1 + 0.1 * rng.standard_normal(h).astype(np.float32)), rnd(rng, (T, h)), rnd(rng, (T, h))
+    y_ref, rstd_ref = L.rmsnorm_fwd(x.astype(np.float64), g.astype(np.float64), 1e-6)
+    xd, gd = dev(H, x), dev(H, g)
+    y = torch.empty((T, h), dtype=torch.bfloat16, device="cuda:0")
+    rstd = torch.empty(T, dtype=torch.float32, device="cuda:0")
+    B.rp_op_rmsnorm_fwd(stream(), xd, gd, y, rstd, T, h, 1e-6)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(y), y_ref) < 4e-3
+    assert rel_l2(rstd.cpu().numpy(), rstd_ref[:, 0]) < 1e-5
+    dx_ref, dg_ref = L.rmsnorm_bwd(dy.astype(np.float64), x.astype(np.float64), g.astype(np.float64), rstd_ref)
+    for f32 in (0, 1):
+        dx = torch.empty((T, h), dtype=torch.bfloat16, device="cuda:0")
+        dg = torch.zeros(h, dtype=torch.float32, device="cuda:0")
+        dyd = torch.from_numpy(dy).cuda() if f32 else dev(H, dy)
+        B.rp_op_rmsnorm_bwd(stream(), dyd, f32, xd, gd, rstd, dev(H, dres), dx, dg, T, h)
+        torch.cuda.synchronize()
+        assert rel_l2(H.to_f32(dx), dx_ref + dres) < 4e-3
+        assert rel_l2(dg.cpu().numpy(), dg_ref) < 1e-4
+
+
+# ----------------------------------------------------------------------------------------------- QK-norm + RoPE
+@pytest.mark.parametrize("d,a,k,use_norm", [(128, 4, 2, 1), (64, 6, 3, 1), (128, 3, 1, 0)])
+def test_qknorm_rope_fwd_bwd(rp, d, a, k, use_norm):
+    B, H = rp
+    rng = np.random.default_rng(d + a)
+    batch, seq = 2, 52
+    T, base, eps = batch * seq, 1.0e6, 1e-6
+    n1 = (a + 2 * k) * d
+    qkv = rnd(rng, (T, n1))
+    gq = synth.bf16_round(1 + 0.1 * rng.standard_normal(d).astype(np.float32))
+    gk = synth.bf16_round(1 + 0.1 * rng.standard_normal(d).astype(np.float32))
+    q_raw = qkv[:, : a * d].reshape(T, a, d).astype(np.float64)
+    k_raw = qkv[:, a * d: (a + k) * d].reshape(T, k, d).astype(np.float64)
+    if use_norm:
+        qn, rq = L.rmsnorm_fwd(q_raw, gq.astype(np.float64), eps)
+        kn, rk = L.rmsnorm_fwd(k_raw, gk.astype(np.float64), eps)
+    else:
+        qn, kn = q_raw, k_raw
+    q_ref, k_ref = L.rope_fwd(qn, batch, seq, base), L.rope_fwd(kn, batch, seq, base)
+
+    cs = torch.empty((seq, d // 2, 2), dtype=torch.float32, device="cuda:0")
+    B.rp_op_rope_table(stream(), cs, seq, d, base)
+    qkvd = dev(H, qkv)
+    qo = torch.empty((T, a * d), dtype=torch.bfloat16, device="cuda:0")
+    ko = torch.empty((T, k * d), dtype=torch.bfloat16, device="cuda:0")
+    rstd_q = torch.zeros((T, a), dtype=torch.float32, device="cuda:0")
+    rstd_k = torch.zeros((T, k), dtype=torch.float32, device="cuda:0")
+    gqd, gkd = dev(H, gq), dev(H, gk)
+    B.rp_op_qknorm_rope(stream(), 0, d, qkvd, qkvd.data_ptr() + a * d * 2, n1, n1, qo, ko, a * d, k * d, gqd, gkd, rstd_q,
+                        rstd_k, None, None, 0, None, None, cs, T, seq, a, k, use_norm, eps)
+    torch.cuda.synchronize()
+    cs_ref_c, cs_ref_s = L.rope_angles(seq, d, base, np.float64)
+    assert np.max(np.abs(cs.cpu().numpy()[..., 0] - cs_ref_c)) < 2e-7
+    assert np.max(np.abs(cs.cpu().numpy()[..., 1] - cs_ref_s)) < 2e-7
+    assert rel_l2(H.to_f32(qo).reshape(T, a, d), q_ref) < 4e-3
+    assert rel_l2(H.to_f32(ko).reshape(T, k, d), k_ref) < 4e-3
+
+    # backward: gradients of the rotated heads -> gradients of the raw heads (written into a fused [T, n1] buffer)
+    dq_r, dk_r = rnd(rng, (T, a, d)), rnd(rng, (T, k, d))
+    dqn = L.rope_bwd(dq_r.astype(np.float64), batch, seq, base)
+    dkn = L.rope_bwd(dk_r.astype(np.float64), batch, seq, base)
+    if use_norm:
+        dq_ref, dgq_ref = L.rmsnorm_bwd(dqn, q_raw, gq.astype(np.float64), rq)
+        dk_ref, dgk_ref = L.rmsnorm_bwd(dkn, k_raw, gk.astype(np.float64), rk)
+    else:
+        dq_ref, dk_ref = dqn, dkn
+    dqkv = torch.zeros((T, n1), dtype=torch.bfloat16, device="cuda:0")
+    dgq = torch.zeros(d, dtype=torch.float32, device="cuda:0")
+    dgk = torch.zeros(d, dtype=torch.float32, device="cuda:0")
+    B.rp_op_qknorm_rope(stream(), 1, d, dev(H, dq_r.reshape(T, -1)), dev(H, dk_r.reshape(T, -1)), a * d, k * d, dqkv,
+                        dqkv.data_ptr() + a * d * 2, n1, n1, gqd, gkd, rstd_q, rstd_k, qkvd, qkvd.data_ptr() + a * d * 2, n1,
+                        dgq, dgk, cs, T, seq, a, k, use_norm, eps)
+    torch.cuda.synchronize()
+    out = H.to_f32(dqkv)
+    assert rel_l2(out[:, : a * d].reshape(T, a, d), dq_ref) < 4e-3
+    assert rel_l2(out[:, a * d: (a + k) * d].reshape(T, k, d), dk_ref) < 4e-3
+    assert np.all(out[:, (a + k) * d:] == 0)
+    if use_norm:
+        assert rel_l2(dgq.cpu().numpy(), dgq_ref) < 1e-4
+        assert rel_l2(dgk.cpu().numpy(), dgk_ref) < 1e-4
+
+
+# ----------------------------------------------------------------------------------------------- SwiGLU
+def test_swiglu_fwd_bwd(rp):
+    B, H = rp
+    rng = np.random.default_rng(5)
+    T, m = 75, 688
+    gu, dact = rnd(rng, (T, 2 * m), 2.0), rnd(rng, (T, m))
+    g64, u64 = gu[:, :m].astype(np.float64), gu[:, m:].astype(np.float64)
+    gud = dev(H, gu)
+    act = torch.empty((T, m), dtype=torch.bfloat16, device="cuda:0")
+    B.rp_op_swiglu_fwd(stream(), gud, act, T, m)
+    dgu = torch.empty((T, 2 * m), dtype=torch.bfloat16, device="cuda:0")
+    B.rp_op_swiglu_bwd(stream(), dev(H, dact), gud, dgu, T, m)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(act), L.swiglu_fwd(g64, u64)) < 4e-3
+    dg_ref, du_ref = L.swiglu_bwd(dact.astype(np.float64), g64, u64)
+    assert rel_l2(H.to_f32(dgu), np.concatenate([dg_ref, du_ref], axis=1)) < 4e-3
+
+
+# ----------------------------------------------------------------------------------------------- attention
+@pytest.mark.parametrize("d,a,kh,batch,seq", [(128, 4, 2, 1, 328), (64, 4, 2, 2, 136), (128, 8, 1, 1, 200), (128, 2, 2, 1, 8)])
+def test_attention_fwd_bwd(rp, d, a, kh, batch, seq):
+    B, H = rp
+    rng = np.random.default_rng(d + a + seq)
+    T = batch * seq
+    q, k, v = rnd(rng, (T, a, d)), rnd(rng, (T, kh, d)), rnd(rng, (T, kh, d))
+    do = rnd(rng, (T, a, d))
+    q64, k64, v64 = q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)
+    o_ref, P, lse_ref = L.attention_fwd(q64, k64, v64, batch, seq)
+    dq_ref, dk_ref, dv_ref = L.attention_bwd(do.astype(np.float64), q64, k64, v64, o_ref, P, batch, seq)
+    # k and v live side by side in one buffer (row stride 2*kh*d), as in the fused projection output
+    kv = np.concatenate([k.reshape(T, -1), v.reshape(T, -1)], axis=1)
+    qd_, kvd = dev(H, q.reshape(T, -1)), dev(H, kv)
+    kp, vp, ldkv = kvd.data_ptr(), kvd.data_ptr() + kh * d * 2, 2 * kh * d
+    o = torch.zeros((T, a * d), dtype=torch.bfloat16, device="cuda:0")
+    lse = torch.zeros((batch, a, seq), dtype=torch.float32, device="cuda:0")
+    B.rp_op_attn_fwd(stream(), qd_, kp, vp, o, lse, a * d, ldkv, ldkv, a * d, batch, seq, a, kh, d)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(o).reshape(T, a, d), o_ref) < 6e-3
+    assert np.max(np.abs(lse.cpu().numpy() - lse_ref)) < 2e-3
+    dq = torch.zeros((T, a * d), dtype=torch.bfloat16, device="cuda:0")
+    dkv = torch.zeros((T, 2 * kh * d), dtype=torch.bfloat16, device="cuda:0")
+    delta = torch.zeros((batch, a, seq), dtype=torch.float32, device="cuda:0")
+    B.rp_op_attn_bwd(stream(), qd_, kp, vp, o, dev(H, do.reshape(T, -1)), lse, delta, dq, dkv, dkv.data_ptr() + kh * d * 2,
+                     a * d, ldkv, ldkv, a * d, a * d, a * d, ldkv, ldkv, batch, seq, a, kh, d)
+    torch.cuda.synchronize()
+    dkv_h = H.to_f32(dkv)
+    assert rel_l2(H.to_f32(dq).reshape(T, a, d), dq_ref) < 1e-2
+    assert rel_l2(dkv_h[:, : kh * d].reshape(T, kh, d), dk_ref) < 1e-2
+    assert rel_l2(dkv_h[:, kh * d:].reshape(T, kh, d), dv_ref) < 1e-2

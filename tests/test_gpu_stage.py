@@ -1,0 +1,192 @@
+"""End-to-end parity of the four hot-path calls (through the C ABI) against the CPU oracle: weight upload, forward
+stage, backward stage with recomputation, LM head + cross-entropy.  Bounds: relative L2 error <= 2e-2 on every output
+and gradient tensor, relative loss error <= 1e-4."""
+import numpy as np
+import pytest
+
+import parity_util as pu
+import synth
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def hz():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2604_27085_amd import harness
+    return harness
+
+
+def test_c1_chain_matches_oracle(hz):
+    """Tiny stage: 2 layers + head, full fine-tune with LoRA on q and v, labels = next token."""
+    c = synth.CONFIGS["C1"]
+    wl = synth.make_workload(c, synth.config_seed("C1"))
+    ref = pu.oracle_chain(c, wl)
+    got = pu.gpu_chain(c, wl, hz)
+    errs = pu.compare_chain(ref, got, c)
+    # loss, head dx, head Wv/gf, out, dx, and per layer 11 base tensors + 4 adapter factors
+    assert len(errs) == 4 + 2 + 2 * (11 + 4), sorted(errs)
+    assert abs(ref["loss"] - np.log(c["vocab"])) < 0.5
+
+
+VARIANTS = {
+    # ragged token count, every adapter on, frozen base, random gains
+    "lora_all_frozen_ragged": dict(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=688, vocab=0,
+                                   n_experts=0, top_k=0, lora_rank=16, lora=synth.LORA_ORDER, train_base=0, batch=1,
+                                   seq=200, x_from="normal", lora_scale=2.0),
+    # head_dim 128, two independent sequences, no QK-norm, full fine-tune without adapters
+    "d128_batch2_nonorm": dict(n_layers=1, hidden=384, n_q_heads=2, n_kv_heads=1, head_dim=128, ffn=1024, vocab=0,
+                               n_experts=0, top_k=0, lora_rank=0, lora=(), train_base=1, batch=2, seq=72,
+                               x_from="normal", qk_norm=0),
+    # adapters on k, o, gate only (partial fused groups), trainable base, group size 4
+    "lora_partial_trainable": dict(n_layers=1, hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=64, ffn=768, vocab=0,
+                                   n_experts=0, top_k=0, lora_rank=8, lora=("k", "o", "gate"), train_base=1, batch=1,
+                                   seq=328, x_from="normal"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(VARIANTS))
+def test_stage_variants_match_oracle(hz, name):
+    c = VARIANTS[name]
+    wl = synth.make_workload(c, 500 + sorted(VARIANTS).index(name), gains_random=True)
+    ref = pu.oracle_chain(c, wl)
+    got = pu.gpu_chain(c, wl, hz, use_upload=(name != "d128_batch2_nonorm"))
+    errs = pu.compare_chain(ref, got, c)
+    n_lora = 2 * len(c["lora"])
+    n_base = (9 + (2 if c.get("qk_norm", 1) else 0)) if c["train_base"] else 0
+    assert len(errs) == 2 + c["n_layers"] * (n_base + n_lora), sorted(errs)
+
+
+def test_head_only_stage_ragged_vocab_and_ignored_rows(hz):
+    """LM head as a stage of its own; vocabulary not a multiple of any tile, several vocabulary chunks are not needed
+    here but the tail tile is; some rows ignored; loss scaling."""
+    c = dict(n_layers=0, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=688, vocab=1000, n_experts=0, top_k=0,
+             lora_rank=0, lora=(), train_base=1, batch=1, seq=136, x_from="normal")
+    wl = synth.make_workload(c, 77, gains_random=True)
+    wl["labels"][::5] = -100
+    wl["x"] = synth.bf16_round(wl["x"] * 3.0)
+    ref = pu.oracle_chain(c, wl, grad_scale=64.0)
+    got = pu.gpu_chain(c, wl, hz, grad_scale=64.0)
+    errs = pu.compare_chain(ref, got, c)
+    assert set(errs) == {"loss", "head_dx", "head.Wv", "head.gf"}
+    assert np.all(got["head_dx"][::5] == 0.0)
+
+
+def test_head_multiple_vocab_chunks_frozen(hz):
+    """Vocabulary larger than one chunk of the second sweep (16384 rows) with a frozen head: only loss and dx."""
+    c = dict(n_layers=0, hidden=128, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=256, vocab=40000, n_experts=0, top_k=0,
+             lora_rank=0, lora=(), train_base=0, batch=1, seq=64, x_from="normal")
+    wl = synth.make_workload(c, 78)
+    ref = pu.oracle_chain(c, wl)
+    got = pu.gpu_chain(c, wl, hz)
+    errs = pu.compare_chain(ref, got, c)
+    assert set(errs) == {"loss", "head_dx"}
+
+
+def test_gradients_accumulate_over_micro_batches(hz):
+    c = VARIANTS["lora_partial_trainable"]
+    wl = synth.make_workload(c, 9)
+    cfg = hz.cfg_from_dict(c, with_head=False)
+    R = hz.StageRunner(cfg, c["batch"], c["seq"])
+    try:
+        R.upload(R.pinned_blob(wl["layers"]))
+        x, dy = hz.bf16_tensor(wl["x"], R.device), hz.bf16_tensor(wl["dy"], R.device)
+        torch.cuda.synchronize()
+        _, dx1 = R.backward(x, dy)
+        R.sync()
+        g1 = R.grads.clone()
+        _, dx2 = R.backward(x, dy)
+        R.sync()
+        assert torch.equal(dx1, dx2)
+        # the big tensors are summed in a fixed order: the second pass exactly doubles them
+        l1, _ = hz.unpack_grads(cfg, g1)
+        l2, _ = hz.unpack_grads(cfg, R.grads)
+        np.testing.assert_array_equal(l2[0]["Wd"], 2 * l1[0]["Wd"])
+        np.testing.assert_allclose(l2[0]["g1"], 2 * l1[0]["g1"], rtol=1e-4, atol=1e-6)
+    finally:
+        R.close()
+
+
+def test_forward_stage_checkpoints_and_matches_backward_recompute(hz):
+    from oracle import stage
+    c = synth.CONFIGS["C1"]
+    wl = synth.make_workload(c, 11)
+    cfg = hz.cfg_from_dict(c, with_head=False)
+    R = hz.StageRunner(cfg, c["batch"], c["seq"])
+    try:
+        R.upload(R.pinned_blob(wl["layers"]))
+        x = hz.bf16_tensor(wl["x"], R.device)
+        dy = hz.bf16_tensor(wl["dy"], R.device)
+        torch.cuda.synchronize()
+        out, keep = R.forward(x, keep_layer_inputs=True)
+        out_b, _ = R.backward(x, dy)
+        R.sync()
+        assert torch.equal(out, out_b)                 # the recomputation reproduces the forward stage bit for bit
+        assert torch.equal(keep[0], x)
+        ocfg = pu.oracle_cfg(dict(c, vocab=0))
+        ref_out, ref_inputs = stage.stage_fwd(wl["x"].astype(np.float64), pu.cast_tree(wl["layers"], np.float64), ocfg,
+                                              c["batch"], c["seq"])
+        assert pu.rel_l2(hz.to_f32(out), ref_out) < 2e-2
+        assert pu.rel_l2(hz.to_f32(keep[1]), ref_inputs[1]) < 2e-2
+    finally:
+        R.close()
+
+
+def test_error_paths_leave_no_work_enqueued(hz):
+    from paper_2604_27085_amd import binding as B
+    c = synth.CONFIGS["C1"]
+    cfg = hz.cfg_from_dict(c)
+    R = hz.StageRunner(cfg, c["batch"], c["seq"])
+    try:
+        x = torch.zeros((R.T, c["hidden"]), dtype=torch.bfloat16, device=R.device)
+        y = torch.zeros_like(x)
+        with pytest.raises(B.RpError) as e:           # nothing uploaded yet
+            B.rp_stage_forward(R.ctx, 0, x, y, None, None, c["batch"], c["seq"], R.ws, R.wsbytes)
+        assert e.value.code == B.RP_ESTATE
+        wl = synth.make_workload(c, 1)
+        host = R.pinned_blob(wl["layers"], wl["head"])
+        with pytest.raises(B.RpError) as e:
+            B.rp_stage_upload_weights(R.ctx, 0, R.slots[0], host, R.wbytes - 256)
+        assert e.value.code == B.RP_EINVAL
+        R.upload(host)
+        with pytest.raises(B.RpError) as e:
+            B.rp_stage_forward(R.ctx, 0, x, y, None, None, c["batch"], c["seq"], R.ws, 1024)
+        assert e.value.code == B.RP_ENOMEM
+        with pytest.raises(B.RpError) as e:
+            B.rp_stage_forward(R.ctx, 0, x, x, None, None, c["batch"], c["seq"], R.ws, R.wsbytes)
+        assert e.value.code == B.RP_EINVAL
+        with pytest.raises(B.RpError) as e:
+            B.rp_stage_forward(R.ctx, 9, x, y, None, None, c["batch"], c["seq"], R.ws, R.wsbytes)
+        assert e.value.code == B.RP_EINVAL
+        R.sync()
+        assert float(y.float().abs().sum()) == 0.0
+    finally:
+        R.close()
+
+
+def test_upload_event_gating_against_poisoned_slot(hz):
+    """The slot is filled with NaN bit patterns on the compute stream right before the upload; the stage must wait for
+    each layer's bytes (per-layer events), so no NaN may reach the output."""
+    c = synth.CONFIGS["C1"]
+    wl = synth.make_workload(c, 21)
+    cfg = hz.cfg_from_dict(c, with_head=False)
+    R = hz.StageRunner(cfg, c["batch"], c["seq"], n_slots=2)
+    try:
+        host = R.pinned_blob(wl["layers"])
+        x = hz.bf16_tensor(wl["x"], R.device)
+        for s in range(2):
+            R.slots[s].fill_(0xFF)
+        torch.cuda.synchronize()
+        outs = []
+        for step in range(4):
+            s = step & 1
+            R.upload(host, slot=s)
+            outs.append(R.forward(x, slot=s))
+        R.sync()
+        for o in outs:
+            assert torch.isfinite(o.float()).all()
+            assert torch.equal(o, outs[0])
+    finally:
+        R.close()
