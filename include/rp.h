@@ -52,6 +52,9 @@ typedef enum {
 /* lora_mask bits, in the order the adapters appear in the weight blob */
 enum { RP_LORA_Q = 1, RP_LORA_K = 2, RP_LORA_V = 4, RP_LORA_O = 8, RP_LORA_GATE = 16, RP_LORA_UP = 32, RP_LORA_DOWN = 64 };
 
+/* phases of rp_stage_backward */
+enum { RP_PHASE_RECOMPUTE = 1, RP_PHASE_BACKWARD = 2, RP_PHASE_BOTH = 3 };
+
 #define RP_MAX_SLOTS 4
 #define RP_IGNORE_INDEX (-100)
 
@@ -150,16 +153,19 @@ RP_API rp_status rp_stage_bind_weights(rp_ctx* ctx, int slot_id, void* dev_slot,
 RP_API rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_out, void* const* layer_inputs_out,
                            const float* router_logits, int batch, int seq, void* workspace, size_t workspace_bytes);
 
-/* Backward stage with recomputation (Sec. 3.2; App. C.3): from the stored stage input x_in the forward is re-run
- * keeping the internals in the workspace, then the backward runs in reverse layer order.
+/* Backward stage with recomputation (Sec. 3.2; App. C.3).  Phase RP_PHASE_RECOMPUTE re-runs the forward from the
+ * stored stage input x_in keeping every layer's internals in the workspace; phase RP_PHASE_BACKWARD runs the backward
+ * in reverse layer order from those internals.  RP_PHASE_BOTH is the ordinary backward stage.  The fused stage of the
+ * last layers (Sec. 3.2: its forward doubles as the recomputation) calls RECOMPUTE, then the LM head on x_out, then
+ * BACKWARD with the head's dx as dy -- with the same workspace, untouched in between, and the same x_in.
  * dy [dev] bf16 [T, h]: gradient of the stage output;  dx [dev] bf16 [T, h]: overwritten with the gradient of x_in;
- * x_out [dev] bf16 [T, h] or NULL: receives the recomputed stage output (the fused forward+backward stage of the
- * last layers uses it);  grads [dev]: fp32 gradient blob, ACCUMULATED (+=) -- the in-place accumulation over
- * micro-batches of Sec. 4.1.1;  router_logits / d_router_logits [dev] fp32 [n_layers, T, E] (MoE only; the
- * latter is overwritten).  Errors as rp_stage_forward. */
-RP_API rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, const void* x_in, const void* dy, void* dx, void* x_out,
-                            void* grads, const float* router_logits, float* d_router_logits, int batch, int seq,
-                            void* workspace, size_t workspace_bytes);
+ * x_out [dev] bf16 [T, h] or NULL: receives the recomputed stage output;  grads [dev]: fp32 gradient blob,
+ * ACCUMULATED (+=) -- the in-place accumulation over micro-batches of Sec. 4.1.1;  router_logits / d_router_logits
+ * [dev] fp32 [n_layers, T, E] (MoE only; the latter is overwritten).  dy, dx, grads are ignored by RECOMPUTE alone,
+ * x_out by BACKWARD alone.  Errors as rp_stage_forward. */
+RP_API rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_in, const void* dy, void* dx,
+                            void* x_out, void* grads, const float* router_logits, float* d_router_logits, int batch,
+                            int seq, void* workspace, size_t workspace_bytes);
 
 /* LM head fused with the mean cross-entropy, forward and backward in one call (the oversized last stage, Sec. 2.3;
  * returns a scalar loss, Sec. 4.1.1).  xf = rmsnorm(x; gf); Z = xf Wv^T is produced tile by tile and reduced on
@@ -168,7 +174,8 @@ RP_API rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, const void* x_in, c
  * x [dev] bf16 [T, h]; labels [dev] int32 [T]; loss_out [dev] one fp32; dx [dev] bf16 [T, h] overwritten;
  * grads [dev]: the stage's fp32 gradient blob (the one rp_stage_backward takes); its head chunk {gf [h], Wv [V, h]}
  * is accumulated when train_base is set; NULL = frozen head.  Uses the head chunk (layer index n_layers) of the
- * slot.  Errors as rp_stage_forward. */
+ * slot.  The workspace is overwritten from its start: between the two phases of a fused last stage give the head
+ * a workspace of its own.  Errors as rp_stage_forward. */
 RP_API rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const int32_t* labels, float* loss_out,
                                void* dx, void* grads, float grad_scale, int batch, int seq, void* workspace,
                                size_t workspace_bytes);

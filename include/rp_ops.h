@@ -50,6 +50,14 @@ RP_API rp_status rp_op_attn_bwd(void* stream, const void* q, const void* k, cons
                          const float* lse, float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv, long ldo,
                          long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh, int d);
 
+/* Per-kernel timeline of the stage calls on a ctx (measurement aid; the only calls that synchronise).
+ * rp_trace_start: from now on every kernel a stage/head call enqueues is preceded by a timing event (at most
+ * max_records ops are recorded).  rp_trace_stop: waits for the compute stream, writes up to cap records
+ * {kernel name, useful FLOPs, algorithmic HBM bytes, milliseconds} in launch order and the count into *n. */
+typedef struct { char name[40]; double flops; double bytes; float ms; } rp_trace_record;
+RP_API rp_status rp_trace_start(rp_ctx* ctx, int max_records);
+RP_API rp_status rp_trace_stop(rp_ctx* ctx, rp_trace_record* out, int cap, int* n);
+
 #ifdef __cplusplus
 }
 #endif

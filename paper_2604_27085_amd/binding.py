@@ -14,6 +14,7 @@ RP_MAX_SLOTS = 4
 IGNORE_INDEX = -100
 LORA_BITS = {"q": 1, "k": 2, "v": 4, "o": 8, "gate": 16, "up": 32, "down": 64}
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
+PHASE_RECOMPUTE, PHASE_BACKWARD, PHASE_BOTH = 1, 2, 3
 
 TENSOR_IDS = ["G1", "WQKV", "GQ", "GK", "WO", "G2", "WGU", "WD", "LA_Q", "LA_K", "LA_V", "LB_Q", "LB_K", "LB_V",
               "LA_O", "LB_O", "LA_GATE", "LA_UP", "LB_GATE", "LB_UP", "LA_DOWN", "LB_DOWN", "GF", "WV"]
@@ -26,6 +27,10 @@ class StageCfg(C.Structure):
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("rope_base", C.c_float), ("rms_eps", C.c_float),
                 ("qk_norm", C.c_int32), ("lora_rank", C.c_int32), ("lora_scale", C.c_float), ("lora_mask", C.c_uint32),
                 ("train_base", C.c_int32)]
+
+
+class TraceRecord(C.Structure):
+    _fields_ = [("name", C.c_char * 40), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
 
 
 class RpError(RuntimeError):
@@ -57,8 +62,10 @@ _SIGS = {
     "rp_stage_upload_weights": [_vp, _i, _vp, _vp, _sz],
     "rp_stage_bind_weights": [_vp, _i, _vp, _sz],
     "rp_stage_forward": [_vp, _i, _vp, _vp, C.POINTER(_vp), _vp, _i, _i, _vp, _sz],
-    "rp_stage_backward": [_vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _vp, _sz],
+    "rp_stage_backward": [_vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _vp, _sz],
     "rp_lmhead_ce_fwd_bwd": [_vp, _i, _vp, _vp, _vp, _vp, _vp, _f, _i, _i, _vp, _sz],
+    "rp_trace_start": [_vp, _i],
+    "rp_trace_stop": [_vp, C.POINTER(TraceRecord), _i, C.POINTER(_i)],
     "rp_op_gemm": [_vp, _i, _i, _vp, _vp, _vp, _i, _i, _i, _l, _l, _l, _f, _i, _vp, _vp, _i, _l, _l, _vp, _l, _i],
     "rp_op_rmsnorm_fwd": [_vp, _vp, _vp, _vp, _vp, _i, _i, _f],
     "rp_op_rmsnorm_bwd": [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i],
@@ -155,9 +162,9 @@ def rp_stage_forward(ctx, slot_id, x_in, x_out, layer_inputs_out, router_logits,
                                 _ptr(workspace), workspace_bytes), ctx)
 
 
-def rp_stage_backward(ctx, slot_id, x_in, dy, dx, x_out, grads, router_logits, d_router_logits, batch, seq, workspace,
-                      workspace_bytes):
-    _check(lib.rp_stage_backward(ctx, slot_id, _ptr(x_in), _ptr(dy), _ptr(dx), _ptr(x_out), _ptr(grads),
+def rp_stage_backward(ctx, slot_id, phases, x_in, dy, dx, x_out, grads, router_logits, d_router_logits, batch, seq,
+                      workspace, workspace_bytes):
+    _check(lib.rp_stage_backward(ctx, slot_id, phases, _ptr(x_in), _ptr(dy), _ptr(dx), _ptr(x_out), _ptr(grads),
                                  _ptr(router_logits), _ptr(d_router_logits), batch, seq, _ptr(workspace),
                                  workspace_bytes), ctx)
 
@@ -169,6 +176,18 @@ def rp_lmhead_ce_fwd_bwd(ctx, slot_id, x, labels, loss_out, dx, grads, grad_scal
 
 
 # ---- rp_ops.h -----------------------------------------------------------------------------------------------------
+def rp_trace_start(ctx, max_records):
+    _check(lib.rp_trace_start(ctx, max_records), ctx)
+
+
+def rp_trace_stop(ctx, cap):
+    """Returns a list of (name, flops, bytes, ms) in launch order."""
+    buf = (TraceRecord * cap)()
+    n = C.c_int()
+    _check(lib.rp_trace_stop(ctx, buf, cap, C.byref(n)), ctx)
+    return [(buf[i].name.decode(), buf[i].flops, buf[i].bytes, buf[i].ms) for i in range(n.value)]
+
+
 def rp_op_gemm(stream, layout, out_f32, A, B, Cm, M, N, K, lda, ldb, ldc, alpha=1.0, beta=0, A2=None, B2=None, K2=0,
                lda2=0, ldb2=0, R=None, ldr=0, tile=0):
     _check(lib.rp_op_gemm(stream, layout, out_f32, _ptr(A), _ptr(B), _ptr(Cm), M, N, K, lda, ldb, ldc, alpha, beta,

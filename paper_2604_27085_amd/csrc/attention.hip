@@ -538,9 +538,9 @@ hipError_t k_attn_delta(hipStream_t st, const void* o, const void* dout, float* 
   return hipGetLastError();
 }
 
-hipError_t k_attn_bwd(hipStream_t st, const void* q, const void* k, const void* v, const void* dout, const float* lse,
-                      const float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv, long lddo, long lddq,
-                      long lddk, long lddv, int batch, int seq, int a, int kh, int d) {
+hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, const void* v, const void* dout,
+                      const float* lse, const float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv,
+                      long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh, int d) {
   if (batch * seq == 0) return hipSuccess;
   AttnArgs p = {};
   p.q = (const bf16*)q; p.k = (const bf16*)k; p.v = (const bf16*)v; p.dout = (const bf16*)dout;
@@ -549,20 +549,24 @@ hipError_t k_attn_bwd(hipStream_t st, const void* q, const void* k, const void* 
   fill_common(p, batch, seq, a, kh, d);
   const int nq = ((seq + 127) / 128) * a * batch;
   const int nk = ((seq + 127) / 128) * kh * batch;
-  if (d == 128) {
-    constexpr int smem = dkv_smem_bytes(128);
-    static bool attr_done = false;
-    if (!attr_done) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_kernel<128>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-      if (e != hipSuccess) return e;
-      attr_done = true;
+  if (d != 128 && d != 64) return hipErrorInvalidValue;
+  if (part == 0) {
+    if (d == 128) {
+      constexpr int smem = dkv_smem_bytes(128);
+      static bool attr_done = false;
+      if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_kernel<128>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+      }
+      hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, dim3(nk), dim3(256), smem, st, p);
+    } else {
+      hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, dim3(nk), dim3(256), dkv_smem_bytes(64), st, p);
     }
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, dim3(nk), dim3(256), smem, st, p);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, dim3(nq), dim3(256), 0, st, p);
-  } else if (d == 64) {
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, dim3(nk), dim3(256), dkv_smem_bytes(64), st, p);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, dim3(nq), dim3(256), 0, st, p);
-  } else return hipErrorInvalidValue;
+  } else {
+    if (d == 128) hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, dim3(nq), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, dim3(nq), dim3(256), 0, st, p);
+  }
   return hipGetLastError();
 }

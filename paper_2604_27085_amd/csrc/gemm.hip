@@ -314,10 +314,15 @@ void gemm_zero_args(GemmArgs& a) {
 
 int gemm_ce_stats_partials(int M) { return 2 * ((M + 255) / 256); }
 
+int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
+  if (a.epi == EPI_CE_STATS) return 1;   // the partial-row numbering assumes 256-row tiles
+  if (tile_hint) return tile_hint;
+  return env_tile() ? env_tile() : choose_tile(a.M, a.N);
+}
+
 hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a, int tile_hint) {
   if (a.M <= 0 || a.N <= 0) return hipSuccess;
-  int tile = tile_hint ? tile_hint : (env_tile() ? env_tile() : choose_tile(a.M, a.N));
-  if (a.epi == EPI_CE_STATS) tile = 1;   // the partial-row numbering assumes 256-row tiles
+  const int tile = gemm_pick_tile(a, tile_hint);
   switch (layout) {
     case GEMM_NT: return launch_tile<false, false>(st, a, tile);
     case GEMM_NN: return launch_tile<false, true>(st, a, tile);

@@ -35,8 +35,8 @@ hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* 
 // delta[batch, a, seq] = rowsum(dO * O)
 hipError_t k_attn_delta(hipStream_t st, const void* o, const void* dout, float* delta, long ldo, long lddo, int batch,
                         int seq, int a, int d);
-// dq [T, a, d] (lddq), dk, dv [T, kh, d] (lddk, lddv), summed over the query heads of each group.
-hipError_t k_attn_bwd(hipStream_t st, const void* q, const void* k, const void* v, const void* dout, const float* lse,
+// part 0: dk, dv [T, kh, d] (lddk, lddv), summed over the query heads of each group;  part 1: dq [T, a, d] (lddq).
+hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, const void* v, const void* dout, const float* lse,
                       const float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv, long lddo, long lddq,
                       long lddk, long lddv, int batch, int seq, int a, int kh, int d);
 

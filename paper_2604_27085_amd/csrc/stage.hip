@@ -33,6 +33,8 @@ char g_err[512];
 
 }  // namespace
 
+struct TraceRec { char name[40]; double flops, bytes; };
+
 struct rp_ctx {
   rp_stage_cfg cfg;
   int device;
@@ -40,6 +42,11 @@ struct rp_ctx {
   Slot slots[RP_MAX_SLOTS];
   BlobLayout wl, gl;
   char err[512];
+  // optional per-kernel timeline: one event before every enqueued op, one after the last
+  bool tracing = false;
+  int trace_cap = 0, trace_n = 0;
+  hipEvent_t* trace_ev = nullptr;   // trace_cap + 1 events
+  TraceRec* trace_rec = nullptr;
 };
 
 namespace {
@@ -58,6 +65,10 @@ rp_status fail(rp_ctx* ctx, rp_status code, const char* fmt, ...) {
     hipError_t e_ = (expr);                                                                             \
     if (e_ != hipSuccess) return fail(ctx, RP_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));      \
   } while (0)
+
+// Enqueue one non-GEMM op: timeline mark (name, useful FLOPs, algorithmic HBM bytes), then the launch.
+#define RUN(X, name, flops, bytes, call) \
+  do { (X).mark(name, (double)(flops), (double)(bytes)); (X).chk(call, name); } while (0)
 
 rp_status validate_cfg(const rp_stage_cfg* c, rp_ctx* ctx) {
   if (!c) return fail(ctx, RP_EINVAL, "cfg is NULL");
@@ -108,6 +119,26 @@ struct Exec {
   const char* where = "";
 
   void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
+  // Called right before an op is enqueued when the timeline is on: records the op's start event and its cost model.
+  void mark(const char* name, double flops, double bytes) {
+    if (!ctx->tracing || ctx->trace_n >= ctx->trace_cap) return;
+    const int i = ctx->trace_n++;
+    snprintf(ctx->trace_rec[i].name, sizeof(ctx->trace_rec[i].name), "%s", name);
+    ctx->trace_rec[i].flops = flops;
+    ctx->trace_rec[i].bytes = bytes;
+    chk(hipEventRecord(ctx->trace_ev[i], st), "trace event");
+  }
+  void mark_gemm(int layout, const GemmArgs& g) {
+    if (!ctx->tracing) return;
+    static const char* lay[3] = {"NT", "NN", "TN"};
+    static const char* til[5] = {"", "256x256", "256x128", "128x128", "64x64"};
+    char nm[40];
+    snprintf(nm, sizeof(nm), "gemm_%s_%s", til[gemm_pick_tile(g)], lay[layout]);
+    const double out_b = (g.epi == EPI_BF16 || g.epi == EPI_CE_DZ) ? 2.0 : (g.epi == EPI_CE_STATS ? 0.0 : 4.0 * (1 + g.beta));
+    mark(nm, 2.0 * g.M * (double)g.N * ((double)g.K + g.K2),
+         2.0 * ((double)g.M * g.K + (double)g.N * g.K + (double)g.M * g.K2 + (double)g.N * g.K2) + out_b * g.M * (double)g.N +
+             (g.R ? 2.0 * g.M * (double)g.N : 0.0));
+  }
   template <typename Tp> Tp* at(size_t off) const { return reinterpret_cast<Tp*>(ws + off); }
 
   // C[M,N] (bf16) = alpha * A * op(B) (+ second pair) (+ R)
@@ -117,6 +148,7 @@ struct Exec {
     GemmArgs g; gemm_zero_args(g);
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
     g.A2 = A2; g.lda2 = lda2; g.B2 = B2; g.ldb2 = ldb2; g.K2 = K2; g.R = R; g.ldr = ldr; g.epi = EPI_BF16;
+    mark_gemm(layout, g);
     chk(gemm_launch(st, layout, g), "gemm_bf16");
   }
   // C[M,N] (fp32) (+)= A^T * B : weight-gradient form, reduction over the rows of A and B
@@ -124,6 +156,7 @@ struct Exec {
     if (!C) return;
     GemmArgs g; gemm_zero_args(g);
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.beta = 1; g.epi = EPI_F32;
+    mark_gemm(GEMM_TN, g);
     chk(gemm_launch(st, GEMM_TN, g), "gemm_wgrad");
   }
 };
@@ -162,7 +195,7 @@ const void* lora_b_matrix(Exec& X, const LayerW& W, const FusedLora& f, int N, s
   if (f.n == 1 && f.row0[0] == 0 && f.row1[0] == N) return W.t(f.b_id[0]);
   LoraSegs s{};
   for (int i = 0; i < f.n; ++i) { s.src[i] = W.t(f.b_id[i]); s.row0[i] = f.row0[i]; s.row1[i] = f.row1[i]; s.col0[i] = i * X.D.r; }
-  X.chk(k_lora_blockdiag(X.st, X.at<void>(bd_off), N, f.n * X.D.r, s, X.D.r), "lora_blockdiag");
+  RUN(X, "lora_blockdiag", 0, 2.0 * N * f.n * X.D.r + 2.0 * N * X.D.r, k_lora_blockdiag(X.st, X.at<void>(bd_off), N, f.n * X.D.r, s, X.D.r));
   return X.at<void>(bd_off);
 }
 
@@ -208,17 +241,21 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z) 
   auto S = [&](size_t off) { return reinterpret_cast<void*>(set + off); };
   bf16_t* qkv = reinterpret_cast<bf16_t*>(S(b.qkv));
 
-  X.chk(k_rmsnorm_fwd(X.st, x, W.t(RP_T_G1), S(b.n1), (float*)S(b.rstd1), T, D.h, c.rms_eps), "rmsnorm1");
+  const double Td = (double)T;
+  RUN(X, "rmsnorm_fwd", 0, 4.0 * Td * D.h, k_rmsnorm_fwd(X.st, x, W.t(RP_T_G1), S(b.n1), (float*)S(b.rstd1), T, D.h, c.rms_eps));
   linear_fwd(X, W, RP_T_WQKV, fused_qkv(D), X.P.bd1, S(b.n1), D.h, qkv, D.n1, S(b.u1), nullptr);
-  X.chk(k_qknorm_rope(X.st, 0, D.d, qkv, qkv + D.qd, D.n1, D.n1, S(b.qr), S(b.kr), D.qd, D.kd, W.t(RP_T_GQ), W.t(RP_T_GK),
-                      (float*)S(b.rstd_q), (float*)S(b.rstd_k), nullptr, nullptr, 0, nullptr, nullptr,
-                      X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps), "qknorm_rope");
-  X.chk(k_attn_fwd(X.st, S(b.qr), S(b.kr), qkv + D.qd + D.kd, S(b.o), (float*)S(b.lse), D.qd, D.kd, D.n1, D.qd, X.batch,
-                   X.seq, D.a, D.kh, D.d), "attn_fwd");
+  RUN(X, "qknorm_rope_fwd", 0, 4.0 * Td * (D.qd + D.kd),
+      k_qknorm_rope(X.st, 0, D.d, qkv, qkv + D.qd, D.n1, D.n1, S(b.qr), S(b.kr), D.qd, D.kd, W.t(RP_T_GQ), W.t(RP_T_GK),
+                    (float*)S(b.rstd_q), (float*)S(b.rstd_k), nullptr, nullptr, 0, nullptr, nullptr,
+                    X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps));
+  const double s2qd = (double)X.batch * X.seq * (double)X.seq * D.qd;   // causal attention: 2 s^2 qd forward per sequence
+  RUN(X, "attn_fwd", 2.0 * s2qd, 2.0 * Td * (2 * D.qd + 2 * D.kd),
+      k_attn_fwd(X.st, S(b.qr), S(b.kr), qkv + D.qd + D.kd, S(b.o), (float*)S(b.lse), D.qd, D.kd, D.n1, D.qd, X.batch,
+                 X.seq, D.a, D.kh, D.d));
   linear_fwd(X, W, RP_T_WO, fused_single(D.lora[3], RP_T_LA_O, RP_T_LB_O, D.h), 0, S(b.o), D.qd, S(b.y), D.h, S(b.u2), x);
-  X.chk(k_rmsnorm_fwd(X.st, S(b.y), W.t(RP_T_G2), S(b.n2), (float*)S(b.rstd2), T, D.h, c.rms_eps), "rmsnorm2");
+  RUN(X, "rmsnorm_fwd", 0, 4.0 * Td * D.h, k_rmsnorm_fwd(X.st, S(b.y), W.t(RP_T_G2), S(b.n2), (float*)S(b.rstd2), T, D.h, c.rms_eps));
   linear_fwd(X, W, RP_T_WGU, fused_gu(D), X.P.bd3, S(b.n2), D.h, S(b.gu), 2 * D.m, S(b.u3), nullptr);
-  X.chk(k_swiglu_fwd(X.st, S(b.gu), S(b.act), T, D.m), "swiglu");
+  RUN(X, "swiglu_fwd", 0, 6.0 * Td * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), T, D.m));
   linear_fwd(X, W, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, S(b.act), D.m, z, D.h, S(b.u4), S(b.y));
 }
 
@@ -236,21 +273,30 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
   // z = y + down(act)
   linear_bwd(X, W, G, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, dz, D.h, S(b.act), D.m,
              X.at<void>(X.P.dact), S(b.u4));
-  X.chk(k_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), X.at<void>(X.P.dgu), T, D.m), "swiglu_bwd");
+  const double Td = (double)T;
+  RUN(X, "swiglu_bwd", 0, 10.0 * Td * D.m, k_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), X.at<void>(X.P.dgu), T, D.m));
   linear_bwd(X, W, G, RP_T_WGU, fused_gu(D), X.P.bd3, X.at<void>(X.P.dgu), 2 * D.m, S(b.n2), D.h, X.at<void>(X.P.dn), S(b.u3));
-  X.chk(k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, S(b.y), W.t(RP_T_G2), (const float*)S(b.rstd2), dz, dy, G.t(RP_T_G2), T, D.h), "rmsnorm2_bwd");
+  RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
+      k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, S(b.y), W.t(RP_T_G2), (const float*)S(b.rstd2), dz, dy, G.t(RP_T_G2), T, D.h));
   // y = x + o_proj(o)
   linear_bwd(X, W, G, RP_T_WO, fused_single(D.lora[3], RP_T_LA_O, RP_T_LB_O, D.h), 0, dy, D.h, S(b.o), D.qd,
              X.at<void>(X.P.dout), S(b.u2));
-  X.chk(k_attn_delta(X.st, S(b.o), X.at<void>(X.P.dout), X.at<float>(X.P.delta), D.qd, D.qd, X.batch, X.seq, D.a, D.d), "attn_delta");
-  X.chk(k_attn_bwd(X.st, S(b.qr), S(b.kr), qkv + D.qd + D.kd, X.at<void>(X.P.dout), (const float*)S(b.lse),
+  RUN(X, "attn_delta", 0, 4.0 * Td * D.qd,
+      k_attn_delta(X.st, S(b.o), X.at<void>(X.P.dout), X.at<float>(X.P.delta), D.qd, D.qd, X.batch, X.seq, D.a, D.d));
+  const double s2qd = (double)X.batch * X.seq * (double)X.seq * D.qd;
+  // useful FLOPs per kernel: dK/dV kernel runs S, dP, dV, dK (4 half-masked products), dQ kernel S, dP, dQ (3)
+  for (int part = 0; part < 2; ++part)
+    RUN(X, part == 0 ? "attn_bwd_dkv" : "attn_bwd_dq", (part == 0 ? 4.0 : 3.0) * s2qd, 2.0 * Td * (3 * D.qd + 4 * D.kd),
+        k_attn_bwd(X.st, part, S(b.qr), S(b.kr), qkv + D.qd + D.kd, X.at<void>(X.P.dout), (const float*)S(b.lse),
                    X.at<float>(X.P.delta), X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), dqkv + D.qd + D.kd, D.qd, D.kd, D.n1, D.qd,
-                   D.qd, D.kd, D.n1, X.batch, X.seq, D.a, D.kh, D.d), "attn_bwd");
-  X.chk(k_qknorm_rope(X.st, 1, D.d, X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), D.qd, D.kd, dqkv, dqkv + D.qd, D.n1, D.n1,
-                      W.t(RP_T_GQ), W.t(RP_T_GK), (float*)S(b.rstd_q), (float*)S(b.rstd_k), qkv, qkv + D.qd, D.n1,
-                      G.t(RP_T_GQ), G.t(RP_T_GK), X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps), "qknorm_rope_bwd");
+                   D.qd, D.kd, D.n1, X.batch, X.seq, D.a, D.kh, D.d));
+  RUN(X, "qknorm_rope_bwd", 0, 6.0 * Td * (D.qd + D.kd),
+      k_qknorm_rope(X.st, 1, D.d, X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), D.qd, D.kd, dqkv, dqkv + D.qd, D.n1, D.n1,
+                    W.t(RP_T_GQ), W.t(RP_T_GK), (float*)S(b.rstd_q), (float*)S(b.rstd_k), qkv, qkv + D.qd, D.n1,
+                    G.t(RP_T_GQ), G.t(RP_T_GK), X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps));
   linear_bwd(X, W, G, RP_T_WQKV, fused_qkv(D), X.P.bd1, dqkv, D.n1, S(b.n1), D.h, X.at<void>(X.P.dn), S(b.u1));
-  X.chk(k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, x, W.t(RP_T_G1), (const float*)S(b.rstd1), dy, dx_out, G.t(RP_T_G1), T, D.h), "rmsnorm1_bwd");
+  RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
+      k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, x, W.t(RP_T_G1), (const float*)S(b.rstd1), dy, dx_out, G.t(RP_T_G1), T, D.h));
 }
 
 rp_status check_call(rp_ctx* ctx, int slot_id, int batch, int seq, const void* ws, size_t ws_bytes, size_t need) {
@@ -271,6 +317,7 @@ rp_status wait_chunk(rp_ctx* ctx, Slot& sl, int chunk) {
 }
 
 rp_status finish_call(rp_ctx* ctx, Slot& sl, Exec& X) {
+  if (ctx->tracing && ctx->trace_n <= ctx->trace_cap) X.chk(hipEventRecord(ctx->trace_ev[ctx->trace_n], ctx->compute), "trace event");
   if (X.err != hipSuccess) return fail(ctx, RP_EHIP, "%s: %s", X.where, hipGetErrorString(X.err));
   HIP_TRY(ctx, hipEventRecord(sl.free_ev, ctx->compute));
   sl.used = true;
@@ -359,6 +406,11 @@ rp_status rp_ctx_destroy(rp_ctx* c) {
     }
     if (c->slots[i].free_ev) (void)hipEventDestroy(c->slots[i].free_ev);
   }
+  if (c->trace_ev) {
+    for (int i = 0; i <= c->trace_cap; ++i) if (c->trace_ev[i]) (void)hipEventDestroy(c->trace_ev[i]);
+    delete[] c->trace_ev;
+  }
+  delete[] c->trace_rec;
   delete c;
   return RP_OK;
 }
@@ -407,14 +459,14 @@ rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_o
   Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
   const int L = ctx->cfg.n_layers;
   const size_t act_bytes = (size_t)X.T * X.D.h * 2;
-  X.chk(k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base), "rope_table");
+  RUN(X, "rope_table", 0, 4.0 * seq * X.D.d, k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base));
   char* set = X.ws + P.layer0;
   void* pp[2] = {set + P.lb.z, X.ws + P.layer0 + P.layer_stride};
   const void* x = x_in;
   for (int l = 0; l < L; ++l) {
     s = wait_chunk(ctx, sl, l);
     if (s != RP_OK) return s;
-    if (layer_inputs_out && layer_inputs_out[l] && layer_inputs_out[l] != x) X.chk(k_copy16(X.st, x, layer_inputs_out[l], (long)act_bytes), "checkpoint copy");
+    if (layer_inputs_out && layer_inputs_out[l] && layer_inputs_out[l] != x) RUN(X, "copy", 0, 2.0 * act_bytes, k_copy16(X.st, x, layer_inputs_out[l], (long)act_bytes));
     void* z = (l == L - 1) ? x_out : pp[l & 1];
     const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
     layer_forward(X, W, set, x, z);
@@ -423,9 +475,9 @@ rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_o
   return finish_call(ctx, sl, X);
 }
 
-rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, const void* x_in, const void* dy, void* dx, void* x_out, void* grads,
-                            const float* router_logits, float* d_router_logits, int batch, int seq, void* workspace,
-                            size_t workspace_bytes_in) {
+rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_in, const void* dy, void* dx, void* x_out,
+                            void* grads, const float* router_logits, float* d_router_logits, int batch, int seq,
+                            void* workspace, size_t workspace_bytes_in) {
   if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
   if (ctx->cfg.n_layers == 0) return fail(ctx, RP_EINVAL, "stage has no decoder layers");
   if (ctx->cfg.n_experts > 0) return fail(ctx, RP_EUNSUPPORTED, "MoE stages are not implemented");
@@ -433,29 +485,38 @@ rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, const void* x_in, const vo
   const Plan P = make_plan(ctx->cfg, batch > 0 ? batch : 1, seq > 0 ? seq : 8);
   rp_status s = check_call(ctx, slot_id, batch, seq, workspace, workspace_bytes_in, P.bwd_bytes);
   if (s != RP_OK) return s;
-  if (!x_in || !dy || !dx) return fail(ctx, RP_EINVAL, "x_in, dy and dx must be non-NULL");
-  if (dx == x_in || dx == dy) return fail(ctx, RP_EINVAL, "dx must not alias x_in or dy");
-  if (!grads && ctx->gl.total > 0) return fail(ctx, RP_EINVAL, "grads is NULL but the stage has trainable tensors");
+  if (phases < 1 || phases > 3) return fail(ctx, RP_EINVAL, "phases must be RP_PHASE_RECOMPUTE, RP_PHASE_BACKWARD or both");
+  const bool do_fwd = phases & RP_PHASE_RECOMPUTE, do_bwd = phases & RP_PHASE_BACKWARD;
+  if (!x_in) return fail(ctx, RP_EINVAL, "x_in must be non-NULL");
+  if (do_bwd) {
+    if (!dy || !dx) return fail(ctx, RP_EINVAL, "dy and dx must be non-NULL for the backward phase");
+    if (dx == x_in || dx == dy) return fail(ctx, RP_EINVAL, "dx must not alias x_in or dy");
+    if (!grads && ctx->gl.total > 0) return fail(ctx, RP_EINVAL, "grads is NULL but the stage has trainable tensors");
+  }
   Slot& sl = ctx->slots[slot_id];
   Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
   const int L = ctx->cfg.n_layers;
   const size_t act_bytes = (size_t)X.T * X.D.h * 2;
-  X.chk(k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base), "rope_table");
+  if (do_fwd) RUN(X, "rope_table", 0, 4.0 * seq * X.D.d, k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base));
   auto set_of = [&](int l) { return X.ws + P.layer0 + P.layer_stride * (size_t)l; };
-  // recomputation: forward over the stage keeping every layer's internals
-  const void* x = x_in;
-  for (int l = 0; l < L; ++l) {
+  for (int l = 0; l < L; ++l) {   // both phases read the weights
     s = wait_chunk(ctx, sl, l);
     if (s != RP_OK) return s;
-    const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
-    void* z = set_of(l) + P.lb.z;
-    layer_forward(X, W, set_of(l), x, z);
-    x = z;
   }
-  if (x_out) X.chk(k_copy16(X.st, x, x_out, (long)act_bytes), "x_out copy");
+  if (do_fwd) {
+    // recomputation: forward over the stage keeping every layer's internals
+    const void* x = x_in;
+    for (int l = 0; l < L; ++l) {
+      const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
+      void* z = set_of(l) + P.lb.z;
+      layer_forward(X, W, set_of(l), x, z);
+      x = z;
+    }
+    if (x_out) RUN(X, "copy", 0, 2.0 * act_bytes, k_copy16(X.st, x, x_out, (long)act_bytes));
+  }
   // backward in reverse layer order
   const void* dz = dy;
-  for (int l = L - 1; l >= 0; --l) {
+  for (int l = L - 1; do_bwd && l >= 0; --l) {
     const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
     const LayerG G{grads ? static_cast<char*>(grads) + ctx->gl.layer_bytes * (size_t)l : nullptr, &ctx->gl};
     const void* xl = l == 0 ? x_in : set_of(l - 1) + P.lb.z;
@@ -487,16 +548,19 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
   const LayerG G{train ? static_cast<char*>(grads) + ctx->gl.layer_bytes * (size_t)L : nullptr, &ctx->gl};
   const bf16_t* Wv = W.t(RP_T_WV);
 
-  X.chk(k_rmsnorm_fwd(X.st, x, W.t(RP_T_GF), X.at<void>(P.h_xf), X.at<float>(P.h_rstd), T, D.h, ctx->cfg.rms_eps), "final norm");
-  X.chk(k_fill_u32(X.st, X.at<void>(P.h_zlab), T, 0u), "zlab fill");
+  const double Td = (double)T;
+  RUN(X, "rmsnorm_fwd", 0, 4.0 * Td * D.h, k_rmsnorm_fwd(X.st, x, W.t(RP_T_GF), X.at<void>(P.h_xf), X.at<float>(P.h_rstd), T, D.h, ctx->cfg.rms_eps));
+  RUN(X, "fill", 0, 4.0 * Td, k_fill_u32(X.st, X.at<void>(P.h_zlab), T, 0u));
   {  // sweep 1: logits tile by tile, reduced to per-token (max, sum exp) partials; nothing of size T x V is stored
     GemmArgs g; gemm_zero_args(g);
     g.A = Wv; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = D.V; g.N = T; g.K = D.h; g.epi = EPI_CE_STATS;
     g.labels = labels; g.zlab = X.at<float>(P.h_zlab); g.part = X.at<float2>(P.h_part); g.part_ld = T;
+    X.mark_gemm(GEMM_NT, g);
     X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head sweep 1");
   }
-  X.chk(k_ce_lse(X.st, X.at<float2>(P.h_part), P.head_parts, T, X.at<float>(P.h_lse), T), "ce lse");
-  X.chk(k_ce_finalize(X.st, X.at<float>(P.h_lse), X.at<float>(P.h_zlab), labels, grad_scale, X.at<float>(P.h_coef), loss_out, T), "ce finalize");
+  RUN(X, "ce_lse", 0, 8.0 * P.head_parts * Td, k_ce_lse(X.st, X.at<float2>(P.h_part), P.head_parts, T, X.at<float>(P.h_lse), T));
+  RUN(X, "ce_finalize", 0, 16.0 * Td,
+      k_ce_finalize(X.st, X.at<float>(P.h_lse), X.at<float>(P.h_zlab), labels, grad_scale, X.at<float>(P.h_coef), loss_out, T));
   // sweep 2: per vocabulary chunk recompute the logits, turn them into dZ^T (bf16), and feed dX and dW
   for (int v0 = 0, ci = 0; v0 < D.V; v0 += P.head_chunk, ++ci) {
     const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
@@ -505,20 +569,65 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
     g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h; g.epi = EPI_CE_DZ;
     g.C = X.at<void>(P.h_dzt); g.ldc = T; g.labels = labels; g.lse = X.at<float>(P.h_lse); g.coef = X.at<float>(P.h_coef);
     g.row_offset = v0;
+    X.mark_gemm(GEMM_NT, g);
     X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head sweep 2");
     GemmArgs d; gemm_zero_args(d);   // dXf[T, h] (+)= dZ^T^T . W_c   (reduction over the chunk's vocabulary rows)
     d.A = X.at<void>(P.h_dzt); d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = X.at<void>(P.h_dxacc);
     d.ldc = D.h; d.beta = ci > 0; d.epi = EPI_F32;
+    X.mark_gemm(GEMM_TN, d);
     X.chk(gemm_launch(X.st, GEMM_TN, d), "lm head dX");
     if (G.t(RP_T_WV)) {
       GemmArgs w; gemm_zero_args(w);  // dW_c[vc, h] += dZ^T . xf
       w.A = X.at<void>(P.h_dzt); w.lda = T; w.B = X.at<void>(P.h_xf); w.ldb = D.h; w.M = vc; w.N = D.h; w.K = T;
       w.C = G.t(RP_T_WV) + (size_t)v0 * D.h; w.ldc = D.h; w.beta = 1; w.epi = EPI_F32;
+      X.mark_gemm(GEMM_NN, w);
       X.chk(gemm_launch(X.st, GEMM_NN, w), "lm head dW");
     }
   }
-  X.chk(k_rmsnorm_bwd(X.st, X.at<void>(P.h_dxacc), 1, x, W.t(RP_T_GF), X.at<float>(P.h_rstd), nullptr, dx, G.t(RP_T_GF), T, D.h), "final norm bwd");
+  RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
+      k_rmsnorm_bwd(X.st, X.at<void>(P.h_dxacc), 1, x, W.t(RP_T_GF), X.at<float>(P.h_rstd), nullptr, dx, G.t(RP_T_GF), T, D.h));
   return finish_call(ctx, sl, X);
+}
+
+// ---- per-kernel timeline ---------------------------------------------------------------------------------------------
+rp_status rp_trace_start(rp_ctx* ctx, int max_records) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (max_records <= 0 || max_records > (1 << 20)) return fail(ctx, RP_EINVAL, "bad max_records");
+  if (ctx->trace_cap < max_records) {
+    if (ctx->trace_ev) {
+      for (int i = 0; i <= ctx->trace_cap; ++i) if (ctx->trace_ev[i]) (void)hipEventDestroy(ctx->trace_ev[i]);
+      delete[] ctx->trace_ev;
+      delete[] ctx->trace_rec;
+      ctx->trace_ev = nullptr; ctx->trace_rec = nullptr; ctx->trace_cap = 0;
+    }
+    ctx->trace_ev = new (std::nothrow) hipEvent_t[max_records + 1]();
+    ctx->trace_rec = new (std::nothrow) TraceRec[max_records];
+    if (!ctx->trace_ev || !ctx->trace_rec) return fail(ctx, RP_ENOMEM, "out of host memory");
+    for (int i = 0; i <= max_records; ++i) HIP_TRY(ctx, hipEventCreate(&ctx->trace_ev[i]));
+    ctx->trace_cap = max_records;
+  }
+  ctx->trace_n = 0;
+  ctx->tracing = true;
+  return RP_OK;
+}
+
+rp_status rp_trace_stop(rp_ctx* ctx, rp_trace_record* out, int cap, int* n_out) {
+  if (!ctx || !n_out) return fail(ctx, RP_EINVAL, "NULL argument");
+  if (!ctx->tracing) return fail(ctx, RP_ESTATE, "trace not started");
+  ctx->tracing = false;
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->compute));
+  const int n = ctx->trace_n < cap ? ctx->trace_n : cap;
+  for (int i = 0; i < n; ++i) {
+    float ms = 0.f;
+    // the end of op i is the start of op i+1 (or the call's trailing event); ops of one stream run back to back
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->trace_ev[i], ctx->trace_ev[i + 1]));
+    if (out) {
+      snprintf(out[i].name, sizeof(out[i].name), "%s", ctx->trace_rec[i].name);
+      out[i].flops = ctx->trace_rec[i].flops; out[i].bytes = ctx->trace_rec[i].bytes; out[i].ms = ms;
+    }
+  }
+  *n_out = n;
+  return RP_OK;
 }
 
 // ---- kernel-level entry points (unit parity tests) ----------------------------------------------------------------
@@ -597,7 +706,8 @@ rp_status rp_op_attn_bwd(void* stream, const void* q, const void* k, const void*
   if (ldq % 8 || ldk % 8 || ldv % 8 || ldo % 8 || lddo % 8 || lddq % 8 || lddk % 8 || lddv % 8) return fail(nullptr, RP_EINVAL, "rp_op_attn_bwd: strides must be multiples of 8");
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   hipError_t e = k_attn_delta(st, o, dout, delta, ldo, lddo, batch, seq, a, d);
-  if (e == hipSuccess) e = k_attn_bwd(st, q, k, v, dout, lse, delta, dq, dk, dv, ldq, ldk, ldv, lddo, lddq, lddk, lddv, batch, seq, a, kh, d);
+  for (int part = 0; part < 2 && e == hipSuccess; ++part)
+    e = k_attn_bwd(st, part, q, k, v, dout, lse, delta, dq, dk, dv, ldq, ldk, ldv, lddo, lddq, lddk, lddv, batch, seq, a, kh, d);
   OP_RET(e);
 }
 

@@ -126,6 +126,10 @@ class StageRunner:
         self.ctx = B.rp_ctx_create(self.device.index or 0, self.compute.cuda_stream, self.copy.cuda_stream, cfg)
         self.slots = [torch.empty(self.wbytes, dtype=torch.uint8, device=self.device) for _ in range(n_slots)]
         self.ws = torch.empty(self.wsbytes, dtype=torch.uint8, device=self.device)
+        # the head gets a workspace of its own so that it can run between the two phases of a fused last stage
+        self.ws_head = self.ws
+        if cfg.vocab > 0 and cfg.n_layers > 0:
+            self.ws_head = torch.empty(self.wsbytes, dtype=torch.uint8, device=self.device)
         self.grads = torch.zeros(max(self.gbytes, 4) // 4, dtype=torch.float32, device=self.device)
         self.T = batch * seq
 
@@ -155,17 +159,30 @@ class StageRunner:
         return (out, keep) if keep_layer_inputs else out
 
     def backward(self, x, dy, slot=0, want_out=True):
+        """Ordinary backward stage: recomputation followed by the backward pass."""
         dx = torch.empty_like(x)
         out = torch.empty_like(x) if want_out else None
-        B.rp_stage_backward(self.ctx, slot, x, dy, dx, out, self.grads if self.gbytes else None, None, None, self.batch,
-                            self.seq, self.ws, self.wsbytes)
+        B.rp_stage_backward(self.ctx, slot, B.PHASE_BOTH, x, dy, dx, out, self.grads if self.gbytes else None, None, None,
+                            self.batch, self.seq, self.ws, self.wsbytes)
         return out, dx
 
-    def head(self, x, labels, grad_scale=1.0, slot=0, train=True):
-        loss = torch.zeros(1, dtype=torch.float32, device=self.device)
-        dx = torch.empty_like(x)
+    def recompute(self, x, out, slot=0):
+        """First half of the fused last stage: forward keeping the internals in the workspace."""
+        B.rp_stage_backward(self.ctx, slot, B.PHASE_RECOMPUTE, x, None, None, out, None, None, None, self.batch, self.seq,
+                            self.ws, self.wsbytes)
+
+    def backward_only(self, x, dy, dx, slot=0):
+        """Second half: backward from the internals the recompute phase left in the workspace."""
+        B.rp_stage_backward(self.ctx, slot, B.PHASE_BACKWARD, x, dy, dx, None, self.grads if self.gbytes else None, None,
+                            None, self.batch, self.seq, self.ws, self.wsbytes)
+
+    def head(self, x, labels, grad_scale=1.0, slot=0, train=True, loss=None, dx=None):
+        if loss is None:
+            loss = torch.empty(1, dtype=torch.float32, device=self.device)
+        if dx is None:
+            dx = torch.empty_like(x)
         B.rp_lmhead_ce_fwd_bwd(self.ctx, slot, x, labels, loss, dx, self.grads if (train and self.gbytes) else None,
-                               grad_scale, self.batch, self.seq, self.ws, self.wsbytes)
+                               grad_scale, self.batch, self.seq, self.ws_head, self.wsbytes)
         return loss, dx
 
     def sync(self):
