@@ -16,26 +16,28 @@ extern "C" {
  * out_f32 0: C bf16 = alpha*acc (+ R, bf16 [M,N], optional);  1: C fp32 = alpha*acc (+ C when beta);  2: atomic +=.
  * (A2, B2, K2): optional second operand pair, same layout, appended to the reduction (LoRA up-projection).
  * K, K2 and all leading dimensions are multiples of 8; N (and M for layout 2) too when that operand is transposed.
- * tile 0 = automatic, 1..4 force 256x256, 256x128, 128x128, 64x64. */
+ * tile 0 = automatic, 1..4 force 256x256, 256x128, 128x128, 128x64. */
 RP_API rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const void* B, void* C, int M, int N, int K,
                      long lda, long ldb, long ldc, float alpha, int beta, const void* A2, const void* B2, int K2, long lda2,
                      long ldb2, const void* R, long ldr, int tile);
 
 /* RMSNorm: y = x * rstd * g, rstd_t = (mean_j x_tj^2 + eps)^(-1/2); rstd fp32 [T] (may be NULL). */
 RP_API rp_status rp_op_rmsnorm_fwd(void* stream, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps);
-/* dx = backward of the above (+ dres, bf16 [T,h], optional); dg fp32 [h] accumulated (optional). dy bf16, or fp32 when dy_is_f32. */
+/* dx = backward of the above (+ dres, bf16 [T,h], optional); dg fp32 [h] accumulated (optional; then scratch, fp32
+ * [512 * h], is required and overwritten). dy bf16, or fp32 when dy_is_f32. */
 RP_API rp_status rp_op_rmsnorm_bwd(void* stream, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
-                            const void* dres, void* dx, float* dg, int T, int h);
+                            const void* dres, void* dx, float* dg, float* scratch, int T, int h);
 
 /* cs: float2 [seq][d/2] = (cos, sin)(pos * base^(-2i/d)) */
 RP_API rp_status rp_op_rope_table(void* stream, void* cs, int seq, int d, float base);
 /* Per-head RMSNorm (optional) + rotary embedding with half-split pairs (i, i + d/2) on a query heads and k key heads.
  * forward: in_* -> out_*;  backward (bwd = 1): in_* are gradients of the rotated heads, raw_* the pre-norm heads,
- * out_* the gradients of the raw heads, dgq/dgk fp32 [d] accumulated.  rstd_* fp32 [T, heads]. */
+ * out_* the gradients of the raw heads, dgq/dgk fp32 [d] accumulated (scratch: fp32 [512 * 2 * d], overwritten).
+ * rstd_* fp32 [T, heads]. */
 RP_API rp_status rp_op_qknorm_rope(void* stream, int bwd, int d, const void* in_q, const void* in_k, long ld_in_q, long ld_in_k,
                             void* out_q, void* out_k, long ld_out_q, long ld_out_k, const void* gq, const void* gk, float* rstd_q,
                             float* rstd_k, const void* raw_q, const void* raw_k, long ld_raw, float* dgq, float* dgk,
-                            const void* cs, int T, int seq, int a, int k, int use_norm, float eps);
+                            float* scratch, const void* cs, int T, int seq, int a, int k, int use_norm, float eps);
 
 /* SwiGLU: act[T,m] = silu(gu[:, :m]) * gu[:, m:];  backward gives dgu [T, 2m]. */
 RP_API rp_status rp_op_swiglu_fwd(void* stream, const void* gu, void* act, long T, int m);

@@ -40,6 +40,13 @@ class RpError(RuntimeError):
 
 
 def _load():
+    # PyTorch wheels bundle their own HIP runtime (same soname as the system one).  A process must talk to exactly one
+    # runtime, or streams and events handed across the boundary belong to a different runtime than the one the
+    # kernels are launched with: load torch's copy first so that librp.so binds to it.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(LIB_PATH):
         raise ImportError("librp.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(or python paper_2604_27085_amd/build.py) first; there is no CPU fallback")
@@ -68,10 +75,10 @@ _SIGS = {
     "rp_trace_stop": [_vp, C.POINTER(TraceRecord), _i, C.POINTER(_i)],
     "rp_op_gemm": [_vp, _i, _i, _vp, _vp, _vp, _i, _i, _i, _l, _l, _l, _f, _i, _vp, _vp, _i, _l, _l, _vp, _l, _i],
     "rp_op_rmsnorm_fwd": [_vp, _vp, _vp, _vp, _vp, _i, _i, _f],
-    "rp_op_rmsnorm_bwd": [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i],
+    "rp_op_rmsnorm_bwd": [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i],
     "rp_op_rope_table": [_vp, _vp, _i, _i, _f],
     "rp_op_qknorm_rope": [_vp, _i, _i, _vp, _vp, _l, _l, _vp, _vp, _l, _l, _vp, _vp, _vp, _vp, _vp, _vp, _l, _vp, _vp,
-                          _vp, _i, _i, _i, _i, _i, _f],
+                          _vp, _vp, _i, _i, _i, _i, _i, _f],
     "rp_op_swiglu_fwd": [_vp, _vp, _vp, _l, _i],
     "rp_op_swiglu_bwd": [_vp, _vp, _vp, _vp, _l, _i],
     "rp_op_attn_fwd": [_vp, _vp, _vp, _vp, _vp, _vp, _l, _l, _l, _l, _i, _i, _i, _i, _i],
@@ -198,9 +205,9 @@ def rp_op_rmsnorm_fwd(stream, x, g, y, rstd, T_, h, eps):
     _check(lib.rp_op_rmsnorm_fwd(stream, _ptr(x), _ptr(g), _ptr(y), _ptr(rstd), T_, h, eps))
 
 
-def rp_op_rmsnorm_bwd(stream, dy, dy_is_f32, x, g, rstd, dres, dx, dg, T_, h):
+def rp_op_rmsnorm_bwd(stream, dy, dy_is_f32, x, g, rstd, dres, dx, dg, scratch, T_, h):
     _check(lib.rp_op_rmsnorm_bwd(stream, _ptr(dy), dy_is_f32, _ptr(x), _ptr(g), _ptr(rstd), _ptr(dres), _ptr(dx),
-                                 _ptr(dg), T_, h))
+                                 _ptr(dg), _ptr(scratch), T_, h))
 
 
 def rp_op_rope_table(stream, cs, seq, d, base):
@@ -208,10 +215,11 @@ def rp_op_rope_table(stream, cs, seq, d, base):
 
 
 def rp_op_qknorm_rope(stream, bwd, d, in_q, in_k, ld_in_q, ld_in_k, out_q, out_k, ld_out_q, ld_out_k, gq, gk, rstd_q,
-                      rstd_k, raw_q, raw_k, ld_raw, dgq, dgk, cs, T_, seq, a, k, use_norm, eps):
+                      rstd_k, raw_q, raw_k, ld_raw, dgq, dgk, scratch, cs, T_, seq, a, k, use_norm, eps):
     _check(lib.rp_op_qknorm_rope(stream, bwd, d, _ptr(in_q), _ptr(in_k), ld_in_q, ld_in_k, _ptr(out_q), _ptr(out_k),
                                  ld_out_q, ld_out_k, _ptr(gq), _ptr(gk), _ptr(rstd_q), _ptr(rstd_k), _ptr(raw_q),
-                                 _ptr(raw_k), ld_raw, _ptr(dgq), _ptr(dgk), _ptr(cs), T_, seq, a, k, use_norm, eps))
+                                 _ptr(raw_k), ld_raw, _ptr(dgq), _ptr(dgk), _ptr(scratch), _ptr(cs), T_, seq, a, k,
+                                 use_norm, eps))
 
 
 def rp_op_swiglu_fwd(stream, gu, act, T_, m):

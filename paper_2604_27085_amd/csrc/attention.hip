@@ -521,8 +521,8 @@ hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* 
   p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.ldo = ldo;
   fill_common(p, batch, seq, a, kh, d);
   const int grid = ((seq + 127) / 128) * a * batch;
-  if (d == 128) hipLaunchKernelGGL(attn_fwd_kernel<128>, dim3(grid), dim3(256), 0, st, p);
-  else if (d == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, dim3(grid), dim3(256), 0, st, p);
+  if (d == 128) RP_LAUNCH(attn_fwd_kernel<128>, dim3(grid), dim3(256), 0, st, p);
+  else if (d == 64) RP_LAUNCH(attn_fwd_kernel<64>, dim3(grid), dim3(256), 0, st, p);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
@@ -532,8 +532,8 @@ hipError_t k_attn_delta(hipStream_t st, const void* o, const void* dout, float* 
   const long items = (long)batch * seq * a * (d / 8);
   if (items == 0) return hipSuccess;
   const int grid = (int)((items + 255) / 256);
-  if (d == 128) hipLaunchKernelGGL(attn_delta_kernel<128>, dim3(grid), dim3(256), 0, st, (const bf16*)o, (const bf16*)dout, delta, ldo, lddo, batch, seq, a);
-  else if (d == 64) hipLaunchKernelGGL(attn_delta_kernel<64>, dim3(grid), dim3(256), 0, st, (const bf16*)o, (const bf16*)dout, delta, ldo, lddo, batch, seq, a);
+  if (d == 128) RP_LAUNCH(attn_delta_kernel<128>, dim3(grid), dim3(256), 0, st, (const bf16*)o, (const bf16*)dout, delta, ldo, lddo, batch, seq, a);
+  else if (d == 64) RP_LAUNCH(attn_delta_kernel<64>, dim3(grid), dim3(256), 0, st, (const bf16*)o, (const bf16*)dout, delta, ldo, lddo, batch, seq, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
@@ -560,13 +560,13 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
         if (e != hipSuccess) return e;
         attr_done = true;
       }
-      hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, dim3(nk), dim3(256), smem, st, p);
+      RP_LAUNCH(attn_bwd_dkv_kernel<128>, dim3(nk), dim3(256), smem, st, p);
     } else {
-      hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, dim3(nk), dim3(256), dkv_smem_bytes(64), st, p);
+      RP_LAUNCH(attn_bwd_dkv_kernel<64>, dim3(nk), dim3(256), dkv_smem_bytes(64), st, p);
     }
   } else {
-    if (d == 128) hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, dim3(nq), dim3(256), 0, st, p);
-    else hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, dim3(nq), dim3(256), 0, st, p);
+    if (d == 128) RP_LAUNCH(attn_bwd_dq_kernel<128>, dim3(nq), dim3(256), 0, st, p);
+    else RP_LAUNCH(attn_bwd_dq_kernel<64>, dim3(nq), dim3(256), 0, st, p);
   }
   return hipGetLastError();
 }

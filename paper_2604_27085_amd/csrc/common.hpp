@@ -12,6 +12,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define RP_DEV __device__ __forceinline__
 
+// Launch with a clean error slate: hipGetLastError() after the launch must report this launch, not an error another
+// library left behind earlier on this thread.
+#define RP_LAUNCH(...)               \
+  do {                               \
+    (void)hipGetLastError();         \
+    hipLaunchKernelGGL(__VA_ARGS__); \
+  } while (0)
+
 static RP_DEV float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 static RP_DEV float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 static RP_DEV float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

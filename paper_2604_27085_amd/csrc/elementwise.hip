@@ -60,12 +60,18 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const bf16* __restrict
 
 // ------------------------------------------------------------------------------------------------ RMSNorm backward
 // dx = rstd*(dy*g) - rstd^3/h * x * sum_j(dy_j g_j x_j)  (+ dres, the gradient arriving over the residual branch);
-// dg += sum_t dy_t * x_t * rstd_t, accumulated per lane over the rows a wave visits, then added atomically.
+// dg partial = sum_t dy_t * x_t * rstd_t over the rows a block visits: accumulated per lane, merged across the block's
+// waves in LDS and written to part[block][h]; a column-sum kernel adds the partials to dg in a fixed order.
 template <int MAXC, typename DyT>
 __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict__ dy, const bf16* __restrict__ x,
                                                           const bf16* __restrict__ g, const float* __restrict__ rstd_in,
                                                           const bf16* __restrict__ dres, bf16* __restrict__ dx,
-                                                          float* __restrict__ dg, int T, int h) {
+                                                          float* __restrict__ part, int T, int h) {
+  extern __shared__ float dg_s[];
+  if (part) {
+    for (int i = threadIdx.x; i < h; i += 256) dg_s[i] = 0.f;
+    __syncthreads();
+  }
   const int lane = threadIdx.x & 63;
   const int wave_id = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int nwaves = gridDim.x * 4;
@@ -131,16 +137,28 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict_
       }
     }
   }
-  if (dg) {
+  if (part) {
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
       const int c = lane + 64 * i;
       if (c < nch) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) atomicAdd(dg + c * 8 + e, dgacc[i][e]);
+        for (int e = 0; e < 8; ++e) atomicAdd(dg_s + c * 8 + e, dgacc[i][e]);
       }
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < h; i += 256) part[(long)blockIdx.x * h + i] = dg_s[i];
   }
+}
+
+// dst[c] += sum_r part[r][c], r = 0..rows-1, one thread per column (coalesced across columns, fixed order)
+__global__ void __launch_bounds__(256) colsum_add_kernel(const float* __restrict__ part, int rows, int ld, int cols,
+                                                         float* __restrict__ dst) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= cols) return;
+  float s = 0.f;
+  for (int r = 0; r < rows; ++r) s += part[(long)r * ld + c];
+  dst[c] += s;
 }
 
 // ------------------------------------------------------------------------------------------------ RoPE table
@@ -167,9 +185,14 @@ __global__ void __launch_bounds__(256) qknorm_rope_kernel(const bf16* __restrict
                                                           const bf16* __restrict__ gq, const bf16* __restrict__ gk,
                                                           float* __restrict__ rstd_q, float* __restrict__ rstd_k,
                                                           const bf16* __restrict__ raw_q, const bf16* __restrict__ raw_k,
-                                                          long ld_raw, float* __restrict__ dgq, float* __restrict__ dgk,
+                                                          long ld_raw, float* __restrict__ part,
                                                           const float2* __restrict__ cs, int T, int seq, int a, int k,
                                                           int use_norm, float eps) {
+  __shared__ float dg_s[2 * D];
+  if (BWD && part) {
+    for (int i = threadIdx.x; i < 2 * D; i += 256) dg_s[i] = 0.f;
+    __syncthreads();
+  }
   constexpr int LPH = D / 8;          // lanes per head
   constexpr int HPW = 64 / LPH;       // heads per wave pass
   const int lane = threadIdx.x & 63;
@@ -271,15 +294,17 @@ __global__ void __launch_bounds__(256) qknorm_rope_kernel(const bf16* __restrict
     }
   }
   if constexpr (BWD) {
-    if (use_norm && dgq) {
-      // lanes with the same `sub` hold partial sums for the same 8 gain entries
+    if (use_norm && part) {
+      // lanes with the same `sub` hold partial sums for the same 8 gain entries; waves merge in LDS, blocks via part[]
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float vq = dgq_acc[e], vk = dgk_acc[e];
 #pragma unroll
         for (int o = LPH; o < 64; o <<= 1) { vq += __shfl_xor(vq, o, 64); vk += __shfl_xor(vk, o, 64); }
-        if (hsel == 0) { atomicAdd(dgq + sub * 8 + e, vq); atomicAdd(dgk + sub * 8 + e, vk); }
+        if (hsel == 0) { atomicAdd(dg_s + sub * 8 + e, vq); atomicAdd(dg_s + D + sub * 8 + e, vk); }
       }
+      __syncthreads();
+      for (int i = threadIdx.x; i < 2 * D; i += 256) part[(long)blockIdx.x * 2 * D + i] = dg_s[i];
     }
   }
 }
@@ -372,83 +397,100 @@ hipError_t k_rmsnorm_fwd(hipStream_t st, const void* x, const void* g, void* y, 
   const int grid = (T + 3) / 4;
   if (grid == 0) return hipSuccess;
   if (h <= 2048)
-    hipLaunchKernelGGL((rmsnorm_fwd_kernel<4>), dim3(grid), dim3(256), 0, st, (const bf16*)x, (const bf16*)g, (bf16*)y, rstd, T, h, eps);
+    RP_LAUNCH((rmsnorm_fwd_kernel<4>), dim3(grid), dim3(256), 0, st, (const bf16*)x, (const bf16*)g, (bf16*)y, rstd, T, h, eps);
   else
-    hipLaunchKernelGGL((rmsnorm_fwd_kernel<16>), dim3(grid), dim3(256), 0, st, (const bf16*)x, (const bf16*)g, (bf16*)y, rstd, T, h, eps);
+    RP_LAUNCH((rmsnorm_fwd_kernel<16>), dim3(grid), dim3(256), 0, st, (const bf16*)x, (const bf16*)g, (bf16*)y, rstd, T, h, eps);
   return hipGetLastError();
 }
 
 hipError_t k_rmsnorm_bwd(hipStream_t st, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
-                         const void* dres, void* dx, float* dg, int T, int h) {
+                         const void* dres, void* dx, float* dg, float* scratch, int T, int h) {
   if (T == 0) return hipSuccess;
+  if (dg && !scratch) return hipErrorInvalidValue;
   int grid = (T + 3) / 4;
-  if (grid > 512) grid = 512;
+  if (grid > RP_PARTIAL_BLOCKS) grid = RP_PARTIAL_BLOCKS;
+  float* part = dg ? scratch : nullptr;
+  const size_t smem = dg ? (size_t)h * 4 : 0;
 #define RP_LAUNCH_RB(MAXC, DT) \
-  hipLaunchKernelGGL((rmsnorm_bwd_kernel<MAXC, DT>), dim3(grid), dim3(256), 0, st, (const DT*)dy, (const bf16*)x, \
-                     (const bf16*)g, rstd, (const bf16*)dres, (bf16*)dx, dg, T, h)
+  RP_LAUNCH((rmsnorm_bwd_kernel<MAXC, DT>), dim3(grid), dim3(256), smem, st, (const DT*)dy, (const bf16*)x, \
+                     (const bf16*)g, rstd, (const bf16*)dres, (bf16*)dx, part, T, h)
   if (h <= 2048) { if (dy_is_f32) RP_LAUNCH_RB(4, float); else RP_LAUNCH_RB(4, bf16); }
   else { if (dy_is_f32) RP_LAUNCH_RB(16, float); else RP_LAUNCH_RB(16, bf16); }
 #undef RP_LAUNCH_RB
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && dg) {
+    RP_LAUNCH(colsum_add_kernel, dim3((h + 255) / 256), dim3(256), 0, st, part, grid, h, h, dg);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 hipError_t k_rope_table(hipStream_t st, float2* cs, int seq, int d, float base) {
   const int n = seq * (d / 2);
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cs, seq, d / 2, log2((double)base));
+  RP_LAUNCH(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, cs, seq, d / 2, log2((double)base));
   return hipGetLastError();
 }
 
 hipError_t k_qknorm_rope(hipStream_t st, int bwd, int d, const void* in_q, const void* in_k, long ld_in_q, long ld_in_k,
                          void* out_q, void* out_k, long ld_out_q, long ld_out_k, const void* gq, const void* gk,
                          float* rstd_q, float* rstd_k, const void* raw_q, const void* raw_k, long ld_raw, float* dgq,
-                         float* dgk, const float2* cs, int T, int seq, int a, int k, int use_norm, float eps) {
+                         float* dgk, float* scratch, const float2* cs, int T, int seq, int a, int k, int use_norm, float eps) {
   if (T == 0) return hipSuccess;
   int grid = (T + 3) / 4;
-  if (bwd && grid > 1024) grid = 1024;
+  if (bwd && grid > RP_PARTIAL_BLOCKS) grid = RP_PARTIAL_BLOCKS;
+  const bool want_dg = bwd && use_norm && dgq && dgk;
+  if (want_dg && !scratch) return hipErrorInvalidValue;
+  float* part = want_dg ? scratch : nullptr;
 #define RP_LAUNCH_QR(D, B) \
-  hipLaunchKernelGGL((qknorm_rope_kernel<D, B>), dim3(grid), dim3(256), 0, st, (const bf16*)in_q, (const bf16*)in_k, \
+  RP_LAUNCH((qknorm_rope_kernel<D, B>), dim3(grid), dim3(256), 0, st, (const bf16*)in_q, (const bf16*)in_k, \
                      ld_in_q, ld_in_k, (bf16*)out_q, (bf16*)out_k, ld_out_q, ld_out_k, (const bf16*)gq, (const bf16*)gk, \
-                     rstd_q, rstd_k, (const bf16*)raw_q, (const bf16*)raw_k, ld_raw, dgq, dgk, cs, T, seq, a, k, use_norm, eps)
+                     rstd_q, rstd_k, (const bf16*)raw_q, (const bf16*)raw_k, ld_raw, part, cs, T, seq, a, k, use_norm, eps)
   if (d == 128) { if (bwd) RP_LAUNCH_QR(128, true); else RP_LAUNCH_QR(128, false); }
   else if (d == 64) { if (bwd) RP_LAUNCH_QR(64, true); else RP_LAUNCH_QR(64, false); }
   else return hipErrorInvalidValue;
 #undef RP_LAUNCH_QR
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && want_dg) {
+    RP_LAUNCH(colsum_add_kernel, dim3(1), dim3(256), 0, st, part, grid, 2 * d, d, dgq);
+    RP_LAUNCH(colsum_add_kernel, dim3(1), dim3(256), 0, st, part + d, grid, 2 * d, d, dgk);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 hipError_t k_swiglu_fwd(hipStream_t st, const void* gu, void* act, long T, int m) {
   if (T == 0) return hipSuccess;
-  hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(grid_for(T * (m / 8))), dim3(256), 0, st, (const bf16*)gu, (bf16*)act, T, m);
+  RP_LAUNCH(swiglu_fwd_kernel, dim3(grid_for(T * (m / 8))), dim3(256), 0, st, (const bf16*)gu, (bf16*)act, T, m);
   return hipGetLastError();
 }
 
 hipError_t k_swiglu_bwd(hipStream_t st, const void* dact, const void* gu, void* dgu, long T, int m) {
   if (T == 0) return hipSuccess;
-  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(grid_for(T * (m / 8))), dim3(256), 0, st, (const bf16*)dact, (const bf16*)gu, (bf16*)dgu, T, m);
+  RP_LAUNCH(swiglu_bwd_kernel, dim3(grid_for(T * (m / 8))), dim3(256), 0, st, (const bf16*)dact, (const bf16*)gu, (bf16*)dgu, T, m);
   return hipGetLastError();
 }
 
 hipError_t k_fill_u32(hipStream_t st, void* p, long n_words, uint32_t v) {
   if (n_words == 0) return hipSuccess;
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(n_words)), dim3(256), 0, st, (uint32_t*)p, n_words, v);
+  RP_LAUNCH(fill_u32_kernel, dim3(grid_for(n_words)), dim3(256), 0, st, (uint32_t*)p, n_words, v);
   return hipGetLastError();
 }
 
 hipError_t k_copy16(hipStream_t st, const void* src, void* dst, long bytes) {
   if (bytes == 0) return hipSuccess;
-  hipLaunchKernelGGL(copy16_kernel, dim3(grid_for(bytes / 16)), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, bytes / 16);
+  RP_LAUNCH(copy16_kernel, dim3(grid_for(bytes / 16)), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, bytes / 16);
   return hipGetLastError();
 }
 
 hipError_t k_cast_f32_bf16(hipStream_t st, const float* src, void* dst, long n) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(cast_f32_bf16_kernel, dim3(grid_for(n / 8)), dim3(256), 0, st, src, (bf16*)dst, n / 8);
+  RP_LAUNCH(cast_f32_bf16_kernel, dim3(grid_for(n / 8)), dim3(256), 0, st, src, (bf16*)dst, n / 8);
   return hipGetLastError();
 }
 
 hipError_t k_lora_blockdiag(hipStream_t st, void* out, int N, int ncols, const LoraSegs& segs, int r) {
   if ((long)N * ncols == 0) return hipSuccess;
-  hipLaunchKernelGGL(lora_blockdiag_kernel, dim3(grid_for((long)N * ncols)), dim3(256), 0, st, (bf16*)out, N, ncols, segs, r);
+  RP_LAUNCH(lora_blockdiag_kernel, dim3(grid_for((long)N * ncols)), dim3(256), 0, st, (bf16*)out, N, ncols, segs, r);
   return hipGetLastError();
 }

@@ -33,6 +33,8 @@ struct GemmArgs {
   // cross-entropy epilogues
   const int* labels; float* zlab; float2* part; long part_ld; const float* lse; const float* coef;
   int row_offset;              // global vocab index of row 0 of A
+  // byte extents of the four operands (filled in by gemm_launch; rows beyond them read as zero)
+  unsigned bytesA, bytesB, bytesA2, bytesB2;
   int part_row0;               // first partial row this launch writes (2 per M tile)
 };
 
@@ -41,5 +43,5 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a, int tile_h
 // Number of partial rows an EPI_CE_STATS launch with M vocab rows writes for tile choice made by gemm_launch.
 int gemm_ce_stats_partials(int M);
 void gemm_zero_args(GemmArgs& a);
-// Tile gemm_launch picks for these arguments: 1..4 = 256x256, 256x128, 128x128, 64x64.
+// Tile gemm_launch picks for these arguments: 1..4 = 256x256, 256x128, 128x128, 128x64.
 int gemm_pick_tile(const GemmArgs& a, int tile_hint = 0);

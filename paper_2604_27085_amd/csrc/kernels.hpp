@@ -10,16 +10,20 @@ struct LoraSegs {           // up to three row segments of a fused projection, e
 
 // y = x * rstd * g, rstd[T] saved (may be NULL).  x, y bf16 [T, h]; g bf16 [h].
 hipError_t k_rmsnorm_fwd(hipStream_t st, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps);
-// dx = rmsnorm backward (+ dres if non-NULL); dg (fp32 [h], may be NULL) accumulated atomically.  dy bf16 or fp32.
+// Gain gradients are reduced block by block into `scratch` and then added to their destination in a fixed order.
+#define RP_PARTIAL_BLOCKS 512
+// dx = rmsnorm backward (+ dres if non-NULL); dg (fp32 [h], may be NULL) += its gradient, using scratch
+// [RP_PARTIAL_BLOCKS * h] floats.  dy bf16 or fp32.
 hipError_t k_rmsnorm_bwd(hipStream_t st, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
-                         const void* dres, void* dx, float* dg, int T, int h);
+                         const void* dres, void* dx, float* dg, float* scratch, int T, int h);
 // cs[seq][d/2] = (cos, sin)(pos * base^(-2i/d))
 hipError_t k_rope_table(hipStream_t st, float2* cs, int seq, int d, float base);
 // forward: (optional per-head RMSNorm) then RoPE on q heads and k heads.  backward: the transpose.
 hipError_t k_qknorm_rope(hipStream_t st, int bwd, int d, const void* in_q, const void* in_k, long ld_in_q, long ld_in_k,
                          void* out_q, void* out_k, long ld_out_q, long ld_out_k, const void* gq, const void* gk,
                          float* rstd_q, float* rstd_k, const void* raw_q, const void* raw_k, long ld_raw, float* dgq,
-                         float* dgk, const float2* cs, int T, int seq, int a, int k, int use_norm, float eps);
+                         float* dgk, float* scratch /* [RP_PARTIAL_BLOCKS * 2 * d] floats, backward with gains */,
+                         const float2* cs, int T, int seq, int a, int k, int use_norm, float eps);
 // act[T, m] = silu(gu[:, :m]) * gu[:, m:]
 hipError_t k_swiglu_fwd(hipStream_t st, const void* gu, void* act, long T, int m);
 hipError_t k_swiglu_bwd(hipStream_t st, const void* dact, const void* gu, void* dgu, long T, int m);

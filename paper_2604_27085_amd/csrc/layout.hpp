@@ -94,10 +94,10 @@ struct LayerBuf {   // byte offsets of one layer's saved internals
 struct Plan {
   size_t rope, bd1, bd3;                          // RoPE table, block-diagonal LoRA B of the fused GEMMs
   size_t layer0, layer_stride;                    // saved internals, one set per layer (backward) or one set (forward)
-  size_t tA, tB, dact, dgu, dn, dout, dqr, dkr, dqkv, delta, ud;   // backward temporaries
+  size_t tA, tB, dact, dgu, dn, dout, dqr, dkr, dqkv, delta, ud, partials;   // backward temporaries
   size_t fwd_bytes, bwd_bytes;
   // head
-  size_t h_xf, h_rstd, h_part, h_zlab, h_lse, h_coef, h_dzt, h_dxacc, head_bytes;
+  size_t h_xf, h_rstd, h_part, h_zlab, h_lse, h_coef, h_dzt, h_dxacc, h_partials, head_bytes;
   int head_chunk, head_parts;
   LayerBuf lb;                                    // offsets relative to a layer set
 };
@@ -135,6 +135,7 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   P.dn = take(T * D.h * 2); P.dout = take(T * D.qd * 2); P.dqr = take(T * D.qd * 2); P.dkr = take(T * D.kd * 2);
   P.dqkv = take(T * D.n1 * 2); P.delta = take(T * D.a * 4);
   P.ud = take(T * (size_t)(3 * D.r) * 2);
+  P.partials = take((size_t)512 * (size_t)(D.h > 2 * D.d ? D.h : 2 * D.d) * 4);
   P.bwd_bytes = o;
   // head
   o = 0;
@@ -145,6 +146,7 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
     P.h_xf = take(T * D.h * 2); P.h_rstd = take(T * 4); P.h_part = take((size_t)P.head_parts * T * 8);
     P.h_zlab = take(T * 4); P.h_lse = take(T * 4); P.h_coef = take(T * 4);
     P.h_dzt = take((size_t)P.head_chunk * T * 2); P.h_dxacc = take(T * D.h * 4);
+    P.h_partials = take((size_t)512 * D.h * 4);
   }
   P.head_bytes = o;
   return P;

@@ -6,20 +6,36 @@
 
 namespace {
 
-// lse[t] = log sum_v exp(z[t, v]) from P partial (max, sum) pairs per token; part is [P][ld] so reads are coalesced.
+// lse[t] = log sum_v exp(z[t, v]) from P partial (max, sum) pairs per token; part is [P][ld] so reads are coalesced
+// over tokens.  A block handles 16 tokens with 16 slices of the partials each, merged through LDS.
 __global__ void __launch_bounds__(256) ce_lse_kernel(const float2* __restrict__ part, int P, long ld, float* __restrict__ lse, int T) {
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  if (t >= T) return;
+  __shared__ float2 red[16][17];
+  const int tl = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int t = blockIdx.x * 16 + tl;
   float m = -INFINITY, s = 0.f;
-  for (int i = 0; i < P; ++i) {
-    const float2 v = part[(long)i * ld + t];
-    if (v.x > -INFINITY) {
-      const float mn = fmaxf(m, v.x);
-      s = s * __expf(m - mn) + v.y * __expf(v.x - mn);
-      m = mn;
+  if (t < T) {
+    for (int i = sl; i < P; i += 16) {
+      const float2 v = part[(long)i * ld + t];
+      if (v.x > -INFINITY) {
+        const float mn = fmaxf(m, v.x);
+        s = s * __expf(m - mn) + v.y * __expf(v.x - mn);
+        m = mn;
+      }
     }
   }
-  lse[t] = m + logf(s);
+  red[sl][tl] = make_float2(m, s);
+  __syncthreads();
+  if (sl == 0 && t < T) {
+    for (int i = 1; i < 16; ++i) {
+      const float2 v = red[i][tl];
+      if (v.x > -INFINITY) {
+        const float mn = fmaxf(m, v.x);
+        s = s * __expf(m - mn) + v.y * __expf(v.x - mn);
+        m = mn;
+      }
+    }
+    lse[t] = m + logf(s);
+  }
 }
 
 // One block: counts the valid tokens, loss = sum(lse - z_label) / n_valid, coef[t] = grad_scale / n_valid or 0.
@@ -55,12 +71,12 @@ __global__ void __launch_bounds__(1024) ce_finalize_kernel(const float* __restri
 
 hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, float* lse, int T) {
   if (T == 0) return hipSuccess;
-  hipLaunchKernelGGL(ce_lse_kernel, dim3((T + 255) / 256), dim3(256), 0, st, part, P, part_ld, lse, T);
+  RP_LAUNCH(ce_lse_kernel, dim3((T + 15) / 16), dim3(256), 0, st, part, P, part_ld, lse, T);
   return hipGetLastError();
 }
 
 hipError_t k_ce_finalize(hipStream_t st, const float* lse, const float* zlab, const int* labels, float grad_scale,
                          float* coef, float* loss_out, int T) {
-  hipLaunchKernelGGL(ce_finalize_kernel, dim3(1), dim3(1024), 0, st, lse, zlab, labels, grad_scale, coef, loss_out, T);
+  RP_LAUNCH(ce_finalize_kernel, dim3(1), dim3(1024), 0, st, lse, zlab, labels, grad_scale, coef, loss_out, T);
   return hipGetLastError();
 }

@@ -131,7 +131,7 @@ struct Exec {
   void mark_gemm(int layout, const GemmArgs& g) {
     if (!ctx->tracing) return;
     static const char* lay[3] = {"NT", "NN", "TN"};
-    static const char* til[5] = {"", "256x256", "256x128", "128x128", "64x64"};
+    static const char* til[5] = {"", "256x256", "256x128", "128x128", "128x64"};
     char nm[40];
     snprintf(nm, sizeof(nm), "gemm_%s_%s", til[gemm_pick_tile(g)], lay[layout]);
     const double out_b = (g.epi == EPI_BF16 || g.epi == EPI_CE_DZ) ? 2.0 : (g.epi == EPI_CE_STATS ? 0.0 : 4.0 * (1 + g.beta));
@@ -246,7 +246,7 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z) 
   linear_fwd(X, W, RP_T_WQKV, fused_qkv(D), X.P.bd1, S(b.n1), D.h, qkv, D.n1, S(b.u1), nullptr);
   RUN(X, "qknorm_rope_fwd", 0, 4.0 * Td * (D.qd + D.kd),
       k_qknorm_rope(X.st, 0, D.d, qkv, qkv + D.qd, D.n1, D.n1, S(b.qr), S(b.kr), D.qd, D.kd, W.t(RP_T_GQ), W.t(RP_T_GK),
-                    (float*)S(b.rstd_q), (float*)S(b.rstd_k), nullptr, nullptr, 0, nullptr, nullptr,
+                    (float*)S(b.rstd_q), (float*)S(b.rstd_k), nullptr, nullptr, 0, nullptr, nullptr, nullptr,
                     X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps));
   const double s2qd = (double)X.batch * X.seq * (double)X.seq * D.qd;   // causal attention: 2 s^2 qd forward per sequence
   RUN(X, "attn_fwd", 2.0 * s2qd, 2.0 * Td * (2 * D.qd + 2 * D.kd),
@@ -277,7 +277,7 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
   RUN(X, "swiglu_bwd", 0, 10.0 * Td * D.m, k_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), X.at<void>(X.P.dgu), T, D.m));
   linear_bwd(X, W, G, RP_T_WGU, fused_gu(D), X.P.bd3, X.at<void>(X.P.dgu), 2 * D.m, S(b.n2), D.h, X.at<void>(X.P.dn), S(b.u3));
   RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
-      k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, S(b.y), W.t(RP_T_G2), (const float*)S(b.rstd2), dz, dy, G.t(RP_T_G2), T, D.h));
+      k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, S(b.y), W.t(RP_T_G2), (const float*)S(b.rstd2), dz, dy, G.t(RP_T_G2), X.at<float>(X.P.partials), T, D.h));
   // y = x + o_proj(o)
   linear_bwd(X, W, G, RP_T_WO, fused_single(D.lora[3], RP_T_LA_O, RP_T_LB_O, D.h), 0, dy, D.h, S(b.o), D.qd,
              X.at<void>(X.P.dout), S(b.u2));
@@ -293,10 +293,10 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
   RUN(X, "qknorm_rope_bwd", 0, 6.0 * Td * (D.qd + D.kd),
       k_qknorm_rope(X.st, 1, D.d, X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), D.qd, D.kd, dqkv, dqkv + D.qd, D.n1, D.n1,
                     W.t(RP_T_GQ), W.t(RP_T_GK), (float*)S(b.rstd_q), (float*)S(b.rstd_k), qkv, qkv + D.qd, D.n1,
-                    G.t(RP_T_GQ), G.t(RP_T_GK), X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps));
+                    G.t(RP_T_GQ), G.t(RP_T_GK), X.at<float>(X.P.partials), X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps));
   linear_bwd(X, W, G, RP_T_WQKV, fused_qkv(D), X.P.bd1, dqkv, D.n1, S(b.n1), D.h, X.at<void>(X.P.dn), S(b.u1));
   RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
-      k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, x, W.t(RP_T_G1), (const float*)S(b.rstd1), dy, dx_out, G.t(RP_T_G1), T, D.h));
+      k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, x, W.t(RP_T_G1), (const float*)S(b.rstd1), dy, dx_out, G.t(RP_T_G1), X.at<float>(X.P.partials), T, D.h));
 }
 
 rp_status check_call(rp_ctx* ctx, int slot_id, int batch, int seq, const void* ws, size_t ws_bytes, size_t need) {
@@ -585,7 +585,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
     }
   }
   RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
-      k_rmsnorm_bwd(X.st, X.at<void>(P.h_dxacc), 1, x, W.t(RP_T_GF), X.at<float>(P.h_rstd), nullptr, dx, G.t(RP_T_GF), T, D.h));
+      k_rmsnorm_bwd(X.st, X.at<void>(P.h_dxacc), 1, x, W.t(RP_T_GF), X.at<float>(P.h_rstd), nullptr, dx, G.t(RP_T_GF), X.at<float>(P.h_partials), T, D.h));
   return finish_call(ctx, sl, X);
 }
 
@@ -654,9 +654,9 @@ rp_status rp_op_rmsnorm_fwd(void* stream, const void* x, const void* g, void* y,
 }
 
 rp_status rp_op_rmsnorm_bwd(void* stream, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
-                            const void* dres, void* dx, float* dg, int T, int h) {
-  if (!dy || !x || !g || !rstd || !dx || h % 8 || h > 8192) return fail(nullptr, RP_EINVAL, "rp_op_rmsnorm_bwd: bad arguments");
-  hipError_t e = k_rmsnorm_bwd(reinterpret_cast<hipStream_t>(stream), dy, dy_is_f32, x, g, rstd, dres, dx, dg, T, h);
+                            const void* dres, void* dx, float* dg, float* scratch, int T, int h) {
+  if (!dy || !x || !g || !rstd || !dx || h % 8 || h > 8192 || (dg && !scratch)) return fail(nullptr, RP_EINVAL, "rp_op_rmsnorm_bwd: bad arguments");
+  hipError_t e = k_rmsnorm_bwd(reinterpret_cast<hipStream_t>(stream), dy, dy_is_f32, x, g, rstd, dres, dx, dg, scratch, T, h);
   OP_RET(e);
 }
 
@@ -669,11 +669,12 @@ rp_status rp_op_rope_table(void* stream, void* cs, int seq, int d, float base) {
 rp_status rp_op_qknorm_rope(void* stream, int bwd, int d, const void* in_q, const void* in_k, long ld_in_q, long ld_in_k,
                             void* out_q, void* out_k, long ld_out_q, long ld_out_k, const void* gq, const void* gk, float* rstd_q,
                             float* rstd_k, const void* raw_q, const void* raw_k, long ld_raw, float* dgq, float* dgk,
-                            const void* cs, int T, int seq, int a, int k, int use_norm, float eps) {
+                            float* scratch, const void* cs, int T, int seq, int a, int k, int use_norm, float eps) {
   if (!in_q || !in_k || !out_q || !out_k || !cs || (d != 64 && d != 128)) return fail(nullptr, RP_EINVAL, "rp_op_qknorm_rope: bad arguments");
   if (use_norm && (!gq || !gk || !rstd_q || !rstd_k || (bwd && (!raw_q || !raw_k)))) return fail(nullptr, RP_EINVAL, "rp_op_qknorm_rope: norm buffers missing");
+  if (bwd && use_norm && dgq && dgk && !scratch) return fail(nullptr, RP_EINVAL, "rp_op_qknorm_rope: scratch missing");
   hipError_t e = k_qknorm_rope(reinterpret_cast<hipStream_t>(stream), bwd, d, in_q, in_k, ld_in_q, ld_in_k, out_q, out_k, ld_out_q,
-                               ld_out_k, gq, gk, rstd_q, rstd_k, raw_q, raw_k, ld_raw, dgq, dgk, static_cast<const float2*>(cs), T,
+                               ld_out_k, gq, gk, rstd_q, rstd_k, raw_q, raw_k, ld_raw, dgq, dgk, scratch, static_cast<const float2*>(cs), T,
                                seq, a, k, use_norm, eps);
   OP_RET(e);
 }

@@ -129,7 +129,8 @@ def test_rmsnorm_fwd_bwd(rp, T, h):
         dx = torch.empty((T, h), dtype=torch.bfloat16, device="cuda:0")
         dg = torch.zeros(h, dtype=torch.float32, device="cuda:0")
         dyd = torch.from_numpy(dy).cuda() if f32 else dev(H, dy)
-        B.rp_op_rmsnorm_bwd(stream(), dyd, f32, xd, gd, rstd, dev(H, dres), dx, dg, T, h)
+        scratch = torch.empty(512 * h, dtype=torch.float32, device="cuda:0")
+        B.rp_op_rmsnorm_bwd(stream(), dyd, f32, xd, gd, rstd, dev(H, dres), dx, dg, scratch, T, h)
         torch.cuda.synchronize()
         assert rel_l2(H.to_f32(dx), dx_ref + dres) < 4e-3
         assert rel_l2(dg.cpu().numpy(), dg_ref) < 1e-4
@@ -164,7 +165,7 @@ def test_qknorm_rope_fwd_bwd(rp, d, a, k, use_norm):
     rstd_k = torch.zeros((T, k), dtype=torch.float32, device="cuda:0")
     gqd, gkd = dev(H, gq), dev(H, gk)
     B.rp_op_qknorm_rope(stream(), 0, d, qkvd, qkvd.data_ptr() + a * d * 2, n1, n1, qo, ko, a * d, k * d, gqd, gkd, rstd_q,
-                        rstd_k, None, None, 0, None, None, cs, T, seq, a, k, use_norm, eps)
+                        rstd_k, None, None, 0, None, None, None, cs, T, seq, a, k, use_norm, eps)
     torch.cuda.synchronize()
     cs_ref_c, cs_ref_s = L.rope_angles(seq, d, base, np.float64)
     assert np.max(np.abs(cs.cpu().numpy()[..., 0] - cs_ref_c)) < 2e-7
@@ -186,7 +187,7 @@ def test_qknorm_rope_fwd_bwd(rp, d, a, k, use_norm):
     dgk = torch.zeros(d, dtype=torch.float32, device="cuda:0")
     B.rp_op_qknorm_rope(stream(), 1, d, dev(H, dq_r.reshape(T, -1)), dev(H, dk_r.reshape(T, -1)), a * d, k * d, dqkv,
                         dqkv.data_ptr() + a * d * 2, n1, n1, gqd, gkd, rstd_q, rstd_k, qkvd, qkvd.data_ptr() + a * d * 2, n1,
-                        dgq, dgk, cs, T, seq, a, k, use_norm, eps)
+                        dgq, dgk, torch.empty(512 * 2 * d, dtype=torch.float32, device="cuda:0"), cs, T, seq, a, k, use_norm, eps)
     torch.cuda.synchronize()
     out = H.to_f32(dqkv)
     assert rel_l2(out[:, : a * d].reshape(T, a, d), dq_ref) < 4e-3
