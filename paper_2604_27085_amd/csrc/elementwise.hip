@@ -151,14 +151,27 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict_
   }
 }
 
-// dst[c] += sum_r part[r][c], r = 0..rows-1, one thread per column (coalesced across columns, fixed order)
+// dst[c] += sum_r part[r][c], r = 0..rows-1.  A block owns 64 columns; its four waves each sum every fourth row
+// (four independent loads in flight per thread) and the four slices are merged in LDS in a fixed order.
 __global__ void __launch_bounds__(256) colsum_add_kernel(const float* __restrict__ part, int rows, int ld, int cols,
                                                          float* __restrict__ dst) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= cols) return;
-  float s = 0.f;
-  for (int r = 0; r < rows; ++r) s += part[(long)r * ld + c];
-  dst[c] += s;
+  __shared__ float red[4][64];
+  const int cl = threadIdx.x & 63, sl = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (c < cols) {
+    int r = sl;
+    for (; r + 12 < rows; r += 16) {
+      s0 += part[(long)r * ld + c];
+      s1 += part[(long)(r + 4) * ld + c];
+      s2 += part[(long)(r + 8) * ld + c];
+      s3 += part[(long)(r + 12) * ld + c];
+    }
+    for (; r < rows; r += 4) s0 += part[(long)r * ld + c];
+  }
+  red[sl][cl] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (sl == 0 && c < cols) dst[c] += (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
 }
 
 // ------------------------------------------------------------------------------------------------ RoPE table
@@ -419,7 +432,7 @@ hipError_t k_rmsnorm_bwd(hipStream_t st, const void* dy, int dy_is_f32, const vo
 #undef RP_LAUNCH_RB
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && dg) {
-    RP_LAUNCH(colsum_add_kernel, dim3((h + 255) / 256), dim3(256), 0, st, part, grid, h, h, dg);
+    RP_LAUNCH(colsum_add_kernel, dim3((h + 63) / 64), dim3(256), 0, st, part, grid, h, h, dg);
     e = hipGetLastError();
   }
   return e;
@@ -452,8 +465,8 @@ hipError_t k_qknorm_rope(hipStream_t st, int bwd, int d, const void* in_q, const
 #undef RP_LAUNCH_QR
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && want_dg) {
-    RP_LAUNCH(colsum_add_kernel, dim3(1), dim3(256), 0, st, part, grid, 2 * d, d, dgq);
-    RP_LAUNCH(colsum_add_kernel, dim3(1), dim3(256), 0, st, part + d, grid, 2 * d, d, dgk);
+    RP_LAUNCH(colsum_add_kernel, dim3((d + 63) / 64), dim3(256), 0, st, part, grid, 2 * d, d, dgq);
+    RP_LAUNCH(colsum_add_kernel, dim3((d + 63) / 64), dim3(256), 0, st, part + d, grid, 2 * d, d, dgk);
     e = hipGetLastError();
   }
   return e;

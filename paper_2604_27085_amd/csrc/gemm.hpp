@@ -35,6 +35,7 @@ struct GemmArgs {
   int row_offset;              // global vocab index of row 0 of A
   // byte extents of the four operands (filled in by gemm_launch; rows beyond them read as zero)
   unsigned bytesA, bytesB, bytesA2, bytesB2;
+  int splits;                  // reduction slices (grid.y), chosen by gemm_launch
   int part_row0;               // first partial row this launch writes (2 per M tile)
 };
 

@@ -1,0 +1,207 @@
+// Device-side building blocks shared by the GEMM kernels: buffer loads, operand tile layouts in LDS, MFMA fragment
+// reads (plain and hardware-transposed), the workgroup -> tile mapping and the LDS-staged epilogue.
+#pragma once
+#include "common.hpp"
+#include "gemm.hpp"
+
+namespace gemm_dev {
+
+constexpr int TM = 4, TN = 2;            // 32x32 MFMA tiles per wave: every wave owns a 128 x 64 block of C
+constexpr int WAVE_M = 128, WAVE_N = 64;
+constexpr int STG_LD = 72;               // epilogue staging row stride in bf16 elements (144 bytes)
+constexpr int STG_BYTES = WAVE_M * STG_LD * 2;
+
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t OOB = 0x80000000u;    // byte offset outside every descriptor (operands are smaller than 2 GiB)
+
+RP_DEV rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+RP_DEV uint4 buf_load16(rsrc_t r, uint32_t voff, uint32_t soff) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// LDS layout of one operand tile.
+//   !TR: the operand is [Xdim, Kdim] in memory (reduction index contiguous): tile [BX][BK + 8]; MFMA fragments are
+//        plain 16-byte LDS reads.
+//    TR: the operand is [Kdim, Xdim] (reduction index strided): tile [BK][BX + 32] -- the memory layout is kept, and
+//        fragments are read with the transposing LDS load (ds_read_b64_tr_b16), which hands every lane four
+//        consecutive reduction indices of its own column.  No register transposes anywhere.
+// The pads (8 resp. 32 elements) keep both kinds of fragment reads free of bank conflicts.
+template <int BX, int BK, bool TR>
+struct TileShape {
+  static constexpr int ROWS = TR ? BK : BX;
+  static constexpr int CH = (TR ? BX : BK) / 8;            // 16-byte data chunks per tile row
+  static constexpr int PADCH = TR ? 4 : 1;                 // 16-byte pad chunks per tile row
+  static constexpr int LDROW = (CH + PADCH) * 8;           // row stride in elements
+  static constexpr int ELEMS = ROWS * LDROW;
+};
+
+// MFMA operand fragment (8 consecutive reduction indices of the lane's row/column) of 16-deep step ks.
+//   !TR: base points at S[x_lane][8*lk];  TR: base points at S[8*lk + (l%16)/4][x_group + 4*(l%4)].
+template <int LDROW, bool TR>
+RP_DEV uint4 read_frag(const bf16* base, int x_tile_off, int ks) {
+  if constexpr (!TR) {
+    return *reinterpret_cast<const uint4*>(base + x_tile_off * LDROW + ks * 16);
+  } else {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+    const bf16* q = base + ks * 16 * LDROW + x_tile_off;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q + 4 * LDROW));
+    const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+    return make_uint4(l2.x, l2.y, h2.x, h2.y);
+  }
+}
+
+// Per-lane offset (elements) of the fragment base inside an operand tile, for the wave whose block starts at x_wave.
+template <int LDROW, bool TR>
+RP_DEV int frag_base(int lane, int x_wave) {
+  const int lr = lane & 31, lk = lane >> 5, l16 = lane & 15, g16 = lane >> 4;
+  return TR ? (8 * lk + (l16 >> 2)) * LDROW + x_wave + 16 * (g16 & 1) + 4 * (l16 & 3) : (x_wave + lr) * LDROW + lk * 8;
+}
+
+// Workgroup -> output tile: XCD-aware remap (consecutive logical ids share an XCD's L2), then groups of 8 tile rows
+// sweep the tile columns.
+RP_DEV void tile_of_block(int M, int N, int BM, int BN, int& tile_m, int& tile_n) {
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int pid = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  constexpr int GM = 8;
+  const int group = pid / (GM * tiles_n);
+  const int first_m = group * GM;
+  const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int in_group = pid - group * GM * tiles_n;
+  tile_m = first_m + in_group % gm;
+  tile_n = in_group / gm;
+}
+
+// Epilogue.  acc[i][j][v] is element (i*32 + 8*(v/4) + 4*lk + v%4, j*32 + lr) of the wave's 128x64 block whose top
+// left corner is (wrow0, wcol0).  Every wave stages its block through its own 18 KB of LDS (all waves must have
+// finished the K loop) so that global accesses are 16 bytes per lane and cover whole 128-byte lines.
+// part_row: row of the cross-entropy partial array this wave writes (EPI_CE_STATS).
+RP_DEV void epilogue(const GemmArgs& p, const f32x16 (&acc)[TM][TN], unsigned char* smem, int wave, int lane, int wrow0,
+                     int wcol0, int part_row) {
+  const int lr = lane & 31, lk = lane >> 5;
+  unsigned char* const stg = smem + wave * STG_BYTES;
+  const int rr = lane >> 3, cc = lane & 7;   // read-back: 8 rows per pass, 8 chunks of 16 bytes per row
+
+  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ) {
+    bf16* s16 = reinterpret_cast<bf16*>(stg);
+    if (p.epi == EPI_BF16) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            s16[(i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3)) * STG_LD + j * 32 + lr] = (bf16)(p.alpha * acc[i][j][v]);
+    } else {
+      // dZ^T = (softmax - onehot) * coef: rows are vocabulary entries, columns tokens
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = wcol0 + j * 32 + lr;
+        const bool colok = col < p.N;
+        const int lab = colok ? p.labels[col] - p.row_offset : -1;
+        const float lse = colok ? p.lse[col] : 0.f, cf = colok ? p.coef[col] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+            float g = __expf(acc[i][j][v] - lse);
+            if (wrow0 + row == lab) g -= 1.f;
+            s16[row * STG_LD + j * 32 + lr] = (bf16)(g * cf);
+          }
+      }
+    }
+    __syncthreads();
+    bf16* Cp = reinterpret_cast<bf16*>(p.C);
+    const int gcol = wcol0 + cc * 8;
+#pragma unroll
+    for (int t = 0; t < WAVE_M / 8; ++t) {
+      const int row = t * 8 + rr, grow = wrow0 + row;
+      if (grow < p.M && gcol < p.N)
+        *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + gcol) = *reinterpret_cast<const uint4*>(s16 + row * STG_LD + cc * 8);
+    }
+  } else if (p.epi == EPI_BF16 || p.epi == EPI_F32) {
+    // fp32 staging, one 32-column half at a time: [128][36] floats (144-byte rows)
+    float* s32 = reinterpret_cast<float*>(stg);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      if (j) __syncthreads();
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s32[(i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3)) * (STG_LD / 2) + lr] = p.alpha * acc[i][j][v];
+      __syncthreads();
+      const int gcol = wcol0 + j * 32 + cc * 4;
+#pragma unroll
+      for (int t = 0; t < WAVE_M / 8; ++t) {
+        const int row = t * 8 + rr, grow = wrow0 + row;
+        if (grow < p.M && gcol < p.N) {
+          float4 x = *reinterpret_cast<const float4*>(s32 + row * (STG_LD / 2) + cc * 4);
+          if (p.epi == EPI_F32) {
+            float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (long)grow * p.ldc + gcol);
+            if (p.beta) { const float4 o = *dst; x.x += o.x; x.y += o.y; x.z += o.z; x.w += o.w; }
+            *dst = x;
+          } else {
+            const uint2 r2 = *reinterpret_cast<const uint2*>(reinterpret_cast<const bf16*>(p.R) + (long)grow * p.ldr + gcol);
+            x.x += bf16_lo(r2.x); x.y += bf16_hi(r2.x); x.z += bf16_lo(r2.y); x.w += bf16_hi(r2.y);
+            *reinterpret_cast<uint2*>(reinterpret_cast<bf16*>(p.C) + (long)grow * p.ldc + gcol) =
+                make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+          }
+        }
+      }
+    }
+  } else if (p.epi == EPI_F32_ATOMIC) {
+    float* Cp = reinterpret_cast<float*>(p.C);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = wcol0 + j * 32 + lr;
+      if (col >= p.N) continue;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+          if (row < p.M) atomicAdd(Cp + (long)row * p.ldc + col, p.alpha * acc[i][j][v]);
+        }
+    }
+  } else if (p.epi == EPI_CE_STATS) {
+    // rows are vocabulary entries, columns are tokens: every lane reduces its own column over the wave's 128 rows
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = wcol0 + j * 32 + lr;
+      const bool colok = col < p.N;
+      const int lab = colok ? p.labels[col] - p.row_offset : -1;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+          if (row < p.M) {
+            mx = fmaxf(mx, acc[i][j][v]);
+            if (row == lab) p.zlab[col] = acc[i][j][v];
+          }
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float s = 0.f;
+      if (mx > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (row < p.M) s += __expf(acc[i][j][v] - mx);
+          }
+      }
+      s += __shfl_xor(s, 32, 64);
+      if (lk == 0 && colok) p.part[(long)part_row * p.part_ld + col] = make_float2(mx, s);
+    }
+  }
+}
+
+}  // namespace gemm_dev

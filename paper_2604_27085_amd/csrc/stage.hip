@@ -561,6 +561,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
   RUN(X, "ce_lse", 0, 8.0 * P.head_parts * Td, k_ce_lse(X.st, X.at<float2>(P.h_part), P.head_parts, T, X.at<float>(P.h_lse), T));
   RUN(X, "ce_finalize", 0, 16.0 * Td,
       k_ce_finalize(X.st, X.at<float>(P.h_lse), X.at<float>(P.h_zlab), labels, grad_scale, X.at<float>(P.h_coef), loss_out, T));
+  RUN(X, "fill", 0, 4.0 * Td * D.h, k_fill_u32(X.st, X.at<void>(P.h_dxacc), (long)T * D.h, 0u));
   // sweep 2: per vocabulary chunk recompute the logits, turn them into dZ^T (bf16), and feed dX and dW
   for (int v0 = 0, ci = 0; v0 < D.V; v0 += P.head_chunk, ++ci) {
     const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
@@ -573,7 +574,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
     X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head sweep 2");
     GemmArgs d; gemm_zero_args(d);   // dXf[T, h] (+)= dZ^T^T . W_c   (reduction over the chunk's vocabulary rows)
     d.A = X.at<void>(P.h_dzt); d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = X.at<void>(P.h_dxacc);
-    d.ldc = D.h; d.beta = ci > 0; d.epi = EPI_F32;
+    d.ldc = D.h; d.beta = 1; d.epi = EPI_F32;
     X.mark_gemm(GEMM_TN, d);
     X.chk(gemm_launch(X.st, GEMM_TN, d), "lm head dX");
     if (G.t(RP_T_WV)) {
