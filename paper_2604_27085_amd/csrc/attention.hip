@@ -3,20 +3,26 @@
 // All three kernels use v_mfma_f32_32x32x16_bf16 with the score tile computed TRANSPOSED relative to the row that is
 // being normalised: the 32x32 accumulator layout gives every lane one column and 16 rows, so with queries (forward,
 // dQ) as columns the softmax reductions are in-lane plus one exchange with lane^32, and the probabilities already sit
-// in the register layout the next MFMA wants as its B operand.  The operand whose reduction index is not contiguous in
-// memory (V for P.V, K for dS.K, Q and dO for the dK/dV products) is transposed in registers (8x8 blocks) on its way
-// into LDS, with the reduction index permuted to match the accumulator layout of the score tile.
+// in the register layout the next MFMA wants as its B operand.  Within a 16-deep step that layout holds, for lane
+// half h, the reduction indices {4h..4h+3, 8+4h..8+4h+3}; the A operand of the same MFMA is read from LDS in exactly
+// that order.  An operand whose reduction index is contiguous in memory (K for Q.K^T, V for dO.V^T, Q and dO in the
+// score products of the dK/dV kernel) is read with plain 16-byte LDS loads from a [rows][D + 8] tile; an operand
+// whose reduction index is the row index of the tile (V for P.V, K for dS.K, Q and dO for dK/dV) is read with the
+// transposing LDS load from a [rows][D + 32] tile.  Tiles needed both ways are stored in LDS twice; nothing is
+// transposed in registers.  Global loads are 16-byte buffer loads whose descriptor ends with the sequence, so rows
+// past the end read as zero without a branch.
 //
-//   forward : block = 128 queries of one head (4 waves x 32), loop over 64-key tiles up to the diagonal
+//   forward : workgroup = NW waves x 32*QT queries of one head, loop over 64-key tiles up to the diagonal
 //   dQ      : same decomposition; recomputes S^T and dP^T, accumulates dQ^T
-//   dK, dV  : block = 128 keys of one kv head (4 waves x 32), loops over the query heads of the group and over 64-query
+//   dK, dV  : workgroup = 4 waves x 32 keys of one kv head, loops over the query heads of the group and over 64-query
 //             tiles from the diagonal on; accumulates dK^T, dV^T in registers, so no atomics and a fixed summation order
 #include "common.hpp"
 #include "kernels.hpp"
+#include <stdlib.h>
 
 namespace {
 
-constexpr int LDT = 72;   // row stride of transposed [D][64 + 8] LDS tiles
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 struct AttnArgs {
   const bf16 *q, *k, *v, *dout;
@@ -29,57 +35,56 @@ struct AttnArgs {
   float scale_log2e, scale;
 };
 
-// ---- 64 x D tile loaders --------------------------------------------------------------------------------------
-template <int D>
-RP_DEV void load_direct64(uint4 (&r)[D / 32], const bf16* __restrict__ base, long ld, int row0, int nrows, int tid) {
-#pragma unroll
-  for (int it = 0; it < D / 32; ++it) {
-    const int c = it * 256 + tid;
-    const int row = row0 + c / (D / 8), ch = c % (D / 8);
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (row < nrows) v = *reinterpret_cast<const uint4*>(base + (long)row * ld + ch * 8);
-    r[it] = v;
-  }
+RP_DEV rsrc_t seq_rsrc(const bf16* base, long ld, int seq, int D) {
+  // covers rows 0..seq-1 of one head: later rows are out of range and read as zero
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, (int)(((long)(seq - 1) * ld + D) * 2), 0x00020000);
 }
-template <int D>
-RP_DEV void store_direct64(const uint4 (&r)[D / 32], bf16* S, int tid) {
-#pragma unroll
-  for (int it = 0; it < D / 32; ++it) {
-    const int c = it * 256 + tid;
-    *reinterpret_cast<uint4*>(S + (c / (D / 8)) * (D + 8) + (c % (D / 8)) * 8) = r[it];
-  }
+RP_DEV uint4 buf_load16(rsrc_t r, uint32_t voff) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
 }
-// 8x8 blocks: thread -> (row block rb of 8 tile rows, column block b of 8 features)
-template <int D>
-RP_DEV void load_trans64(uint4 (&r)[8], const bf16* __restrict__ base, long ld, int row0, int nrows, int tid) {
-  const int rb = (tid >> 1) & 7;
-  const int b = (tid & 1) | ((tid >> 4) << 1);
+
+// ---- 64 x D tile: global -> registers -> LDS -----------------------------------------------------------------
+template <int D, int NT>
+struct Tile64 {
+  static constexpr int CH = D / 8, NREG = 64 * CH / NT;
+  static_assert((64 * CH) % NT == 0, "tile does not divide over the threads");
+  // rows row0..row0+63 of a [seq, D] view with row stride ld (elements)
+  static RP_DEV void load(uint4 (&r)[NREG], rsrc_t rs, long ld, int row0, int tid) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = row0 + rb * 8 + i;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (b < D / 8 && row < nrows) v = *reinterpret_cast<const uint4*>(base + (long)row * ld + b * 8);
-    r[i] = v;
-  }
-}
-// Writes the transposed tile St[feature][64 tile rows] with the tile-row index permuted inside every group of 16:
-// tile row 16g + 8p + 4h + e is stored at column 16g + 8h + 4p + e, which is the order in which a lane of the 32x32
-// accumulator (half h) holds its 8 values of that group.
-template <int D>
-RP_DEV void store_trans64_perm(const uint4 (&r)[8], bf16* St, int tid) {
-  const int rb = (tid >> 1) & 7;
-  const int b = (tid & 1) | ((tid >> 4) << 1);
-  if (b < D / 8) {
-    uint4 t[8];
-    transpose8x8_bf16(r, t);
-    const int g = rb >> 1, pp = rb & 1;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      bf16* row = St + (b * 8 + c) * LDT + 16 * g + 4 * pp;
-      *reinterpret_cast<uint2*>(row) = make_uint2(t[c].x, t[c].y);
-      *reinterpret_cast<uint2*>(row + 8) = make_uint2(t[c].z, t[c].w);
+    for (int it = 0; it < NREG; ++it) {
+      const int c = it * NT + tid;
+      r[it] = buf_load16(rs, (uint32_t)(((long)(row0 + c / CH) * ld + (c % CH) * 8) * 2));
     }
   }
+  template <int LDS_LD>
+  static RP_DEV void store(const uint4 (&r)[NREG], bf16* S, int tid) {
+#pragma unroll
+    for (int it = 0; it < NREG; ++it) {
+      const int c = it * NT + tid;
+      *reinterpret_cast<uint4*>(S + (c / CH) * LDS_LD + (c % CH) * 8) = r[it];
+    }
+  }
+};
+
+// A-operand fragment from a [64][LD] tile whose rows are the reduction index (keys or queries) and whose columns are
+// the MFMA rows: the 8 values are tile rows {16g + 4h + e, 16g + 8 + 4h + e}, e = 0..3, at column x -- the order in
+// which the 32x32 accumulator of the score tile holds them.  base = S + (4h + (l%16)/4)*LD + 16*((l/16)&1) + 4*(l%4).
+template <int LD>
+RP_DEV uint4 read_frag_tr(const bf16* base, int g, int x_off) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+  const bf16* q = base + 16 * g * LD + x_off;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q + 8 * LD));
+  const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+  return make_uint4(l2.x, l2.y, h2.x, h2.y);
+}
+template <int LD>
+RP_DEV int tr_base(int lane) {
+  const int lk = lane >> 5, l16 = lane & 15, g16 = lane >> 4;
+  return (4 * lk + (l16 >> 2)) * LD + 16 * (g16 & 1) + 4 * (l16 & 3);
 }
 
 RP_DEV uint4 pack_frag(const f32x16& s, int off) {
@@ -112,123 +117,157 @@ RP_DEV void store_acc_T(const f32x16 (&acc)[D / 32], float mul, bf16* stage /* [
       *reinterpret_cast<uint4*>(out + (long)(row0 + row) * ld + ch * 8) =
           *reinterpret_cast<const uint4*>(stage + row * (D + 8) + ch * 8);
   }
+  __syncthreads();
 }
 
 // ================================================================================================ forward
-template <int D>
-__global__ void __launch_bounds__(256) attn_fwd_kernel(const AttnArgs p) {
-  constexpr int LDKD = D + 8, KS = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) bf16 smem[64 * LDKD + D * LDT];
+template <int D, int QT, int NW>
+__global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnArgs p) {
+  constexpr int LDK = D + 8, LDV = D + 32, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
+  using T64 = Tile64<D, NT>;
+  constexpr int MAIN = 64 * LDK + 64 * LDV, STG = NW * 32 * LDK;
+  __shared__ __attribute__((aligned(16))) bf16 smem[MAIN > STG ? MAIN : STG];
   bf16* const Ks = smem;
-  bf16* const Vt = smem + 64 * LDKD;
+  bf16* const Vs = smem + 64 * LDK;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lr = lane & 31, lk = lane >> 5;
-  const int nQ = (p.seq + 127) / 128;
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nQ = (p.seq + BQ - 1) / BQ;
   int bid = blockIdx.x;
-  const int qt = nQ - 1 - (bid % nQ);
+  const int qtile = nQ - 1 - (bid % nQ);     // heaviest query tiles first
   bid /= nQ;
   const int hq = bid % p.a, b = bid / p.a;
   const int g = hq / (p.a / p.kh);
-  const int q0 = qt * 128;
+  const int q0 = qtile * BQ, qw0 = q0 + w * 32 * QT;
   const long tok0 = (long)b * p.seq;
   const bf16* qb = p.q + tok0 * p.ldq + hq * D;
-  const bf16* kb = p.k + tok0 * p.ldk + g * D;
-  const bf16* vb = p.v + tok0 * p.ldv + g * D;
-  const int qpos = q0 + 32 * w + lr;
+  const rsrc_t rk = seq_rsrc(p.k + tok0 * p.ldk + g * D, p.ldk, p.seq, D);
+  const rsrc_t rv = seq_rsrc(p.v + tok0 * p.ldv + g * D, p.ldv, p.seq, D);
 
-  uint4 qf[KS];
+  uint4 qf[QT][KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    qf[ks] = make_uint4(0u, 0u, 0u, 0u);
-    if (qpos < p.seq) qf[ks] = *reinterpret_cast<const uint4*>(qb + (long)qpos * p.ldq + 16 * ks + 8 * lk);
+  for (int t = 0; t < QT; ++t) {
+    const int qpos = qw0 + 32 * t + lr;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[t][ks] = make_uint4(0u, 0u, 0u, 0u);
+      if (qpos < p.seq) qf[t][ks] = *reinterpret_cast<const uint4*>(qb + (long)qpos * p.ldq + 16 * ks + 8 * lk);
+    }
   }
-  const int kv_end = (q0 + 128 < p.seq) ? (q0 + 128) : p.seq;
+  const int kv_end = (q0 + BQ < p.seq) ? (q0 + BQ) : p.seq;
   const int nkv = (kv_end + 63) / 64;
 
-  float m_run = -INFINITY, l_run = 0.f;
-  f32x16 oacc[DT];
+  float m_run[QT], l_run[QT];
+  f32x16 oacc[QT][DT];
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+  for (int t = 0; t < QT; ++t) {
+    m_run[t] = -INFINITY;
+    l_run[t] = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[t][dt][v] = 0.f;
+  }
 
-  uint4 kreg[D / 32], vreg[8];
-  load_direct64<D>(kreg, kb, p.ldk, 0, p.seq, tid);
-  load_trans64<D>(vreg, vb, p.ldv, 0, p.seq, tid);
+  const bf16* kfrag = Ks + lr * LDK + 8 * lk;
+  const bf16* vfrag = Vs + tr_base<LDV>(lane);
+  uint4 kreg[T64::NREG], vreg[T64::NREG];
+  T64::load(kreg, rk, p.ldk, 0, tid);
+  T64::load(vreg, rv, p.ldv, 0, tid);
 
   for (int j = 0; j < nkv; ++j) {
     __syncthreads();
-    store_direct64<D>(kreg, Ks, tid);
-    store_trans64_perm<D>(vreg, Vt, tid);
+    T64::template store<LDK>(kreg, Ks, tid);
+    T64::template store<LDV>(vreg, Vs, tid);
     __syncthreads();
     if (j + 1 < nkv) {
-      load_direct64<D>(kreg, kb, p.ldk, (j + 1) * 64, p.seq, tid);
-      load_trans64<D>(vreg, vb, p.ldv, (j + 1) * 64, p.seq, tid);
+      T64::load(kreg, rk, p.ldk, (j + 1) * 64, tid);
+      T64::load(vreg, rv, p.ldv, (j + 1) * 64, tid);
     }
     const int kv0 = j * 64;
-    if (kv0 <= q0 + 32 * w + 31) {
-      f32x16 sT[2];
+    if (kv0 <= qw0 + 32 * QT - 1) {   // the wave has at least one unmasked (query, key) pair
+      f32x16 sT[QT][2];
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int t = 0; t < QT; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sT[kt][v] = 0.f;
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sT[t][kt][v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
-          const uint4 a = *reinterpret_cast<const uint4*>(Ks + (32 * kt + lr) * LDKD + 16 * ks + 8 * lk);
-          sT[kt] = mfma32(a, qf[ks], sT[kt]);
+          const uint4 a = *reinterpret_cast<const uint4*>(kfrag + 32 * kt * LDK + 16 * ks);
+#pragma unroll
+          for (int t = 0; t < QT; ++t) sT[t][kt] = mfma32(a, qf[t][ks], sT[t][kt]);
         }
-      const bool need_mask = (kv0 + 63 > q0 + 32 * w) || (kv0 + 64 > p.seq);
-      float mx = -INFINITY;
+      const bool need_mask = (kv0 + 63 > qw0) || (kv0 + 64 > p.seq);   // wave-uniform
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int t = 0; t < QT; ++t) {
+        const int qpos = qw0 + 32 * t + lr;
+        if (need_mask) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float s = sT[kt][v] * p.scale_log2e;
-          if (need_mask) {
-            const int kpos = kv0 + 32 * kt + 8 * (v >> 2) + 4 * lk + (v & 3);
-            if (kpos > qpos || kpos >= p.seq) s = -INFINITY;
+          for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int kpos = kv0 + 32 * kt + 8 * (v >> 2) + 4 * lk + (v & 3);
+              const float s = sT[t][kt][v] * p.scale_log2e;
+              sT[t][kt][v] = (kpos > qpos || kpos >= p.seq) ? -INFINITY : s;
+            }
+        } else {
+#pragma unroll
+          for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sT[t][kt][v] *= p.scale_log2e;
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sT[t][kt][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // the first key tile always contains key 0 <= qpos, so m_new is finite from the first iteration on
+        const float m_new = fmaxf(m_run[t], mx);
+        const float alpha = fast_exp2(m_run[t] - m_new);
+        float psum = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float e = fast_exp2(sT[t][kt][v] - m_new);
+            sT[t][kt][v] = e;
+            psum += e;
           }
-          sT[kt][v] = s;
-          mx = fmaxf(mx, s);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = fast_exp2(m_run - m_new);
-      float psum = 0.f;
+        l_run[t] = l_run[t] * alpha + psum;
+        m_run[t] = m_new;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float e = fast_exp2(sT[kt][v] - m_new);
-          sT[kt][v] = e;
-          psum += e;
-        }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+          for (int v = 0; v < 16; ++v) oacc[t][dt][v] *= alpha;
+      }
 #pragma unroll
       for (int gk = 0; gk < 4; ++gk) {
-        const uint4 pf = pack_frag(sT[gk >> 1], 8 * (gk & 1));
+        uint4 pf[QT];
+#pragma unroll
+        for (int t = 0; t < QT; ++t) pf[t] = pack_frag(sT[t][gk >> 1], 8 * (gk & 1));
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-          const uint4 a = *reinterpret_cast<const uint4*>(Vt + (32 * dt + lr) * LDT + 16 * gk + 8 * lk);
-          oacc[dt] = mfma32(a, pf, oacc[dt]);
+          const uint4 a = read_frag_tr<LDV>(vfrag, gk, 32 * dt);
+#pragma unroll
+          for (int t = 0; t < QT; ++t) oacc[t][dt] = mfma32(a, pf[t], oacc[t][dt]);
         }
       }
     }
   }
 
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv = 1.f / l_tot;
-  if (lk == 0 && qpos < p.seq)
-    p.lse[((long)b * p.a + hq) * p.seq + qpos] = m_run * 0.6931471805599453f + logf(l_tot);
   __syncthreads();
-  store_acc_T<D>(oacc, inv, smem + w * 32 * LDKD, p.o + tok0 * p.ldo + hq * D, p.ldo, q0 + 32 * w, p.seq, lane);
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const int qpos = qw0 + 32 * t + lr;
+    const float l_tot = l_run[t] + __shfl_xor(l_run[t], 32, 64);
+    if (lk == 0 && qpos < p.seq) p.lse[((long)b * p.a + hq) * p.seq + qpos] = m_run[t] * 0.6931471805599453f + logf(l_tot);
+    store_acc_T<D>(oacc[t], 1.f / l_tot, smem + w * 32 * LDK, p.o + tok0 * p.ldo + hq * D, p.ldo, qw0 + 32 * t, p.seq, lane);
+  }
 }
 
 // ================================================================================================ delta = rowsum(dO * O)
@@ -262,137 +301,165 @@ __global__ void __launch_bounds__(256) attn_delta_kernel(const bf16* __restrict_
 }
 
 // ================================================================================================ dQ
-template <int D>
-__global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const AttnArgs p) {
-  constexpr int LDKD = D + 8, KS = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) bf16 smem[2 * 64 * LDKD + D * LDT];
+template <int D, int QT, int NW>
+__global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const AttnArgs p) {
+  constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
+  using T64 = Tile64<D, NT>;
+  constexpr int MAIN = 2 * 64 * LDK + 64 * LDT, STG = NW * 32 * LDK;
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);
+  static_assert(MAIN >= STG, "staging does not fit");
   bf16* const Ks = smem;
-  bf16* const Vs = smem + 64 * LDKD;
-  bf16* const Kt = smem + 2 * 64 * LDKD;
+  bf16* const Vs = smem + 64 * LDK;
+  bf16* const Kt = smem + 2 * 64 * LDK;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lr = lane & 31, lk = lane >> 5;
-  const int nQ = (p.seq + 127) / 128;
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nQ = (p.seq + BQ - 1) / BQ;
   int bid = blockIdx.x;
-  const int qt = nQ - 1 - (bid % nQ);
+  const int qtile = nQ - 1 - (bid % nQ);
   bid /= nQ;
   const int hq = bid % p.a, b = bid / p.a;
   const int g = hq / (p.a / p.kh);
-  const int q0 = qt * 128;
+  const int q0 = qtile * BQ, qw0 = q0 + w * 32 * QT;
   const long tok0 = (long)b * p.seq;
   const bf16* qb = p.q + tok0 * p.ldq + hq * D;
   const bf16* dob = p.dout + tok0 * p.lddo + hq * D;
-  const bf16* kb = p.k + tok0 * p.ldk + g * D;
-  const bf16* vb = p.v + tok0 * p.ldv + g * D;
-  const int qpos = q0 + 32 * w + lr;
-  const bool qok = qpos < p.seq;
+  const rsrc_t rk = seq_rsrc(p.k + tok0 * p.ldk + g * D, p.ldk, p.seq, D);
+  const rsrc_t rv = seq_rsrc(p.v + tok0 * p.ldv + g * D, p.ldv, p.seq, D);
 
-  uint4 qf[KS], dof[KS];
+  uint4 qf[QT][KS], dof[QT][KS];
+  float lse2[QT], dl[QT];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    qf[ks] = make_uint4(0u, 0u, 0u, 0u);
-    dof[ks] = make_uint4(0u, 0u, 0u, 0u);
-    if (qok) {
-      qf[ks] = *reinterpret_cast<const uint4*>(qb + (long)qpos * p.ldq + 16 * ks + 8 * lk);
-      dof[ks] = *reinterpret_cast<const uint4*>(dob + (long)qpos * p.lddo + 16 * ks + 8 * lk);
+  for (int t = 0; t < QT; ++t) {
+    const int qpos = qw0 + 32 * t + lr;
+    const bool qok = qpos < p.seq;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[t][ks] = make_uint4(0u, 0u, 0u, 0u);
+      dof[t][ks] = make_uint4(0u, 0u, 0u, 0u);
+      if (qok) {
+        qf[t][ks] = *reinterpret_cast<const uint4*>(qb + (long)qpos * p.ldq + 16 * ks + 8 * lk);
+        dof[t][ks] = *reinterpret_cast<const uint4*>(dob + (long)qpos * p.lddo + 16 * ks + 8 * lk);
+      }
     }
+    const long stat = ((long)b * p.a + hq) * p.seq + qpos;
+    lse2[t] = qok ? p.lse_in[stat] * 1.4426950408889634f : INFINITY;   // padded rows get P = 0
+    dl[t] = qok ? p.delta[stat] : 0.f;
   }
-  const long stat = ((long)b * p.a + hq) * p.seq + qpos;
-  const float lse2 = qok ? p.lse_in[stat] * 1.4426950408889634f : INFINITY;   // padded rows get P = 0
-  const float dl = qok ? p.delta[stat] : 0.f;
 
-  const int kv_end = (q0 + 128 < p.seq) ? (q0 + 128) : p.seq;
+  const int kv_end = (q0 + BQ < p.seq) ? (q0 + BQ) : p.seq;
   const int nkv = (kv_end + 63) / 64;
-  f32x16 dqacc[DT];
+  f32x16 dqacc[QT][DT];
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+  for (int t = 0; t < QT; ++t)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) dqacc[dt][v] = 0.f;
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dqacc[t][dt][v] = 0.f;
 
-  uint4 kreg[D / 32], vreg[D / 32], ktreg[8];
-  load_direct64<D>(kreg, kb, p.ldk, 0, p.seq, tid);
-  load_direct64<D>(vreg, vb, p.ldv, 0, p.seq, tid);
-  load_trans64<D>(ktreg, kb, p.ldk, 0, p.seq, tid);
+  const bf16* kfrag = Ks + lr * LDK + 8 * lk;
+  const bf16* vfrag = Vs + lr * LDK + 8 * lk;
+  const bf16* ktfrag = Kt + tr_base<LDT>(lane);
+  uint4 kreg[T64::NREG], vreg[T64::NREG];
+  T64::load(kreg, rk, p.ldk, 0, tid);
+  T64::load(vreg, rv, p.ldv, 0, tid);
 
   for (int j = 0; j < nkv; ++j) {
     __syncthreads();
-    store_direct64<D>(kreg, Ks, tid);
-    store_direct64<D>(vreg, Vs, tid);
-    store_trans64_perm<D>(ktreg, Kt, tid);
+    T64::template store<LDK>(kreg, Ks, tid);
+    T64::template store<LDT>(kreg, Kt, tid);
+    T64::template store<LDK>(vreg, Vs, tid);
     __syncthreads();
     if (j + 1 < nkv) {
-      load_direct64<D>(kreg, kb, p.ldk, (j + 1) * 64, p.seq, tid);
-      load_direct64<D>(vreg, vb, p.ldv, (j + 1) * 64, p.seq, tid);
-      load_trans64<D>(ktreg, kb, p.ldk, (j + 1) * 64, p.seq, tid);
+      T64::load(kreg, rk, p.ldk, (j + 1) * 64, tid);
+      T64::load(vreg, rv, p.ldv, (j + 1) * 64, tid);
     }
     const int kv0 = j * 64;
-    if (kv0 <= q0 + 32 * w + 31) {
-      f32x16 sT[2], dpT[2];
+    if (kv0 <= qw0 + 32 * QT - 1) {
+      f32x16 sT[QT][2], dpT[QT][2];
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int t = 0; t < QT; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sT[kt][v] = 0.f; dpT[kt][v] = 0.f; }
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) { sT[t][kt][v] = 0.f; dpT[t][kt][v] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
-          const uint4 ak = *reinterpret_cast<const uint4*>(Ks + (32 * kt + lr) * LDKD + 16 * ks + 8 * lk);
-          sT[kt] = mfma32(ak, qf[ks], sT[kt]);
-          const uint4 av = *reinterpret_cast<const uint4*>(Vs + (32 * kt + lr) * LDKD + 16 * ks + 8 * lk);
-          dpT[kt] = mfma32(av, dof[ks], dpT[kt]);
-        }
-      const bool need_mask = (kv0 + 63 > q0 + 32 * w) || (kv0 + 64 > p.seq);
+          const uint4 ak = *reinterpret_cast<const uint4*>(kfrag + 32 * kt * LDK + 16 * ks);
+          const uint4 av = *reinterpret_cast<const uint4*>(vfrag + 32 * kt * LDK + 16 * ks);
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float pr = fast_exp2(sT[kt][v] * p.scale_log2e - lse2);
-          if (need_mask) {
-            const int kpos = kv0 + 32 * kt + 8 * (v >> 2) + 4 * lk + (v & 3);
-            if (kpos > qpos || kpos >= p.seq) pr = 0.f;
+          for (int t = 0; t < QT; ++t) {
+            sT[t][kt] = mfma32(ak, qf[t][ks], sT[t][kt]);
+            dpT[t][kt] = mfma32(av, dof[t][ks], dpT[t][kt]);
           }
-          sT[kt][v] = pr * (dpT[kt][v] - dl);   // dS^T
         }
+      const bool need_mask = (kv0 + 63 > qw0) || (kv0 + 64 > p.seq);
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        const int qpos = qw0 + 32 * t + lr;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            float pr = fast_exp2(sT[t][kt][v] * p.scale_log2e - lse2[t]);
+            if (need_mask) {
+              const int kpos = kv0 + 32 * kt + 8 * (v >> 2) + 4 * lk + (v & 3);
+              pr = (kpos > qpos || kpos >= p.seq) ? 0.f : pr;
+            }
+            sT[t][kt][v] = pr * (dpT[t][kt][v] - dl[t]);   // dS^T
+          }
+      }
 #pragma unroll
       for (int gk = 0; gk < 4; ++gk) {
-        const uint4 df = pack_frag(sT[gk >> 1], 8 * (gk & 1));
+        uint4 df[QT];
+#pragma unroll
+        for (int t = 0; t < QT; ++t) df[t] = pack_frag(sT[t][gk >> 1], 8 * (gk & 1));
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-          const uint4 a = *reinterpret_cast<const uint4*>(Kt + (32 * dt + lr) * LDT + 16 * gk + 8 * lk);
-          dqacc[dt] = mfma32(a, df, dqacc[dt]);
+          const uint4 a = read_frag_tr<LDT>(ktfrag, gk, 32 * dt);
+#pragma unroll
+          for (int t = 0; t < QT; ++t) dqacc[t][dt] = mfma32(a, df[t], dqacc[t][dt]);
         }
       }
     }
   }
   __syncthreads();
-  store_acc_T<D>(dqacc, p.scale, smem + w * 32 * LDKD, p.dq + tok0 * p.lddq + hq * D, p.lddq, q0 + 32 * w, p.seq, lane);
+#pragma unroll
+  for (int t = 0; t < QT; ++t)
+    store_acc_T<D>(dqacc[t], p.scale, smem + w * 32 * LDK, p.dq + tok0 * p.lddq + hq * D, p.lddq, qw0 + 32 * t, p.seq, lane);
 }
 
 // ================================================================================================ dK, dV
 template <int D>
 __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
-  constexpr int LDKD = D + 8, KS = D / 16, DT = D / 32;
+  constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32;
+  using T64 = Tile64<D, 256>;
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
   float* const stats = reinterpret_cast<float*>(dyn_smem);          // 128 floats: lse (log2 units), delta
-  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem + 512);       // 2*64*LDKD + 2*D*LDT elements
+  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem + 512);       // 2*64*LDK + 2*64*LDT elements
   bf16* const Qs = smem;
-  bf16* const dOs = smem + 64 * LDKD;
-  bf16* const Qt = smem + 2 * 64 * LDKD;
-  bf16* const dOt = Qt + D * LDT;
+  bf16* const dOs = smem + 64 * LDK;
+  bf16* const Qt = smem + 2 * 64 * LDK;
+  bf16* const dOt = Qt + 64 * LDT;
   float* const lse_s = stats;
   float* const dl_s = stats + 64;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, lr = lane & 31, lk = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nK = (p.seq + 127) / 128;
   int bid = blockIdx.x;
-  const int kvt = bid % nK;
+  const int kvt = bid % nK;                  // key tile 0 sees every query: heaviest first
   bid /= nK;
   const int g = bid % p.kh, b = bid / p.kh;
   const int grp = p.a / p.kh;
-  const int kv0 = kvt * 128;
+  const int kv0 = kvt * 128, kw0 = kv0 + 32 * w;
   const long tok0 = (long)b * p.seq;
   const bf16* kb = p.k + tok0 * p.ldk + g * D;
   const bf16* vb = p.v + tok0 * p.ldv + g * D;
-  const int kpos = kv0 + 32 * w + lr;
+  const int kpos = kw0 + lr;
   const bool kok = kpos < p.seq;
 
   uint4 kf[KS], vf[KS];
@@ -416,37 +483,40 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
   const int per_head = nQ - qt0;
   const int niter = grp * per_head;
 
-  uint4 qreg[D / 32], doreg[D / 32], qtreg[8], dotreg[8];
+  const bf16* qfrag = Qs + lr * LDK + 8 * lk;
+  const bf16* dofrag = dOs + lr * LDK + 8 * lk;
+  const bf16* qtfrag = Qt + tr_base<LDT>(lane);
+  const bf16* dotfrag = dOt + tr_base<LDT>(lane);
+
+  uint4 qreg[T64::NREG], doreg[T64::NREG];
   float st_reg = 0.f;
   auto prefetch = [&](int it) {
     const int hq = g * grp + it / per_head;
     const int q0 = (qt0 + it % per_head) * 64;
-    const bf16* qb = p.q + tok0 * p.ldq + hq * D;
-    const bf16* dob = p.dout + tok0 * p.lddo + hq * D;
-    load_direct64<D>(qreg, qb, p.ldq, q0, p.seq, tid);
-    load_direct64<D>(doreg, dob, p.lddo, q0, p.seq, tid);
-    load_trans64<D>(qtreg, qb, p.ldq, q0, p.seq, tid);
-    load_trans64<D>(dotreg, dob, p.lddo, q0, p.seq, tid);
+    const rsrc_t rq = seq_rsrc(p.q + tok0 * p.ldq + hq * D, p.ldq, p.seq, D);
+    const rsrc_t rdo = seq_rsrc(p.dout + tok0 * p.lddo + hq * D, p.lddo, p.seq, D);
+    T64::load(qreg, rq, p.ldq, q0, tid);
+    T64::load(doreg, rdo, p.lddo, q0, tid);
     if (tid < 128) {
       const int qi = q0 + (tid & 63);
-      const long sidx = ((long)b * p.a + hq) * p.seq + qi;
-      if (tid < 64) st_reg = (qi < p.seq) ? p.lse_in[sidx] * 1.4426950408889634f : INFINITY;
-      else st_reg = (qi < p.seq) ? p.delta[sidx] : 0.f;
+      const long sidx = ((long)b * p.a + hq) * p.seq + (qi < p.seq ? qi : 0);
+      const float v = tid < 64 ? p.lse_in[sidx] * 1.4426950408889634f : p.delta[sidx];
+      st_reg = qi < p.seq ? v : (tid < 64 ? INFINITY : 0.f);   // padded query rows get P = 0
     }
   };
   if (niter > 0) prefetch(0);
 
   for (int it = 0; it < niter; ++it) {
     __syncthreads();
-    store_direct64<D>(qreg, Qs, tid);
-    store_direct64<D>(doreg, dOs, tid);
-    store_trans64_perm<D>(qtreg, Qt, tid);
-    store_trans64_perm<D>(dotreg, dOt, tid);
+    T64::template store<LDK>(qreg, Qs, tid);
+    T64::template store<LDT>(qreg, Qt, tid);
+    T64::template store<LDK>(doreg, dOs, tid);
+    T64::template store<LDT>(doreg, dOt, tid);
     if (tid < 128) stats[tid] = st_reg;
     __syncthreads();
     if (it + 1 < niter) prefetch(it + 1);
     const int q0 = (qt0 + it % per_head) * 64;
-    if (q0 + 63 >= kv0 + 32 * w) {
+    if (q0 + 63 >= kw0) {   // the wave has at least one (query >= key) pair
       f32x16 s[2], dp[2];
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
@@ -456,12 +526,12 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
       for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
-          const uint4 aq = *reinterpret_cast<const uint4*>(Qs + (32 * t2 + lr) * LDKD + 16 * ks + 8 * lk);
+          const uint4 aq = *reinterpret_cast<const uint4*>(qfrag + 32 * t2 * LDK + 16 * ks);
           s[t2] = mfma32(aq, kf[ks], s[t2]);
-          const uint4 ad = *reinterpret_cast<const uint4*>(dOs + (32 * t2 + lr) * LDKD + 16 * ks + 8 * lk);
+          const uint4 ad = *reinterpret_cast<const uint4*>(dofrag + 32 * t2 * LDK + 16 * ks);
           dp[t2] = mfma32(ad, vf[ks], dp[t2]);
         }
-      const bool need_mask = (q0 < kv0 + 32 * w + 31) || !kok;
+      const bool need_mask = (q0 < kw0 + 31) || (kw0 + 32 > p.seq);   // wave-uniform
       // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
@@ -475,9 +545,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
           for (int e = 0; e < 4; ++e) {
             const int v = 4 * vg + e;
             float pr = fast_exp2(s[t2][v] * p.scale_log2e - lv[e]);
-            if (need_mask) {
-              if (kpos > q0 + ql + e || !kok) pr = 0.f;
-            }
+            if (need_mask) pr = (kpos > q0 + ql + e || !kok) ? 0.f : pr;
             s[t2][v] = pr;                             // P
             dp[t2][v] = pr * (dp[t2][v] - dv4[e]);     // dS
           }
@@ -488,31 +556,65 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
         const uint4 df = pack_frag(dp[gq >> 1], 8 * (gq & 1));
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-          const uint4 ado = *reinterpret_cast<const uint4*>(dOt + (32 * dt + lr) * LDT + 16 * gq + 8 * lk);
+          const uint4 ado = read_frag_tr<LDT>(dotfrag, gq, 32 * dt);
           dvacc[dt] = mfma32(ado, pf, dvacc[dt]);
-          const uint4 aq = *reinterpret_cast<const uint4*>(Qt + (32 * dt + lr) * LDT + 16 * gq + 8 * lk);
+          const uint4 aq = read_frag_tr<LDT>(qtfrag, gq, 32 * dt);
           dkacc[dt] = mfma32(aq, df, dkacc[dt]);
         }
       }
     }
   }
   __syncthreads();
-  store_acc_T<D>(dkacc, p.scale, smem + w * 32 * LDKD, p.dk + tok0 * p.lddk + g * D, p.lddk, kv0 + 32 * w, p.seq, lane);
-  __syncthreads();
-  store_acc_T<D>(dvacc, 1.f, smem + w * 32 * LDKD, p.dv + tok0 * p.lddv + g * D, p.lddv, kv0 + 32 * w, p.seq, lane);
+  store_acc_T<D>(dkacc, p.scale, smem + w * 32 * LDK, p.dk + tok0 * p.lddk + g * D, p.lddk, kw0, p.seq, lane);
+  store_acc_T<D>(dvacc, 1.f, smem + w * 32 * LDK, p.dv + tok0 * p.lddv + g * D, p.lddv, kw0, p.seq, lane);
 }
 
-}  // namespace
+constexpr int dq_smem_bytes(int d) { return (2 * 64 * (d + 8) + 64 * (d + 32)) * 2; }
+constexpr int dkv_smem_bytes(int d) { return 512 + (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
 
-// ------------------------------------------------------------------------------------------------ launchers
-static constexpr int dkv_smem_bytes(int d) { return 512 + (2 * 64 * (d + 8) + 2 * d * LDT) * 2; }
-
-static void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
+void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
   p.batch = batch; p.seq = seq; p.a = a; p.kh = kh;
   p.scale = 1.0f / sqrtf((float)d);
   p.scale_log2e = p.scale * 1.4426950408889634f;
 }
 
+template <typename K>
+hipError_t set_smem(K kern, int bytes, bool& done) {
+  if (done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
+// Shape of the forward / dQ workgroup: 1 = 4 waves x 32 queries, 2 = 4 waves x 64 queries (RP_ATTN_FWD, RP_ATTN_DQ).
+int env_shape(const char* name, int dflt) {
+  const char* s = getenv(name);
+  const int v = s ? atoi(s) : dflt;
+  return (v == 1 || v == 2) ? v : dflt;
+}
+
+template <int D, int QT, int NW>
+hipError_t launch_fwd(hipStream_t st, const AttnArgs& p) {
+  constexpr int BQ = NW * 32 * QT;
+  const int grid = ((p.seq + BQ - 1) / BQ) * p.a * p.batch;
+  RP_LAUNCH((attn_fwd_kernel<D, QT, NW>), dim3(grid), dim3(NW * 64), 0, st, p);
+  return hipGetLastError();
+}
+
+template <int D, int QT, int NW>
+hipError_t launch_dq(hipStream_t st, const AttnArgs& p) {
+  constexpr int BQ = NW * 32 * QT;
+  static bool done = false;
+  hipError_t e = set_smem(attn_bwd_dq_kernel<D, QT, NW>, dq_smem_bytes(D), done);
+  if (e != hipSuccess) return e;
+  const int grid = ((p.seq + BQ - 1) / BQ) * p.a * p.batch;
+  RP_LAUNCH((attn_bwd_dq_kernel<D, QT, NW>), dim3(grid), dim3(NW * 64), dq_smem_bytes(D), st, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------ launchers
 hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* v, void* o, float* lse, long ldq,
                       long ldk, long ldv, long ldo, int batch, int seq, int a, int kh, int d) {
   if (batch * seq == 0) return hipSuccess;
@@ -520,11 +622,10 @@ hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* 
   p.q = (const bf16*)q; p.k = (const bf16*)k; p.v = (const bf16*)v; p.o = (bf16*)o; p.lse = lse;
   p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.ldo = ldo;
   fill_common(p, batch, seq, a, kh, d);
-  const int grid = ((seq + 127) / 128) * a * batch;
-  if (d == 128) RP_LAUNCH(attn_fwd_kernel<128>, dim3(grid), dim3(256), 0, st, p);
-  else if (d == 64) RP_LAUNCH(attn_fwd_kernel<64>, dim3(grid), dim3(256), 0, st, p);
-  else return hipErrorInvalidValue;
-  return hipGetLastError();
+  static const int shape = env_shape("RP_ATTN_FWD", 1);
+  if (d == 128) return shape == 2 ? launch_fwd<128, 2, 4>(st, p) : launch_fwd<128, 1, 4>(st, p);
+  if (d == 64) return shape == 2 ? launch_fwd<64, 2, 4>(st, p) : launch_fwd<64, 1, 4>(st, p);
+  return hipErrorInvalidValue;
 }
 
 hipError_t k_attn_delta(hipStream_t st, const void* o, const void* dout, float* delta, long ldo, long lddo, int batch,
@@ -547,26 +648,23 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
   p.lse_in = lse; p.delta = delta; p.dq = (bf16*)dq; p.dk = (bf16*)dk; p.dv = (bf16*)dv;
   p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.lddo = lddo; p.lddq = lddq; p.lddk = lddk; p.lddv = lddv;
   fill_common(p, batch, seq, a, kh, d);
-  const int nq = ((seq + 127) / 128) * a * batch;
-  const int nk = ((seq + 127) / 128) * kh * batch;
   if (d != 128 && d != 64) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
   if (part == 0) {
+    const int nk = ((seq + 127) / 128) * kh * batch;
     if (d == 128) {
-      constexpr int smem = dkv_smem_bytes(128);
-      static bool attr_done = false;
-      if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_kernel<128>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-      }
-      RP_LAUNCH(attn_bwd_dkv_kernel<128>, dim3(nk), dim3(256), smem, st, p);
+      static bool done = false;
+      if ((e = set_smem(attn_bwd_dkv_kernel<128>, dkv_smem_bytes(128), done)) != hipSuccess) return e;
+      RP_LAUNCH(attn_bwd_dkv_kernel<128>, dim3(nk), dim3(256), dkv_smem_bytes(128), st, p);
     } else {
+      static bool done = false;
+      if ((e = set_smem(attn_bwd_dkv_kernel<64>, dkv_smem_bytes(64), done)) != hipSuccess) return e;
       RP_LAUNCH(attn_bwd_dkv_kernel<64>, dim3(nk), dim3(256), dkv_smem_bytes(64), st, p);
     }
   } else {
-    if (d == 128) RP_LAUNCH(attn_bwd_dq_kernel<128>, dim3(nq), dim3(256), 0, st, p);
-    else RP_LAUNCH(attn_bwd_dq_kernel<64>, dim3(nq), dim3(256), 0, st, p);
+    static const int shape = env_shape("RP_ATTN_DQ", 1);
+    if (d == 128) return shape == 2 ? launch_dq<128, 2, 4>(st, p) : launch_dq<128, 1, 4>(st, p);
+    return shape == 2 ? launch_dq<64, 2, 4>(st, p) : launch_dq<64, 1, 4>(st, p);
   }
   return hipGetLastError();
 }
