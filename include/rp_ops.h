@@ -47,10 +47,13 @@ RP_API rp_status rp_op_swiglu_bwd(void* stream, const void* dact, const void* gu
  * row strides ld* in elements; lse fp32 [batch, a, seq] (natural log). */
 RP_API rp_status rp_op_attn_fwd(void* stream, const void* q, const void* k, const void* v, void* o, float* lse, long ldq, long ldk,
                          long ldv, long ldo, int batch, int seq, int a, int kh, int d);
-/* delta fp32 [batch, a, seq] is scratch (rowsum(dO*O)); dq [T,a,d], dk, dv [T,kh,d] overwritten. */
+/* delta fp32 [batch, a, seq] is scratch (rowsum(dO*O)); dq [T,a,d], dk, dv [T,kh,d] overwritten.  scratch: device
+ * fp32 [2, T, a, d], needed when a > kh (per-query-head partials of dk, dv, summed in head order); may be NULL when
+ * a == kh. */
 RP_API rp_status rp_op_attn_bwd(void* stream, const void* q, const void* k, const void* v, const void* o, const void* dout,
-                         const float* lse, float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv, long ldo,
-                         long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh, int d);
+                         const float* lse, float* delta, void* dq, void* dk, void* dv, float* scratch, long ldq, long ldk,
+                         long ldv, long ldo, long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh,
+                         int d);
 
 /* Per-kernel timeline of the stage calls on a ctx (measurement aid; the only calls that synchronise).
  * rp_trace_start: from now on every kernel a stage/head call enqueues is preceded by a timing event (at most

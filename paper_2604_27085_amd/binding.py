@@ -82,7 +82,7 @@ _SIGS = {
     "rp_op_swiglu_fwd": [_vp, _vp, _vp, _l, _i],
     "rp_op_swiglu_bwd": [_vp, _vp, _vp, _vp, _l, _i],
     "rp_op_attn_fwd": [_vp, _vp, _vp, _vp, _vp, _vp, _l, _l, _l, _l, _i, _i, _i, _i, _i],
-    "rp_op_attn_bwd": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _l, _l, _l, _l, _l, _l, _l, _l, _i, _i, _i,
+    "rp_op_attn_bwd": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _l, _l, _l, _l, _l, _l, _l, _l, _i, _i, _i,
                        _i, _i],
 }
 EXPORTS = sorted(list(_SIGS) + ["rp_last_error"])
@@ -235,7 +235,8 @@ def rp_op_attn_fwd(stream, q, k, v, o, lse, ldq, ldk, ldv, ldo, batch, seq, a, k
                               kh, d))
 
 
-def rp_op_attn_bwd(stream, q, k, v, o, dout, lse, delta, dq, dk, dv, ldq, ldk, ldv, ldo, lddo, lddq, lddk, lddv, batch,
-                   seq, a, kh, d):
+def rp_op_attn_bwd(stream, q, k, v, o, dout, lse, delta, dq, dk, dv, scratch, ldq, ldk, ldv, ldo, lddo, lddq, lddk, lddv,
+                   batch, seq, a, kh, d):
     _check(lib.rp_op_attn_bwd(stream, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(dout), _ptr(lse), _ptr(delta), _ptr(dq),
-                              _ptr(dk), _ptr(dv), ldq, ldk, ldv, ldo, lddo, lddq, lddk, lddv, batch, seq, a, kh, d))
+                              _ptr(dk), _ptr(dv), _ptr(scratch), ldq, ldk, ldv, ldo, lddo, lddq, lddk, lddv, batch, seq, a,
+                              kh, d))

@@ -14,8 +14,11 @@
 //
 //   forward : workgroup = NW waves x 32*QT queries of one head, loop over 64-key tiles up to the diagonal
 //   dQ      : same decomposition; recomputes S^T and dP^T, accumulates dQ^T
-//   dK, dV  : workgroup = 4 waves x 32 keys of one kv head, loops over the query heads of the group and over 64-query
-//             tiles from the diagonal on; accumulates dK^T, dV^T in registers, so no atomics and a fixed summation order
+//   dK, dV  : workgroup = 4 waves x 32 keys against ONE query head, loops over 64-query tiles from the diagonal on
+//             and accumulates dK^T, dV^T in registers.  With grouped queries every query head of a group writes an
+//             fp32 partial and a small kernel adds the group's partials in head order (no atomics, fixed order);
+//             one workgroup per query head rather than per kv head doubles the workgroup count, which is what lets
+//             the triangular work balance over the CUs.
 #include "common.hpp"
 #include "kernels.hpp"
 #include <stdlib.h>
@@ -30,6 +33,7 @@ struct AttnArgs {
   float* lse;
   const float* lse_in;
   const float* delta;
+  float *dk_part, *dv_part;   // fp32 [T, a*d] partials of the dK/dV kernel when a > kh
   long ldq, ldk, ldv, ldo, lddo, lddq, lddk, lddv;
   int batch, seq, a, kh;
   float scale_log2e, scale;
@@ -120,9 +124,32 @@ RP_DEV void store_acc_T(const f32x16 (&acc)[D / 32], float mul, bf16* stage /* [
   __syncthreads();
 }
 
+// Same for an fp32 destination; stage is [32][D + 4] floats per wave.
+template <int D>
+RP_DEV void store_acc_T_f32(const f32x16 (&acc)[D / 32], float mul, float* stage, float* __restrict__ out, long ld,
+                            int row0, int nrows, int lane) {
+  const int lr = lane & 31, lk = lane >> 5;
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg)
+      *reinterpret_cast<float4*>(stage + lr * (D + 4) + 32 * dt + 8 * vg + 4 * lk) =
+          make_float4(acc[dt][4 * vg] * mul, acc[dt][4 * vg + 1] * mul, acc[dt][4 * vg + 2] * mul, acc[dt][4 * vg + 3] * mul);
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < (32 * (D / 4)) / 64; ++it) {
+    const int idx = it * 64 + lane;
+    const int row = idx / (D / 4), ch = idx % (D / 4);
+    if (row0 + row < nrows)
+      *reinterpret_cast<float4*>(out + (long)(row0 + row) * ld + ch * 4) =
+          *reinterpret_cast<const float4*>(stage + row * (D + 4) + ch * 4);
+  }
+  __syncthreads();
+}
+
 // ================================================================================================ forward
 template <int D, int QT, int NW>
-__global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnArgs p) {
+__global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(const AttnArgs p) {
   constexpr int LDK = D + 8, LDV = D + 32, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
   using T64 = Tile64<D, NT>;
   constexpr int MAIN = 64 * LDK + 64 * LDV, STG = NW * 32 * LDK;
@@ -133,10 +160,10 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnArgs p) {
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nQ = (p.seq + BQ - 1) / BQ;
-  int bid = blockIdx.x;
-  const int qtile = nQ - 1 - (bid % nQ);     // heaviest query tiles first
-  bid /= nQ;
-  const int hq = bid % p.a, b = bid / p.a;
+  const int nhb = p.a * p.batch;
+  const int qtile = nQ - 1 - (int)blockIdx.x / nhb;     // the heaviest query tiles of every head go first
+  const int hb = (int)blockIdx.x % nhb;
+  const int hq = hb % p.a, b = hb / p.a;
   const int g = hq / (p.a / p.kh);
   const int q0 = qtile * BQ, qw0 = q0 + w * 32 * QT;
   const long tok0 = (long)b * p.seq;
@@ -211,39 +238,39 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const AttnArgs p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               const int kpos = kv0 + 32 * kt + 8 * (v >> 2) + 4 * lk + (v & 3);
-              const float s = sT[t][kt][v] * p.scale_log2e;
-              sT[t][kt][v] = (kpos > qpos || kpos >= p.seq) ? -INFINITY : s;
+              sT[t][kt][v] = (kpos > qpos || kpos >= p.seq) ? -INFINITY : sT[t][kt][v];
             }
-        } else {
-#pragma unroll
-          for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sT[t][kt][v] *= p.scale_log2e;
         }
         float mx = -INFINITY;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sT[t][kt][v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // the first key tile always contains key 0 <= qpos, so m_new is finite from the first iteration on
-        const float m_new = fmaxf(m_run[t], mx);
-        const float alpha = fast_exp2(m_run[t] - m_new);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * p.scale_log2e;
+        // m_run is the reference exponent (log2 units), not necessarily the running maximum: it only moves when the
+        // maximum outgrows it by more than 2^8, which keeps every exp2 argument <= 8 and skips most rescales of the
+        // accumulator.  The first key tile contains key 0 <= qpos, so the reference is finite from then on.
+        const bool grow = mx > m_run[t] + 8.f;
+        if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+          const float m_new = grow ? mx : m_run[t];
+          const float alpha = fast_exp2(m_run[t] - m_new);
+          l_run[t] *= alpha;
+          m_run[t] = m_new;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[t][dt][v] *= alpha;
+        }
         float psum = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const float e = fast_exp2(sT[t][kt][v] - m_new);
+            const float e = fast_exp2(__builtin_fmaf(sT[t][kt][v], p.scale_log2e, -m_run[t]));
             sT[t][kt][v] = e;
             psum += e;
           }
-        l_run[t] = l_run[t] * alpha + psum;
-        m_run[t] = m_new;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[t][dt][v] *= alpha;
+        l_run[t] += psum;
       }
 #pragma unroll
       for (int gk = 0; gk < 4; ++gk) {
@@ -316,10 +343,10 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const AttnArgs p) 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nQ = (p.seq + BQ - 1) / BQ;
-  int bid = blockIdx.x;
-  const int qtile = nQ - 1 - (bid % nQ);
-  bid /= nQ;
-  const int hq = bid % p.a, b = bid / p.a;
+  const int nhb = p.a * p.batch;
+  const int qtile = nQ - 1 - (int)blockIdx.x / nhb;
+  const int hb = (int)blockIdx.x % nhb;
+  const int hq = hb % p.a, b = hb / p.a;
   const int g = hq / (p.a / p.kh);
   const int q0 = qtile * BQ, qw0 = q0 + w * 32 * QT;
   const long tok0 = (long)b * p.seq;
@@ -449,12 +476,12 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nK = (p.seq + 127) / 128;
-  int bid = blockIdx.x;
-  const int kvt = bid % nK;                  // key tile 0 sees every query: heaviest first
-  bid /= nK;
-  const int g = bid % p.kh, b = bid / p.kh;
+  const int nhb = p.a * p.batch;
+  const int kvt = (int)blockIdx.x / nhb;     // key tile 0 sees every query: heaviest first, for every head
+  const int hb = (int)blockIdx.x % nhb;
+  const int hq = hb % p.a, b = hb / p.a;
   const int grp = p.a / p.kh;
+  const int g = hq / grp;
   const int kv0 = kvt * 128, kw0 = kv0 + 32 * w;
   const long tok0 = (long)b * p.seq;
   const bf16* kb = p.k + tok0 * p.ldk + g * D;
@@ -480,8 +507,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
 
   const int nQ = (p.seq + 63) / 64;
   const int qt0 = kv0 / 64;
-  const int per_head = nQ - qt0;
-  const int niter = grp * per_head;
+  const int niter = nQ - qt0;
 
   const bf16* qfrag = Qs + lr * LDK + 8 * lk;
   const bf16* dofrag = dOs + lr * LDK + 8 * lk;
@@ -490,11 +516,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
 
   uint4 qreg[T64::NREG], doreg[T64::NREG];
   float st_reg = 0.f;
+  const rsrc_t rq = seq_rsrc(p.q + tok0 * p.ldq + hq * D, p.ldq, p.seq, D);
+  const rsrc_t rdo = seq_rsrc(p.dout + tok0 * p.lddo + hq * D, p.lddo, p.seq, D);
   auto prefetch = [&](int it) {
-    const int hq = g * grp + it / per_head;
-    const int q0 = (qt0 + it % per_head) * 64;
-    const rsrc_t rq = seq_rsrc(p.q + tok0 * p.ldq + hq * D, p.ldq, p.seq, D);
-    const rsrc_t rdo = seq_rsrc(p.dout + tok0 * p.lddo + hq * D, p.lddo, p.seq, D);
+    const int q0 = (qt0 + it) * 64;
     T64::load(qreg, rq, p.ldq, q0, tid);
     T64::load(doreg, rdo, p.lddo, q0, tid);
     if (tid < 128) {
@@ -515,7 +540,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
     if (tid < 128) stats[tid] = st_reg;
     __syncthreads();
     if (it + 1 < niter) prefetch(it + 1);
-    const int q0 = (qt0 + it % per_head) * 64;
+    const int q0 = (qt0 + it) * 64;
     if (q0 + 63 >= kw0) {   // the wave has at least one (query >= key) pair
       f32x16 s[2], dp[2];
 #pragma unroll
@@ -565,8 +590,43 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
     }
   }
   __syncthreads();
-  store_acc_T<D>(dkacc, p.scale, smem + w * 32 * LDK, p.dk + tok0 * p.lddk + g * D, p.lddk, kw0, p.seq, lane);
-  store_acc_T<D>(dvacc, 1.f, smem + w * 32 * LDK, p.dv + tok0 * p.lddv + g * D, p.lddv, kw0, p.seq, lane);
+  if (grp == 1) {
+    store_acc_T<D>(dkacc, p.scale, smem + w * 32 * LDK, p.dk + tok0 * p.lddk + g * D, p.lddk, kw0, p.seq, lane);
+    store_acc_T<D>(dvacc, 1.f, smem + w * 32 * LDK, p.dv + tok0 * p.lddv + g * D, p.lddv, kw0, p.seq, lane);
+  } else {
+    float* const stage = reinterpret_cast<float*>(smem) + w * 32 * (D + 4);
+    const long ldp = (long)p.a * D;
+    store_acc_T_f32<D>(dkacc, p.scale, stage, p.dk_part + tok0 * ldp + hq * D, ldp, kw0, p.seq, lane);
+    store_acc_T_f32<D>(dvacc, 1.f, stage, p.dv_part + tok0 * ldp + hq * D, ldp, kw0, p.seq, lane);
+  }
+}
+
+// dk[t, g, :] = sum over the query heads of group g of the fp32 partials, in head order; same for dv.
+template <int D>
+__global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __restrict__ dk_part, const float* __restrict__ dv_part,
+                                                              bf16* __restrict__ dk, bf16* __restrict__ dv, long lddk,
+                                                              long lddv, long T, int a, int kh) {
+  constexpr int CH = D / 8;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  const long per = T * kh * CH;
+  if (idx >= 2 * per) return;
+  const bool is_v = idx >= per;
+  const long i = is_v ? idx - per : idx;
+  const int ch = (int)(i % CH);
+  const int g = (int)((i / CH) % kh);
+  const long t = i / ((long)CH * kh);
+  const int grp = a / kh;
+  const float* src = (is_v ? dv_part : dk_part) + t * (long)a * D + (long)g * grp * D + ch * 8;
+  float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
+  for (int j = 0; j < grp; ++j) {
+    const float4 x0 = *reinterpret_cast<const float4*>(src + (long)j * D);
+    const float4 x1 = *reinterpret_cast<const float4*>(src + (long)j * D + 4);
+    s0.x += x0.x; s0.y += x0.y; s0.z += x0.z; s0.w += x0.w;
+    s1.x += x1.x; s1.y += x1.y; s1.z += x1.z; s1.w += x1.w;
+  }
+  bf16* dst = is_v ? dv + t * lddv + g * D + ch * 8 : dk + t * lddk + g * D + ch * 8;
+  *reinterpret_cast<uint4*>(dst) = make_uint4(pack_bf16x2(s0.x, s0.y), pack_bf16x2(s0.z, s0.w), pack_bf16x2(s1.x, s1.y),
+                                              pack_bf16x2(s1.z, s1.w));
 }
 
 constexpr int dq_smem_bytes(int d) { return (2 * 64 * (d + 8) + 64 * (d + 32)) * 2; }
@@ -640,8 +700,9 @@ hipError_t k_attn_delta(hipStream_t st, const void* o, const void* dout, float* 
 }
 
 hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, const void* v, const void* dout,
-                      const float* lse, const float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv,
-                      long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh, int d) {
+                      const float* lse, const float* delta, void* dq, void* dk, void* dv, float* scratch, long ldq,
+                      long ldk, long ldv, long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh,
+                      int d) {
   if (batch * seq == 0) return hipSuccess;
   AttnArgs p = {};
   p.q = (const bf16*)q; p.k = (const bf16*)k; p.v = (const bf16*)v; p.dout = (const bf16*)dout;
@@ -649,9 +710,21 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
   p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.lddo = lddo; p.lddq = lddq; p.lddk = lddk; p.lddv = lddv;
   fill_common(p, batch, seq, a, kh, d);
   if (d != 128 && d != 64) return hipErrorInvalidValue;
+  if (a != kh && !scratch) return hipErrorInvalidValue;
+  const long T = (long)batch * seq;
+  p.dk_part = scratch;
+  p.dv_part = scratch ? scratch + T * a * d : nullptr;
   hipError_t e = hipSuccess;
+  if (part == 2) {   // sum of the group's partials
+    if (a == kh) return hipSuccess;
+    const long items = 2 * T * kh * (d / 8);
+    const int grid = (int)((items + 255) / 256);
+    if (d == 128) RP_LAUNCH(attn_dkv_reduce_kernel<128>, dim3(grid), dim3(256), 0, st, p.dk_part, p.dv_part, p.dk, p.dv, lddk, lddv, T, a, kh);
+    else RP_LAUNCH(attn_dkv_reduce_kernel<64>, dim3(grid), dim3(256), 0, st, p.dk_part, p.dv_part, p.dk, p.dv, lddk, lddv, T, a, kh);
+    return hipGetLastError();
+  }
   if (part == 0) {
-    const int nk = ((seq + 127) / 128) * kh * batch;
+    const int nk = ((seq + 127) / 128) * a * batch;   // one workgroup per 128 keys and query head
     if (d == 128) {
       static bool done = false;
       if ((e = set_smem(attn_bwd_dkv_kernel<128>, dkv_smem_bytes(128), done)) != hipSuccess) return e;

@@ -29,7 +29,12 @@ static RP_DEV uint32_t f32_to_bf16_bits(float f) {
   bf16 h = (bf16)f;
   return (uint32_t)__builtin_bit_cast(unsigned short, h);
 }
-static RP_DEV uint32_t pack_bf16x2(float lo, float hi) { return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16); }
+static RP_DEV uint32_t pack_bf16x2(float lo, float hi) {   // one v_cvt_pk_bf16_f32 (round to nearest even)
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
 // 8x8 transpose of bf16 held as 8 uint4 rows (row r = 8 consecutive columns) -> 8 uint4 (entry c = column c, rows 0..7)
 static RP_DEV void transpose8x8_bf16(const uint4 (&in)[8], uint4 (&out)[8]) {

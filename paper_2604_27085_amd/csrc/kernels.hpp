@@ -39,10 +39,11 @@ hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* 
 // delta[batch, a, seq] = rowsum(dO * O)
 hipError_t k_attn_delta(hipStream_t st, const void* o, const void* dout, float* delta, long ldo, long lddo, int batch,
                         int seq, int a, int d);
-// part 0: dk, dv [T, kh, d] (lddk, lddv), summed over the query heads of each group;  part 1: dq [T, a, d] (lddq).
+// part 0: dk, dv [T, kh, d] (lddk, lddv) when a == kh, else per-query-head fp32 partials into scratch (2*T*a*d
+// floats);  part 2: sum of each group's partials into dk, dv (nothing to do when a == kh);  part 1: dq [T, a, d].
 hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, const void* v, const void* dout, const float* lse,
-                      const float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv, long lddo, long lddq,
-                      long lddk, long lddv, int batch, int seq, int a, int kh, int d);
+                      const float* delta, void* dq, void* dk, void* dv, float* scratch, long ldq, long ldk, long ldv,
+                      long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh, int d);
 
 // Cross-entropy helpers.  part [P, T] (max, sumexp) partials -> lse[T]; then loss / coef from lse, label logits, labels.
 hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, float* lse, int T);

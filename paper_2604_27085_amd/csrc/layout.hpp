@@ -95,6 +95,7 @@ struct Plan {
   size_t rope, bd1, bd3;                          // RoPE table, block-diagonal LoRA B of the fused GEMMs
   size_t layer0, layer_stride;                    // saved internals, one set per layer (backward) or one set (forward)
   size_t tA, tB, dact, dgu, dn, dout, dqr, dkr, dqkv, delta, ud, partials;   // backward temporaries
+  size_t dkvp;   // per-query-head dK/dV partials of grouped attention; shares memory with dact|dgu, dead by then
   size_t fwd_bytes, bwd_bytes;
   // head
   size_t h_xf, h_rstd, h_part, h_zlab, h_lse, h_coef, h_dzt, h_dxacc, h_partials, head_bytes;
@@ -132,6 +133,8 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   }
   o += set * (size_t)(D.L > 0 ? D.L : 0);
   P.tA = take(T * D.h * 2); P.tB = take(T * D.h * 2); P.dact = take(T * D.m * 2); P.dgu = take(T * 2 * D.m * 2);
+  P.dkvp = P.dact;
+  if (D.a != D.kh && P.dkvp + 2 * T * D.qd * 4 > o) take(P.dkvp + 2 * T * D.qd * 4 - o);
   P.dn = take(T * D.h * 2); P.dout = take(T * D.qd * 2); P.dqr = take(T * D.qd * 2); P.dkr = take(T * D.kd * 2);
   P.dqkv = take(T * D.n1 * 2); P.delta = take(T * D.a * 4);
   P.ud = take(T * (size_t)(3 * D.r) * 2);

@@ -285,11 +285,18 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
       k_attn_delta(X.st, S(b.o), X.at<void>(X.P.dout), X.at<float>(X.P.delta), D.qd, D.qd, X.batch, X.seq, D.a, D.d));
   const double s2qd = (double)X.batch * X.seq * (double)X.seq * D.qd;
   // useful FLOPs per kernel: dK/dV kernel runs S, dP, dV, dK (4 half-masked products), dQ kernel S, dP, dQ (3)
-  for (int part = 0; part < 2; ++part)
-    RUN(X, part == 0 ? "attn_bwd_dkv" : "attn_bwd_dq", (part == 0 ? 4.0 : 3.0) * s2qd, 2.0 * Td * (3 * D.qd + 4 * D.kd),
+  static const int parts[3] = {0, 2, 1};
+  static const char* const part_name[3] = {"attn_bwd_dkv", "attn_bwd_dq", "attn_dkv_reduce"};
+  for (int i = 0; i < 3; ++i) {
+    const int part = parts[i];
+    if (part == 2 && D.a == D.kh) continue;
+    const double fl = part == 0 ? 4.0 * s2qd : part == 1 ? 3.0 * s2qd : 0.0;
+    const double by = part == 2 ? Td * (8.0 * D.qd + 4.0 * D.kd) : 2.0 * Td * (3 * D.qd + 4 * D.kd);
+    RUN(X, part_name[part], fl, by,
         k_attn_bwd(X.st, part, S(b.qr), S(b.kr), qkv + D.qd + D.kd, X.at<void>(X.P.dout), (const float*)S(b.lse),
-                   X.at<float>(X.P.delta), X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), dqkv + D.qd + D.kd, D.qd, D.kd, D.n1, D.qd,
-                   D.qd, D.kd, D.n1, X.batch, X.seq, D.a, D.kh, D.d));
+                   X.at<float>(X.P.delta), X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), dqkv + D.qd + D.kd,
+                   X.at<float>(X.P.dkvp), D.qd, D.kd, D.n1, D.qd, D.qd, D.kd, D.n1, X.batch, X.seq, D.a, D.kh, D.d));
+  }
   RUN(X, "qknorm_rope_bwd", 0, 6.0 * Td * (D.qd + D.kd),
       k_qknorm_rope(X.st, 1, D.d, X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), D.qd, D.kd, dqkv, dqkv + D.qd, D.n1, D.n1,
                     W.t(RP_T_GQ), W.t(RP_T_GK), (float*)S(b.rstd_q), (float*)S(b.rstd_k), qkv, qkv + D.qd, D.n1,
@@ -701,15 +708,19 @@ rp_status rp_op_attn_fwd(void* stream, const void* q, const void* k, const void*
 }
 
 rp_status rp_op_attn_bwd(void* stream, const void* q, const void* k, const void* v, const void* o, const void* dout,
-                         const float* lse, float* delta, void* dq, void* dk, void* dv, long ldq, long ldk, long ldv, long ldo,
-                         long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh, int d) {
+                         const float* lse, float* delta, void* dq, void* dk, void* dv, float* scratch, long ldq, long ldk,
+                         long ldv, long ldo, long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh,
+                         int d) {
   if (!q || !k || !v || !o || !dout || !lse || !delta || !dq || !dk || !dv || (d != 64 && d != 128) || a <= 0 || kh <= 0 || a % kh)
     return fail(nullptr, RP_EINVAL, "rp_op_attn_bwd: bad arguments");
+  if (a != kh && !scratch) return fail(nullptr, RP_EINVAL, "rp_op_attn_bwd: grouped queries need the scratch buffer");
   if (ldq % 8 || ldk % 8 || ldv % 8 || ldo % 8 || lddo % 8 || lddq % 8 || lddk % 8 || lddv % 8) return fail(nullptr, RP_EINVAL, "rp_op_attn_bwd: strides must be multiples of 8");
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   hipError_t e = k_attn_delta(st, o, dout, delta, ldo, lddo, batch, seq, a, d);
-  for (int part = 0; part < 2 && e == hipSuccess; ++part)
-    e = k_attn_bwd(st, part, q, k, v, dout, lse, delta, dq, dk, dv, ldq, ldk, ldv, lddo, lddq, lddk, lddv, batch, seq, a, kh, d);
+  static const int parts[3] = {0, 2, 1};
+  for (int i = 0; i < 3 && e == hipSuccess; ++i)
+    e = k_attn_bwd(st, parts[i], q, k, v, dout, lse, delta, dq, dk, dv, scratch, ldq, ldk, ldv, lddo, lddq, lddk, lddv, batch, seq,
+                   a, kh, d);
   OP_RET(e);
 }
 

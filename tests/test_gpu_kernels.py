@@ -240,8 +240,9 @@ def test_attention_fwd_bwd(rp, d, a, kh, batch, seq):
     dq = torch.zeros((T, a * d), dtype=torch.bfloat16, device="cuda:0")
     dkv = torch.zeros((T, 2 * kh * d), dtype=torch.bfloat16, device="cuda:0")
     delta = torch.zeros((batch, a, seq), dtype=torch.float32, device="cuda:0")
+    scratch = torch.full((2, T, a * d), float("nan"), dtype=torch.float32, device="cuda:0") if a != kh else None
     B.rp_op_attn_bwd(stream(), qd_, kp, vp, o, dev(H, do.reshape(T, -1)), lse, delta, dq, dkv, dkv.data_ptr() + kh * d * 2,
-                     a * d, ldkv, ldkv, a * d, a * d, a * d, ldkv, ldkv, batch, seq, a, kh, d)
+                     scratch, a * d, ldkv, ldkv, a * d, a * d, a * d, ldkv, ldkv, batch, seq, a, kh, d)
     torch.cuda.synchronize()
     dkv_h = H.to_f32(dkv)
     assert rel_l2(H.to_f32(dq).reshape(T, a, d), dq_ref) < 1e-2
