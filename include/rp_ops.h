@@ -16,7 +16,8 @@ extern "C" {
  * out_f32 0: C bf16 = alpha*acc (+ R, bf16 [M,N], optional);  1: C fp32 = alpha*acc (+ C when beta);  2: atomic +=.
  * (A2, B2, K2): optional second operand pair, same layout, appended to the reduction (LoRA up-projection).
  * K, K2 and all leading dimensions are multiples of 8; N (and M for layout 2) too when that operand is transposed.
- * tile 0 = automatic, 1..4 force 256x256, 256x128, 128x128, 128x64. */
+ * tile 0 = automatic, 1..4 force 256x256, 256x128, 128x128, 128x64; 5 = 256x128 worked on by two wave groups that
+ * split every K tile (for outputs too small to fill the chip with 256x256 tiles). */
 RP_API rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const void* B, void* C, int M, int N, int K,
                      long lda, long ldb, long ldc, float alpha, int beta, const void* A2, const void* B2, int K2, long lda2,
                      long ldb2, const void* R, long ldr, int tile);

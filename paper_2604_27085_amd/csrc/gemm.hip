@@ -87,25 +87,32 @@ struct StepHint {
   }
 };
 
-template <int WGM, int WGN, int BK, bool TA, bool TB>
+// KG wave groups share one output tile: group g runs the 16-deep steps [g*KS/KG, (g+1)*KS/KG) of every K tile, and the
+// groups' accumulators are added through LDS before the epilogue.  With KG = 2 a 256x128 tile is worked on by eight
+// waves of 128x64 each, which fills the chip with half as many output elements as the 256x256 tile needs.
+template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1>
 struct Cfg {
-  static constexpr int BM = WGM * WAVE_M, BN = WGN * WAVE_N, NW = WGM * WGN, NTHR = NW * 64;
+  static constexpr int BM = WGM * WAVE_M, BN = WGN * WAVE_N, NWT = WGM * WGN, NW = NWT * KG, NTHR = NW * 64;
+  static_assert((BK / 16) % KG == 0, "the K tile does not divide over the wave groups");
+  static_assert(KG == 1 || NWT * (TM * 16 * 64 * 4) <= 160 * 1024, "accumulator exchange does not fit in LDS");
   using LA = TileLoader<BM, BK, NTHR, TA>;
   using LB = TileLoader<BN, BK, NTHR, TB>;
   static constexpr int MAIN_BYTES = 2 * (LA::S::ELEMS + LB::S::ELEMS) * 2;
-  static constexpr int SMEM = MAIN_BYTES > NW * STG_BYTES ? MAIN_BYTES : NW * STG_BYTES;
+  static constexpr int XCH_BYTES = KG > 1 ? NWT * (TM * 16 * 64 * 4) : 0;   // one column of MFMA tiles per exchange
+  static constexpr int SMEM0 = MAIN_BYTES > NWT * STG_BYTES ? MAIN_BYTES : NWT * STG_BYTES;
+  static constexpr int SMEM = SMEM0 > XCH_BYTES ? SMEM0 : XCH_BYTES;
   // waves per SIMD the register budget is set for
   static constexpr int WPS = (NW == 8) ? 2 : (SMEM * 2 <= 160 * 1024 ? 2 : 1);
 };
 
-template <int WGM, int WGN, int BK, bool TA, bool TB>
-__global__ void __launch_bounds__(WGM* WGN * 64)
-    __attribute__((amdgpu_waves_per_eu(Cfg<WGM, WGN, BK, TA, TB>::WPS, Cfg<WGM, WGN, BK, TA, TB>::WPS)))
+template <int WGM, int WGN, int BK, bool TA, bool TB, int KG>
+__global__ void __launch_bounds__(WGM* WGN* KG * 64)
+    __attribute__((amdgpu_waves_per_eu(Cfg<WGM, WGN, BK, TA, TB, KG>::WPS, Cfg<WGM, WGN, BK, TA, TB, KG>::WPS)))
     gemm_kernel(const GemmArgs p) {
-  using C = Cfg<WGM, WGN, BK, TA, TB>;
+  using C = Cfg<WGM, WGN, BK, TA, TB, KG>;
   using LA = typename C::LA;
   using LB = typename C::LB;
-  constexpr int BM = C::BM, BN = C::BN, KS = BK / 16;
+  constexpr int BM = C::BM, BN = C::BN, KS = BK / 16, KSL = KS / KG;
   constexpr int LDA = LA::S::LDROW, LDB = LB::S::LDROW;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* const sA0 = reinterpret_cast<bf16*>(smem);
@@ -115,7 +122,9 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
+  const int kg = wave / C::NWT, wmn = wave % C::NWT;   // wave group, wave within the output tile
+  const int wm = wmn / WGN, wn = wmn % WGN;
+  const int ks0 = kg * KSL;
 
   int tile_m, tile_n;
   tile_of_block(p.M, p.N, BM, BN, tile_m, tile_n);
@@ -187,13 +196,13 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
     constexpr bool MORE = decltype(more_tag)::value;
     const bf16* pa = ((kt & 1) ? sA1 : sA0) + offA;
     const bf16* pb = ((kt & 1) ? sB1 : sB0) + offB;
-    load_frags(0, pa, pb, 0);
+    load_frags(0, pa, pb, ks0);
     if constexpr (MORE) fetch(kt + 1);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) load_frags((ks + 1) & 1, pa, pb, ks + 1);
+    for (int ks = 0; ks < KSL; ++ks) {
+      if (ks + 1 < KSL) load_frags((ks + 1) & 1, pa, pb, ks0 + ks + 1);
       if constexpr (MORE) {
-        if (ks == KS - 1) {
+        if (ks == KSL - 1) {
           la.store(ra, (kt & 1) ? sA0 : sA1);
           lb.store(rb, (kt & 1) ? sB0 : sB1);
         }
@@ -201,8 +210,8 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
       mfma_step(ks & 1);
       constexpr int NLD = LA::NREG + LB::NREG;
       constexpr int NDS = TM * (TA ? 2 : 1) + TN * (TB ? 2 : 1);
-      if (ks == 0) StepHint<0, TM * TN, (KS > 1) ? NDS : 0, MORE ? NLD : 0, (MORE && KS == 1) ? NLD : 0>::go();
-      else if (ks + 1 < KS) StepHint<0, TM * TN, NDS, 0, 0>::go();
+      if (ks == 0) StepHint<0, TM * TN, (KSL > 1) ? NDS : 0, MORE ? NLD : 0, (MORE && KSL == 1) ? NLD : 0>::go();
+      else if (ks + 1 < KSL) StepHint<0, TM * TN, NDS, 0, 0>::go();
       else StepHint<0, TM * TN, 0, 0, MORE ? NLD : 0>::go();
     }
     __syncthreads();
@@ -210,14 +219,42 @@ __global__ void __launch_bounds__(WGM* WGN * 64)
   for (int kt = 0; kt + 1 < nk; ++kt) tile(kt, std::true_type{});
   if (nk > 0) tile(nk - 1, std::false_type{});
 
-  epilogue(p, acc, smem, wave, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
+  if constexpr (KG > 1) {
+    // the K loop ended with a barrier, so the operand tiles are dead: groups 1.. hand their accumulators to group 0,
+    // one column of MFMA tiles at a time, [wave][register][lane] (conflict-free)
+    float* const xch = reinterpret_cast<float*>(smem) + wmn * (TM * 16 * 64) + lane;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int g = 1; g < KG; ++g) {
+        if (kg == g) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) xch[(i * 16 + v) * 64] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (kg == 0) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] += xch[(i * 16 + v) * 64];
+        }
+        __syncthreads();
+      }
+    if (kg != 0) {   // wave-uniform: only the barriers of the epilogue
+      epilogue_barriers(p);
+      return;
+    }
+  }
+  epilogue(p, acc, smem, wmn, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
 }
 
-template <int WGM, int WGN, int BK, bool TA, bool TB>
+template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1>
 hipError_t launch_one(hipStream_t st, const GemmArgs& a) {
-  using C = Cfg<WGM, WGN, BK, TA, TB>;
+  using C = Cfg<WGM, WGN, BK, TA, TB, KG>;
   static bool attr_done = false;
-  auto kern = gemm_kernel<WGM, WGN, BK, TA, TB>;
+  auto kern = gemm_kernel<WGM, WGN, BK, TA, TB, KG>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return e;
@@ -234,6 +271,7 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& a, int tile) {
     case 1: return launch_one<2, 4, 64, TA, TB>(st, a);
     case 2: return launch_one<2, 2, 32, TA, TB>(st, a);
     case 3: return launch_one<1, 2, 32, TA, TB>(st, a);
+    case 5: return launch_one<2, 2, 64, TA, TB, 2>(st, a);
     default: return launch_one<1, 1, 32, TA, TB>(st, a);
   }
 }
@@ -258,18 +296,22 @@ int env_tile() {
 
 // Picks the tile with the smallest modelled time: n = workgroups on the busiest CU, each costing its area divided by
 // a relative efficiency that was measured with one workgroup per CU and with the CU fully occupied.
-int choose_tile(int M, int N) {
-  static const int bm[4] = {256, 256, 128, 128}, bn[4] = {256, 128, 128, 64};
-  static const int per_cu[4] = {1, 2, 3, 5};
-  static const double eff_full[4] = {1.0, 0.83, 0.7, 0.4}, eff_single[4] = {1.0, 0.375, 0.25, 0.15};
+// atomic_nk: K tiles of 64 when the output accumulates in fp32, so that an under-filled 256x256 launch can be split
+// along the reduction (merged by atomic adds, which only pays off for long reductions); else 0.
+int choose_tile(int M, int N, bool plain_epilogue, int atomic_nk) {
+  static const int bm[5] = {256, 256, 128, 128, 256}, bn[5] = {256, 128, 128, 64, 128};
+  static const int per_cu[5] = {1, 2, 3, 5, 1};
+  static const double eff_full[5] = {1.0, 0.83, 0.7, 0.4, 0.75}, eff_single[5] = {1.0, 0.375, 0.25, 0.15, 0.75};
   int best = 1;
   double best_cost = 1e300;
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < (plain_epilogue ? 5 : 4); ++t) {
     const long tiles = (long)((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]);
     const long n = (tiles + 255) / 256;
     double e = eff_full[t];
     if (n < per_cu[t]) e = eff_single[t] + (eff_full[t] - eff_single[t]) * (double)(n - 1) / (per_cu[t] - 1);
-    const double cost = (double)n * bm[t] * bn[t] / e;
+    double rounds = (double)n;
+    if (t == 0 && atomic_nk >= 128 && tiles <= 128) rounds = 0.55;
+    const double cost = rounds * bm[t] * bn[t] / e;
     if (cost < best_cost) { best_cost = cost; best = t + 1; }
   }
   return best;
@@ -294,7 +336,10 @@ int gemm_ce_stats_partials(int M) { return 2 * ((M + 255) / 256); }
 int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
   if (a.epi == EPI_CE_STATS) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
   if (tile_hint) return tile_hint;
-  return env_tile() ? env_tile() : choose_tile(a.M, a.N);
+  // the eight-wave 256x128 tile supports the epilogues whose barrier pattern epilogue_barriers() knows
+  const bool plain = a.epi == EPI_BF16 || a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC;
+  const int atomic_nk = (a.epi == EPI_F32 && a.beta && env_splitk()) ? (a.K + 63) / 64 + (a.K2 + 63) / 64 : 0;
+  return env_tile() ? env_tile() : choose_tile(a.M, a.N, plain, atomic_nk);
 }
 
 hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int tile_hint) {

@@ -44,5 +44,6 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a, int tile_h
 // Number of partial rows an EPI_CE_STATS launch with M vocab rows writes for tile choice made by gemm_launch.
 int gemm_ce_stats_partials(int M);
 void gemm_zero_args(GemmArgs& a);
-// Tile gemm_launch picks for these arguments: 1..4 = 256x256, 256x128, 128x128, 128x64.
+// Tile gemm_launch picks for these arguments: 1..4 = 256x256, 256x128, 128x128, 128x64 (8, 4, 2, 1 waves),
+// 5 = 256x128 with eight waves in two groups that split every K tile.
 int gemm_pick_tile(const GemmArgs& a, int tile_hint = 0);

@@ -77,6 +77,16 @@ RP_DEV void tile_of_block(int M, int N, int BM, int BN, int& tile_m, int& tile_n
   tile_n = in_group / gm;
 }
 
+// The barriers epilogue() executes for these arguments, for waves of the workgroup that hold no part of the result.
+RP_DEV void epilogue_barriers(const GemmArgs& p) {
+  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ) {
+    __syncthreads();
+  } else if (p.epi == EPI_BF16 || p.epi == EPI_F32) {
+#pragma unroll
+    for (int j = 0; j < 2 * TN - 1; ++j) __syncthreads();
+  }
+}
+
 // Epilogue.  acc[i][j][v] is element (i*32 + 8*(v/4) + 4*lk + v%4, j*32 + lr) of the wave's 128x64 block whose top
 // left corner is (wrow0, wcol0).  Every wave stages its block through its own 18 KB of LDS (all waves must have
 // finished the K loop) so that global accesses are 16 bytes per lane and cover whole 128-byte lines.

@@ -131,7 +131,7 @@ struct Exec {
   void mark_gemm(int layout, const GemmArgs& g) {
     if (!ctx->tracing) return;
     static const char* lay[3] = {"NT", "NN", "TN"};
-    static const char* til[5] = {"", "256x256", "256x128", "128x128", "128x64"};
+    static const char* til[6] = {"", "256x256", "256x128", "128x128", "128x64", "256x128k2"};
     char nm[40];
     snprintf(nm, sizeof(nm), "gemm_%s_%s", til[gemm_pick_tile(g)], lay[layout]);
     const double out_b = (g.epi == EPI_BF16 || g.epi == EPI_CE_DZ) ? 2.0 : (g.epi == EPI_CE_STATS ? 0.0 : 4.0 * (1 + g.beta));
@@ -644,7 +644,7 @@ rp_status rp_trace_stop(rp_ctx* ctx, rp_trace_record* out, int cap, int* n_out) 
 rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const void* B, void* C, int M, int N, int K,
                      long lda, long ldb, long ldc, float alpha, int beta, const void* A2, const void* B2, int K2, long lda2,
                      long ldb2, const void* R, long ldr, int tile) {
-  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 4)
+  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 5)
     return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad arguments");
   if ((layout != GEMM_NT) && (N % 8 || (layout == GEMM_TN && M % 8))) return fail(nullptr, RP_EINVAL, "rp_op_gemm: transposed operands need multiples of 8");
   GemmArgs g; gemm_zero_args(g);

@@ -39,7 +39,7 @@ def stream():
 
 
 # ----------------------------------------------------------------------------------------------- GEMM
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
 @pytest.mark.parametrize("layout", [0, 1, 2])
 def test_gemm_layouts_ragged(rp, layout, tile):
     B, H = rp
@@ -73,17 +73,18 @@ def test_gemm_second_pair_residual_and_atomic(rp):
     u, bl = rnd(rng, (M, K2)), rnd(rng, (N, K2), 0.1)
     res = rnd(rng, (M, N))
     ref = x.astype(np.float64) @ w.T.astype(np.float64) + u.astype(np.float64) @ bl.T.astype(np.float64) + res
-    Cm = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
-    B.rp_op_gemm(stream(), 0, 0, dev(H, x), dev(H, w), Cm, M, N, K, K, K, N, A2=dev(H, u), B2=dev(H, bl), K2=K2, lda2=K2,
-                 ldb2=K2, R=dev(H, res), ldr=N)
-    torch.cuda.synchronize()
-    assert rel_l2(H.to_f32(Cm), ref) < 4e-3
+    for tile in (0, 1, 5):
+        Cm = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
+        B.rp_op_gemm(stream(), 0, 0, dev(H, x), dev(H, w), Cm, M, N, K, K, K, N, A2=dev(H, u), B2=dev(H, bl), K2=K2,
+                     lda2=K2, ldb2=K2, R=dev(H, res), ldr=N, tile=tile)
+        torch.cuda.synchronize()
+        assert rel_l2(H.to_f32(Cm), ref) < 4e-3, tile
     # NN with a second pair (activation gradient of a LoRA linear): dx = dy W + ud A
     dy, ud, a_l = rnd(rng, (M, N)), rnd(rng, (M, K2)), rnd(rng, (K2, K), 0.1)
     ref2 = dy.astype(np.float64) @ w.astype(np.float64) + ud.astype(np.float64) @ a_l.astype(np.float64)
     C2 = torch.zeros((M, K), dtype=torch.bfloat16, device="cuda:0")
     B.rp_op_gemm(stream(), 1, 0, dev(H, dy), dev(H, w), C2, M, K, N, N, K, K, A2=dev(H, ud), B2=dev(H, a_l), K2=K2,
-                 lda2=K2, ldb2=K)
+                 lda2=K2, ldb2=K, tile=5)
     torch.cuda.synchronize()
     assert rel_l2(H.to_f32(C2), ref2) < 4e-3
     # atomic accumulation, skinny output (LoRA gradient shape): dB[N, r] += dy^T u
