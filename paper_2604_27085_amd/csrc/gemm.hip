@@ -67,6 +67,18 @@ struct TileLoader {
 #pragma unroll
     for (int it = 0; it < NREG; ++it) *reinterpret_cast<uint4*>(Sm + (row0 + it * RSTEP) * S::LDROW + ch * 8) = r[it];
   }
+
+  // One chunk at a time, for the steady state of the K loop; `other` is the loader of the second operand pair (same
+  // thread -> chunk mapping), selected without a branch when second is set.
+  RP_DEV uint4 load_one(int it, const TileLoader& other, bool second, rsrc_t rs, int k0, int Klim) const {
+    const uint32_t vo = second ? other.voff[it] : voff[it];
+    const uint32_t kst = second ? other.kstep : kstep;
+    const bool kok = TR ? (k0 + row0 + it * RSTEP) < Klim : (k0 + ch * 8) < Klim;
+    return buf_load16(rs, kok ? vo : OOB, (uint32_t)k0 * kst);
+  }
+  RP_DEV void store_one(int it, const uint4& r, bf16* Sm) const {
+    *reinterpret_cast<uint4*>(Sm + (row0 + it * RSTEP) * S::LDROW + ch * 8) = r;
+  }
 };
 
 // Scheduling hints for one 16-deep step of the K loop: after each of the NM MFMAs, its share of the step's NDS LDS
@@ -80,8 +92,8 @@ struct StepHint {
       constexpr int vm = ((I + 1) * NVM) / NM - (I * NVM) / NM;
       constexpr int dw = ((I + 1) * NDW) / NM - (I * NDW) / NM;
       if constexpr (ds > 0) __builtin_amdgcn_sched_group_barrier(0x100, ds, 0);
+      if constexpr (dw > 0) __builtin_amdgcn_sched_group_barrier(0x200, dw, 0);   // a chunk is stored before it is reloaded
       if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(0x020, vm, 0);
-      if constexpr (dw > 0) __builtin_amdgcn_sched_group_barrier(0x200, dw, 0);
       StepHint<I + 1, NM, NDS, NVM, NDW>::go();
     }
   }
@@ -142,23 +154,35 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   lb.init(p.ldb, n0, p.N, tid);
   const rsrc_t rsA = make_rsrc(p.A, p.bytesA), rsB = make_rsrc(p.B, p.bytesB);
   rsrc_t rsA2 = rsA, rsB2 = rsB;
+  la2 = la;
+  lb2 = lb;
   if (p.K2 > 0) {
     la2.init(p.lda2, m0, p.M, tid);
     lb2.init(p.ldb2, n0, p.N, tid);
     rsA2 = make_rsrc(p.A2, p.bytesA2);
     rsB2 = make_rsrc(p.B2, p.bytesB2);
   }
-  uint4 ra[LA::NREG], rb[LB::NREG];
-
-  auto fetch = [&](int kt_local) {
+  // Staging registers: chunk r < LA::NREG belongs to the A tile, the others to the B tile.  In the steady state
+  // every chunk rotates on its own: at its slot of K tile kt it is stored to LDS (it holds tile kt+1, loaded one
+  // tile earlier) and immediately reloaded with tile kt+2, so global loads and LDS stores are spread evenly over
+  // the MFMAs of a tile instead of arriving in bursts, and every load has a full tile of time to return.
+  constexpr int NLD = LA::NREG + LB::NREG;
+  static_assert(NLD % KSL == 0, "staging chunks do not divide over the steps of a K tile");
+  constexpr int PER = NLD / KSL;
+  uint4 rg[NLD];
+  struct Seg { bool second; int k0, Klim; };
+  auto seg_of = [&](int kt_local) {
     const int kt = kt0 + kt_local;
-    if (kt < nk1) {
-      la.load(ra, rsA, kt * BK, p.K);
-      lb.load(rb, rsB, kt * BK, p.K);
-    } else {
-      la2.load(ra, rsA2, (kt - nk1) * BK, p.K2);
-      lb2.load(rb, rsB2, (kt - nk1) * BK, p.K2);
-    }
+    const bool second = kt >= nk1;
+    return Seg{second, (second ? kt - nk1 : kt) * BK, second ? p.K2 : p.K};
+  };
+  auto load_chunk = [&](int r, const Seg& sg) {
+    if (r < LA::NREG) rg[r] = la.load_one(r, la2, sg.second, sg.second ? rsA2 : rsA, sg.k0, sg.Klim);
+    else rg[r] = lb.load_one(r - LA::NREG, lb2, sg.second, sg.second ? rsB2 : rsB, sg.k0, sg.Klim);
+  };
+  auto store_chunk = [&](int r, bf16* sa, bf16* sb) {
+    if (r < LA::NREG) la.store_one(r, rg[r], sa);
+    else lb.store_one(r - LA::NREG, rg[r], sb);
   };
 
   f32x16 acc[TM][TN];
@@ -170,9 +194,16 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   if (nk > 0) {
-    fetch(0);
-    la.store(ra, sA0);
-    lb.store(rb, sB0);
+    const Seg s0 = seg_of(0);
+#pragma unroll
+    for (int r = 0; r < NLD; ++r) load_chunk(r, s0);
+#pragma unroll
+    for (int r = 0; r < NLD; ++r) store_chunk(r, sA0, sB0);
+    if (nk > 1) {
+      const Seg s1 = seg_of(1);
+#pragma unroll
+      for (int r = 0; r < NLD; ++r) load_chunk(r, s1);
+    }
   }
   __syncthreads();
 
@@ -192,32 +223,43 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
       for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(af[buf][i], bfr[buf][j], acc[i][j]);
   };
 
-  auto tile = [&](int kt, auto more_tag) {
-    constexpr bool MORE = decltype(more_tag)::value;
+  // STORE: tile kt+1 exists (its chunks are in the staging registers); LOAD: tile kt+2 exists.
+  auto tile = [&](int kt, auto store_tag, auto load_tag) {
+    constexpr bool STORE = decltype(store_tag)::value, LOAD = decltype(load_tag)::value;
     const bf16* pa = ((kt & 1) ? sA1 : sA0) + offA;
     const bf16* pb = ((kt & 1) ? sB1 : sB0) + offB;
+    bf16* const na = (kt & 1) ? sA0 : sA1;
+    bf16* const nb = (kt & 1) ? sB0 : sB1;
+    const Seg sg = seg_of(kt + 2);
     load_frags(0, pa, pb, ks0);
-    if constexpr (MORE) fetch(kt + 1);
+    // Every MFMA is followed by its share of the step's memory instructions -- one fragment read for the next step
+    // (front-loaded, so they have returned when the step ends) and the chunk rotations spread evenly -- and a
+    // scheduling barrier keeps the compiler from regrouping them.
+    constexpr int NM = TM * TN, NF = TM + TN;
+    static_assert(NF <= NM, "more fragments than MFMAs in a step");
 #pragma unroll
     for (int ks = 0; ks < KSL; ++ks) {
-      if (ks + 1 < KSL) load_frags((ks + 1) & 1, pa, pb, ks0 + ks + 1);
-      if constexpr (MORE) {
-        if (ks == KSL - 1) {
-          la.store(ra, (kt & 1) ? sA0 : sA1);
-          lb.store(rb, (kt & 1) ? sB0 : sB1);
+      const int cur = ks & 1, nxt = cur ^ 1;
+#pragma unroll
+      for (int I = 0; I < NM; ++I) {
+        acc[I / TN][I % TN] = mfma32(af[cur][I / TN], bfr[cur][I % TN], acc[I / TN][I % TN]);
+        if (ks + 1 < KSL && I < NF) {
+          if (I < TM) af[nxt][I] = read_frag<LDA, TA>(pa, I * 32, ks0 + ks + 1);
+          else bfr[nxt][I - TM] = read_frag<LDB, TB>(pb, (I - TM) * 32, ks0 + ks + 1);
         }
+#pragma unroll
+        for (int c = (I * PER) / NM; c < ((I + 1) * PER) / NM; ++c) {
+          if constexpr (STORE) store_chunk(ks * PER + c, na, nb);
+          if constexpr (LOAD) load_chunk(ks * PER + c, sg);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      mfma_step(ks & 1);
-      constexpr int NLD = LA::NREG + LB::NREG;
-      constexpr int NDS = TM * (TA ? 2 : 1) + TN * (TB ? 2 : 1);
-      if (ks == 0) StepHint<0, TM * TN, (KSL > 1) ? NDS : 0, MORE ? NLD : 0, (MORE && KSL == 1) ? NLD : 0>::go();
-      else if (ks + 1 < KSL) StepHint<0, TM * TN, NDS, 0, 0>::go();
-      else StepHint<0, TM * TN, 0, 0, MORE ? NLD : 0>::go();
     }
     __syncthreads();
   };
-  for (int kt = 0; kt + 1 < nk; ++kt) tile(kt, std::true_type{});
-  if (nk > 0) tile(nk - 1, std::false_type{});
+  for (int kt = 0; kt + 2 < nk; ++kt) tile(kt, std::true_type{}, std::true_type{});
+  if (nk > 1) tile(nk - 2, std::true_type{}, std::false_type{});
+  if (nk > 0) tile(nk - 1, std::false_type{}, std::false_type{});
 
   if constexpr (KG > 1) {
     // the K loop ended with a barrier, so the operand tiles are dead: groups 1.. hand their accumulators to group 0,
@@ -301,7 +343,7 @@ int env_tile() {
 int choose_tile(int M, int N, bool plain_epilogue, int atomic_nk) {
   static const int bm[5] = {256, 256, 128, 128, 256}, bn[5] = {256, 128, 128, 64, 128};
   static const int per_cu[5] = {1, 2, 3, 5, 1};
-  static const double eff_full[5] = {1.0, 0.83, 0.7, 0.4, 0.75}, eff_single[5] = {1.0, 0.375, 0.25, 0.15, 0.75};
+  static const double eff_full[5] = {1.0, 0.7, 0.6, 0.4, 0.75}, eff_single[5] = {1.0, 0.375, 0.25, 0.15, 0.75};
   int best = 1;
   double best_cost = 1e300;
   for (int t = 0; t < (plain_epilogue ? 5 : 4); ++t) {
@@ -365,8 +407,9 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   // Reduction split: only for outputs that accumulate in fp32 (the merge is an atomic add), when the 256x256 tiling
   // would leave at least half of the CUs without work and every slice still gets a long K loop.
   a.splits = 1;
-  if (tile == 1 && a.epi == EPI_F32 && a.beta && env_splitk()) {
-    const long tiles = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+  if ((tile == 1 || tile == 5) && a.epi == EPI_F32 && a.beta && env_splitk()) {
+    const int bn = tile == 1 ? 256 : 128;
+    const long tiles = (long)((a.M + 255) / 256) * ((a.N + bn - 1) / bn);
     const int nk = (a.K + 63) / 64 + (a.K2 + 63) / 64;
     int sp = (int)(256 / tiles);
     while (sp > 1 && nk / sp < 16) --sp;
