@@ -216,14 +216,17 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
 #pragma unroll
     for (int j = 0; j < TN; ++j) bfr[buf][j] = read_frag<LDB, TB>(pb, j * 32, ks);
   };
-  auto mfma_step = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(af[buf][i], bfr[buf][j], acc[i][j]);
-  };
-
-  // STORE: tile kt+1 exists (its chunks are in the staging registers); LOAD: tile kt+2 exists.
+  // One K tile.  STORE: tile kt+1 exists (its chunks are in the staging registers); LOAD: tile kt+2 exists.
+  // The tile is a flat sequence of S = KSL * NM slots, one MFMA each, followed by that slot's share of the memory
+  // instructions, with a scheduling barrier so that the compiler keeps the order:
+  //   - the fragments of the next 16-deep step, one read per slot at the start of a step;
+  //   - the chunk rotations, spread evenly over slots 0 .. S-5;
+  //   - before slot S-4 the workgroup barrier: by then every wave has stored its chunks of tile kt+1 and has all its
+  //     fragments of tile kt in registers, so the first fragments of tile kt+1 are read under the last four MFMAs
+  //     and the next tile may overwrite this tile's buffer.
+  constexpr int NM = TM * TN, NF = TM + TN, S = KSL * NM, TAIL = 4;
+  static_assert(NF <= NM && KSL % 2 == 0 && NLD <= S - TAIL, "slot plan does not fit");
+  load_frags(0, sA0 + offA, sB0 + offB, ks0);
   auto tile = [&](int kt, auto store_tag, auto load_tag) {
     constexpr bool STORE = decltype(store_tag)::value, LOAD = decltype(load_tag)::value;
     const bf16* pa = ((kt & 1) ? sA1 : sA0) + offA;
@@ -231,35 +234,35 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
     bf16* const na = (kt & 1) ? sA0 : sA1;
     bf16* const nb = (kt & 1) ? sB0 : sB1;
     const Seg sg = seg_of(kt + 2);
-    load_frags(0, pa, pb, ks0);
-    // Every MFMA is followed by its share of the step's memory instructions -- one fragment read for the next step
-    // (front-loaded, so they have returned when the step ends) and the chunk rotations spread evenly -- and a
-    // scheduling barrier keeps the compiler from regrouping them.
-    constexpr int NM = TM * TN, NF = TM + TN;
-    static_assert(NF <= NM, "more fragments than MFMAs in a step");
 #pragma unroll
-    for (int ks = 0; ks < KSL; ++ks) {
-      const int cur = ks & 1, nxt = cur ^ 1;
-#pragma unroll
-      for (int I = 0; I < NM; ++I) {
-        acc[I / TN][I % TN] = mfma32(af[cur][I / TN], bfr[cur][I % TN], acc[I / TN][I % TN]);
-        if (ks + 1 < KSL && I < NF) {
-          if (I < TM) af[nxt][I] = read_frag<LDA, TA>(pa, I * 32, ks0 + ks + 1);
-          else bfr[nxt][I - TM] = read_frag<LDB, TB>(pb, (I - TM) * 32, ks0 + ks + 1);
-        }
-#pragma unroll
-        for (int c = (I * PER) / NM; c < ((I + 1) * PER) / NM; ++c) {
-          if constexpr (STORE) store_chunk(ks * PER + c, na, nb);
-          if constexpr (LOAD) load_chunk(ks * PER + c, sg);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    for (int sl = 0; sl < S; ++sl) {
+      const int ks = sl / NM, I = sl % NM, cur = ks & 1;
+      if (STORE && sl == S - TAIL) __syncthreads();
+      acc[I / TN][I % TN] = mfma32(af[cur][I / TN], bfr[cur][I % TN], acc[I / TN][I % TN]);
+      if (ks + 1 < KSL && I < NF) {
+        if (I < TM) af[cur ^ 1][I] = read_frag<LDA, TA>(pa, I * 32, ks0 + ks + 1);
+        else bfr[cur ^ 1][I - TM] = read_frag<LDB, TB>(pb, (I - TM) * 32, ks0 + ks + 1);
       }
+      if (STORE && sl >= S - TAIL) {   // first step of tile kt+1, from the other buffer, into the idle fragment set
+#pragma unroll
+        for (int f = ((sl - (S - TAIL)) * NF) / TAIL; f < ((sl - (S - TAIL) + 1) * NF) / TAIL; ++f) {
+          if (f < TM) af[0][f] = read_frag<LDA, TA>(na + offA, f * 32, ks0);
+          else bfr[0][f - TM] = read_frag<LDB, TB>(nb + offB, (f - TM) * 32, ks0);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < NLD; ++q)
+        if (((q + 1) * (S - TAIL)) / NLD - 1 == sl) {
+          if constexpr (STORE) store_chunk(q, na, nb);
+          if constexpr (LOAD) load_chunk(q, sg);
+        }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
   };
   for (int kt = 0; kt + 2 < nk; ++kt) tile(kt, std::true_type{}, std::true_type{});
   if (nk > 1) tile(nk - 2, std::true_type{}, std::false_type{});
   if (nk > 0) tile(nk - 1, std::false_type{}, std::false_type{});
+  __syncthreads();   // every wave is done with the operand tiles: the epilogue reuses the LDS
 
   if constexpr (KG > 1) {
     // the K loop ended with a barrier, so the operand tiles are dead: groups 1.. hand their accumulators to group 0,
