@@ -36,6 +36,21 @@ def algorithmic_flops(c):
     return layers, head
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc summary kept under profiles/ (FETCH_SIZE and WRITE_SIZE
+    scaled by a copy kernel of known size), or None when that summary has no line for this workload and kernel."""
+    path = os.path.join(ROOT, "profiles", "bench_%s_hbm_traffic.md" % workload)
+    try:
+        with open(path) as f:
+            for ln in f:
+                w = ln.split()
+                if len(w) >= 3 and w[0] == "traffic_bytes_per_launch" and w[1] == kernel:
+                    return float(w[2])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(c_full, sample_seq, seed):
     """The oracle as it stands (numpy fp32) on the same shapes with a shorter sequence; returns tokens/s and threads."""
     import numpy as np
@@ -67,7 +82,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--cpu-seq", type=int, default=512, help="sequence length of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-seq", type=int, default=2048, help="sequence length of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--no-upload-leg", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -159,6 +174,7 @@ def main():
         roofline = {"kernel": dname, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None, "launches_per_step": dn / tsteps,
                     "avg_launch_us": round(dms / dn * 1e3, 2)}
+    roofline["traffic"] = measured_traffic(args.config, dname)
     # class roll-ups against the targets: GEMMs and attention as fractions of the bf16 MFMA peak
     gemm_ms = sum(a[1] for k, a in agg.items() if k.startswith("gemm_"))
     gemm_fl = sum(a[2] for k, a in agg.items() if k.startswith("gemm_"))

@@ -4,15 +4,22 @@
 // such waves.  Two waves per SIMD keep the matrix pipeline fed: while one wave waits at a barrier, on LDS or on HBM,
 // the other one issues MFMAs.
 //
-//   256x256 (2x4 waves, K tile 64, the whole LDS of a CU), 256x128 (2x2), 128x128 (1x2), 128x64 (one wave; K tile 32)
+//   256x256 (2x4 waves, K tile 64, the whole LDS of a CU), 256x128 (2x2), 128x128 (1x2), 128x64 (one wave; K tile 32),
+//   256x128 with two groups of 2x2 waves (K tile 64)
 //
 // Operands are staged through registers (16-byte buffer loads; rows outside the matrix read as zero through the
-// descriptor, so the loop has no branch), LDS is double buffered (one barrier per K tile), the fragments of step k+1
-// are read while the MFMAs of step k run, the next tile's global loads are issued during the first step and its LDS
-// stores during the last (pinned with sched_group_barrier).  Measured on MI355X the 256x256 tile is bound by the
-// L2 -> CU fill bandwidth (128 FLOP per byte fetched), not by load latency: a variant with direct HBM -> LDS loads
-// and a four-deep ring was not faster.  GEMMs that accumulate into an fp32 output and would leave CUs idle are split
-// along the reduction and merged with fp32 atomics.
+// descriptor, so the loop has no branch) and LDS is double buffered.  The K loop is written slot by slot -- one MFMA
+// followed by that slot's share of memory instructions, pinned with scheduling barriers: the fragments of the next
+// 16-deep step are read at the start of a step; every 16-byte staging chunk rotates on its own (stored to LDS, then
+// reloaded with the tile after next), so that global loads and LDS stores arrive evenly instead of in bursts that
+// stall MFMA issue behind a full memory queue, and every load has a whole tile of time to return; the workgroup
+// barrier sits before the last four MFMAs of a tile and the first fragments of the next tile are read under them.
+// Measured on MI355X the 256x256 tile asks L2 for one byte per 128 FLOP; the chip runs power-limited near 1.8 GHz
+// under this kernel.  Tried and dropped: direct HBM -> LDS loads with a four-deep ring, touching lines two tiles
+// ahead to pull them into L2, staggered K-loop starts, a reduction split merged through scratch memory, a 128x128
+// wave tile with one wave per SIMD.  Outputs too small to fill the chip with 256x256 tiles use a 256x128 tile worked
+// on by two wave groups that split every K tile (merged through LDS); GEMMs that accumulate into an fp32 output and
+// would still leave CUs idle are split along the reduction and merged with fp32 atomics.
 //
 // Operands whose reduction index is not contiguous in memory (the weight in an activation-gradient GEMM, both operands
 // of a weight-gradient GEMM) keep their memory layout in LDS and are read with the transposing LDS load, so all
@@ -78,24 +85,6 @@ struct TileLoader {
   }
   RP_DEV void store_one(int it, const uint4& r, bf16* Sm) const {
     *reinterpret_cast<uint4*>(Sm + (row0 + it * RSTEP) * S::LDROW + ch * 8) = r;
-  }
-};
-
-// Scheduling hints for one 16-deep step of the K loop: after each of the NM MFMAs, its share of the step's NDS LDS
-// reads, NVM global loads and NDW LDS writes is pinned, so that memory instructions issue under the MFMA pipeline.
-template <int I, int NM, int NDS, int NVM, int NDW>
-struct StepHint {
-  static RP_DEV void go() {
-    if constexpr (I < NM) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      constexpr int ds = ((I + 1) * NDS) / NM - (I * NDS) / NM;
-      constexpr int vm = ((I + 1) * NVM) / NM - (I * NVM) / NM;
-      constexpr int dw = ((I + 1) * NDW) / NM - (I * NDW) / NM;
-      if constexpr (ds > 0) __builtin_amdgcn_sched_group_barrier(0x100, ds, 0);
-      if constexpr (dw > 0) __builtin_amdgcn_sched_group_barrier(0x200, dw, 0);   // a chunk is stored before it is reloaded
-      if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(0x020, vm, 0);
-      StepHint<I + 1, NM, NDS, NVM, NDW>::go();
-    }
   }
 };
 

@@ -31,6 +31,89 @@ def test_c1_chain_matches_oracle(hz):
     assert abs(ref["loss"] - np.log(c["vocab"])) < 0.5
 
 
+@pytest.mark.timeout(900)
+def test_c2_full_size_every_stage_call_matches_oracle(hz, capsys):
+    """The benchmark's workload at its full size and in the launch configuration bench.py times (Qwen3-1.7B-shaped
+    layers, 4096 tokens, vocabulary 151936, 256x256 GEMM tiles, 16384-row vocabulary chunks).  Every call is checked
+    against the oracle ON THE SAME INPUTS: the 4-layer forward produces the layer inputs, the head runs on the stage
+    output the GPU produced, and each layer's backward stage (recomputation + backward, one layer per call) gets the
+    GPU's own layer input and incoming gradient, so the bound applies to each call and not to a sum of their
+    errors.  The oracle runs in fp32 here (its fp64 run takes minutes; fp32 rounding is three orders of magnitude
+    below the bf16 bound)."""
+    from oracle import stage
+
+    def say(msg):                                  # a minute or two of work: say which part is running
+        with capsys.disabled():
+            print("[c2 full size] " + msg, flush=True)
+
+    c = synth.CONFIGS["C2"]
+    L, B_, S_ = c["n_layers"], c["batch"], c["seq"]
+    say("generating the workload")
+    wl = synth.make_workload(c, synth.config_seed("C2"))
+    ocfg = pu.oracle_cfg(c)
+    f32 = np.float32
+
+    say("HIP path: 4-layer forward, head")
+    cfg = hz.cfg_from_dict(c, with_head=True)
+    R = hz.StageRunner(cfg, B_, S_)
+    try:
+        R.upload(R.pinned_blob(wl["layers"], wl["head"]))
+        x = hz.bf16_tensor(wl["x"], R.device)
+        labels = torch.from_numpy(wl["labels"]).to(R.device)
+        torch.cuda.synchronize()
+        out, keep = R.forward(x, keep_layer_inputs=True)
+        loss, head_dx = R.head(out, labels, 1.0, train=True)
+        R.sync()
+        xs = [hz.to_f32(k) for k in keep]
+        out_np, head_dx_np, loss_v = hz.to_f32(out), hz.to_f32(head_dx), float(loss.item())
+        _, head_g = hz.unpack_grads(cfg, R.grads)
+    finally:
+        R.close()
+
+    errs = {}
+    say("oracle: head on the GPU's stage output")
+    ref_loss, ref_dx, ref_hg = stage.head_fwd_bwd(out_np, pu.cast_tree(wl["head"], f32), wl["labels"], ocfg, 1.0, want_dW=True)
+    errs["loss"] = abs(loss_v - float(ref_loss)) / abs(float(ref_loss))
+    errs["head_dx"] = pu.rel_l2(head_dx_np, ref_dx)
+    for k, v in ref_hg.items():
+        errs["head." + k] = pu.rel_l2(head_g[k], v)
+    del ref_dx, ref_hg, head_g
+
+    c1 = dict(c, n_layers=1, vocab=0)
+    cfg1 = hz.cfg_from_dict(c1, with_head=False)
+    ocfg1 = pu.oracle_cfg(c1)
+    dy_np = head_dx_np
+    for l in reversed(range(L)):
+        say("layer %d: HIP backward stage, oracle" % l)
+        R1 = hz.StageRunner(cfg1, B_, S_)
+        try:
+            R1.upload(R1.pinned_blob([wl["layers"][l]]))
+            xl, dyl = hz.bf16_tensor(xs[l], R1.device), hz.bf16_tensor(dy_np, R1.device)
+            torch.cuda.synchronize()
+            o_l, dx_l = R1.backward(xl, dyl)
+            R1.sync()
+            g_l, _ = hz.unpack_grads(cfg1, R1.grads)
+            o_np, dx_np = hz.to_f32(o_l), hz.to_f32(dx_l)
+        finally:
+            R1.close()
+        r_out, r_dx, r_g = stage.stage_fwd_bwd(xs[l], dy_np, [pu.cast_tree(wl["layers"][l], f32)], ocfg1, B_, S_)
+        errs["L%d.out" % l] = pu.rel_l2(o_np, r_out)
+        errs["L%d.dx" % l] = pu.rel_l2(dx_np, r_dx)
+        for k, v in r_g[0].items():
+            if k != "lora":
+                errs["L%d.%s" % (l, k)] = pu.rel_l2(g_l[0][k], v)
+        # the stage output of layer l must be the next layer's input (or the stage output) of the 4-layer call
+        nxt = xs[l + 1] if l + 1 < L else out_np
+        assert np.array_equal(o_np, nxt), "layer %d: single-layer and 4-layer calls disagree" % l
+        dy_np = dx_np
+    worst = max((v, k) for k, v in errs.items() if k != "loss")
+    say("worst relative error %.2e (%s), loss error %.1e" % (worst + (errs["loss"],)))
+    assert len(errs) == 4 + L * 13, sorted(errs)
+    bad = {k: v for k, v in errs.items() if not v <= (1e-4 if k == "loss" else 2e-2)}
+    assert not bad, "parity violations: %s\nall: %s" % (bad, errs)
+    assert abs(loss_v - np.log(c["vocab"])) < 0.5
+
+
 VARIANTS = {
     # ragged token count, every adapter on, frozen base, random gains
     "lora_all_frozen_ragged": dict(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=688, vocab=0,
