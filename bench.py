@@ -28,7 +28,8 @@ def algorithmic_flops(c):
     T, s, b = c["batch"] * c["seq"], c["seq"], c["batch"]
     h, d, m, V = c["hidden"], c["head_dim"], c["ffn"], c["vocab"]
     qd, kd = c["n_q_heads"] * d, c["n_kv_heads"] * d
-    gemm_fwd = 2.0 * T * (h * (qd + 2 * kd) + qd * h + h * 2 * m + m * h)
+    ffn_rows = T * c["top_k"] if c["n_experts"] else T     # every token runs top_k experts of width m
+    gemm_fwd = 2.0 * T * (h * (qd + 2 * kd) + qd * h) + 2.0 * ffn_rows * (h * 2 * m + m * h)
     attn_fwd = 2.0 * b * s * s * qd
     wgrad = 1.0 if c["train_base"] else 0.0
     layers = c["n_layers"] * (gemm_fwd * (2.0 + wgrad) + attn_fwd * 3.5)
@@ -98,25 +99,33 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     c = synth.CONFIGS[args.config]
-    assert c["n_experts"] == 0, "MoE stages are not implemented"
     seed = synth.config_seed(args.config)
-    t_gen = time.perf_counter()
+
+    def say(msg):          # progress on stderr: generating the larger workloads takes a while
+        print("[bench %s] %s" % (args.config, msg), file=sys.stderr, flush=True)
+
+    say("generating the synthetic workload on the host")
     wl = synth.make_workload(c, seed)
-    t_gen = time.perf_counter() - t_gen
     has_head = wl["head"] is not None
     cfg = H.cfg_from_dict(c, with_head=has_head)
     R = H.StageRunner(cfg, c["batch"], c["seq"], n_slots=2)
+    say("packing the weight blob (%.2f GB, pinned)" % (R.wbytes / 1e9))
     host = R.pinned_blob(wl["layers"], wl["head"])
     wl["layers"] = None
     wl["head"] = None
     x = H.bf16_tensor(wl["x"], R.device)
     dy_in = H.bf16_tensor(wl["dy"], R.device)
     labels = torch.from_numpy(wl["labels"]).to(R.device) if has_head else None
+    router = None
+    if wl.get("router_logits") is not None:
+        router = torch.from_numpy(np.stack(wl["router_logits"])).to(R.device)
+    d_router = torch.empty_like(router) if router is not None else None
     out = torch.empty_like(x)
     dx = torch.empty_like(x)
     dy_head = torch.empty_like(x)
     loss_buf = torch.empty(1, dtype=torch.float32, device=R.device)
     torch.cuda.synchronize()
+    say("uploading %.2f GB of weights" % (R.wbytes / 1e9))
     R.upload(host, slot=0)
     R.sync()
     T = R.T
@@ -128,10 +137,11 @@ def main():
             loss, dy = R.head(out, labels, 1.0, slot, loss=loss_buf, dx=dy_head)
             R.backward_only(x, dy, dx, slot)
             return loss
-        B.rp_stage_backward(R.ctx, slot, B.PHASE_BOTH, x, dy_in, dx, out, R.grads if R.gbytes else None, None, None,
+        B.rp_stage_backward(R.ctx, slot, B.PHASE_BOTH, x, dy_in, dx, out, R.grads if R.gbytes else None, router, d_router,
                             R.batch, R.seq, R.ws, R.wsbytes)
         return None
 
+    say("warm-up and timed steps")
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -211,7 +221,8 @@ def main():
 
     cpu = None
     if args.cpu_seq > 0:
-        cpu = cpu_baseline(c, args.cpu_seq, seed)
+        say("CPU oracle sample")
+        cpu = cpu_baseline(c, min(args.cpu_seq, c["seq"]), seed)
 
     tot_fl = fl_layers + fl_head
     line = {
@@ -219,9 +230,11 @@ def main():
         "value": round(T / (ms_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "%s: %d Qwen3-shaped decoder layers (h=%d, %d/%d heads x %d, ffn %d)%s, batch %d x seq %d, "
+        "config": {"workload": "%s: %d Qwen3-shaped decoder layers (h=%d, %d/%d heads x %d, ffn %d%s)%s, batch %d x seq %d, "
                                "%s" % (args.config, c["n_layers"], c["hidden"], c["n_q_heads"], c["n_kv_heads"],
-                                       c["head_dim"], c["ffn"], " + LM head V=%d with cross-entropy" % c["vocab"] if has_head else "",
+                                       c["head_dim"], c["ffn"],
+                                       " x %d experts, top-%d" % (c["n_experts"], c["top_k"]) if c["n_experts"] else "",
+                                       " + LM head V=%d with cross-entropy" % c["vocab"] if has_head else "",
                                        c["batch"], c["seq"],
                                        "full fine-tune, fp32 weight gradients" if c["train_base"] else "frozen base, LoRA r=%d" % c["lora_rank"]),
                    "tokens_per_step": T, "weights_resident_in_hbm": True},

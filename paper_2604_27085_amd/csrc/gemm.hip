@@ -43,7 +43,8 @@ struct TileLoader {
   uint32_t kstep;
   int row0, ch;
 
-  RP_DEV void init(long ld, int x0, int Xdim, int tid) {
+  // row_map (only for operands whose rows are the tile rows): row gx is read from row row_map[gx] of the buffer.
+  RP_DEV void init(long ld, int x0, int Xdim, int tid, const int* row_map = nullptr) {
     row0 = tid / S::CH;
     ch = tid % S::CH;
     kstep = TR ? (uint32_t)ld * 2u : 2u;
@@ -52,7 +53,8 @@ struct TileLoader {
       const int row = row0 + it * RSTEP;
       if constexpr (!TR) {
         const int gx = x0 + row;
-        voff[it] = gx < Xdim ? (uint32_t)((long)gx * ld + ch * 8) * 2u : OOB;
+        const long src = (row_map && gx < Xdim) ? row_map[gx] : gx;
+        voff[it] = gx < Xdim ? (uint32_t)(src * ld + ch * 8) * 2u : OOB;
       } else {
         const int gx = x0 + ch * 8;
         voff[it] = gx < Xdim ? (uint32_t)((long)row * ld + gx) * 2u : OOB;
@@ -127,9 +129,22 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   const int wm = wmn / WGN, wn = wmn % WGN;
   const int ks0 = kg * KSL;
 
-  int tile_m, tile_n;
-  tile_of_block(p.M, p.N, BM, BN, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  int tile_m, tile_n, m0, Mlim = p.M;
+  const bf16* Bbase = static_cast<const bf16*>(p.B);
+  if (p.grp_tab) {   // uniform over the grid
+    const int tiles_n = (p.N + BN - 1) / BN;
+    tile_m = (int)blockIdx.x / tiles_n;
+    tile_n = (int)blockIdx.x % tiles_n;
+    if (tile_m >= *p.grp_ntiles) return;
+    const int4 g = p.grp_tab[tile_m];
+    m0 = g.y;
+    Mlim = g.y + g.z;
+    Bbase += (long)g.x * p.grp_strideB;
+  } else {
+    tile_of_block(p.M, p.N, BM, BN, tile_m, tile_n);
+    m0 = tile_m * BM;
+  }
+  const int n0 = tile_n * BN;
   const int nk1 = (p.K + BK - 1) / BK;
   const int nk_all = nk1 + (p.K2 + BK - 1) / BK;
   // split along the reduction: slice blockIdx.y takes K tiles [kt0, kt0 + nk)
@@ -139,9 +154,9 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
 
   LA la, la2;
   LB lb, lb2;
-  la.init(p.lda, m0, p.M, tid);
+  la.init(p.lda, m0, Mlim, tid, TA ? nullptr : p.row_map);
   lb.init(p.ldb, n0, p.N, tid);
-  const rsrc_t rsA = make_rsrc(p.A, p.bytesA), rsB = make_rsrc(p.B, p.bytesB);
+  const rsrc_t rsA = make_rsrc(p.A, p.bytesA), rsB = make_rsrc(Bbase, p.bytesB);
   rsrc_t rsA2 = rsA, rsB2 = rsB;
   la2 = la;
   lb2 = lb;
@@ -281,7 +296,7 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
       return;
     }
   }
-  epilogue(p, acc, smem, wmn, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
+  epilogue(p, Mlim, acc, smem, wmn, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
 }
 
 template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1>
@@ -294,7 +309,8 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& a) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  const int tiles = ((a.M + C::BM - 1) / C::BM) * ((a.N + C::BN - 1) / C::BN);
+  int tiles = ((a.M + C::BM - 1) / C::BM) * ((a.N + C::BN - 1) / C::BN);
+  if (a.grp_tab) tiles = a.grp_max_tiles * ((a.N + C::BN - 1) / C::BN);
   RP_LAUNCH(kern, dim3(tiles, a.splits > 0 ? a.splits : 1), dim3(C::NTHR), C::SMEM, st, a);
   return hipGetLastError();
 }
@@ -395,7 +411,15 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   a.bytesB2 = tb ? extent_bytes(a.K2, a.N, a.ldb2) : extent_bytes(a.N, a.K2, a.ldb2);
   // operands are addressed with 32-bit byte offsets
   if (a.bytesA == ~0u || a.bytesB == ~0u || a.bytesA2 == ~0u || a.bytesB2 == ~0u) return hipErrorInvalidValue;
-  const int tile = gemm_pick_tile(a, tile_hint);
+  int tile = gemm_pick_tile(a, tile_hint);
+  if (a.grp_tab) {   // grouped: 256-row tiles as in the table, rows of A are tile rows, one operand pair
+    if (ta || a.K2 || !a.grp_ntiles || a.grp_max_tiles <= 0 || (a.epi != EPI_BF16 && a.epi != EPI_F32)) return hipErrorInvalidValue;
+    tile = 1;
+    if (a.row_map) {
+      a.bytesA = extent_bytes(a.row_map_rows, a.K, a.lda);
+      if (a.bytesA == ~0u || a.row_map_rows <= 0) return hipErrorInvalidValue;
+    }
+  }
   // Reduction split: only for outputs that accumulate in fp32 (the merge is an atomic add), when the 256x256 tiling
   // would leave at least half of the CUs without work and every slice still gets a long K loop.
   a.splits = 1;

@@ -35,6 +35,13 @@ struct GemmArgs {
   int row_offset;              // global vocab index of row 0 of A
   // byte extents of the four operands (filled in by gemm_launch; rows beyond them read as zero)
   unsigned bytesA, bytesB, bytesA2, bytesB2;
+  // Grouped mode (mixture of experts): the rows of A and C are sorted by group, every group multiplies with its own B.
+  // grp_tab[i] = {group, first row, rows (<= 256), 0} for the i-th 256-row tile, *grp_ntiles of them (device memory:
+  // the grid is sized for grp_max_tiles and surplus workgroups exit); B of group g starts grp_strideB elements after
+  // B.  row_map (optional): row r of A is read from row row_map[r] of the A buffer (gather fused into the loads).
+  // 256x256 tiles, NT or NN, no second operand pair.
+  const int4* grp_tab; const int* grp_ntiles; int grp_max_tiles; long grp_strideB; const int* row_map;
+  int row_map_rows;            // rows of the A buffer that row_map indexes
   int splits;                  // reduction slices (grid.y), chosen by gemm_launch
   int part_row0;               // first partial row this launch writes (2 per M tile)
 };

@@ -91,8 +91,9 @@ RP_DEV void epilogue_barriers(const GemmArgs& p) {
 // left corner is (wrow0, wcol0).  Every wave stages its block through its own 18 KB of LDS (all waves must have
 // finished the K loop) so that global accesses are 16 bytes per lane and cover whole 128-byte lines.
 // part_row: row of the cross-entropy partial array this wave writes (EPI_CE_STATS).
-RP_DEV void epilogue(const GemmArgs& p, const f32x16 (&acc)[TM][TN], unsigned char* smem, int wave, int lane, int wrow0,
-                     int wcol0, int part_row) {
+// M: rows of C that exist (the end of the group's rows in grouped mode).
+RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsigned char* smem, int wave, int lane,
+                     int wrow0, int wcol0, int part_row) {
   const int lr = lane & 31, lk = lane >> 5;
   unsigned char* const stg = smem + wave * STG_BYTES;
   const int rr = lane >> 3, cc = lane & 7;   // read-back: 8 rows per pass, 8 chunks of 16 bytes per row
@@ -132,7 +133,7 @@ RP_DEV void epilogue(const GemmArgs& p, const f32x16 (&acc)[TM][TN], unsigned ch
 #pragma unroll
     for (int t = 0; t < WAVE_M / 8; ++t) {
       const int row = t * 8 + rr, grow = wrow0 + row;
-      if (grow < p.M && gcol < p.N)
+      if (grow < M && gcol < p.N)
         *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + gcol) = *reinterpret_cast<const uint4*>(s16 + row * STG_LD + cc * 8);
     }
   } else if (p.epi == EPI_BF16 || p.epi == EPI_F32) {
@@ -150,7 +151,7 @@ RP_DEV void epilogue(const GemmArgs& p, const f32x16 (&acc)[TM][TN], unsigned ch
 #pragma unroll
       for (int t = 0; t < WAVE_M / 8; ++t) {
         const int row = t * 8 + rr, grow = wrow0 + row;
-        if (grow < p.M && gcol < p.N) {
+        if (grow < M && gcol < p.N) {
           float4 x = *reinterpret_cast<const float4*>(s32 + row * (STG_LD / 2) + cc * 4);
           if (p.epi == EPI_F32) {
             float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (long)grow * p.ldc + gcol);
@@ -176,7 +177,7 @@ RP_DEV void epilogue(const GemmArgs& p, const f32x16 (&acc)[TM][TN], unsigned ch
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-          if (row < p.M) atomicAdd(Cp + (long)row * p.ldc + col, p.alpha * acc[i][j][v]);
+          if (row < M) atomicAdd(Cp + (long)row * p.ldc + col, p.alpha * acc[i][j][v]);
         }
     }
   } else if (p.epi == EPI_CE_STATS) {
@@ -192,7 +193,7 @@ RP_DEV void epilogue(const GemmArgs& p, const f32x16 (&acc)[TM][TN], unsigned ch
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-          if (row < p.M) {
+          if (row < M) {
             mx = fmaxf(mx, acc[i][j][v]);
             if (row == lab) p.zlab[col] = acc[i][j][v];
           }
@@ -205,7 +206,7 @@ RP_DEV void epilogue(const GemmArgs& p, const f32x16 (&acc)[TM][TN], unsigned ch
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-            if (row < p.M) s += __expf(acc[i][j][v] - mx);
+            if (row < M) s += __expf(acc[i][j][v] - mx);
           }
       }
       s += __shfl_xor(s, 32, 64);

@@ -45,6 +45,25 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
                       const float* delta, void* dq, void* dk, void* dv, float* scratch, long ldq, long ldk, long ldv,
                       long lddo, long lddq, long lddk, long lddv, int batch, int seq, int a, int kh, int d);
 
+// Mixture-of-experts FFN, everything but the grouped GEMMs.  Entries are (token, choice) pairs, i = t*top_k + j; slots
+// are the same entries sorted by expert (stable).
+// idx [T, top_k] = experts with the largest logits (descending, ties -> lower index), w = softmax over those logits.
+hipError_t k_moe_route(hipStream_t st, const float* logits, int* idx, float* w, int T, int E, int top_k);
+// counts [E], seg [E+1] (first slot of every expert), tile_tab (int4 {expert, first row, rows, 0} per 256-row tile, at
+// most T*top_k/256 + E of them), *ntiles, slot_of [T*top_k], row_tok [T*top_k] (token of every slot).
+hipError_t k_moe_plan(hipStream_t st, const int* idx, int T, int E, int top_k, int* counts, int* seg, void* tile_tab,
+                      int* ntiles, int* slot_of, int* row_tok);
+// out[t] = (res[t] if res) + sum_j (w[t,j] if w else 1) * src[slot_of[t,j]];  src bf16 [T*top_k, h], out bf16 [T, h].
+hipError_t k_moe_combine(hipStream_t st, const void* src, const int* slot_of, const float* w, const void* res, void* out,
+                         int T, int h, int top_k);
+hipError_t k_moe_scatter_w(hipStream_t st, const float* w, const int* slot_of, float* w_slot, long n);
+// dw_slot[r] = <dact[r], swiglu(gu[r])>;  dgu[r] = swiglu backward of w_slot[r] * dact[r].
+hipError_t k_moe_swiglu_bwd(hipStream_t st, const void* dact, const void* gu, const float* w_slot, void* dgu, float* dw_slot,
+                            long rows, int m);
+// dlogits [T, E] = w_te (dw_te - sum_e' w_te' dw_te') on the selected experts, 0 elsewhere.
+hipError_t k_moe_dlogits(hipStream_t st, const int* idx, const float* w, const int* slot_of, const float* dw_slot,
+                         float* dlogits, long T, int E, int top_k);
+
 // Cross-entropy helpers.  part [P, T] (max, sumexp) partials -> lse[T]; then loss / coef from lse, label logits, labels.
 hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, float* lse, int T);
 hipError_t k_ce_finalize(hipStream_t st, const float* lse, const float* zlab, const int* labels, float grad_scale,

@@ -88,13 +88,20 @@ inline BlobLayout blob_layout(const rp_stage_cfg& c, bool grads) {
 
 // ---- workspace plan ---------------------------------------------------------------------------------------------
 struct LayerBuf {   // byte offsets of one layer's saved internals
-  size_t z, rstd1, n1, qkv, rstd_q, rstd_k, qr, kr, o, lse, y, rstd2, n2, gu, act, u1, u2, u3, u4, end;
+  size_t z, rstd1, n1, qkv, rstd_q, rstd_k, qr, kr, o, lse, y, rstd2, n2, gu, act, u1, u2, u3, u4;
+  // mixture of experts: routing (expert and weight per (token, choice)), the slot of every entry, the token of every
+  // slot, per-expert counts and first slots, the tile table of the grouped GEMMs and its length
+  size_t m_idx, m_w, m_slot, m_tok, m_cnt, m_seg, m_tab, m_ntiles;
+  size_t end;
 };
 
 struct Plan {
   size_t rope, bd1, bd3;                          // RoPE table, block-diagonal LoRA B of the fused GEMMs
   size_t layer0, layer_stride;                    // saved internals, one set per layer (backward) or one set (forward)
   size_t tA, tB, dact, dgu, dn, dout, dqr, dkr, dqkv, delta, ud, partials;   // backward temporaries
+  size_t moe_f_fwd, moe_f_bwd;   // expert outputs / expert input gradients per slot [T*top_k, h] (transient in a layer)
+  size_t moe_wslot, moe_dw;      // routing weight per slot, its gradient per slot (backward)
+  int moe_max_tiles;             // capacity of the tile table
   size_t dkvp;   // per-query-head dK/dV partials of grouped attention; shares memory with dact|dgu, dead by then
   size_t fwd_bytes, bwd_bytes;
   // head
@@ -114,9 +121,18 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   b.z = take(T * D.h * 2); b.rstd1 = take(T * 4); b.n1 = take(T * D.h * 2); b.qkv = take(T * D.n1 * 2);
   b.rstd_q = take(T * D.a * 4); b.rstd_k = take(T * D.kh * 4); b.qr = take(T * D.qd * 2); b.kr = take(T * D.kd * 2);
   b.o = take(T * D.qd * 2); b.lse = take(T * D.a * 4); b.y = take(T * D.h * 2); b.rstd2 = take(T * 4);
-  b.n2 = take(T * D.h * 2); b.gu = take(T * 2 * D.m * 2); b.act = take(T * D.m * 2);
+  // with experts, gate/up and act hold one row per (token, choice), sorted by expert
+  const size_t Tk = D.E > 0 ? T * (size_t)D.topk : T;
+  const size_t max_tiles = Tk / 256 + (size_t)(D.E > 0 ? D.E : 0) + 1;
+  P.moe_max_tiles = (int)max_tiles;
+  b.n2 = take(T * D.h * 2); b.gu = take(Tk * 2 * D.m * 2); b.act = take(Tk * D.m * 2);
   b.u1 = take(T * (size_t)(D.n_qkv * D.r) * 2); b.u2 = take(T * (size_t)D.r * 2);
   b.u3 = take(T * (size_t)(D.n_gu * D.r) * 2); b.u4 = take(T * (size_t)D.r * 2);
+  if (D.E > 0) {
+    b.m_idx = take(Tk * 4); b.m_w = take(Tk * 4); b.m_slot = take(Tk * 4); b.m_tok = take(Tk * 4);
+    b.m_cnt = take((size_t)D.E * 4); b.m_seg = take((size_t)(D.E + 1) * 4); b.m_tab = take(max_tiles * 16);
+    b.m_ntiles = take(4);
+  }
   b.end = o;
   const size_t set = o;
   o = 0;
@@ -129,10 +145,12 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   {
     size_t f = o + set;
     f = align_up(f + T * D.h * 2, 256);
+    if (D.E > 0) { P.moe_f_fwd = f; f = align_up(f + Tk * D.h * 2, 256); }
     P.fwd_bytes = f;
   }
   o += set * (size_t)(D.L > 0 ? D.L : 0);
-  P.tA = take(T * D.h * 2); P.tB = take(T * D.h * 2); P.dact = take(T * D.m * 2); P.dgu = take(T * 2 * D.m * 2);
+  P.tA = take(T * D.h * 2); P.tB = take(T * D.h * 2); P.dact = take(Tk * D.m * 2); P.dgu = take(Tk * 2 * D.m * 2);
+  if (D.E > 0) { P.moe_f_bwd = take(Tk * D.h * 2); P.moe_wslot = take(Tk * 4); P.moe_dw = take(Tk * 4); }
   P.dkvp = P.dact;
   if (D.a != D.kh && P.dkvp + 2 * T * D.qd * 4 > o) take(P.dkvp + 2 * T * D.qd * 4 - o);
   P.dn = take(T * D.h * 2); P.dout = take(T * D.qd * 2); P.dqr = take(T * D.qd * 2); P.dkr = take(T * D.kd * 2);

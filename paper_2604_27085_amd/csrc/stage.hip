@@ -83,6 +83,9 @@ rp_status validate_cfg(const rp_stage_cfg* c, rp_ctx* ctx) {
     if (c->lora_rank < 0 || c->lora_rank % 8 || c->lora_rank > 64) return fail(ctx, RP_EUNSUPPORTED, "lora_rank must be a multiple of 8, at most 64");
     if (c->lora_mask >> 7) return fail(ctx, RP_EINVAL, "lora_mask has unknown bits");
     if (c->n_experts < 0 || c->top_k < 0 || (c->n_experts > 0 && (c->top_k <= 0 || c->top_k > c->n_experts))) return fail(ctx, RP_EINVAL, "bad n_experts/top_k");
+    if (c->n_experts > 1024 || c->top_k > 64) return fail(ctx, RP_EUNSUPPORTED, "at most 1024 experts and top_k 64");
+    if (c->n_experts > 0 && c->train_base) return fail(ctx, RP_EUNSUPPORTED, "expert weights are frozen in this build: train_base must be 0 for MoE stages");
+    if (c->n_experts > 0 && c->lora_rank > 0 && (c->lora_mask & (RP_LORA_GATE | RP_LORA_UP | RP_LORA_DOWN))) return fail(ctx, RP_EUNSUPPORTED, "LoRA on expert projections is not implemented");
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 1.f)) return fail(ctx, RP_EINVAL, "bad rms_eps / rope_base");
   }
   return RP_OK;
@@ -117,6 +120,8 @@ struct Exec {
   Plan P;
   hipError_t err = hipSuccess;
   const char* where = "";
+  const float* router = nullptr;   // router logits of the layer being run, fp32 [T, E] (mixture of experts)
+  float* d_router = nullptr;       // their gradient (optional)
 
   void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
   // Called right before an op is enqueued when the timeline is on: records the op's start event and its cost model.
@@ -150,6 +155,26 @@ struct Exec {
     g.A2 = A2; g.lda2 = lda2; g.B2 = B2; g.ldb2 = ldb2; g.K2 = K2; g.R = R; g.ldr = ldr; g.epi = EPI_BF16;
     mark_gemm(layout, g);
     chk(gemm_launch(st, layout, g), "gemm_bf16");
+  }
+  // Grouped GEMM over expert-sorted slot rows: C[slot, N] = A[row_map ? row_map[slot] : slot, K] * op(B_e), B_e the
+  // matrix of the expert that owns the slot.  set = the layer's saved internals (routing plan).
+  void gemm_grouped(int layout, const char* set, const void* A, long lda, int a_rows, bool gather, const void* B, long ldb,
+                    long strideB, void* C, long ldc, int N, int K) {
+    GemmArgs g; gemm_zero_args(g);
+    const long Tk = T * D.topk;
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = (int)Tk; g.N = N; g.K = K; g.epi = EPI_BF16;
+    g.grp_tab = reinterpret_cast<const int4*>(set + P.lb.m_tab);
+    g.grp_ntiles = reinterpret_cast<const int*>(set + P.lb.m_ntiles);
+    g.grp_max_tiles = P.moe_max_tiles;
+    g.grp_strideB = strideB;
+    if (gather) { g.row_map = reinterpret_cast<const int*>(set + P.lb.m_tok); g.row_map_rows = a_rows; }
+    if (ctx->tracing) {
+      char nm[40];
+      snprintf(nm, sizeof(nm), "gemm_grouped_%s", layout == GEMM_NT ? "NT" : "NN");
+      // every expert's weights are read once; rows as in the dense case
+      mark(nm, 2.0 * Tk * (double)N * K, 2.0 * ((double)Tk * K + (double)D.E * N * K) + 2.0 * Tk * (double)N);
+    }
+    chk(gemm_launch(st, layout, g), "gemm_grouped");
   }
   // C[M,N] (fp32) (+)= A^T * B : weight-gradient form, reduction over the rows of A and B
   void gemm_wgrad(const void* A, long lda, const void* B, long ldb, float* C, long ldc, int M, int N, int K) {
@@ -233,7 +258,8 @@ void linear_bwd(Exec& X, const LayerW& W, const LayerG& G, int w_id, const Fused
   }
 }
 
-void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z) {
+// moe_f_off: workspace offset of the per-slot expert output buffer of the plan in use (forward or backward stage).
+void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z, size_t moe_f_off) {
   const Dims& D = X.D;
   const LayerBuf& b = X.P.lb;
   const rp_stage_cfg& c = X.ctx->cfg;
@@ -254,6 +280,24 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z) 
                  X.seq, D.a, D.kh, D.d));
   linear_fwd(X, W, RP_T_WO, fused_single(D.lora[3], RP_T_LA_O, RP_T_LB_O, D.h), 0, S(b.o), D.qd, S(b.y), D.h, S(b.u2), x);
   RUN(X, "rmsnorm_fwd", 0, 4.0 * Td * D.h, k_rmsnorm_fwd(X.st, S(b.y), W.t(RP_T_G2), S(b.n2), (float*)S(b.rstd2), T, D.h, c.rms_eps));
+  if (D.E > 0) {
+    // top-k mixture of experts (App. B.2, MoE layer): route, sort the (token, choice) entries by expert, run the
+    // experts' gate/up and down projections as grouped GEMMs over the sorted rows, weighted sum per token + residual
+    const long Tk = (long)T * D.topk;
+    const double Tkd = (double)Tk;
+    int* idx = (int*)S(b.m_idx);
+    float* w = (float*)S(b.m_w);
+    int* slot_of = (int*)S(b.m_slot);
+    void* f = X.at<void>(moe_f_off);
+    RUN(X, "moe_route", 0, 4.0 * Td * D.E + 8.0 * Tkd, k_moe_route(X.st, X.router, idx, w, T, D.E, D.topk));
+    RUN(X, "moe_plan", 0, 8.0 * Tkd * D.E, k_moe_plan(X.st, idx, T, D.E, D.topk, (int*)S(b.m_cnt), (int*)S(b.m_seg), S(b.m_tab),
+                                                     (int*)S(b.m_ntiles), slot_of, (int*)S(b.m_tok)));
+    X.gemm_grouped(GEMM_NT, set, S(b.n2), D.h, T, true, W.t(RP_T_WGU), D.h, (long)2 * D.m * D.h, S(b.gu), 2 * D.m, 2 * D.m, D.h);
+    RUN(X, "swiglu_fwd", 0, 6.0 * Tkd * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), Tk, D.m));
+    X.gemm_grouped(GEMM_NT, set, S(b.act), D.m, (int)Tk, false, W.t(RP_T_WD), D.m, (long)D.h * D.m, f, D.h, D.h, D.m);
+    RUN(X, "moe_combine", 0, 2.0 * Tkd * D.h + 4.0 * Td * D.h, k_moe_combine(X.st, f, slot_of, w, S(b.y), z, T, D.h, D.topk));
+    return;
+  }
   linear_fwd(X, W, RP_T_WGU, fused_gu(D), X.P.bd3, S(b.n2), D.h, S(b.gu), 2 * D.m, S(b.u3), nullptr);
   RUN(X, "swiglu_fwd", 0, 6.0 * Td * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), T, D.m));
   linear_fwd(X, W, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, S(b.act), D.m, z, D.h, S(b.u4), S(b.y));
@@ -270,12 +314,35 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
   bf16_t* dqkv = X.at<bf16_t>(X.P.dqkv);
   void* dy = X.at<void>(X.P.tA);
 
-  // z = y + down(act)
-  linear_bwd(X, W, G, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, dz, D.h, S(b.act), D.m,
-             X.at<void>(X.P.dact), S(b.u4));
   const double Td = (double)T;
-  RUN(X, "swiglu_bwd", 0, 10.0 * Td * D.m, k_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), X.at<void>(X.P.dgu), T, D.m));
-  linear_bwd(X, W, G, RP_T_WGU, fused_gu(D), X.P.bd3, X.at<void>(X.P.dgu), 2 * D.m, S(b.n2), D.h, X.at<void>(X.P.dn), S(b.u3));
+  if (D.E > 0) {
+    // z = y + sum_j w_j FFN_ej(n2): per slot dact = Wd_e^T dz_t (the routing weight is applied inside the SwiGLU
+    // backward, which also yields dw = <dact, act>), dgu, then the expert input gradients summed per token
+    const long Tk = (long)T * D.topk;
+    const double Tkd = (double)Tk;
+    const int* idx = (const int*)S(b.m_idx);
+    const float* w = (const float*)S(b.m_w);
+    const int* slot_of = (const int*)S(b.m_slot);
+    float* w_slot = X.at<float>(X.P.moe_wslot);
+    float* dw_slot = X.at<float>(X.P.moe_dw);
+    void* dxp = X.at<void>(X.P.moe_f_bwd);
+    X.gemm_grouped(GEMM_NN, set, dz, D.h, T, true, W.t(RP_T_WD), D.m, (long)D.h * D.m, X.at<void>(X.P.dact), D.m, D.m, D.h);
+    RUN(X, "moe_scatter_w", 0, 12.0 * Tkd, k_moe_scatter_w(X.st, w, slot_of, w_slot, Tk));
+    RUN(X, "moe_swiglu_bwd", 0, 10.0 * Tkd * D.m,
+        k_moe_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), w_slot, X.at<void>(X.P.dgu), dw_slot, Tk, D.m));
+    if (X.d_router)
+      RUN(X, "moe_dlogits", 0, 4.0 * Td * D.E + 12.0 * Tkd, k_moe_dlogits(X.st, idx, w, slot_of, dw_slot, X.d_router, T, D.E, D.topk));
+    X.gemm_grouped(GEMM_NN, set, X.at<void>(X.P.dgu), 2 * D.m, (int)Tk, false, W.t(RP_T_WGU), D.h, (long)2 * D.m * D.h, dxp, D.h,
+                   D.h, 2 * D.m);
+    RUN(X, "moe_combine", 0, 2.0 * Tkd * D.h + 2.0 * Td * D.h,
+        k_moe_combine(X.st, dxp, slot_of, nullptr, nullptr, X.at<void>(X.P.dn), T, D.h, D.topk));
+  } else {
+    // z = y + down(act)
+    linear_bwd(X, W, G, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, dz, D.h, S(b.act), D.m,
+               X.at<void>(X.P.dact), S(b.u4));
+    RUN(X, "swiglu_bwd", 0, 10.0 * Td * D.m, k_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), X.at<void>(X.P.dgu), T, D.m));
+    linear_bwd(X, W, G, RP_T_WGU, fused_gu(D), X.P.bd3, X.at<void>(X.P.dgu), 2 * D.m, S(b.n2), D.h, X.at<void>(X.P.dn), S(b.u3));
+  }
   RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
       k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, S(b.y), W.t(RP_T_G2), (const float*)S(b.rstd2), dz, dy, G.t(RP_T_G2), X.at<float>(X.P.partials), T, D.h));
   // y = x + o_proj(o)
@@ -456,8 +523,7 @@ rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_o
                            const float* router_logits, int batch, int seq, void* workspace, size_t workspace_bytes_in) {
   if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
   if (ctx->cfg.n_layers == 0) return fail(ctx, RP_EINVAL, "stage has no decoder layers");
-  if (ctx->cfg.n_experts > 0) return fail(ctx, RP_EUNSUPPORTED, "MoE stages are not implemented");
-  (void)router_logits;
+  if (ctx->cfg.n_experts > 0 && !router_logits) return fail(ctx, RP_EINVAL, "MoE stage needs router_logits");
   const Plan P = make_plan(ctx->cfg, batch > 0 ? batch : 1, seq > 0 ? seq : 8);
   rp_status s = check_call(ctx, slot_id, batch, seq, workspace, workspace_bytes_in, P.fwd_bytes);
   if (s != RP_OK) return s;
@@ -476,7 +542,8 @@ rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_o
     if (layer_inputs_out && layer_inputs_out[l] && layer_inputs_out[l] != x) RUN(X, "copy", 0, 2.0 * act_bytes, k_copy16(X.st, x, layer_inputs_out[l], (long)act_bytes));
     void* z = (l == L - 1) ? x_out : pp[l & 1];
     const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
-    layer_forward(X, W, set, x, z);
+    if (router_logits) X.router = router_logits + (size_t)l * X.T * X.D.E;
+    layer_forward(X, W, set, x, z, P.moe_f_fwd);
     x = z;
   }
   return finish_call(ctx, sl, X);
@@ -487,8 +554,7 @@ rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_
                             void* workspace, size_t workspace_bytes_in) {
   if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
   if (ctx->cfg.n_layers == 0) return fail(ctx, RP_EINVAL, "stage has no decoder layers");
-  if (ctx->cfg.n_experts > 0) return fail(ctx, RP_EUNSUPPORTED, "MoE stages are not implemented");
-  (void)router_logits; (void)d_router_logits;
+  if (ctx->cfg.n_experts > 0 && !router_logits) return fail(ctx, RP_EINVAL, "MoE stage needs router_logits");
   const Plan P = make_plan(ctx->cfg, batch > 0 ? batch : 1, seq > 0 ? seq : 8);
   rp_status s = check_call(ctx, slot_id, batch, seq, workspace, workspace_bytes_in, P.bwd_bytes);
   if (s != RP_OK) return s;
@@ -516,7 +582,8 @@ rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_
     for (int l = 0; l < L; ++l) {
       const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
       void* z = set_of(l) + P.lb.z;
-      layer_forward(X, W, set_of(l), x, z);
+      if (router_logits) X.router = router_logits + (size_t)l * X.T * X.D.E;
+      layer_forward(X, W, set_of(l), x, z, P.moe_f_bwd);
       x = z;
     }
     if (x_out) RUN(X, "copy", 0, 2.0 * act_bytes, k_copy16(X.st, x, x_out, (long)act_bytes));
@@ -528,6 +595,7 @@ rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_
     const LayerG G{grads ? static_cast<char*>(grads) + ctx->gl.layer_bytes * (size_t)l : nullptr, &ctx->gl};
     const void* xl = l == 0 ? x_in : set_of(l - 1) + P.lb.z;
     void* dxl = l == 0 ? dx : X.at<void>(P.tB);
+    X.d_router = (d_router_logits && X.D.E > 0) ? d_router_logits + (size_t)l * X.T * X.D.E : nullptr;
     layer_backward(X, W, G, set_of(l), xl, dz, dxl);
     dz = dxl;
   }

@@ -150,20 +150,21 @@ class StageRunner:
     def bind(self, slot=0):
         B.rp_stage_bind_weights(self.ctx, slot, self.slots[slot], self.wbytes)
 
-    def forward(self, x, slot=0, keep_layer_inputs=False):
+    def forward(self, x, slot=0, keep_layer_inputs=False, router=None):
+        """router: fp32 device tensor [n_layers, T, E] of router logits (MoE stages)."""
         out = torch.empty_like(x)
         keep = None
         if keep_layer_inputs:
             keep = [torch.empty_like(x) for _ in range(self.cfg.n_layers)]
-        B.rp_stage_forward(self.ctx, slot, x, out, keep, None, self.batch, self.seq, self.ws, self.wsbytes)
+        B.rp_stage_forward(self.ctx, slot, x, out, keep, router, self.batch, self.seq, self.ws, self.wsbytes)
         return (out, keep) if keep_layer_inputs else out
 
-    def backward(self, x, dy, slot=0, want_out=True):
+    def backward(self, x, dy, slot=0, want_out=True, router=None, d_router=None):
         """Ordinary backward stage: recomputation followed by the backward pass."""
         dx = torch.empty_like(x)
         out = torch.empty_like(x) if want_out else None
-        B.rp_stage_backward(self.ctx, slot, B.PHASE_BOTH, x, dy, dx, out, self.grads if self.gbytes else None, None, None,
-                            self.batch, self.seq, self.ws, self.wsbytes)
+        B.rp_stage_backward(self.ctx, slot, B.PHASE_BOTH, x, dy, dx, out, self.grads if self.gbytes else None, router,
+                            d_router, self.batch, self.seq, self.ws, self.wsbytes)
         return out, dx
 
     def recompute(self, x, out, slot=0):

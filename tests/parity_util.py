@@ -33,16 +33,17 @@ def oracle_chain(c, wl, dtype=np.float64, grad_scale=1.0):
     cfg = oracle_cfg(c)
     layers = cast_tree(wl["layers"], dtype)
     x = wl["x"].astype(dtype)
+    router = None if wl.get("router_logits") is None else [r.astype(dtype) for r in wl["router_logits"]]
     res = {}
     if wl["head"] is not None:
-        out, _ = stage.stage_fwd(x, layers, cfg, c["batch"], c["seq"])
+        out, _ = stage.stage_fwd(x, layers, cfg, c["batch"], c["seq"], router)
         loss, dy, gh = stage.head_fwd_bwd(out, cast_tree(wl["head"], dtype), wl["labels"], cfg, grad_scale,
                                           want_dW=cfg.train_base)
         res.update(loss=float(loss), head_dx=dy, head_grads=gh)
     else:
         dy = wl["dy"].astype(dtype)
     if c["n_layers"] > 0:
-        out, dx, grads = stage.stage_fwd_bwd(x, dy, layers, cfg, c["batch"], c["seq"])
+        out, dx, grads = stage.stage_fwd_bwd(x, dy, layers, cfg, c["batch"], c["seq"], router)
         res.update(out=out, dx=dx, grads=grads)
     return res
 
@@ -60,13 +61,17 @@ def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True):
             torch.cuda.synchronize()
             R.bind()
         x = harness.bf16_tensor(wl["x"], R.device)
+        router = d_router = None
+        if wl.get("router_logits") is not None:
+            router = torch.from_numpy(np.stack(wl["router_logits"])).to(R.device)
+            d_router = torch.full_like(router, float("nan"))
         torch.cuda.synchronize()
         res = {}
         if wl["head"] is not None:
             labels = torch.from_numpy(wl["labels"]).to(R.device)
             torch.cuda.synchronize()
             if c["n_layers"] > 0:
-                out = R.forward(x)
+                out = R.forward(x, router=router)
             else:
                 out = x
             loss, dy = R.head(out, labels, grad_scale, train=bool(c["train_base"]))
@@ -76,9 +81,11 @@ def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True):
             dy = harness.bf16_tensor(wl["dy"], R.device)
             torch.cuda.synchronize()
         if c["n_layers"] > 0:
-            out2, dx = R.backward(x, dy)
+            out2, dx = R.backward(x, dy, router=router, d_router=d_router)
             R.sync()
             res.update(out=harness.to_f32(out2), dx=harness.to_f32(dx))
+            if d_router is not None:
+                res["d_router"] = d_router.cpu().numpy()
         R.sync()
         layer_g, head_g = harness.unpack_grads(cfg, R.grads)
         res.update(grads=layer_g, head_grads=head_g)
@@ -102,7 +109,9 @@ def compare_chain(ref, got, c, tol=2e-2, loss_tol=1e-4, report=None):
         for li, g in enumerate(ref["grads"]):
             gg = got["grads"][li]
             for k, v in g.items():
-                if k == "lora":
+                if k == "router_logits":
+                    errs["L%d.router_logits" % li] = rel_l2(got["d_router"][li], v)
+                elif k == "lora":
                     for nm, (dA, dB) in v.items():
                         errs["L%d.lora.%s.A" % (li, nm)] = rel_l2(gg["lora"][nm][0], dA)
                         errs["L%d.lora.%s.B" % (li, nm)] = rel_l2(gg["lora"][nm][1], dB)

@@ -130,6 +130,31 @@ VARIANTS = {
 }
 
 
+MOE_VARIANTS = {
+    # 8 experts, top-2, expert rows far below one 256-row tile; group size 2, LoRA on attention only, frozen base
+    "small": dict(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=96, vocab=0, n_experts=8, top_k=2,
+                  lora_rank=8, lora=("q", "k", "v", "o"), train_base=0, batch=1, seq=136, x_from="normal"),
+    # more rows per expert than a tile (several tiles per expert, ragged tails), top-4 of 6, no adapters at all
+    "tiles": dict(n_layers=1, hidden=128, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=64, vocab=0, n_experts=6, top_k=4,
+                  lora_rank=0, lora=(), train_base=0, batch=2, seq=520, x_from="normal"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MOE_VARIANTS))
+def test_moe_stage_matches_oracle(hz, name):
+    """Top-k mixture-of-experts FFN: routing decisions are taken from the same fp32 logits on both sides, so they are
+    identical; outputs, input gradient, router-logit gradients and adapter gradients within the bf16 bound."""
+    c = MOE_VARIANTS[name]
+    wl = synth.make_workload(c, 900 + sorted(MOE_VARIANTS).index(name), gains_random=True)
+    ref = pu.oracle_chain(c, wl)
+    got = pu.gpu_chain(c, wl, hz)
+    errs = pu.compare_chain(ref, got, c)
+    assert len(errs) == 2 + c["n_layers"] * (1 + 2 * len(c["lora"])), sorted(errs)
+    # unselected experts get exactly zero gradient, selected ones do not
+    for li in range(c["n_layers"]):
+        assert np.array_equal(got["d_router"][li] == 0.0, ref["grads"][li]["router_logits"] == 0.0)
+
+
 @pytest.mark.parametrize("name", sorted(VARIANTS))
 def test_stage_variants_match_oracle(hz, name):
     c = VARIANTS[name]
