@@ -25,7 +25,7 @@ RP_API rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A
 /* RMSNorm: y = x * rstd * g, rstd_t = (mean_j x_tj^2 + eps)^(-1/2); rstd fp32 [T] (may be NULL). */
 RP_API rp_status rp_op_rmsnorm_fwd(void* stream, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps);
 /* dx = backward of the above (+ dres, bf16 [T,h], optional); dg fp32 [h] accumulated (optional; then scratch, fp32
- * [512 * h], is required and overwritten). dy bf16, or fp32 when dy_is_f32. */
+ * [1024 * h], is required and overwritten). dy bf16, or fp32 when dy_is_f32. */
 RP_API rp_status rp_op_rmsnorm_bwd(void* stream, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
                             const void* dres, void* dx, float* dg, float* scratch, int T, int h);
 
@@ -33,7 +33,7 @@ RP_API rp_status rp_op_rmsnorm_bwd(void* stream, const void* dy, int dy_is_f32, 
 RP_API rp_status rp_op_rope_table(void* stream, void* cs, int seq, int d, float base);
 /* Per-head RMSNorm (optional) + rotary embedding with half-split pairs (i, i + d/2) on a query heads and k key heads.
  * forward: in_* -> out_*;  backward (bwd = 1): in_* are gradients of the rotated heads, raw_* the pre-norm heads,
- * out_* the gradients of the raw heads, dgq/dgk fp32 [d] accumulated (scratch: fp32 [512 * 2 * d], overwritten).
+ * out_* the gradients of the raw heads, dgq/dgk fp32 [d] accumulated (scratch: fp32 [1024 * 2 * d], overwritten).
  * rstd_* fp32 [T, heads]. */
 RP_API rp_status rp_op_qknorm_rope(void* stream, int bwd, int d, const void* in_q, const void* in_k, long ld_in_q, long ld_in_k,
                             void* out_q, void* out_k, long ld_out_q, long ld_out_k, const void* gq, const void* gk, float* rstd_q,

@@ -60,43 +60,40 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const bf16* __restrict
 
 // ------------------------------------------------------------------------------------------------ RMSNorm backward
 // dx = rstd*(dy*g) - rstd^3/h * x * sum_j(dy_j g_j x_j)  (+ dres, the gradient arriving over the residual branch);
-// dg partial = sum_t dy_t * x_t * rstd_t over the rows a block visits: accumulated per lane, merged across the block's
-// waves in LDS and written to part[block][h]; a column-sum kernel adds the partials to dg in a fixed order.
+// dg partial = sum_t dy_t * x_t * rstd_t over the rows a block visits, written to part[block][h]; a column-sum kernel
+// adds the partials to dg in a fixed order.
+// One BLOCK per row: the four waves split the row's columns (chunk (4i + wave)*64 + lane, i < MAXC, so
+// h <= 2048*MAXC), the row's dot product crosses the waves through LDS (one barrier per row), and every lane owns its
+// columns for all the rows of the block, so the gain-gradient partial is written straight from registers.
 template <int MAXC, typename DyT>
 __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict__ dy, const bf16* __restrict__ x,
-                                                          const bf16* __restrict__ g, const float* __restrict__ rstd_in,
-                                                          const bf16* __restrict__ dres, bf16* __restrict__ dx,
-                                                          float* __restrict__ part, int T, int h) {
-  extern __shared__ float dg_s[];
-  if (part) {
-    for (int i = threadIdx.x; i < h; i += 256) dg_s[i] = 0.f;
-    __syncthreads();
-  }
-  const int lane = threadIdx.x & 63;
-  const int wave_id = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int nwaves = gridDim.x * 4;
+                                                               const bf16* __restrict__ g, const float* __restrict__ rstd_in,
+                                                               const bf16* __restrict__ dres, bf16* __restrict__ dx,
+                                                               float* __restrict__ part, int T, int h) {
+  __shared__ float s_dot[2][4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nch = h >> 3;
   const uint4* gr = reinterpret_cast<const uint4*>(g);
-  float dgacc[MAXC][8];
+  float gg[MAXC][8], dgacc[MAXC][8];
 #pragma unroll
-  for (int i = 0; i < MAXC; ++i)
+  for (int i = 0; i < MAXC; ++i) {
+    const int c = (4 * i + wave) * 64 + lane;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) dgacc[i][e] = 0.f;
-
-  for (int row = wave_id; row < T; row += nwaves) {
+    for (int e = 0; e < 8; ++e) { dgacc[i][e] = 0.f; gg[i][e] = 0.f; }
+    if (c < nch) unpack8(gr[c], gg[i]);
+  }
+  int par = 0;
+  for (int row = blockIdx.x; row < T; row += gridDim.x, par ^= 1) {
     const float rstd = rstd_in[row];
-    const uint4* xr = reinterpret_cast<const uint4*>(x + (long)row * h);
-    float dyv[MAXC][8];
-    uint4 xv[MAXC];
+    float dyv[MAXC][8], xf[MAXC][8];
     float dot = 0.f;
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
-      const int c = lane + 64 * i;
-      xv[i] = make_uint4(0u, 0u, 0u, 0u);
+      const int c = (4 * i + wave) * 64 + lane;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dyv[i][e] = 0.f;
+      for (int e = 0; e < 8; ++e) { dyv[i][e] = 0.f; xf[i][e] = 0.f; }
       if (c < nch) {
-        xv[i] = xr[c];
+        unpack8(reinterpret_cast<const uint4*>(x + (long)row * h)[c], xf[i]);
         if constexpr (sizeof(DyT) == 4) {
           const float4* dr = reinterpret_cast<const float4*>(dy + (long)row * h) + 2 * c;
           const float4 a = dr[0], b = dr[1];
@@ -105,73 +102,75 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict_
         } else {
           unpack8(reinterpret_cast<const uint4*>(dy + (long)row * h)[c], dyv[i]);
         }
-        float xf[8], gg[8];
-        unpack8(xv[i], xf);
-        unpack8(gr[c], gg);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          dot += dyv[i][e] * gg[e] * xf[e];
-          dgacc[i][e] += dyv[i][e] * xf[e] * rstd;
+          dot += dyv[i][e] * gg[i][e] * xf[i][e];
+          dgacc[i][e] += dyv[i][e] * xf[i][e] * rstd;
         }
       }
     }
     dot = wave_sum(dot);
+    if (lane == 0) s_dot[par][wave] = dot;
+    __syncthreads();   // the other parity's slots are rewritten only after the next barrier
+    dot = (s_dot[par][0] + s_dot[par][1]) + (s_dot[par][2] + s_dot[par][3]);
     const float k2 = rstd * rstd * rstd * dot / (float)h;
-    uint4* dxr = reinterpret_cast<uint4*>(dx + (long)row * h);
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
-      const int c = lane + 64 * i;
+      const int c = (4 * i + wave) * 64 + lane;
       if (c < nch) {
-        float xf[8], gg[8], o[8];
-        unpack8(xv[i], xf);
-        unpack8(gr[c], gg);
+        float o[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = rstd * dyv[i][e] * gg[e] - k2 * xf[e];
+        for (int e = 0; e < 8; ++e) o[e] = rstd * dyv[i][e] * gg[i][e] - k2 * xf[i][e];
         if (dres) {
           float rr[8];
           unpack8(reinterpret_cast<const uint4*>(dres + (long)row * h)[c], rr);
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] += rr[e];
         }
-        dxr[c] = pack8(o);
+        reinterpret_cast<uint4*>(dx + (long)row * h)[c] = pack8(o);
       }
     }
   }
   if (part) {
 #pragma unroll
     for (int i = 0; i < MAXC; ++i) {
-      const int c = lane + 64 * i;
+      const int c = (4 * i + wave) * 64 + lane;
       if (c < nch) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) atomicAdd(dg_s + c * 8 + e, dgacc[i][e]);
+        float4* o = reinterpret_cast<float4*>(part + (long)blockIdx.x * h + c * 8);
+        o[0] = make_float4(dgacc[i][0], dgacc[i][1], dgacc[i][2], dgacc[i][3]);
+        o[1] = make_float4(dgacc[i][4], dgacc[i][5], dgacc[i][6], dgacc[i][7]);
       }
     }
-    __syncthreads();
-    for (int i = threadIdx.x; i < h; i += 256) part[(long)blockIdx.x * h + i] = dg_s[i];
   }
 }
 
-// dst[c] += sum_r part[r][c], r = 0..rows-1.  A block owns 64 columns; its four waves each sum every fourth row
-// (four independent loads in flight per thread) and the four slices are merged in LDS in a fixed order.
-__global__ void __launch_bounds__(256) colsum_add_kernel(const float* __restrict__ part, int rows, int ld, int cols,
-                                                         float* __restrict__ dst) {
-  __shared__ float red[4][64];
+// dst[c] += sum_r part[r][c], r = 0..rows-1 (columns from cols1 on go to dst2).  A block owns 64 columns; its sixteen
+// waves each sum every sixteenth row (four independent loads in flight per thread) and the slices are merged in LDS in
+// a fixed order.
+__global__ void __launch_bounds__(1024) colsum_add_kernel(const float* __restrict__ part, int rows, int ld, int cols,
+                                                          float* __restrict__ dst, int cols1, float* __restrict__ dst2) {
+  __shared__ float red[16][64];
   const int cl = threadIdx.x & 63, sl = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
   float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
   if (c < cols) {
     int r = sl;
-    for (; r + 12 < rows; r += 16) {
+    for (; r + 48 < rows; r += 64) {
       s0 += part[(long)r * ld + c];
-      s1 += part[(long)(r + 4) * ld + c];
-      s2 += part[(long)(r + 8) * ld + c];
-      s3 += part[(long)(r + 12) * ld + c];
+      s1 += part[(long)(r + 16) * ld + c];
+      s2 += part[(long)(r + 32) * ld + c];
+      s3 += part[(long)(r + 48) * ld + c];
     }
-    for (; r < rows; r += 4) s0 += part[(long)r * ld + c];
+    for (; r < rows; r += 16) s0 += part[(long)r * ld + c];
   }
   red[sl][cl] = (s0 + s1) + (s2 + s3);
   __syncthreads();
-  if (sl == 0 && c < cols) dst[c] += (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
+  if (sl == 0 && c < cols) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) t += red[k][cl];
+    if (c < cols1) dst[c] += t; else dst2[c - cols1] += t;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ RoPE table
@@ -192,7 +191,7 @@ __global__ void rope_table_kernel(float2* __restrict__ cs, int seq, int half, do
 // (i, i + D/2) sits D/16 lanes away.  Heads 0..a-1 are query heads, a..a+k-1 key heads, both read from the fused
 // projection output (row stride ld_in) and written to dense [T, a, D] / [T, k, D] buffers.
 template <int D, bool BWD>
-__global__ void __launch_bounds__(256) qknorm_rope_kernel(const bf16* __restrict__ in_q, const bf16* __restrict__ in_k,
+__global__ void __launch_bounds__(512) qknorm_rope_kernel(const bf16* __restrict__ in_q, const bf16* __restrict__ in_k,
                                                           long ld_in_q, long ld_in_k, bf16* __restrict__ out_q,
                                                           bf16* __restrict__ out_k, long ld_out_q, long ld_out_k,
                                                           const bf16* __restrict__ gq, const bf16* __restrict__ gk,
@@ -203,15 +202,15 @@ __global__ void __launch_bounds__(256) qknorm_rope_kernel(const bf16* __restrict
                                                           int use_norm, float eps) {
   __shared__ float dg_s[2 * D];
   if (BWD && part) {
-    for (int i = threadIdx.x; i < 2 * D; i += 256) dg_s[i] = 0.f;
+    for (int i = threadIdx.x; i < 2 * D; i += (int)blockDim.x) dg_s[i] = 0.f;
     __syncthreads();
   }
   constexpr int LPH = D / 8;          // lanes per head
   constexpr int HPW = 64 / LPH;       // heads per wave pass
   const int lane = threadIdx.x & 63;
   const int sub = lane % LPH, hsel = lane / LPH;
-  const int wave_id = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int nwaves = gridDim.x * 4;
+  const int wave_id = blockIdx.x * ((int)blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int nwaves = gridDim.x * ((int)blockDim.x >> 6);
   const bool first_half = sub < LPH / 2;
   float gqv[8], gkv[8];
 #pragma unroll
@@ -317,7 +316,7 @@ __global__ void __launch_bounds__(256) qknorm_rope_kernel(const bf16* __restrict
         if (hsel == 0) { atomicAdd(dg_s + sub * 8 + e, vq); atomicAdd(dg_s + D + sub * 8 + e, vk); }
       }
       __syncthreads();
-      for (int i = threadIdx.x; i < 2 * D; i += 256) part[(long)blockIdx.x * 2 * D + i] = dg_s[i];
+      for (int i = threadIdx.x; i < 2 * D; i += (int)blockDim.x) part[(long)blockIdx.x * 2 * D + i] = dg_s[i];
     }
   }
 }
@@ -420,19 +419,18 @@ hipError_t k_rmsnorm_bwd(hipStream_t st, const void* dy, int dy_is_f32, const vo
                          const void* dres, void* dx, float* dg, float* scratch, int T, int h) {
   if (T == 0) return hipSuccess;
   if (dg && !scratch) return hipErrorInvalidValue;
-  int grid = (T + 3) / 4;
-  if (grid > RP_PARTIAL_BLOCKS) grid = RP_PARTIAL_BLOCKS;
+  const int grid = T < RP_PARTIAL_BLOCKS ? T : RP_PARTIAL_BLOCKS;
   float* part = dg ? scratch : nullptr;
-  const size_t smem = dg ? (size_t)h * 4 : 0;
-#define RP_LAUNCH_RB(MAXC, DT) \
-  RP_LAUNCH((rmsnorm_bwd_kernel<MAXC, DT>), dim3(grid), dim3(256), smem, st, (const DT*)dy, (const bf16*)x, \
+#define RP_LAUNCH_RR(MAXC, DT) \
+  RP_LAUNCH((rmsnorm_bwd_kernel<MAXC, DT>), dim3(grid), dim3(256), 0, st, (const DT*)dy, (const bf16*)x, \
                      (const bf16*)g, rstd, (const bf16*)dres, (bf16*)dx, part, T, h)
-  if (h <= 2048) { if (dy_is_f32) RP_LAUNCH_RB(4, float); else RP_LAUNCH_RB(4, bf16); }
-  else { if (dy_is_f32) RP_LAUNCH_RB(16, float); else RP_LAUNCH_RB(16, bf16); }
-#undef RP_LAUNCH_RB
+  if (h <= 2048) { if (dy_is_f32) RP_LAUNCH_RR(1, float); else RP_LAUNCH_RR(1, bf16); }
+  else if (h <= 4096) { if (dy_is_f32) RP_LAUNCH_RR(2, float); else RP_LAUNCH_RR(2, bf16); }
+  else { if (dy_is_f32) RP_LAUNCH_RR(4, float); else RP_LAUNCH_RR(4, bf16); }
+#undef RP_LAUNCH_RR
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && dg) {
-    RP_LAUNCH(colsum_add_kernel, dim3((h + 63) / 64), dim3(256), 0, st, part, grid, h, h, dg);
+    RP_LAUNCH(colsum_add_kernel, dim3((h + 63) / 64), dim3(1024), 0, st, part, grid, h, h, dg, h, (float*)nullptr);
     e = hipGetLastError();
   }
   return e;
@@ -450,13 +448,14 @@ hipError_t k_qknorm_rope(hipStream_t st, int bwd, int d, const void* in_q, const
                          float* rstd_q, float* rstd_k, const void* raw_q, const void* raw_k, long ld_raw, float* dgq,
                          float* dgk, float* scratch, const float2* cs, int T, int seq, int a, int k, int use_norm, float eps) {
   if (T == 0) return hipSuccess;
-  int grid = (T + 3) / 4;
+  const int nthr = 256;
+  int grid = (T + nthr / 64 - 1) / (nthr / 64);
   if (bwd && grid > RP_PARTIAL_BLOCKS) grid = RP_PARTIAL_BLOCKS;
   const bool want_dg = bwd && use_norm && dgq && dgk;
   if (want_dg && !scratch) return hipErrorInvalidValue;
   float* part = want_dg ? scratch : nullptr;
 #define RP_LAUNCH_QR(D, B) \
-  RP_LAUNCH((qknorm_rope_kernel<D, B>), dim3(grid), dim3(256), 0, st, (const bf16*)in_q, (const bf16*)in_k, \
+  RP_LAUNCH((qknorm_rope_kernel<D, B>), dim3(grid), dim3(nthr), 0, st, (const bf16*)in_q, (const bf16*)in_k, \
                      ld_in_q, ld_in_k, (bf16*)out_q, (bf16*)out_k, ld_out_q, ld_out_k, (const bf16*)gq, (const bf16*)gk, \
                      rstd_q, rstd_k, (const bf16*)raw_q, (const bf16*)raw_k, ld_raw, part, cs, T, seq, a, k, use_norm, eps)
   if (d == 128) { if (bwd) RP_LAUNCH_QR(128, true); else RP_LAUNCH_QR(128, false); }
@@ -465,8 +464,7 @@ hipError_t k_qknorm_rope(hipStream_t st, int bwd, int d, const void* in_q, const
 #undef RP_LAUNCH_QR
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && want_dg) {
-    RP_LAUNCH(colsum_add_kernel, dim3((d + 63) / 64), dim3(256), 0, st, part, grid, 2 * d, d, dgq);
-    RP_LAUNCH(colsum_add_kernel, dim3((d + 63) / 64), dim3(256), 0, st, part + d, grid, 2 * d, d, dgk);
+    RP_LAUNCH(colsum_add_kernel, dim3((2 * d + 63) / 64), dim3(1024), 0, st, part, grid, 2 * d, 2 * d, dgq, d, dgk);
     e = hipGetLastError();
   }
   return e;

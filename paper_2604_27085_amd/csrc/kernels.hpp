@@ -11,7 +11,7 @@ struct LoraSegs {           // up to three row segments of a fused projection, e
 // y = x * rstd * g, rstd[T] saved (may be NULL).  x, y bf16 [T, h]; g bf16 [h].
 hipError_t k_rmsnorm_fwd(hipStream_t st, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps);
 // Gain gradients are reduced block by block into `scratch` and then added to their destination in a fixed order.
-#define RP_PARTIAL_BLOCKS 512
+#define RP_PARTIAL_BLOCKS 1024
 // dx = rmsnorm backward (+ dres if non-NULL); dg (fp32 [h], may be NULL) += its gradient, using scratch
 // [RP_PARTIAL_BLOCKS * h] floats.  dy bf16 or fp32.
 hipError_t k_rmsnorm_bwd(hipStream_t st, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,

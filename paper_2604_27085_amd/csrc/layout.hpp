@@ -3,6 +3,7 @@
 #include <stddef.h>
 #include <stdint.h>
 #include "../../include/rp.h"
+#include "kernels.hpp"   // RP_PARTIAL_BLOCKS
 
 namespace rp {
 
@@ -156,7 +157,7 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   P.dn = take(T * D.h * 2); P.dout = take(T * D.qd * 2); P.dqr = take(T * D.qd * 2); P.dkr = take(T * D.kd * 2);
   P.dqkv = take(T * D.n1 * 2); P.delta = take(T * D.a * 4);
   P.ud = take(T * (size_t)(3 * D.r) * 2);
-  P.partials = take((size_t)512 * (size_t)(D.h > 2 * D.d ? D.h : 2 * D.d) * 4);
+  P.partials = take((size_t)RP_PARTIAL_BLOCKS * (size_t)(D.h > 2 * D.d ? D.h : 2 * D.d) * 4);
   P.bwd_bytes = o;
   // head
   o = 0;
@@ -167,7 +168,7 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
     P.h_xf = take(T * D.h * 2); P.h_rstd = take(T * 4); P.h_part = take((size_t)P.head_parts * T * 8);
     P.h_zlab = take(T * 4); P.h_lse = take(T * 4); P.h_coef = take(T * 4);
     P.h_dzt = take((size_t)P.head_chunk * T * 2); P.h_dxacc = take(T * D.h * 4);
-    P.h_partials = take((size_t)512 * D.h * 4);
+    P.h_partials = take((size_t)RP_PARTIAL_BLOCKS * D.h * 4);
   }
   P.head_bytes = o;
   return P;

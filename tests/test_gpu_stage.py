@@ -135,6 +135,9 @@ MOE_VARIANTS = {
     "small": dict(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=96, vocab=0, n_experts=8, top_k=2,
                   lora_rank=8, lora=("q", "k", "v", "o"), train_base=0, batch=1, seq=136, x_from="normal"),
     # more rows per expert than a tile (several tiles per expert, ragged tails), top-4 of 6, no adapters at all
+    # the shape of C5 scaled down: 128 experts, top-8, head_dim 128 with 16 query heads per kv head, LoRA on attention
+    "c5_like": dict(n_layers=1, hidden=256, n_q_heads=16, n_kv_heads=1, head_dim=128, ffn=96, vocab=0, n_experts=128,
+                    top_k=8, lora_rank=8, lora=("q", "k", "v", "o"), train_base=0, batch=1, seq=1064, x_from="normal"),
     "tiles": dict(n_layers=1, hidden=128, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=64, vocab=0, n_experts=6, top_k=4,
                   lora_rank=0, lora=(), train_base=0, batch=2, seq=520, x_from="normal"),
 }
