@@ -83,7 +83,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
-    ap.add_argument("--cpu-seq", type=int, default=2048, help="sequence length of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-seq", type=int, default=4096, help="sequence length of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--no-upload-leg", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

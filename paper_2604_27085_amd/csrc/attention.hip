@@ -212,21 +212,19 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
       T64::load(vreg, rv, p.ldv, (j + 1) * 64, tid);
     }
     const int kv0 = j * 64;
-    if (kv0 <= qw0 + 32 * QT - 1) {   // the wave has at least one unmasked (query, key) pair
+    // Waves whose queries all precede this tile's keys (the last tile of the two upper waves) run it fully masked
+    // rather than skip it: they would wait at the next barrier anyway, and a skipped update would make the compiler
+    // keep a second copy of the accumulator.
+    {
       f32x16 sT[QT][2];
-#pragma unroll
-      for (int t = 0; t < QT; ++t)
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) sT[t][kt][v] = 0.f;
+      const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
           const uint4 a = *reinterpret_cast<const uint4*>(kfrag + 32 * kt * LDK + 16 * ks);
 #pragma unroll
-          for (int t = 0; t < QT; ++t) sT[t][kt] = mfma32(a, qf[t][ks], sT[t][kt]);
+          for (int t = 0; t < QT; ++t) sT[t][kt] = mfma32(a, qf[t][ks], ks == 0 ? zero16 : sT[t][kt]);
         }
       const bool need_mask = (kv0 + 63 > qw0) || (kv0 + 64 > p.seq);   // wave-uniform
 #pragma unroll
@@ -247,12 +245,11 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
 #pragma unroll
           for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sT[t][kt][v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * p.scale_log2e;
-        // m_run is the reference exponent (log2 units), not necessarily the running maximum: it only moves when the
-        // maximum outgrows it by more than 2^8, which keeps every exp2 argument <= 8 and skips most rescales of the
-        // accumulator.  The first key tile contains key 0 <= qpos, so the reference is finite from then on.
-        const bool grow = mx > m_run[t] + 8.f;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-          const float m_new = grow ? mx : m_run[t];
+        // The accumulator is rescaled on every key tile, without a branch: a conditional rescale (only when the
+        // maximum grows) makes the compiler carry a second copy of the accumulator through the loop, which costs more
+        // than the multiplies.  The first key tile contains key 0 <= qpos, so m_run is finite from then on.
+        {
+          const float m_new = fmaxf(m_run[t], mx);
           const float alpha = fast_exp2(m_run[t] - m_new);
           l_run[t] *= alpha;
           m_run[t] = m_new;
@@ -403,7 +400,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const AttnArgs p) 
       T64::load(vreg, rv, p.ldv, (j + 1) * 64, tid);
     }
     const int kv0 = j * 64;
-    if (kv0 <= qw0 + 32 * QT - 1) {
+    {   // a wave whose queries all precede this tile's keys runs it fully masked (see the forward kernel)
       f32x16 sT[QT][2], dpT[QT][2];
 #pragma unroll
       for (int t = 0; t < QT; ++t)
@@ -541,7 +538,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
     __syncthreads();
     if (it + 1 < niter) prefetch(it + 1);
     const int q0 = (qt0 + it) * 64;
-    if (q0 + 63 >= kw0) {   // the wave has at least one (query >= key) pair
+    {   // a wave whose keys all follow this tile's queries runs it fully masked (see the forward kernel)
       f32x16 s[2], dp[2];
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
