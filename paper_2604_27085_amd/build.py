@@ -11,6 +11,9 @@ LIB = os.path.join(HERE, "librp.so")
 SOURCES = ["gemm.hip", "elementwise.hip", "attention.hip", "lmhead.hip", "moe.hip", "stage.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Xclang", "-target-feature",
          "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+# attention: the score tiles go from the MFMA straight into the softmax arithmetic; keeping MFMA results in ordinary
+# VGPRs saves a v_accvgpr_read/write pair per score element and iteration
+EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _hipcc():
@@ -26,7 +29,7 @@ def build(verbose=False, jobs=5):
 
     def compile_one(src):
         obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-        cmd = [cc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [cc] + FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stderr[-4000:]))

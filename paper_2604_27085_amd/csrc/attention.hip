@@ -326,7 +326,7 @@ __global__ void __launch_bounds__(256) attn_delta_kernel(const bf16* __restrict_
 
 // ================================================================================================ dQ
 template <int D, int QT, int NW>
-__global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const AttnArgs p) {
+__global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_bwd_dq_kernel(const AttnArgs p) {
   constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
   using T64 = Tile64<D, NT>;
   constexpr int MAIN = 2 * 64 * LDK + 64 * LDT, STG = NW * 32 * LDK;
@@ -401,51 +401,46 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const AttnArgs p) 
     }
     const int kv0 = j * 64;
     {   // a wave whose queries all precede this tile's keys runs it fully masked (see the forward kernel)
-      f32x16 sT[QT][2], dpT[QT][2];
+      const bool need_mask = (kv0 + 63 > qw0) || (kv0 + 64 > p.seq);
+      const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      // the two 32-key halves of the tile one after the other: half as many score registers live at a time
 #pragma unroll
-      for (int t = 0; t < QT; ++t)
+      for (int kt = 0; kt < 2; ++kt) {
+        f32x16 sT[QT], dpT[QT];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) { sT[t][kt][v] = 0.f; dpT[t][kt][v] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int ks = 0; ks < KS; ++ks) {
           const uint4 ak = *reinterpret_cast<const uint4*>(kfrag + 32 * kt * LDK + 16 * ks);
           const uint4 av = *reinterpret_cast<const uint4*>(vfrag + 32 * kt * LDK + 16 * ks);
 #pragma unroll
           for (int t = 0; t < QT; ++t) {
-            sT[t][kt] = mfma32(ak, qf[t][ks], sT[t][kt]);
-            dpT[t][kt] = mfma32(av, dof[t][ks], dpT[t][kt]);
+            sT[t] = mfma32(ak, qf[t][ks], ks == 0 ? zero16 : sT[t]);
+            dpT[t] = mfma32(av, dof[t][ks], ks == 0 ? zero16 : dpT[t]);
           }
         }
-      const bool need_mask = (kv0 + 63 > qw0) || (kv0 + 64 > p.seq);
 #pragma unroll
-      for (int t = 0; t < QT; ++t) {
-        const int qpos = qw0 + 32 * t + lr;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int t = 0; t < QT; ++t) {
+          const int qpos = qw0 + 32 * t + lr;
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            float pr = fast_exp2(sT[t][kt][v] * p.scale_log2e - lse2[t]);
+            float pr = fast_exp2(__builtin_fmaf(sT[t][v], p.scale_log2e, -lse2[t]));
             if (need_mask) {
               const int kpos = kv0 + 32 * kt + 8 * (v >> 2) + 4 * lk + (v & 3);
               pr = (kpos > qpos || kpos >= p.seq) ? 0.f : pr;
             }
-            sT[t][kt][v] = pr * (dpT[t][kt][v] - dl[t]);   // dS^T
+            sT[t][v] = pr * (dpT[t][v] - dl[t]);   // dS^T
           }
-      }
+        }
 #pragma unroll
-      for (int gk = 0; gk < 4; ++gk) {
-        uint4 df[QT];
+        for (int g2 = 0; g2 < 2; ++g2) {
+          uint4 df[QT];
 #pragma unroll
-        for (int t = 0; t < QT; ++t) df[t] = pack_frag(sT[t][gk >> 1], 8 * (gk & 1));
+          for (int t = 0; t < QT; ++t) df[t] = pack_frag(sT[t], 8 * g2);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const uint4 a = read_frag_tr<LDT>(ktfrag, gk, 32 * dt);
+          for (int dt = 0; dt < DT; ++dt) {
+            const uint4 a = read_frag_tr<LDT>(ktfrag, 2 * kt + g2, 32 * dt);
 #pragma unroll
-          for (int t = 0; t < QT; ++t) dqacc[t][dt] = mfma32(a, df[t], dqacc[t][dt]);
+            for (int t = 0; t < QT; ++t) dqacc[t][dt] = mfma32(a, df[t], dqacc[t][dt]);
+          }
         }
       }
     }
@@ -539,24 +534,20 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
     if (it + 1 < niter) prefetch(it + 1);
     const int q0 = (qt0 + it) * 64;
     {   // a wave whose keys all follow this tile's queries runs it fully masked (see the forward kernel)
-      f32x16 s[2], dp[2];
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) { s[t2][v] = 0.f; dp[t2][v] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-          const uint4 aq = *reinterpret_cast<const uint4*>(qfrag + 32 * t2 * LDK + 16 * ks);
-          s[t2] = mfma32(aq, kf[ks], s[t2]);
-          const uint4 ad = *reinterpret_cast<const uint4*>(dofrag + 32 * t2 * LDK + 16 * ks);
-          dp[t2] = mfma32(ad, vf[ks], dp[t2]);
-        }
       const bool need_mask = (q0 < kw0 + 31) || (kw0 + 32 > p.seq);   // wave-uniform
-      // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
+      const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      // the two 32-query halves of the tile one after the other: half as many score registers live at a time
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
+      for (int t2 = 0; t2 < 2; ++t2) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const uint4 aq = *reinterpret_cast<const uint4*>(qfrag + 32 * t2 * LDK + 16 * ks);
+          const uint4 ad = *reinterpret_cast<const uint4*>(dofrag + 32 * t2 * LDK + 16 * ks);
+          s = mfma32(aq, kf[ks], ks == 0 ? zero16 : s);
+          dp = mfma32(ad, vf[ks], ks == 0 ? zero16 : dp);
+        }
+        // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
           const int ql = 32 * t2 + 8 * vg + 4 * lk;
@@ -566,22 +557,24 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int v = 4 * vg + e;
-            float pr = fast_exp2(s[t2][v] * p.scale_log2e - lv[e]);
+            float pr = fast_exp2(__builtin_fmaf(s[v], p.scale_log2e, -lv[e]));
             if (need_mask) pr = (kpos > q0 + ql + e || !kok) ? 0.f : pr;
-            s[t2][v] = pr;                             // P
-            dp[t2][v] = pr * (dp[t2][v] - dv4[e]);     // dS
+            s[v] = pr;                         // P
+            dp[v] = pr * (dp[v] - dv4[e]);     // dS
           }
         }
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const uint4 pf = pack_frag(s[gq >> 1], 8 * (gq & 1));
-        const uint4 df = pack_frag(dp[gq >> 1], 8 * (gq & 1));
+        for (int g2 = 0; g2 < 2; ++g2) {
+          const int gq = 2 * t2 + g2;
+          const uint4 pf = pack_frag(s, 8 * g2);
+          const uint4 df = pack_frag(dp, 8 * g2);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const uint4 ado = read_frag_tr<LDT>(dotfrag, gq, 32 * dt);
-          dvacc[dt] = mfma32(ado, pf, dvacc[dt]);
-          const uint4 aq = read_frag_tr<LDT>(qtfrag, gq, 32 * dt);
-          dkacc[dt] = mfma32(aq, df, dkacc[dt]);
+          for (int dt = 0; dt < DT; ++dt) {
+            const uint4 ado = read_frag_tr<LDT>(dotfrag, gq, 32 * dt);
+            dvacc[dt] = mfma32(ado, pf, dvacc[dt]);
+            const uint4 aq = read_frag_tr<LDT>(qtfrag, gq, 32 * dt);
+            dkacc[dt] = mfma32(aq, df, dkacc[dt]);
+          }
         }
       }
     }
