@@ -451,9 +451,12 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_bwd_dq_kernel(c
     store_acc_T<D>(dqacc[t], p.scale, smem + w * 32 * LDK, p.dq + tok0 * p.lddq + hq * D, p.lddq, qw0 + 32 * t, p.seq, lane);
 }
 
-// ================================================================================================ dK, dV
+// ================================================================================================ dK, dV in one kernel
+// One wave per SIMD (the K and V fragments plus both accumulators take more than 256 registers per lane), four
+// recomputed/updated products per tile.  The better choice for short sequences, where the loops are short and the
+// second launch of the split version costs more than the lower occupancy.
 template <int D>
-__global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
+__global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs p) {
   constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32;
   using T64 = Tile64<D, 256>;
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
@@ -591,6 +594,155 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const AttnArgs p) {
   }
 }
 
+// ================================================================================================ dK, dV
+// Two launches of one template, each at two waves per SIMD (one kernel holding K, V fragments and both accumulators
+// needs more than 256 registers per lane and runs alone on its SIMD; measured at long sequences that costs more than
+// the score recomputation that the split adds):
+//   WHAT = 0: dV^T += dO^T P      (S recomputed; K fragments in registers, Q and dO^T tiles in LDS)
+//   WHAT = 1: dK^T += Q^T dS      (S and dP recomputed; K and V fragments in registers, Q, dO and Q^T tiles in LDS)
+template <int D, int WHAT>
+__global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) {
+  constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32;
+  constexpr bool DV = WHAT == 0;
+  using T64 = Tile64<D, 256>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+  float* const stats = reinterpret_cast<float*>(dyn_smem);          // 128 floats: lse (log2 units), delta
+  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem + 512);
+  // dV: Qs [64][LDK] | dOt [64][LDT];   dK: Qs | dOs [64][LDK] | Qt [64][LDT]
+  bf16* const Qs = smem;
+  bf16* const dOs = smem + 64 * LDK;                     // dK only
+  bf16* const Tt = smem + (DV ? 1 : 2) * 64 * LDK;       // the transposed-read tile: dO (dV) or Q (dK)
+  float* const lse_s = stats;
+  float* const dl_s = stats + 64;
+
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nhb = p.a * p.batch;
+  const int kvt = (int)blockIdx.x / nhb;     // key tile 0 sees every query: heaviest first, for every head
+  const int hb = (int)blockIdx.x % nhb;
+  const int hq = hb % p.a, b = hb / p.a;
+  const int grp = p.a / p.kh;
+  const int g = hq / grp;
+  const int kv0 = kvt * 128, kw0 = kv0 + 32 * w;
+  const long tok0 = (long)b * p.seq;
+  const bf16* kb = p.k + tok0 * p.ldk + g * D;
+  const bf16* vb = p.v + tok0 * p.ldv + g * D;
+  const int kpos = kw0 + lr;
+  const bool kok = kpos < p.seq;
+
+  uint4 kf[KS], vf[DV ? 1 : KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = make_uint4(0u, 0u, 0u, 0u);
+    if (kok) kf[ks] = *reinterpret_cast<const uint4*>(kb + (long)kpos * p.ldk + 16 * ks + 8 * lk);
+    if constexpr (!DV) {
+      vf[ks] = make_uint4(0u, 0u, 0u, 0u);
+      if (kok) vf[ks] = *reinterpret_cast<const uint4*>(vb + (long)kpos * p.ldv + 16 * ks + 8 * lk);
+    }
+  }
+  f32x16 acc[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
+
+  const int nQ = (p.seq + 63) / 64;
+  const int qt0 = kv0 / 64;
+  const int niter = nQ - qt0;
+
+  const bf16* qfrag = Qs + lr * LDK + 8 * lk;
+  const bf16* dofrag = dOs + lr * LDK + 8 * lk;
+  const bf16* tfrag = Tt + tr_base<LDT>(lane);
+
+  uint4 qreg[T64::NREG], doreg[T64::NREG];
+  float st_reg = 0.f;
+  const rsrc_t rq = seq_rsrc(p.q + tok0 * p.ldq + hq * D, p.ldq, p.seq, D);
+  const rsrc_t rdo = seq_rsrc(p.dout + tok0 * p.lddo + hq * D, p.lddo, p.seq, D);
+  auto prefetch = [&](int it) {
+    const int q0 = (qt0 + it) * 64;
+    T64::load(qreg, rq, p.ldq, q0, tid);
+    T64::load(doreg, rdo, p.lddo, q0, tid);
+    if (tid < (DV ? 64 : 128)) {
+      const int qi = q0 + (tid & 63);
+      const long sidx = ((long)b * p.a + hq) * p.seq + (qi < p.seq ? qi : 0);
+      const float v = tid < 64 ? p.lse_in[sidx] * 1.4426950408889634f : p.delta[sidx];
+      st_reg = qi < p.seq ? v : (tid < 64 ? INFINITY : 0.f);   // padded query rows get P = 0
+    }
+  };
+  if (niter > 0) prefetch(0);
+
+  for (int it = 0; it < niter; ++it) {
+    __syncthreads();
+    T64::template store<LDK>(qreg, Qs, tid);
+    if constexpr (DV) {
+      T64::template store<LDT>(doreg, Tt, tid);
+    } else {
+      T64::template store<LDK>(doreg, dOs, tid);
+      T64::template store<LDT>(qreg, Tt, tid);
+    }
+    if (tid < (DV ? 64 : 128)) stats[tid] = st_reg;
+    __syncthreads();
+    if (it + 1 < niter) prefetch(it + 1);
+    const int q0 = (qt0 + it) * 64;
+    // a wave whose keys all follow this tile's queries runs it fully masked (see the forward kernel)
+    const bool need_mask = (q0 < kw0 + 31) || (kw0 + 32 > p.seq);   // wave-uniform
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // the two 32-query halves of the tile one after the other: half as many score registers live at a time
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const uint4 aq = *reinterpret_cast<const uint4*>(qfrag + 32 * t2 * LDK + 16 * ks);
+        s = mfma32(aq, kf[ks], ks == 0 ? zero16 : s);
+        if constexpr (!DV) {
+          const uint4 ad = *reinterpret_cast<const uint4*>(dofrag + 32 * t2 * LDK + 16 * ks);
+          dp = mfma32(ad, vf[ks], ks == 0 ? zero16 : dp);
+        }
+      }
+      // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int ql = 32 * t2 + 8 * vg + 4 * lk;
+        const float4 l4 = *reinterpret_cast<const float4*>(lse_s + ql);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+        float dv4[4] = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (!DV) {
+          const float4 d4 = *reinterpret_cast<const float4*>(dl_s + ql);
+          dv4[0] = d4.x; dv4[1] = d4.y; dv4[2] = d4.z; dv4[3] = d4.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int v = 4 * vg + e;
+          float pr = fast_exp2(__builtin_fmaf(s[v], p.scale_log2e, -lv[e]));
+          if (need_mask) pr = (kpos > q0 + ql + e || !kok) ? 0.f : pr;
+          if constexpr (DV) s[v] = pr;                         // P
+          else s[v] = pr * (dp[v] - dv4[e]);                   // dS
+        }
+      }
+#pragma unroll
+      for (int g2 = 0; g2 < 2; ++g2) {
+        const uint4 bfrag = pack_frag(s, 8 * g2);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const uint4 at = read_frag_tr<LDT>(tfrag, 2 * t2 + g2, 32 * dt);
+          acc[dt] = mfma32(at, bfrag, acc[dt]);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const float mul = DV ? 1.f : p.scale;
+  if (grp == 1) {
+    bf16* out = DV ? p.dv + tok0 * p.lddv + g * D : p.dk + tok0 * p.lddk + g * D;
+    store_acc_T<D>(acc, mul, smem + w * 32 * LDK, out, DV ? p.lddv : p.lddk, kw0, p.seq, lane);
+  } else {
+    float* const stage = reinterpret_cast<float*>(smem) + w * 32 * (D + 4);
+    const long ldp = (long)p.a * D;
+    store_acc_T_f32<D>(acc, mul, stage, (DV ? p.dv_part : p.dk_part) + tok0 * ldp + hq * D, ldp, kw0, p.seq, lane);
+  }
+}
+
 // dk[t, g, :] = sum over the query heads of group g of the fp32 partials, in head order; same for dv.
 template <int D>
 __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __restrict__ dk_part, const float* __restrict__ dv_part,
@@ -620,7 +772,13 @@ __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __res
 }
 
 constexpr int dq_smem_bytes(int d) { return (2 * 64 * (d + 8) + 64 * (d + 32)) * 2; }
-constexpr int dkv_smem_bytes(int d) { return 512 + (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
+constexpr int dkv_fused_smem_bytes(int d) { return 512 + (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
+// operand tiles of the loop, or the four waves' fp32 staging of the epilogue, whichever is larger
+constexpr int dkv_smem_bytes(int d, int what) {
+  const int loop = ((what == 0 ? 1 : 2) * 64 * (d + 8) + 64 * (d + 32)) * 2;
+  const int stage = 4 * 32 * (d + 4) * 4;
+  return 512 + (loop > stage ? loop : stage);
+}
 
 void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
   p.batch = batch; p.seq = seq; p.a = a; p.kh = kh;
@@ -640,7 +798,7 @@ hipError_t set_smem(K kern, int bytes, bool& done) {
 int env_shape(const char* name, int dflt) {
   const char* s = getenv(name);
   const int v = s ? atoi(s) : dflt;
-  return (v == 1 || v == 2) ? v : dflt;
+  return (v == 1 || v == 2) ? v : dflt;   // anything else: the default
 }
 
 template <int D, int QT, int NW>
@@ -648,6 +806,24 @@ hipError_t launch_fwd(hipStream_t st, const AttnArgs& p) {
   constexpr int BQ = NW * 32 * QT;
   const int grid = ((p.seq + BQ - 1) / BQ) * p.a * p.batch;
   RP_LAUNCH((attn_fwd_kernel<D, QT, NW>), dim3(grid), dim3(NW * 64), 0, st, p);
+  return hipGetLastError();
+}
+
+template <int D, int WHAT>
+hipError_t launch_dkv(hipStream_t st, const AttnArgs& p, int grid) {
+  static bool done = false;
+  hipError_t e = set_smem(attn_bwd_dkv_kernel<D, WHAT>, dkv_smem_bytes(D, WHAT), done);
+  if (e != hipSuccess) return e;
+  RP_LAUNCH((attn_bwd_dkv_kernel<D, WHAT>), dim3(grid), dim3(256), dkv_smem_bytes(D, WHAT), st, p);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_dkv_fused(hipStream_t st, const AttnArgs& p, int grid) {
+  static bool done = false;
+  hipError_t e = set_smem(attn_bwd_dkv_fused_kernel<D>, dkv_fused_smem_bytes(D), done);
+  if (e != hipSuccess) return e;
+  RP_LAUNCH((attn_bwd_dkv_fused_kernel<D>), dim3(grid), dim3(256), dkv_fused_smem_bytes(D), st, p);
   return hipGetLastError();
 }
 
@@ -715,15 +891,13 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
   }
   if (part == 0) {
     const int nk = ((seq + 127) / 128) * a * batch;   // one workgroup per 128 keys and query head
-    if (d == 128) {
-      static bool done = false;
-      if ((e = set_smem(attn_bwd_dkv_kernel<128>, dkv_smem_bytes(128), done)) != hipSuccess) return e;
-      RP_LAUNCH(attn_bwd_dkv_kernel<128>, dim3(nk), dim3(256), dkv_smem_bytes(128), st, p);
-    } else {
-      static bool done = false;
-      if ((e = set_smem(attn_bwd_dkv_kernel<64>, dkv_smem_bytes(64), done)) != hipSuccess) return e;
-      RP_LAUNCH(attn_bwd_dkv_kernel<64>, dim3(nk), dim3(256), dkv_smem_bytes(64), st, p);
-    }
+    // one kernel for short sequences, two kernels at twice the occupancy for long ones (RP_ATTN_DKV: 1 / 2 forces)
+    static const int forced = env_shape("RP_ATTN_DKV", 0);
+    const bool split = forced ? forced == 2 : seq >= 8192;
+    if (!split) return d == 128 ? launch_dkv_fused<128>(st, p, nk) : launch_dkv_fused<64>(st, p, nk);
+    if (d == 128) { if ((e = launch_dkv<128, 0>(st, p, nk)) == hipSuccess) e = launch_dkv<128, 1>(st, p, nk); }
+    else { if ((e = launch_dkv<64, 0>(st, p, nk)) == hipSuccess) e = launch_dkv<64, 1>(st, p, nk); }
+    return e;
   } else {
     static const int shape = env_shape("RP_ATTN_DQ", 1);
     if (d == 128) return shape == 2 ? launch_dq<128, 2, 4>(st, p) : launch_dq<128, 1, 4>(st, p);

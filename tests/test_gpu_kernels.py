@@ -218,7 +218,9 @@ def test_swiglu_fwd_bwd(rp):
 
 
 # ----------------------------------------------------------------------------------------------- attention
-@pytest.mark.parametrize("d,a,kh,batch,seq", [(128, 4, 2, 1, 328), (64, 4, 2, 2, 136), (128, 8, 1, 1, 200), (128, 2, 2, 1, 8)])
+# the last two cases are long enough for the two-kernel dK/dV path (sequences of 8192 tokens and more)
+@pytest.mark.parametrize("d,a,kh,batch,seq", [(128, 4, 2, 1, 328), (64, 4, 2, 2, 136), (128, 8, 1, 1, 200), (128, 2, 2, 1, 8),
+                                              (128, 2, 1, 1, 8264), (64, 1, 1, 1, 8192)])
 def test_attention_fwd_bwd(rp, d, a, kh, batch, seq):
     B, H = rp
     rng = np.random.default_rng(d + a + seq)
