@@ -103,6 +103,7 @@ struct Plan {
   size_t moe_f_fwd, moe_f_bwd;   // expert outputs / expert input gradients per slot [T*top_k, h] (transient in a layer)
   size_t moe_wslot, moe_dw;      // routing weight per slot, its gradient per slot (backward)
   int moe_max_tiles;             // capacity of the tile table
+  size_t skinny_fwd, skinny_bwd;   // fp32 [T, 3r]: a skinny LoRA product before its conversion to bf16
   size_t dkvp;   // per-query-head dK/dV partials of grouped attention; shares memory with dact|dgu, dead by then
   size_t fwd_bytes, bwd_bytes;
   // head
@@ -147,6 +148,8 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
     size_t f = o + set;
     f = align_up(f + T * D.h * 2, 256);
     if (D.E > 0) { P.moe_f_fwd = f; f = align_up(f + Tk * D.h * 2, 256); }
+    P.skinny_fwd = f;
+    f = align_up(f + T * (size_t)(3 * D.r) * 4, 256);
     P.fwd_bytes = f;
   }
   o += set * (size_t)(D.L > 0 ? D.L : 0);
@@ -157,6 +160,7 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   P.dn = take(T * D.h * 2); P.dout = take(T * D.qd * 2); P.dqr = take(T * D.qd * 2); P.dkr = take(T * D.kd * 2);
   P.dqkv = take(T * D.n1 * 2); P.delta = take(T * D.a * 4);
   P.ud = take(T * (size_t)(3 * D.r) * 2);
+  P.skinny_bwd = take(T * (size_t)(3 * D.r) * 4);
   P.partials = take((size_t)RP_PARTIAL_BLOCKS * (size_t)(D.h > 2 * D.d ? D.h : 2 * D.d) * 4);
   P.bwd_bytes = o;
   // head

@@ -120,6 +120,7 @@ struct Exec {
   Plan P;
   hipError_t err = hipSuccess;
   const char* where = "";
+  bool fwd_only = false;           // the forward-stage plan of the workspace is in use (rp_stage_forward)
   const float* router = nullptr;   // router logits of the layer being run, fp32 [T, E] (mixture of experts)
   float* d_router = nullptr;       // their gradient (optional)
 
@@ -155,6 +156,22 @@ struct Exec {
     g.A2 = A2; g.lda2 = lda2; g.B2 = B2; g.ldb2 = ldb2; g.K2 = K2; g.R = R; g.ldr = ldr; g.epi = EPI_BF16;
     mark_gemm(layout, g);
     chk(gemm_launch(st, layout, g), "gemm_bf16");
+  }
+  // C[M,N] (bf16) = alpha * A * op(B) for a skinny N (the LoRA down-projections, N = a few ranks): the product is bound by
+  // reading A once, and with so few output tiles only a reduction split puts enough workgroups on the chip.  The
+  // slices add into a zeroed fp32 buffer (tmp32, [M, N]), which is then converted.
+  void gemm_skinny_bf16(int layout, const void* A, long lda, const void* B, long ldb, void* C, int M, int N, int K, float alpha,
+                        size_t tmp32_off) {
+    float* tmp = at<float>(tmp32_off);
+    mark("fill", 0, 4.0 * M * N);
+    chk(k_fill_u32(st, tmp, (long)M * N, 0u), "fill");
+    GemmArgs g; gemm_zero_args(g);
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = tmp; g.ldc = N; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
+    g.beta = 1; g.epi = EPI_F32;
+    mark_gemm(layout, g);
+    chk(gemm_launch(st, layout, g), "gemm_skinny");
+    mark("cast", 0, 6.0 * M * N);
+    chk(k_cast_f32_bf16(st, tmp, C, (long)M * N), "cast");
   }
   // Grouped GEMM over expert-sorted slot rows: C[slot, N] = A[row_map ? row_map[slot] : slot, K] * op(B_e), B_e the
   // matrix of the expert that owns the slot.  set = the layer's saved internals (routing plan).
@@ -227,11 +244,12 @@ const void* lora_b_matrix(Exec& X, const LayerW& W, const FusedLora& f, int N, s
 // Y[T,N] = X W^T (+ LoRA) (+ R).  u_buf receives U = s * X A^T (kept for the backward).
 void linear_fwd(Exec& X, const LayerW& W, int w_id, const FusedLora& f, size_t bd_off, const void* x, int K, void* y,
                 int N, void* u_buf, const void* R) {
+  const size_t skinny_off = X.fwd_only ? X.P.skinny_fwd : X.P.skinny_bwd;
   const int nr = f.n * X.D.r;
   const void* Bm = nullptr;
   if (f.n) {
     Bm = lora_b_matrix(X, W, f, N, bd_off);
-    X.gemm_bf16(GEMM_NT, x, K, W.t(f.a_id[0]), K, u_buf, nr, (int)X.T, nr, K, X.ctx->cfg.lora_scale);
+    X.gemm_skinny_bf16(GEMM_NT, x, K, W.t(f.a_id[0]), K, u_buf, (int)X.T, nr, K, X.ctx->cfg.lora_scale, skinny_off);
   }
   X.gemm_bf16(GEMM_NT, x, K, W.t(w_id), K, y, N, (int)X.T, N, K, 1.f, f.n ? u_buf : nullptr, nr, Bm, nr, f.n ? nr : 0, R, N);
 }
@@ -244,7 +262,7 @@ void linear_bwd(Exec& X, const LayerW& W, const LayerG& G, int w_id, const Fused
   const void* Bm = nullptr;
   if (f.n) {
     Bm = lora_b_matrix(X, W, f, N, bd_off);
-    X.gemm_bf16(GEMM_NN, dy, N, Bm, nr, ud, nr, (int)X.T, nr, N, X.ctx->cfg.lora_scale);
+    X.gemm_skinny_bf16(GEMM_NN, dy, N, Bm, nr, ud, (int)X.T, nr, N, X.ctx->cfg.lora_scale, X.P.skinny_bwd);
   }
   X.gemm_bf16(GEMM_NN, dy, N, W.t(w_id), K, dx, K, (int)X.T, K, N, 1.f, f.n ? ud : nullptr, nr, f.n ? W.t(f.a_id[0]) : nullptr,
               K, f.n ? nr : 0);
@@ -530,6 +548,7 @@ rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_o
   if (!x_in || !x_out || x_in == x_out) return fail(ctx, RP_EINVAL, "x_in / x_out must be distinct non-NULL buffers");
   Slot& sl = ctx->slots[slot_id];
   Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
+  X.fwd_only = true;
   const int L = ctx->cfg.n_layers;
   const size_t act_bytes = (size_t)X.T * X.D.h * 2;
   RUN(X, "rope_table", 0, 4.0 * seq * X.D.d, k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base));
