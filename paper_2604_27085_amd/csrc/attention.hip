@@ -794,7 +794,7 @@ hipError_t set_smem(K kern, int bytes, bool& done) {
   return e;
 }
 
-// Shape of the forward / dQ workgroup: 1 = 4 waves x 32 queries, 2 = 4 waves x 64 queries (RP_ATTN_FWD, RP_ATTN_DQ).
+// Reads a 1/2 switch from the environment (RP_ATTN_DKV: 1 = one dK/dV kernel, 2 = two kernels).
 int env_shape(const char* name, int dflt) {
   const char* s = getenv(name);
   const int v = s ? atoi(s) : dflt;
@@ -848,9 +848,9 @@ hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* 
   p.q = (const bf16*)q; p.k = (const bf16*)k; p.v = (const bf16*)v; p.o = (bf16*)o; p.lse = lse;
   p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.ldo = ldo;
   fill_common(p, batch, seq, a, kh, d);
-  static const int shape = env_shape("RP_ATTN_FWD", 1);
-  if (d == 128) return shape == 2 ? launch_fwd<128, 2, 4>(st, p) : launch_fwd<128, 1, 4>(st, p);
-  if (d == 64) return shape == 2 ? launch_fwd<64, 2, 4>(st, p) : launch_fwd<64, 1, 4>(st, p);
+  // workgroup = 4 waves x 32 queries; 64 queries per wave halve the LDS reads per MFMA but spill at d = 128
+  if (d == 128) return launch_fwd<128, 1, 4>(st, p);
+  if (d == 64) return launch_fwd<64, 1, 4>(st, p);
   return hipErrorInvalidValue;
 }
 
@@ -899,9 +899,7 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
     else { if ((e = launch_dkv<64, 0>(st, p, nk)) == hipSuccess) e = launch_dkv<64, 1>(st, p, nk); }
     return e;
   } else {
-    static const int shape = env_shape("RP_ATTN_DQ", 1);
-    if (d == 128) return shape == 2 ? launch_dq<128, 2, 4>(st, p) : launch_dq<128, 1, 4>(st, p);
-    return shape == 2 ? launch_dq<64, 2, 4>(st, p) : launch_dq<64, 1, 4>(st, p);
+    return d == 128 ? launch_dq<128, 1, 4>(st, p) : launch_dq<64, 1, 4>(st, p);
   }
   return hipGetLastError();
 }

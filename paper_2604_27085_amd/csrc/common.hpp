@@ -36,20 +36,6 @@ static RP_DEV uint32_t pack_bf16x2(float lo, float hi) {   // one v_cvt_pk_bf16_
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-// 8x8 transpose of bf16 held as 8 uint4 rows (row r = 8 consecutive columns) -> 8 uint4 (entry c = column c, rows 0..7)
-static RP_DEV void transpose8x8_bf16(const uint4 (&in)[8], uint4 (&out)[8]) {
-  const uint32_t* w = reinterpret_cast<const uint32_t*>(in);  // w[r*4 + j] holds columns 2j (lo), 2j+1 (hi) of row r
-  uint32_t* o = reinterpret_cast<uint32_t*>(out);             // o[c*4 + j] holds rows 2j (lo), 2j+1 (hi) of column c
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {      // column pair (2j, 2j+1)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {    // row pair (2i, 2i+1)
-      uint32_t a = w[(2 * i) * 4 + j], b = w[(2 * i + 1) * 4 + j];
-      o[(2 * j) * 4 + i] = (a & 0xffffu) | (b << 16);
-      o[(2 * j + 1) * 4 + i] = (a >> 16) | (b & 0xffff0000u);
-    }
-  }
-}
 
 static RP_DEV f32x16 mfma32(const uint4& a, const uint4& b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
