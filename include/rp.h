@@ -104,7 +104,10 @@ typedef enum {
 
 /* Creates a context for one stage shape on `device`.  compute_stream / copy_stream are hipStream_t
  * handles owned by the caller (both non-NULL, default priority).  Creates the per-slot, per-layer
- * events.  Errors: RP_EINVAL (NULL, struct_size mismatch), RP_EUNSUPPORTED (shape), RP_EHIP. */
+ * events.  Mixture-of-experts stages (n_experts > 0; the MoE layer of App. B.2): the top_k experts of every token are
+ * chosen from router logits the caller supplies; expert weights are frozen (train_base must be 0) and LoRA may adapt
+ * the attention projections only -- other combinations return RP_EUNSUPPORTED.
+ * Errors: RP_EINVAL (NULL, struct_size mismatch), RP_EUNSUPPORTED (shape), RP_EHIP. */
 RP_API rp_status rp_ctx_create(rp_ctx** out, int device, void* compute_stream, void* copy_stream, const rp_stage_cfg* cfg);
 
 /* Destroys events and frees the context.  The caller must have synchronised both streams. */
@@ -161,7 +164,8 @@ RP_API rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, vo
  * dy [dev] bf16 [T, h]: gradient of the stage output;  dx [dev] bf16 [T, h]: overwritten with the gradient of x_in;
  * x_out [dev] bf16 [T, h] or NULL: receives the recomputed stage output;  grads [dev]: fp32 gradient blob,
  * ACCUMULATED (+=) -- the in-place accumulation over micro-batches of Sec. 4.1.1;  router_logits / d_router_logits
- * [dev] fp32 [n_layers, T, E] (MoE only; the latter is overwritten).  dy, dx, grads are ignored by RECOMPUTE alone,
+ * [dev] fp32 [n_layers, T, E] (MoE only; the latter may be NULL, else it is overwritten with the gradient of the
+ * router logits: w_e (dw_e - sum_e' w_e' dw_e') on the selected experts, zero elsewhere).  dy, dx, grads are ignored by RECOMPUTE alone,
  * x_out by BACKWARD alone.  Errors as rp_stage_forward. */
 RP_API rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_in, const void* dy, void* dx,
                             void* x_out, void* grads, const float* router_logits, float* d_router_logits, int batch,
