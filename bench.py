@@ -42,7 +42,8 @@ def fl_gemm_fwd(c):
     h, d, m = c["hidden"], c["head_dim"], c["ffn"]
     qd, kd = c["n_q_heads"] * d, c["n_kv_heads"] * d
     ffn_rows = T * c["top_k"] if c["n_experts"] else T
-    return 2.0 * T * (h * (qd + 2 * kd) + qd * h) + 2.0 * ffn_rows * (h * 2 * m + m * h)
+    router = 2.0 * T * c["n_experts"] * h if c.get("moe_router") else 0.0
+    return 2.0 * T * (h * (qd + 2 * kd) + qd * h) + 2.0 * ffn_rows * (h * 2 * m + m * h) + router
 
 
 def measured_traffic(workload, kernel):
@@ -127,6 +128,8 @@ def main():
     router = None
     if wl.get("router_logits") is not None:
         router = torch.from_numpy(np.stack(wl["router_logits"])).to(R.device)
+    elif c.get("moe_router"):      # the stage computes the logits into this buffer
+        router = torch.empty((c["n_layers"], R.T, c["n_experts"]), dtype=torch.float32, device=R.device)
     d_router = torch.empty_like(router) if router is not None else None
     out = torch.empty_like(x)
     dx = torch.empty_like(x)
@@ -268,10 +271,10 @@ def main():
         "value": round(T / (ms_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "%s: %d Qwen3-shaped decoder layers (h=%d, %d/%d heads x %d, ffn %d%s)%s, batch %d x seq %d, "
+        "config": {"workload": "%s: %d decoder layers (h=%d, %d/%d heads x %d, ffn %d%s)%s, batch %d x seq %d, "
                                "%s" % (args.config, c["n_layers"], c["hidden"], c["n_q_heads"], c["n_kv_heads"],
                                        c["head_dim"], c["ffn"],
-                                       " x %d experts, top-%d" % (c["n_experts"], c["top_k"]) if c["n_experts"] else "",
+                                       " x %d experts, top-%d%s" % (c["n_experts"], c["top_k"], ", router in the layer" if c.get("moe_router") else "") if c["n_experts"] else "",
                                        " + LM head V=%d with cross-entropy" % c["vocab"] if has_head else "",
                                        c["batch"], c["seq"],
                                        "full fine-tune, fp32 weight gradients" if c["train_base"] else "frozen base, LoRA r=%d" % c["lora_rank"]),

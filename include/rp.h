@@ -77,6 +77,8 @@ typedef struct {
   float lora_scale;    /* s in y = x W^T + s (x A^T) B^T */
   uint32_t lora_mask;  /* RP_LORA_* bits */
   int32_t train_base;  /* 1: base weights and norm gains receive fp32 gradients; 0: frozen */
+  int32_t moe_router;  /* MoE only.  1: the layer chunk holds the router Wr [E, h] and the stage computes the router
+                          logits n2 Wr^T itself (fp32);  0: the caller supplies the logits */
 } rp_stage_cfg;
 
 /* Tensor ids inside one layer's chunk of the weight blob (and of the gradient blob). */
@@ -89,6 +91,7 @@ typedef enum {
   RP_T_G2,       /* [h]                 post-attention RMSNorm gain */
   RP_T_WGU,      /* dense [2m, h]: gate rows then up rows;  MoE [E, 2m, h] */
   RP_T_WD,       /* dense [h, m];  MoE [E, h, m] */
+  RP_T_WR,       /* [E, h]              router (present only with moe_router) */
   RP_T_LA_Q, RP_T_LA_K, RP_T_LA_V,          /* LoRA A [r, h]  (enabled ones are adjacent)      */
   RP_T_LB_Q, RP_T_LB_K, RP_T_LB_V,          /* LoRA B [a*d, r], [k*d, r], [k*d, r]             */
   RP_T_LA_O, RP_T_LB_O,                     /* [r, a*d], [h, r]                                */
@@ -150,11 +153,12 @@ RP_API rp_status rp_stage_bind_weights(rp_ctx* ctx, int slot_id, void* dev_slot,
 /* Forward stage (Sec. 3.2): x_out = layers(x_in).  x_in, x_out [dev] bf16 [T, h] (may not alias).
  * layer_inputs_out [host array of n_layers dev pointers, or NULL]: entry l, when non-NULL, receives a copy of the
  * input of layer l (the activation checkpoint kept under full recomputation, Sec. 2.1.1).
- * router_logits [dev] fp32 [n_layers, T, E] for MoE stages, else NULL.
+ * router_logits [dev] fp32 [n_layers, T, E] for MoE stages, else NULL: read when the caller supplies the logits,
+ * overwritten with the logits the stage computed when cfg.moe_router is set (the library keeps no copy of its own).
  * Waits on the slot's per-layer upload events.  workspace [dev], at least workspace_bytes of rp_query_sizes.
  * Errors: RP_EINVAL, RP_ENOMEM (workspace), RP_ESTATE (slot not uploaded), RP_EHIP. */
 RP_API rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_out, void* const* layer_inputs_out,
-                           const float* router_logits, int batch, int seq, void* workspace, size_t workspace_bytes);
+                           float* router_logits, int batch, int seq, void* workspace, size_t workspace_bytes);
 
 /* Backward stage with recomputation (Sec. 3.2; App. C.3).  Phase RP_PHASE_RECOMPUTE re-runs the forward from the
  * stored stage input x_in keeping every layer's internals in the workspace; phase RP_PHASE_BACKWARD runs the backward
@@ -165,10 +169,11 @@ RP_API rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, vo
  * x_out [dev] bf16 [T, h] or NULL: receives the recomputed stage output;  grads [dev]: fp32 gradient blob,
  * ACCUMULATED (+=) -- the in-place accumulation over micro-batches of Sec. 4.1.1;  router_logits / d_router_logits
  * [dev] fp32 [n_layers, T, E] (MoE only; the latter may be NULL, else it is overwritten with the gradient of the
- * router logits: w_e (dw_e - sum_e' w_e' dw_e') on the selected experts, zero elsewhere).  dy, dx, grads are ignored by RECOMPUTE alone,
- * x_out by BACKWARD alone.  Errors as rp_stage_forward. */
+ * router logits: w_e (dw_e - sum_e' w_e' dw_e') on the selected experts, zero elsewhere).  With cfg.moe_router the
+ * RECOMPUTE phase writes router_logits, and the BACKWARD phase adds dlogits Wr to the gradient of n2.
+ * dy, dx, grads are ignored by RECOMPUTE alone, x_out by BACKWARD alone.  Errors as rp_stage_forward. */
 RP_API rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_in, const void* dy, void* dx,
-                            void* x_out, void* grads, const float* router_logits, float* d_router_logits, int batch,
+                            void* x_out, void* grads, float* router_logits, float* d_router_logits, int batch,
                             int seq, void* workspace, size_t workspace_bytes);
 
 /* LM head fused with the mean cross-entropy, forward and backward in one call (the oversized last stage, Sec. 2.3;

@@ -23,6 +23,7 @@ class StageConfig:
     lora_scale: float = 1.0
     lora_targets: Tuple[str, ...] = field(default_factory=tuple)
     train_base: bool = True
+    moe_router: bool = False   # MoE: the layer holds the router Wr [E, h]; logits = n2 Wr^T instead of being an input
 
     @property
     def qd(self):

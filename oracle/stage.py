@@ -11,7 +11,9 @@ Gradients accumulate in place across micro-batches (Sec. 4.1.1).
 Per-layer parameters are a dict:
   g1, g2 [h]; Wq [qd,h]; Wk, Wv [kd,h]; Wo [h,qd]; gq, gk [d] (when cfg.qk_norm)
   dense:  Wg, Wu [m,h]; Wd [h,m]
-  MoE:    Wg, Wu [E,m,h]; Wd [E,h,m]   (router logits are an input of the layer)
+  MoE:    Wg, Wu [E,m,h]; Wd [E,h,m]   (router logits are an input of the layer, or, with cfg.moe_router,
+          logits = n2 Wr^T with the router Wr [E,h] a parameter of the layer: the "top-k softmax router" of the
+          MoE layer in App. B.2 taken as one linear map of the normalised activation)
   lora:   {name: (A [r,in], B [out,r])} for name in cfg.lora_targets
 """
 import numpy as np
@@ -48,6 +50,9 @@ def layer_fwd(x, p, cfg, batch, seq, router_logits=None):
     n2, c["rstd2"] = L.rmsnorm_fwd(y, p["g2"], cfg.rms_eps)
     c["n2"] = n2
     if cfg.n_experts > 0:
+        if cfg.moe_router:
+            router_logits = n2 @ p["Wr"].T
+        c["logits"] = router_logits
         f, c["route"] = L.moe_ffn_fwd(n2, p["Wg"], p["Wu"], p["Wd"], router_logits, cfg.top_k)
         z = y + f
     else:
@@ -82,6 +87,10 @@ def layer_bwd(dz, c, p, cfg, batch, seq):
     if cfg.n_experts > 0:
         dn2, dlog, dWs = L.moe_ffn_bwd(dz, c["n2"], p["Wg"], p["Wu"], p["Wd"], c["route"], want_dW=tb)
         g["router_logits"] = dlog
+        if cfg.moe_router:
+            dn2 = dn2 + dlog @ p["Wr"]
+            if tb:
+                g["Wr"] = dlog.T @ c["n2"]
         if tb:
             g["Wg"], g["Wu"], g["Wd"] = dWs
     else:
@@ -107,17 +116,20 @@ def layer_bwd(dz, c, p, cfg, batch, seq):
     return dx, g
 
 
-def stage_fwd(x, params, cfg, batch, seq, router_logits=None):
-    """Forward of layers params[0..L-1].  Returns the boundary activation and the list of each layer's input."""
+def stage_fwd(x, params, cfg, batch, seq, router_logits=None, logits_out=None):
+    """Forward of layers params[0..L-1].  Returns the boundary activation and the list of each layer's input.
+    logits_out: optional list that receives every MoE layer's router logits."""
     layer_inputs = []
     for li, p in enumerate(params):
         layer_inputs.append(x)
         rl = None if router_logits is None else router_logits[li]
-        x, _ = layer_fwd(x, p, cfg, batch, seq, rl)
+        x, c = layer_fwd(x, p, cfg, batch, seq, rl)
+        if logits_out is not None:
+            logits_out.append(c.get("logits"))
     return x, layer_inputs
 
 
-def stage_fwd_bwd(x_in, dy, params, cfg, batch, seq, router_logits=None):
+def stage_fwd_bwd(x_in, dy, params, cfg, batch, seq, router_logits=None, logits_out=None):
     """Backward stage with recomputation: forward keeping internals, then backward in reverse order.
     Returns the stage output, dx and the per-layer gradient dicts."""
     caches = []
@@ -125,6 +137,8 @@ def stage_fwd_bwd(x_in, dy, params, cfg, batch, seq, router_logits=None):
     for li, p in enumerate(params):
         rl = None if router_logits is None else router_logits[li]
         x, c = layer_fwd(x, p, cfg, batch, seq, rl)
+        if logits_out is not None:
+            logits_out.append(c.get("logits"))
         caches.append(c)
     out = x
     grads = [None] * len(params)

@@ -16,7 +16,7 @@ LORA_BITS = {"q": 1, "k": 2, "v": 4, "o": 8, "gate": 16, "up": 32, "down": 64}
 GEMM_NT, GEMM_NN, GEMM_TN = 0, 1, 2
 PHASE_RECOMPUTE, PHASE_BACKWARD, PHASE_BOTH = 1, 2, 3
 
-TENSOR_IDS = ["G1", "WQKV", "GQ", "GK", "WO", "G2", "WGU", "WD", "LA_Q", "LA_K", "LA_V", "LB_Q", "LB_K", "LB_V",
+TENSOR_IDS = ["G1", "WQKV", "GQ", "GK", "WO", "G2", "WGU", "WD", "WR", "LA_Q", "LA_K", "LA_V", "LB_Q", "LB_K", "LB_V",
               "LA_O", "LB_O", "LA_GATE", "LA_UP", "LB_GATE", "LB_UP", "LA_DOWN", "LB_DOWN", "GF", "WV"]
 T = {name: i for i, name in enumerate(TENSOR_IDS)}
 
@@ -26,7 +26,7 @@ class StageCfg(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32),
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("rope_base", C.c_float), ("rms_eps", C.c_float),
                 ("qk_norm", C.c_int32), ("lora_rank", C.c_int32), ("lora_scale", C.c_float), ("lora_mask", C.c_uint32),
-                ("train_base", C.c_int32)]
+                ("train_base", C.c_int32), ("moe_router", C.c_int32)]
 
 
 class TraceRecord(C.Structure):
@@ -110,12 +110,13 @@ def _check(code, ctx=None):
 
 
 def make_cfg(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab=0, n_experts=0, top_k=0, rope_base=1.0e6,
-             rms_eps=1.0e-6, qk_norm=1, lora_rank=0, lora_scale=1.0, lora=(), train_base=1):
+             rms_eps=1.0e-6, qk_norm=1, lora_rank=0, lora_scale=1.0, lora=(), train_base=1, moe_router=0):
     mask = 0
     for name in lora:
         mask |= LORA_BITS[name]
     return StageCfg(C.sizeof(StageCfg), n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, n_experts, top_k,
-                    rope_base, rms_eps, int(qk_norm), lora_rank, lora_scale, mask if lora_rank > 0 else 0, int(train_base))
+                    rope_base, rms_eps, int(qk_norm), lora_rank, lora_scale, mask if lora_rank > 0 else 0, int(train_base),
+                    int(moe_router))
 
 
 # ---- rp.h ---------------------------------------------------------------------------------------------------------

@@ -38,6 +38,7 @@ inline size_t tensor_elems(const rp_stage_cfg& c, int id) {
     case RP_T_WO: return (size_t)D.h * D.qd;
     case RP_T_WGU: return e * 2 * D.m * D.h;
     case RP_T_WD: return e * (size_t)D.h * D.m;
+    case RP_T_WR: return (D.E > 0 && c.moe_router) ? (size_t)D.E * D.h : 0;
     case RP_T_LA_Q: return D.lora[0] ? r * D.h : 0;
     case RP_T_LA_K: return D.lora[1] ? r * D.h : 0;
     case RP_T_LA_V: return D.lora[2] ? r * D.h : 0;
@@ -102,6 +103,7 @@ struct Plan {
   size_t tA, tB, dact, dgu, dn, dout, dqr, dkr, dqkv, delta, ud, partials;   // backward temporaries
   size_t moe_f_fwd, moe_f_bwd;   // expert outputs / expert input gradients per slot [T*top_k, h] (transient in a layer)
   size_t moe_wslot, moe_dw;      // routing weight per slot, its gradient per slot (backward)
+  size_t moe_dlog, moe_dlog16;   // router in the stage: gradient of the logits fp32 [T, E] and its bf16 copy
   int moe_max_tiles;             // capacity of the tile table
   size_t skinny_fwd, skinny_bwd;   // fp32 [T, 3r]: a skinny LoRA product before its conversion to bf16
   size_t dkvp;   // per-query-head dK/dV partials of grouped attention; shares memory with dact|dgu, dead by then
@@ -155,6 +157,7 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   o += set * (size_t)(D.L > 0 ? D.L : 0);
   P.tA = take(T * D.h * 2); P.tB = take(T * D.h * 2); P.dact = take(Tk * D.m * 2); P.dgu = take(Tk * 2 * D.m * 2);
   if (D.E > 0) { P.moe_f_bwd = take(Tk * D.h * 2); P.moe_wslot = take(Tk * 4); P.moe_dw = take(Tk * 4); }
+  if (D.E > 0 && c.moe_router) { P.moe_dlog = take(T * D.E * 4); P.moe_dlog16 = take(T * D.E * 2); }
   P.dkvp = P.dact;
   if (D.a != D.kh && P.dkvp + 2 * T * D.qd * 4 > o) take(P.dkvp + 2 * T * D.qd * 4 - o);
   P.dn = take(T * D.h * 2); P.dout = take(T * D.qd * 2); P.dqr = take(T * D.qd * 2); P.dkr = take(T * D.kd * 2);

@@ -85,6 +85,9 @@ rp_status validate_cfg(const rp_stage_cfg* c, rp_ctx* ctx) {
     if (c->n_experts < 0 || c->top_k < 0 || (c->n_experts > 0 && (c->top_k <= 0 || c->top_k > c->n_experts))) return fail(ctx, RP_EINVAL, "bad n_experts/top_k");
     if (c->n_experts > 1024 || c->top_k > 64) return fail(ctx, RP_EUNSUPPORTED, "at most 1024 experts and top_k 64");
     if (c->n_experts > 0 && c->train_base) return fail(ctx, RP_EUNSUPPORTED, "expert weights are frozen in this build: train_base must be 0 for MoE stages");
+    if (c->moe_router != 0 && c->moe_router != 1) return fail(ctx, RP_EINVAL, "moe_router must be 0 or 1");
+    if (c->moe_router && c->n_experts == 0) return fail(ctx, RP_EINVAL, "moe_router needs n_experts > 0");
+    if (c->moe_router && c->n_experts % 8) return fail(ctx, RP_EUNSUPPORTED, "with moe_router, n_experts must be a multiple of 8");
     if (c->n_experts > 0 && c->lora_rank > 0 && (c->lora_mask & (RP_LORA_GATE | RP_LORA_UP | RP_LORA_DOWN))) return fail(ctx, RP_EUNSUPPORTED, "LoRA on expert projections is not implemented");
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 1.f)) return fail(ctx, RP_EINVAL, "bad rms_eps / rope_base");
   }
@@ -121,7 +124,8 @@ struct Exec {
   hipError_t err = hipSuccess;
   const char* where = "";
   bool fwd_only = false;           // the forward-stage plan of the workspace is in use (rp_stage_forward)
-  const float* router = nullptr;   // router logits of the layer being run, fp32 [T, E] (mixture of experts)
+  float* router = nullptr;         // router logits of the layer being run, fp32 [T, E] (mixture of experts): read, or
+                                   // written first when the stage holds the router weights
   float* d_router = nullptr;       // their gradient (optional)
 
   void chk(hipError_t e, const char* w) { if (err == hipSuccess && e != hipSuccess) { err = e; where = w; } }
@@ -192,6 +196,13 @@ struct Exec {
       mark(nm, 2.0 * Tk * (double)N * K, 2.0 * ((double)Tk * K + (double)D.E * N * K) + 2.0 * Tk * (double)N);
     }
     chk(gemm_launch(st, layout, g), "gemm_grouped");
+  }
+  // C[M,N] (fp32) = A * B^T, overwritten; one pass, no reduction split, so the result does not depend on scheduling
+  void gemm_f32_nt(const void* A, long lda, const void* B, long ldb, float* C, long ldc, int M, int N, int K) {
+    GemmArgs g; gemm_zero_args(g);
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.beta = 0; g.epi = EPI_F32;
+    mark_gemm(GEMM_NT, g);
+    chk(gemm_launch(st, GEMM_NT, g), "gemm_f32_nt");
   }
   // C[M,N] (fp32) (+)= A^T * B : weight-gradient form, reduction over the rows of A and B
   void gemm_wgrad(const void* A, long lda, const void* B, long ldb, float* C, long ldc, int M, int N, int K) {
@@ -307,6 +318,8 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z, 
     float* w = (float*)S(b.m_w);
     int* slot_of = (int*)S(b.m_slot);
     void* f = X.at<void>(moe_f_off);
+    // router in the stage: logits = n2 Wr^T in fp32 (bf16 operands), so that the selection is a function of n2 alone
+    if (c.moe_router) X.gemm_f32_nt(S(b.n2), D.h, W.t(RP_T_WR), D.h, X.router, D.E, T, D.E, D.h);
     RUN(X, "moe_route", 0, 4.0 * Td * D.E + 8.0 * Tkd, k_moe_route(X.st, X.router, idx, w, T, D.E, D.topk));
     RUN(X, "moe_plan", 0, 8.0 * Tkd * D.E, k_moe_plan(X.st, idx, T, D.E, D.topk, (int*)S(b.m_cnt), (int*)S(b.m_seg), S(b.m_tab),
                                                      (int*)S(b.m_ntiles), slot_of, (int*)S(b.m_tok)));
@@ -348,12 +361,20 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
     RUN(X, "moe_scatter_w", 0, 12.0 * Tkd, k_moe_scatter_w(X.st, w, slot_of, w_slot, Tk));
     RUN(X, "moe_swiglu_bwd", 0, 10.0 * Tkd * D.m,
         k_moe_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), w_slot, X.at<void>(X.P.dgu), dw_slot, Tk, D.m));
-    if (X.d_router)
-      RUN(X, "moe_dlogits", 0, 4.0 * Td * D.E + 12.0 * Tkd, k_moe_dlogits(X.st, idx, w, slot_of, dw_slot, X.d_router, T, D.E, D.topk));
+    float* dlog = X.d_router ? X.d_router : (c.moe_router ? X.at<float>(X.P.moe_dlog) : nullptr);
+    if (dlog)
+      RUN(X, "moe_dlogits", 0, 4.0 * Td * D.E + 12.0 * Tkd, k_moe_dlogits(X.st, idx, w, slot_of, dw_slot, dlog, T, D.E, D.topk));
     X.gemm_grouped(GEMM_NN, set, X.at<void>(X.P.dgu), 2 * D.m, (int)Tk, false, W.t(RP_T_WGU), D.h, (long)2 * D.m * D.h, dxp, D.h,
                    D.h, 2 * D.m);
     RUN(X, "moe_combine", 0, 2.0 * Tkd * D.h + 2.0 * Td * D.h,
         k_moe_combine(X.st, dxp, slot_of, nullptr, nullptr, X.at<void>(X.P.dn), T, D.h, D.topk));
+    if (c.moe_router) {
+      // logits = n2 Wr^T: the gradient of n2 gains dlogits Wr (bf16 operands like every activation gradient)
+      void* dl16 = X.at<void>(X.P.moe_dlog16);
+      RUN(X, "cast", 0, 6.0 * Td * D.E, k_cast_f32_bf16(X.st, dlog, dl16, (long)T * D.E));
+      X.gemm_bf16(GEMM_NN, dl16, D.E, W.t(RP_T_WR), D.h, X.at<void>(X.P.dn), D.h, T, D.h, D.E, 1.f, nullptr, 0, nullptr, 0, 0,
+                  X.at<void>(X.P.dn), D.h);
+    }
   } else {
     // z = y + down(act)
     linear_bwd(X, W, G, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, dz, D.h, S(b.act), D.m,
@@ -538,7 +559,7 @@ rp_status rp_stage_bind_weights(rp_ctx* ctx, int slot_id, void* dev_slot, size_t
 }
 
 rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_out, void* const* layer_inputs_out,
-                           const float* router_logits, int batch, int seq, void* workspace, size_t workspace_bytes_in) {
+                           float* router_logits, int batch, int seq, void* workspace, size_t workspace_bytes_in) {
   if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
   if (ctx->cfg.n_layers == 0) return fail(ctx, RP_EINVAL, "stage has no decoder layers");
   if (ctx->cfg.n_experts > 0 && !router_logits) return fail(ctx, RP_EINVAL, "MoE stage needs router_logits");
@@ -569,7 +590,7 @@ rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_o
 }
 
 rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_in, const void* dy, void* dx, void* x_out,
-                            void* grads, const float* router_logits, float* d_router_logits, int batch, int seq,
+                            void* grads, float* router_logits, float* d_router_logits, int batch, int seq,
                             void* workspace, size_t workspace_bytes_in) {
   if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
   if (ctx->cfg.n_layers == 0) return fail(ctx, RP_EINVAL, "stage has no decoder layers");

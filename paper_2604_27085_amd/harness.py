@@ -24,7 +24,8 @@ def cfg_from_dict(c, with_head=None, n_layers=None):
                       n_q_heads=c["n_q_heads"], n_kv_heads=c["n_kv_heads"], head_dim=c["head_dim"], ffn=c["ffn"],
                       vocab=vocab, n_experts=c["n_experts"], top_k=c["top_k"], rope_base=c.get("rope_base", 1.0e6),
                       rms_eps=c.get("rms_eps", 1.0e-6), qk_norm=c.get("qk_norm", 1), lora_rank=c["lora_rank"],
-                      lora_scale=c.get("lora_scale", 1.0), lora=c["lora"], train_base=c["train_base"])
+                      lora_scale=c.get("lora_scale", 1.0), lora=c["lora"], train_base=c["train_base"],
+                      moe_router=c.get("moe_router", 0))
 
 
 def _layer_tensors(p, cfg):
@@ -35,6 +36,8 @@ def _layer_tensors(p, cfg):
         out["GQ"], out["GK"] = p["gq"], p["gk"]
     if cfg.n_experts > 0:
         out["WGU"] = np.concatenate([p["Wg"], p["Wu"]], axis=1)      # [E, 2m, h]
+        if cfg.moe_router:
+            out["WR"] = p["Wr"]
     else:
         out["WGU"] = np.concatenate([p["Wg"], p["Wu"]], axis=0)      # [2m, h]
     for name, (A, Bm) in p.get("lora", {}).items():
@@ -151,7 +154,8 @@ class StageRunner:
         B.rp_stage_bind_weights(self.ctx, slot, self.slots[slot], self.wbytes)
 
     def forward(self, x, slot=0, keep_layer_inputs=False, router=None):
-        """router: fp32 device tensor [n_layers, T, E] of router logits (MoE stages)."""
+        """router: fp32 device tensor [n_layers, T, E] of router logits (MoE stages): input, or with cfg.moe_router the
+        buffer that receives the logits the stage computes."""
         out = torch.empty_like(x)
         keep = None
         if keep_layer_inputs:

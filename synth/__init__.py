@@ -4,9 +4,10 @@ Data only: this module draws random numbers, rounds them to bf16 (round-to-neare
 arithmetic) and names the workload shapes.  It contains none of the method's arithmetic and imports
 neither the oracle nor the HIP package.
 
-The workloads are the five synthetic Qwen3-shaped stage configurations this build is measured on
-(shapes after the paper's Table "Model Configs"); weights N(0, 0.02), LoRA A N(0, 0.02), LoRA B
-N(0, 0.01), norm gains 1, token ids uniform, labels = next token.
+The workloads are the synthetic stage configurations this build is measured on (shapes after the
+paper's Table "Model Configs": five Qwen3-shaped ones and a GPT-OSS-20B-shaped mixture of experts
+whose router is part of the layer); weights N(0, 0.02), LoRA A N(0, 0.02), LoRA B N(0, 0.01), norm
+gains 1, token ids uniform, labels = next token.
 """
 import numpy as np
 
@@ -30,6 +31,11 @@ CONFIGS = {
     "C5": dict(n_layers=1, hidden=4096, n_q_heads=64, n_kv_heads=4, head_dim=128, ffn=1536, vocab=0,
                n_experts=128, top_k=8, lora_rank=8, lora=("q", "k", "v", "o"), train_base=0, batch=1,
                seq=31744, x_from="normal", stream=1),
+    # GPT-OSS-20B row of the table: h = m = 2880 (not a multiple of the 256-wide GEMM tiles), 4 of 32 experts,
+    # router weights in the layer
+    "C6": dict(n_layers=4, hidden=2880, n_q_heads=64, n_kv_heads=8, head_dim=64, ffn=2880, vocab=0,
+               n_experts=32, top_k=4, lora_rank=8, lora=("q", "k", "v", "o"), train_base=0, batch=1,
+               seq=8192, x_from="normal", stream=1, moe_router=1),
 }
 ROPE_BASE = 1.0e6
 RMS_EPS = 1.0e-6
@@ -83,6 +89,8 @@ def make_layer(rng, c, gains_random=False):
         p["Wg"] = _normal(rng, (m, h), 0.02)
         p["Wu"] = _normal(rng, (m, h), 0.02)
         p["Wd"] = _normal(rng, (h, m), 0.02)
+    if E > 0 and c.get("moe_router"):
+        p["Wr"] = _normal(rng, (E, h), 0.02)
     r = c["lora_rank"]
     p["lora"] = {}
     if r > 0:
@@ -104,7 +112,7 @@ def make_head(rng, c, gains_random=False):
 def make_workload(c, seed, gains_random=False, with_head=None):
     """Draws everything one stage call needs.  Returns a dict:
     layers (list of layer dicts), head (or None), x [T,h], dy [T,h], labels int32 [T] (or None),
-    router_logits (list of fp32 [T,E] per layer, or None)."""
+    router_logits (list of fp32 [T,E] per layer; None for dense stages and for stages that hold their router)."""
     rng = np.random.default_rng(seed)
     T = c["batch"] * c["seq"]
     h = c["hidden"]
@@ -127,9 +135,33 @@ def make_workload(c, seed, gains_random=False, with_head=None):
             labels = rng.integers(0, c["vocab"], size=T, dtype=np.int64).astype(np.int32)
     dy = _normal(rng, (T, h), 1.0)
     router = None
-    if c["n_experts"] > 0:
+    if c["n_experts"] > 0 and not c.get("moe_router"):      # else the layers hold a router and compute the logits
         router = [rng.standard_normal((T, c["n_experts"]), dtype=np.float32) for _ in range(c["n_layers"])]
     return dict(layers=layers, head=head, x=np.ascontiguousarray(x), dy=dy, labels=labels, router_logits=router)
+
+
+def plant_routing(wl, c, seed, beta=0.25, level0=8.0, step=2.0, noise=0.002):
+    """Rewrites a drawn workload so that every token has a decisive router preference (a trained router's logits are
+    well separated; independent normal draws have near-ties that make the chosen expert set depend on the last bit).
+    Token t gets top_k hidden coordinates set to the levels level0, level0+step, ...; layer l's router row of expert e
+    is beta on coordinate perm_l[e] plus N(0, noise).  The residual stream carries the planted coordinates through the
+    layers, so the gaps between the logits stay near beta*step/rms(x).  Data only: nothing here evaluates the layer."""
+    rng = np.random.default_rng(seed + 7919)
+    E, k, h = c["n_experts"], c["top_k"], c["hidden"]
+    assert c.get("moe_router") and h >= E
+    T = wl["x"].shape[0]
+    x = wl["x"].copy()
+    x[:, :E] = bf16_round(0.5 * x[:, :E])
+    levels = (level0 + step * np.arange(k)).astype(np.float32)
+    for t in range(T):
+        x[t, rng.permutation(E)[:k]] = levels
+    wl["x"] = bf16_round(x)
+    for p in wl["layers"]:
+        Wr = rng.standard_normal((E, h), dtype=np.float32) * np.float32(noise)
+        perm = rng.permutation(E)
+        Wr[np.arange(E), perm] = beta
+        p["Wr"] = bf16_round(Wr)
+    return wl
 
 
 def shrink(c, **over):

@@ -9,7 +9,7 @@ def oracle_cfg(c):
                        head_dim=c["head_dim"], ffn=c["ffn"], vocab=c["vocab"], n_experts=c["n_experts"], top_k=c["top_k"],
                        rope_base=c.get("rope_base", 1.0e6), rms_eps=c.get("rms_eps", 1.0e-6), qk_norm=bool(c.get("qk_norm", 1)),
                        lora_rank=c["lora_rank"], lora_scale=c.get("lora_scale", 1.0), lora_targets=tuple(c["lora"]),
-                       train_base=bool(c["train_base"]))
+                       train_base=bool(c["train_base"]), moe_router=bool(c.get("moe_router", 0)))
 
 
 def cast_tree(obj, dtype):
@@ -43,8 +43,11 @@ def oracle_chain(c, wl, dtype=np.float64, grad_scale=1.0):
     else:
         dy = wl["dy"].astype(dtype)
     if c["n_layers"] > 0:
-        out, dx, grads = stage.stage_fwd_bwd(x, dy, layers, cfg, c["batch"], c["seq"], router)
+        logits = []
+        out, dx, grads = stage.stage_fwd_bwd(x, dy, layers, cfg, c["batch"], c["seq"], router, logits_out=logits)
         res.update(out=out, dx=dx, grads=grads)
+        if cfg.moe_router:
+            res["logits"] = logits
     return res
 
 
@@ -64,6 +67,9 @@ def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True):
         router = d_router = None
         if wl.get("router_logits") is not None:
             router = torch.from_numpy(np.stack(wl["router_logits"])).to(R.device)
+            d_router = torch.full_like(router, float("nan"))
+        elif c.get("moe_router"):     # the stage computes the logits into this buffer
+            router = torch.full((c["n_layers"], R.T, c["n_experts"]), float("nan"), dtype=torch.float32, device=R.device)
             d_router = torch.full_like(router, float("nan"))
         torch.cuda.synchronize()
         res = {}
@@ -86,6 +92,8 @@ def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True):
             res.update(out=harness.to_f32(out2), dx=harness.to_f32(dx))
             if d_router is not None:
                 res["d_router"] = d_router.cpu().numpy()
+            if c.get("moe_router"):
+                res["logits"] = router.cpu().numpy()
         R.sync()
         layer_g, head_g = harness.unpack_grads(cfg, R.grads)
         res.update(grads=layer_g, head_grads=head_g)
@@ -106,6 +114,8 @@ def compare_chain(ref, got, c, tol=2e-2, loss_tol=1e-4, report=None):
     if "out" in ref:
         errs["out"] = rel_l2(got["out"], ref["out"])
         errs["dx"] = rel_l2(got["dx"], ref["dx"])
+        for li, lg in enumerate(ref.get("logits", [])):
+            errs["L%d.logits" % li] = rel_l2(got["logits"][li], lg)
         for li, g in enumerate(ref["grads"]):
             gg = got["grads"][li]
             for k, v in g.items():

@@ -158,6 +158,64 @@ def test_moe_stage_matches_oracle(hz, name):
         assert np.array_equal(got["d_router"][li] == 0.0, ref["grads"][li]["router_logits"] == 0.0)
 
 
+ROUTER_VARIANTS = {
+    # the GPT-OSS-20B row scaled down: hidden and FFN width not multiples of the GEMM tiles (360 = 1.4 x 256), 4 of 32
+    # experts, head_dim 64, eight query heads per kv head; two layers so that the second router sees a computed stream
+    "oss_like": dict(n_layers=2, hidden=360, n_q_heads=8, n_kv_heads=1, head_dim=64, ffn=360, vocab=0, n_experts=32,
+                     top_k=4, lora_rank=8, lora=("q", "k", "v", "o"), train_base=0, batch=1, seq=1032, x_from="normal",
+                     moe_router=1),
+    "e8": dict(n_layers=1, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=96, vocab=0, n_experts=8, top_k=2,
+               lora_rank=0, lora=(), train_base=0, batch=2, seq=136, x_from="normal", moe_router=1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(ROUTER_VARIANTS))
+def test_moe_router_in_stage_matches_oracle(hz, name):
+    """Router weights in the layer: logits = n2 Wr^T computed by the stage, selection from them, and the gradient of the
+    logits flowing back into n2.  The input has a planted, decisive preference per token, and the test first checks on
+    the oracle's logits that every gap that decides the selection is far above the bf16 error of the logits -- then
+    both sides must select the same experts, and everything is compared as for the other stages."""
+    c = ROUTER_VARIANTS[name]
+    seed = 1300 + sorted(ROUTER_VARIANTS).index(name)
+    wl = synth.plant_routing(synth.make_workload(c, seed, gains_random=True), c, seed)
+    ref = pu.oracle_chain(c, wl)
+    k = c["top_k"]
+    for lg in ref["logits"]:
+        srt = -np.sort(-lg, axis=1)
+        assert np.min(srt[:, k - 1] - srt[:, k]) > 0.05, "planted routing is not decisive"
+    got = pu.gpu_chain(c, wl, hz)
+    errs = pu.compare_chain(ref, got, c)
+    assert len(errs) == 2 + c["n_layers"] * (2 + 2 * len(c["lora"])), sorted(errs)
+    for li in range(c["n_layers"]):
+        assert np.array_equal(got["d_router"][li] != 0.0, ref["grads"][li]["router_logits"] != 0.0)
+
+
+def test_moe_router_in_stage_selection_is_topk_of_its_own_logits(hz):
+    """Unstructured random router and input: near-ties exist, so the expert sets of the two sides may differ on a few
+    tokens.  What is unique is checked -- the logits (floating point, within the bound) -- and the rest is checked for
+    validity: the experts the stage selected (the non-zero pattern of the logit gradient) are exactly the top-k of the
+    logits it reported, ties to the lower index, decided in the fp32 the kernel computes them in."""
+    from oracle import layers as OL
+    c = dict(ROUTER_VARIANTS["oss_like"], n_layers=1, seq=776)
+    wl = synth.make_workload(c, 1400, gains_random=True)
+    for p in wl["layers"]:
+        p["Wr"] = synth.bf16_round(p["Wr"] * 3.0)        # logits of order one
+    ref = pu.oracle_chain(c, wl)
+    got = pu.gpu_chain(c, wl, hz)
+    assert pu.rel_l2(got["logits"][0], ref["logits"][0]) <= 2e-2
+    idx, _ = OL.moe_route(got["logits"][0], c["top_k"])
+    sel = np.zeros_like(got["logits"][0], dtype=bool)
+    np.put_along_axis(sel, idx, True, axis=1)
+    assert np.array_equal(got["d_router"][0] != 0.0, sel)
+    # tokens whose selection is decisive on the oracle's side agree with it
+    srt = -np.sort(-ref["logits"][0], axis=1)
+    decisive = (srt[:, c["top_k"] - 1] - srt[:, c["top_k"]]) > 0.05
+    assert decisive.mean() > 0.5
+    ref_sel = ref["grads"][0]["router_logits"] != 0.0
+    assert np.array_equal(sel[decisive], ref_sel[decisive])
+    assert pu.rel_l2(got["out"][decisive], ref["out"][decisive]) <= 2e-2
+
+
 @pytest.mark.parametrize("name", sorted(VARIANTS))
 def test_stage_variants_match_oracle(hz, name):
     c = VARIANTS[name]

@@ -81,6 +81,53 @@ def test_moe_layer_backward_matches_finite_differences():
         fd_param(f, params[0][name], grads[0][name])
 
 
+def test_moe_router_in_stage_backward_matches_finite_differences():
+    """Router held by the layer: logits = n2 Wr^T.  Finite differences through the whole layer see both paths of n2
+    (into the experts and into the logits); a dropped dlogits Wr term or a transposed Wr fails the x and g2 probes."""
+    cfg = tiny_cfg(n_layers=2, n_experts=6, top_k=3, ffn=6, lora_targets=("q", "k", "v", "o"), moe_router=True)
+    batch, seq = 1, 5
+    T = batch * seq
+    params = [draw_layer(cfg) for _ in range(2)]
+    for p in params:
+        p["Wr"] = RNG.standard_normal((6, cfg.hidden)) * 1.5
+    x = RNG.standard_normal((T, cfg.hidden))
+    dy = RNG.standard_normal((T, cfg.hidden))
+    out, dx, grads = stage.stage_fwd_bwd(x, dy, params, cfg, batch, seq)
+    f = lambda: float(np.sum(dy * stage.stage_fwd(x, params, cfg, batch, seq)[0]))
+    fd_param(f, x, dx, n_probe=16)
+    for li in range(2):
+        for name in ("Wr", "g2", "Wo", "Wd", "g1"):
+            fd_param(f, params[li][name], grads[li][name], n_probe=8)
+
+
+def test_moe_router_in_stage_equals_supplying_its_logits():
+    """With the same logits fed from outside, forward and the expert part of the backward are identical, and the
+    input gradient differs exactly by the path through the router."""
+    cfg_in = tiny_cfg(n_layers=1, n_experts=6, top_k=2, ffn=6, lora_rank=0, lora_targets=(), moe_router=True)
+    cfg_ext = tiny_cfg(n_layers=1, n_experts=6, top_k=2, ffn=6, lora_rank=0, lora_targets=())
+    batch, seq = 1, 7
+    p = draw_layer(cfg_in)
+    p["Wr"] = RNG.standard_normal((6, cfg_in.hidden))
+    x = RNG.standard_normal((7, cfg_in.hidden))
+    dz = RNG.standard_normal((7, cfg_in.hidden))
+    z_in, c_in = stage.layer_fwd(x, p, cfg_in, batch, seq)
+    logits = c_in["n2"] @ p["Wr"].T
+    np.testing.assert_array_equal(c_in["logits"], logits)
+    z_ext, c_ext = stage.layer_fwd(x, p, cfg_ext, batch, seq, logits)
+    np.testing.assert_array_equal(z_in, z_ext)
+    dx_in, g_in = stage.layer_bwd(dz, c_in, p, cfg_in, batch, seq)
+    dx_ext, g_ext = stage.layer_bwd(dz, c_ext, p, cfg_ext, batch, seq)
+    np.testing.assert_array_equal(g_in["router_logits"], g_ext["router_logits"])
+    np.testing.assert_array_equal(g_in["Wd"], g_ext["Wd"])
+    # the router path alone: d n2 = dlogits Wr, pushed through the post-attention norm and the attention block
+    assert np.linalg.norm(dx_in - dx_ext) > 1e-3 * np.linalg.norm(dx_ext)
+    np.testing.assert_allclose(g_in["Wr"], g_in["router_logits"].T @ c_in["n2"], rtol=1e-13)
+    # logits by brute force
+    for t in (0, 3, 6):
+        for e in (0, 5):
+            assert abs(sum(c_in["n2"][t, j] * p["Wr"][e, j] for j in range(cfg_in.hidden)) - logits[t, e]) < 1e-12
+
+
 def test_frozen_base_returns_no_base_weight_grads_but_same_dx():
     cfg_t = tiny_cfg()
     cfg_f = tiny_cfg(train_base=False)
