@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--cpu-seq", type=int, default=4096, help="sequence length of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--no-upload-leg", action="store_true")
+    ap.add_argument("--round-streams", type=int, default=1, help="transfer streams per direction in that leg (1 or 2)")
+    ap.add_argument("--round-micro", type=int, default=4, help="micro-batches per round in the multi-stream leg")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures the one-GPU worker; a stage runs whole on one GPU and nothing here uses a "
@@ -260,6 +262,52 @@ def main():
                   "rounds": sweep, "smallest_m_r_hidden": first_hidden,
                   "note": "a round = one upload into the other slot while M_R micro-batches run on this one"}
 
+    # ---- a round of the multi-stream worker (Sec. 4.2): backward stage over M_R micro-batches whose activations live in
+    # pinned host memory, the next stage's weights streaming in and a finished gradient blob streaming out in the round's
+    # windows.  Compared with the same M_R backward stages on device-resident activations and nothing else in flight.
+    round_leg = None
+    if not args.no_upload_leg and c["n_layers"] > 0 and not c["n_experts"]:
+        m_r = args.round_micro
+        R.enable_rounds(args.round_streams)
+        pin = lambda: torch.empty((T, c["hidden"]), dtype=torch.bfloat16).pin_memory()
+        xh, dyh, oh = [pin() for _ in range(m_r)], [pin() for _ in range(m_r)], [pin() for _ in range(m_r)]
+        for t in xh:
+            t.copy_(x)
+        for t in dyh:
+            t.copy_(dy_in)
+        g_host = torch.empty(max(R.gbytes, 4) // 4, dtype=torch.float32).pin_memory() if R.gbytes else None
+
+        def plain():
+            for _ in range(m_r):
+                B.rp_stage_backward(R.ctx, 0, B.PHASE_BOTH, x, dy_in, dx, out, R.grads if R.gbytes else None, None, None,
+                                    R.batch, R.seq, R.ws, R.wsbytes)
+
+        def rnd(i):
+            R.round(xh, oh, slot=i & 1, dy_host=dyh, next_slot=(i + 1) & 1, next_host_blob=host,
+                    done_grads_dev=R.grads if R.gbytes else None, done_grads_host=g_host)
+
+        R.upload(host, slot=0)
+        plain()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(2):
+            plain()
+        torch.cuda.synchronize()
+        t_plain = (time.perf_counter() - t0) / 2 * 1e3
+        rnd(0)
+        R.sync()
+        t0 = time.perf_counter()
+        for i in range(1, 4):
+            rnd(i)
+        R.sync()
+        t_round = (time.perf_counter() - t0) / 3 * 1e3
+        moved = 3 * m_r * T * c["hidden"] * 2 + R.wbytes + R.gbytes
+        round_leg = {"m_r": m_r, "round_ms": round(t_round, 3), "resident_ms": round(t_plain, 3),
+                     "exposed_ms": round(max(0.0, t_round - t_plain), 3), "tokens_per_s": round(m_r * T / (t_round * 1e-3), 1),
+                     "bytes_moved": moved, "link_gbs_if_serial": round(moved / (t_round * 1e-3) / 1e9, 1),
+                     "note": "backward stage only (no head); per round: %d activation uploads (x, dy) and downloads (dx), the "
+                             "whole weight blob up, the whole gradient blob down" % m_r}
+
     cpu = None
     if args.cpu_seq > 0:
         say("CPU oracle sample")
@@ -284,7 +332,7 @@ def main():
         "frac_of_bf16_mfma_peak": round(tot_fl / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "loss": loss_val,
         "roofline": roofline, "classes": classes, "traced_ms_per_step": round(traced_ms, 3), "kernels": kernels,
-        "forward_stage": fwd_stage, "upload": upload, "cpu_baseline": cpu,
+        "forward_stage": fwd_stage, "upload": upload, "round": round_leg, "cpu_baseline": cpu,
         "context": "paper reports only 8-GPU end-to-end speedups (1.48-2.16x on 8x RTX 4090); no per-stage number exists",
     }
     R.close()

@@ -189,6 +189,74 @@ RP_API rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, c
                                void* dx, void* grads, float grad_scale, int batch, int seq, void* workspace,
                                size_t workspace_bytes);
 
+/* ---- a round: one stage over M micro-batches whose activations live in host memory (Sec. 4.2) ---------------- */
+
+/* One piece of a transfer plan: bytes [offset, offset + bytes) of item `item`, sent in window `window`. */
+typedef struct {
+  int32_t item;
+  int32_t window;
+  size_t offset;
+  size_t bytes;
+} rp_piece;
+
+/* Packing of parameter / gradient transfers into the n_windows data-transfer windows of a round (Sec. 4.2, "Scheduling
+ * parameter transfers"): items (tensors) larger than max_piece_bytes are first split into equal pieces (multiples of
+ * 256 bytes, the last one shorter); the pieces are taken in descending size (ties: lower item, lower offset) and each
+ * goes to the window that holds the fewest bytes so far (ties: lower window) -- longest-processing-time-first.
+ * pieces [host, capacity entries] receives them in the order they were assigned; *n_pieces their number.
+ * Pure host function.  Errors: RP_EINVAL (NULL, n_windows <= 0, max_piece_bytes 0 or not a multiple of 256),
+ * RP_ENOMEM (capacity too small; *n_pieces then holds the number needed). */
+RP_API rp_status rp_plan_transfers(const size_t* item_bytes, int n_items, int n_windows, size_t max_piece_bytes,
+                            rp_piece* pieces, int capacity, int* n_pieces);
+
+/* The three further transfer streams of the multi-stream worker (Sec. 4.2, "The multi-stream architecture"):
+ * activation upload, activation download, gradient download; the copy stream given at creation is the parameter
+ * upload stream.  hipStream_t handles owned by the caller, default priority.  Needed by the rp_round_* calls only. */
+RP_API rp_status rp_ctx_set_transfer_streams(rp_ctx* ctx, void* act_upload_stream, void* act_download_stream,
+                                      void* grad_download_stream);
+
+/* What a round moves.  Every [pinned] array has n_micro entries of bf16 [T, h]; the [dev] staging buffers are bf16
+ * [T, h] each, two per direction (micro-batch j uses entry j & 1). */
+typedef struct {
+  uint32_t struct_size;
+  int32_t n_micro;             /* M in [1, 256]: micro-batches the stage processes with one set of weights (Sec. 3.1) */
+  const void* const* x_host;   /* [pinned] stage inputs */
+  const void* const* dy_host;  /* [pinned] gradients of the stage outputs (backward rounds; else NULL) */
+  void* const* out_host;       /* [pinned] forward round: stage outputs;  backward round: gradients of the inputs */
+  void* x_dev[2];              /* [dev] */
+  void* dy_dev[2];             /* [dev] backward rounds */
+  void* out_dev[2];            /* [dev] */
+  int32_t next_slot;           /* slot that receives the next stage's weights during this round, or -1 */
+  void* next_dev_slot;         /* [dev]    as in rp_stage_upload_weights */
+  const void* next_host_blob;  /* [pinned] */
+  const void* done_grads_dev;  /* [dev] fp32 gradient blob of a stage that has finished, to be sent home, or NULL */
+  void* done_grads_host;       /* [pinned] receives it */
+  size_t max_piece_bytes;      /* tensors above this are split before scheduling; 0 = 64 MiB */
+} rp_round_io;
+
+/* Runs the stage in slot `slot_id` over n_micro micro-batches the way the paper's worker does (Sec. 4.2, Fig.
+ * "multi-stream workflow"): micro-batch j+1's activations are uploaded while micro-batch j computes (one micro-batch
+ * early), results are downloaded while the next one computes (one micro-batch late), the compute stream meets the two
+ * activation streams once per micro-batch through events, and the round's M windows each carry one chunk of the next
+ * stage's parameters (upload) and of a finished stage's gradients (download), placed behind the window's activation
+ * transfer so that they do not compete with it; the chunks are those of rp_plan_transfers over the tensors of the
+ * respective blob.  When the call returns everything is enqueued; out_host / done_grads_host are complete once the
+ * activation-download / gradient-download streams have drained, next_slot is usable by later calls on this ctx at once
+ * (they wait on its events).  Forward round: out = layers(x).  Backward round: recomputation + backward per micro-batch,
+ * weight gradients accumulated into `grads` [dev] over the M micro-batches (Sec. 4.1.1).  Dense stages only.
+ * Consecutive rounds on the same staging buffers overlap like the micro-batches inside one (the first upload of a
+ * round waits only for the predecessor's last use of that buffer); with other buffers the round first waits for
+ * everything enqueued on the compute and activation-download streams so far.  A stream may serve several roles (the
+ * activation upload may share the parameter-upload stream, the gradient download the activation-download stream):
+ * with the runtime's default of four hardware queues per process, one transfer stream per direction is the faster
+ * arrangement.
+ * Errors: as rp_stage_forward / rp_stage_backward, RP_ESTATE when the transfer streams were not set, RP_EUNSUPPORTED
+ * for MoE stages. */
+RP_API rp_status rp_round_forward(rp_ctx* ctx, int slot_id, const rp_round_io* io, int batch, int seq, void* workspace,
+                           size_t workspace_bytes);
+RP_API rp_status rp_round_backward(rp_ctx* ctx, int slot_id, const rp_round_io* io, void* grads, int batch, int seq,
+                            void* workspace, size_t workspace_bytes);
+
 #ifdef __cplusplus
 }
 #endif

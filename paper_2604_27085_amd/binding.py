@@ -29,6 +29,18 @@ class StageCfg(C.Structure):
                 ("train_base", C.c_int32), ("moe_router", C.c_int32)]
 
 
+class Piece(C.Structure):
+    _fields_ = [("item", C.c_int32), ("window", C.c_int32), ("offset", C.c_size_t), ("bytes", C.c_size_t)]
+
+
+class RoundIO(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_micro", C.c_int32), ("x_host", C.POINTER(C.c_void_p)),
+                ("dy_host", C.POINTER(C.c_void_p)), ("out_host", C.POINTER(C.c_void_p)), ("x_dev", C.c_void_p * 2),
+                ("dy_dev", C.c_void_p * 2), ("out_dev", C.c_void_p * 2), ("next_slot", C.c_int32),
+                ("next_dev_slot", C.c_void_p), ("next_host_blob", C.c_void_p), ("done_grads_dev", C.c_void_p),
+                ("done_grads_host", C.c_void_p), ("max_piece_bytes", C.c_size_t)]
+
+
 class TraceRecord(C.Structure):
     _fields_ = [("name", C.c_char * 40), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
 
@@ -71,6 +83,10 @@ _SIGS = {
     "rp_stage_forward": [_vp, _i, _vp, _vp, C.POINTER(_vp), _vp, _i, _i, _vp, _sz],
     "rp_stage_backward": [_vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _vp, _sz],
     "rp_lmhead_ce_fwd_bwd": [_vp, _i, _vp, _vp, _vp, _vp, _vp, _f, _i, _i, _vp, _sz],
+    "rp_plan_transfers": [_psz, _i, _i, _sz, C.POINTER(Piece), _i, C.POINTER(_i)],
+    "rp_ctx_set_transfer_streams": [_vp, _vp, _vp, _vp],
+    "rp_round_forward": [_vp, _i, C.POINTER(RoundIO), _i, _i, _vp, _sz],
+    "rp_round_backward": [_vp, _i, C.POINTER(RoundIO), _vp, _i, _i, _vp, _sz],
     "rp_trace_start": [_vp, _i],
     "rp_trace_stop": [_vp, C.POINTER(TraceRecord), _i, C.POINTER(_i)],
     "rp_op_gemm": [_vp, _i, _i, _vp, _vp, _vp, _i, _i, _i, _l, _l, _l, _f, _i, _vp, _vp, _i, _l, _l, _vp, _l, _i],
@@ -181,6 +197,60 @@ def rp_lmhead_ce_fwd_bwd(ctx, slot_id, x, labels, loss_out, dx, grads, grad_scal
                          workspace_bytes):
     _check(lib.rp_lmhead_ce_fwd_bwd(ctx, slot_id, _ptr(x), _ptr(labels), _ptr(loss_out), _ptr(dx), _ptr(grads),
                                     grad_scale, batch, seq, _ptr(workspace), workspace_bytes), ctx)
+
+
+def rp_plan_transfers(item_bytes, n_windows, max_piece_bytes):
+    """Returns the pieces as (item, window, offset, bytes) tuples in the order they were assigned."""
+    n = len(item_bytes)
+    arr = (C.c_size_t * max(n, 1))(*item_bytes)
+    cnt = C.c_int()
+    code = lib.rp_plan_transfers(arr, n, n_windows, max_piece_bytes, None, 0, C.byref(cnt))
+    if code not in (RP_OK, RP_ENOMEM):
+        raise RpError(code, "rp_plan_transfers: bad arguments")
+    buf = (Piece * max(cnt.value, 1))()
+    code = lib.rp_plan_transfers(arr, n, n_windows, max_piece_bytes, buf, cnt.value, C.byref(cnt))
+    if code != RP_OK:
+        raise RpError(code, "rp_plan_transfers failed")
+    return [(buf[i].item, buf[i].window, buf[i].offset, buf[i].bytes) for i in range(cnt.value)]
+
+
+def rp_ctx_set_transfer_streams(ctx, act_up, act_down, grad_down):
+    _check(lib.rp_ctx_set_transfer_streams(ctx, act_up, act_down, grad_down), ctx)
+
+
+def make_round_io(x_host, out_host, x_dev, out_dev, dy_host=None, dy_dev=None, next_slot=-1, next_dev_slot=None,
+                  next_host_blob=None, done_grads_dev=None, done_grads_host=None, max_piece_bytes=0):
+    """Lists of torch tensors (pinned host / device) -> RoundIO.  The returned object keeps the pointer arrays alive."""
+    m = len(x_host)
+    io = RoundIO()
+    io.struct_size = C.sizeof(RoundIO)
+    io.n_micro = m
+    io._keep = [(C.c_void_p * m)(*[_ptr(t) for t in x_host]), (C.c_void_p * m)(*[_ptr(t) for t in out_host]),
+                (C.c_void_p * m)(*[_ptr(t) for t in dy_host]) if dy_host is not None else None]
+    io.x_host = C.cast(io._keep[0], C.POINTER(C.c_void_p))
+    io.out_host = C.cast(io._keep[1], C.POINTER(C.c_void_p))
+    if dy_host is not None:
+        io.dy_host = C.cast(io._keep[2], C.POINTER(C.c_void_p))
+    for b in range(2):
+        io.x_dev[b] = _ptr(x_dev[b])
+        io.out_dev[b] = _ptr(out_dev[b])
+        if dy_dev is not None:
+            io.dy_dev[b] = _ptr(dy_dev[b])
+    io.next_slot = next_slot
+    io.next_dev_slot = _ptr(next_dev_slot)
+    io.next_host_blob = _ptr(next_host_blob)
+    io.done_grads_dev = _ptr(done_grads_dev)
+    io.done_grads_host = _ptr(done_grads_host)
+    io.max_piece_bytes = max_piece_bytes
+    return io
+
+
+def rp_round_forward(ctx, slot_id, io, batch, seq, workspace, workspace_bytes):
+    _check(lib.rp_round_forward(ctx, slot_id, C.byref(io), batch, seq, _ptr(workspace), workspace_bytes), ctx)
+
+
+def rp_round_backward(ctx, slot_id, io, grads, batch, seq, workspace, workspace_bytes):
+    _check(lib.rp_round_backward(ctx, slot_id, C.byref(io), _ptr(grads), batch, seq, _ptr(workspace), workspace_bytes), ctx)
 
 
 # ---- rp_ops.h -----------------------------------------------------------------------------------------------------

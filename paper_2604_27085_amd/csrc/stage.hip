@@ -12,6 +12,7 @@
 #include "gemm.hpp"
 #include "kernels.hpp"
 #include "layout.hpp"
+#include "transfers.hpp"
 
 using namespace rp;
 
@@ -47,6 +48,15 @@ struct rp_ctx {
   int trace_cap = 0, trace_n = 0;
   hipEvent_t* trace_ev = nullptr;   // trace_cap + 1 events
   TraceRec* trace_rec = nullptr;
+  // rounds: activation upload / download and gradient download streams, and the events that tie them to compute
+  hipStream_t act_up = nullptr, act_down = nullptr, grad_down = nullptr;
+  hipEvent_t* round_ev = nullptr;   // two halves, used by alternate rounds, so that a round can wait on its predecessor's
+  int round_ev_n = 0;               // events while recording its own
+  // the previous round: its staging buffers and the events of the last compute / download that used each of them
+  int round_parity = 0;
+  bool prev_round = false;
+  void* prev_x[2] = {nullptr, nullptr}; void* prev_out[2] = {nullptr, nullptr}; void* prev_dy[2] = {nullptr, nullptr};
+  hipEvent_t prev_done[2] = {nullptr, nullptr}, prev_down[2] = {nullptr, nullptr};
 };
 
 namespace {
@@ -524,6 +534,10 @@ rp_status rp_ctx_destroy(rp_ctx* c) {
     delete[] c->trace_ev;
   }
   delete[] c->trace_rec;
+  if (c->round_ev) {
+    for (int i = 0; i < c->round_ev_n; ++i) if (c->round_ev[i]) (void)hipEventDestroy(c->round_ev[i]);
+    delete[] c->round_ev;
+  }
   delete c;
   return RP_OK;
 }
@@ -830,6 +844,189 @@ rp_status rp_op_attn_bwd(void* stream, const void* q, const void* k, const void*
     e = k_attn_bwd(st, parts[i], q, k, v, dout, lse, delta, dq, dk, dv, scratch, ldq, ldk, ldv, lddo, lddq, lddk, lddv, batch, seq,
                    a, kh, d);
   OP_RET(e);
+}
+
+
+// ---- rounds ---------------------------------------------------------------------------------------------------------
+rp_status rp_ctx_set_transfer_streams(rp_ctx* ctx, void* act_upload_stream, void* act_download_stream, void* grad_download_stream) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (!act_upload_stream || !act_download_stream || !grad_download_stream) return fail(ctx, RP_EINVAL, "all three streams must be non-NULL");
+  ctx->act_up = reinterpret_cast<hipStream_t>(act_upload_stream);
+  ctx->act_down = reinterpret_cast<hipStream_t>(act_download_stream);
+  ctx->grad_down = reinterpret_cast<hipStream_t>(grad_download_stream);
+  return RP_OK;
+}
+
+namespace {
+
+rp_status ensure_round_events(rp_ctx* ctx, int n) {
+  if (ctx->round_ev_n >= n) return RP_OK;
+  ctx->prev_round = false;   // the handles move: fall back to waiting for everything enqueued so far
+  hipEvent_t* ev = new (std::nothrow) hipEvent_t[n]();
+  if (!ev) return fail(ctx, RP_ENOMEM, "out of host memory");
+  for (int i = 0; i < ctx->round_ev_n; ++i) ev[i] = ctx->round_ev[i];
+  delete[] ctx->round_ev;
+  ctx->round_ev = ev;
+  for (int i = ctx->round_ev_n; i < n; ++i) {
+    if (hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) != hipSuccess) { ctx->round_ev_n = i; return fail(ctx, RP_EHIP, "hipEventCreate failed"); }
+  }
+  ctx->round_ev_n = n;
+  return RP_OK;
+}
+
+// Byte ranges of the tensors of a blob (all layer chunks, then the head chunk), in blob order.
+void blob_items(const rp_stage_cfg& c, const BlobLayout& B, size_t es, std::vector<size_t>& off, std::vector<size_t>& bytes) {
+  for (int l = 0; l <= c.n_layers; ++l)
+    for (int id = 0; id < RP_T_COUNT; ++id) {
+      if (is_head_tensor(id) != (l == c.n_layers) || B.elems[id] == 0) continue;
+      off.push_back(B.layer_bytes * (size_t)l + B.off[id]);
+      bytes.push_back(B.elems[id] * es);
+    }
+}
+
+rp_status round_run(rp_ctx* ctx, int slot_id, const rp_round_io* io, bool backward, void* grads, int batch, int seq,
+                    void* workspace, size_t workspace_bytes_in) {
+  if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
+  if (!io || io->struct_size != sizeof(rp_round_io)) return fail(ctx, RP_EINVAL, "io is NULL or io.struct_size != %zu", sizeof(rp_round_io));
+  if (!ctx->act_up) return fail(ctx, RP_ESTATE, "rp_ctx_set_transfer_streams has not been called");
+  if (ctx->cfg.n_layers == 0) return fail(ctx, RP_EINVAL, "stage has no decoder layers");
+  if (ctx->cfg.n_experts > 0) return fail(ctx, RP_EUNSUPPORTED, "rounds cover dense stages only");
+  const int M = io->n_micro;
+  if (M < 1 || M > 256) return fail(ctx, RP_EINVAL, "n_micro must be in [1, 256]");
+  const Plan P = make_plan(ctx->cfg, batch > 0 ? batch : 1, seq > 0 ? seq : 8);
+  rp_status s = check_call(ctx, slot_id, batch, seq, workspace, workspace_bytes_in, backward ? P.bwd_bytes : P.fwd_bytes);
+  if (s != RP_OK) return s;
+  if (!io->x_host || !io->out_host || (backward && !io->dy_host)) return fail(ctx, RP_EINVAL, "host activation arrays must be non-NULL");
+  for (int j = 0; j < M; ++j)
+    if (!io->x_host[j] || !io->out_host[j] || (backward && !io->dy_host[j])) return fail(ctx, RP_EINVAL, "host activation pointer %d is NULL", j);
+  for (int b = 0; b < 2; ++b) {
+    if (!io->x_dev[b] || !io->out_dev[b] || (backward && !io->dy_dev[b])) return fail(ctx, RP_EINVAL, "device staging buffers must be non-NULL");
+    if (io->x_dev[b] == io->out_dev[b]) return fail(ctx, RP_EINVAL, "x_dev and out_dev must be distinct");
+  }
+  if (io->x_dev[0] == io->x_dev[1] || io->out_dev[0] == io->out_dev[1] || (backward && io->dy_dev[0] == io->dy_dev[1]))
+    return fail(ctx, RP_EINVAL, "the two staging buffers of a direction must be distinct");
+  if (backward && !grads && ctx->gl.total > 0) return fail(ctx, RP_EINVAL, "grads is NULL but the stage has trainable tensors");
+  const bool up = io->next_slot >= 0;
+  if (up) {
+    if (io->next_slot >= RP_MAX_SLOTS || io->next_slot == slot_id) return fail(ctx, RP_EINVAL, "next_slot must be another valid slot");
+    if (!io->next_dev_slot || !io->next_host_blob) return fail(ctx, RP_EINVAL, "next_dev_slot / next_host_blob are NULL");
+    if (reinterpret_cast<uintptr_t>(io->next_dev_slot) % 256) return fail(ctx, RP_EINVAL, "next_dev_slot must be 256-byte aligned");
+  }
+  const bool down = io->done_grads_dev != nullptr && ctx->gl.total > 0;
+  if (down && !io->done_grads_host) return fail(ctx, RP_EINVAL, "done_grads_host is NULL");
+  const size_t max_piece = io->max_piece_bytes ? io->max_piece_bytes : ((size_t)64 << 20);
+  if (max_piece % 256) return fail(ctx, RP_EINVAL, "max_piece_bytes must be a multiple of 256");
+  const int half = 3 * 256 + 2;                      // events of one round at the largest n_micro
+  s = ensure_round_events(ctx, 2 * half);
+  if (s != RP_OK) return s;
+  hipEvent_t* const pool = ctx->round_ev + (ctx->round_parity ? half : 0);
+  hipEvent_t* const e_up = pool;                     // activation upload of micro-batch j has landed
+  hipEvent_t* const e_done = pool + M;               // compute of micro-batch j has finished
+  hipEvent_t* const e_down = pool + 2 * M;           // result of micro-batch j has left its staging buffer
+  const hipEvent_t e_start = pool[3 * M], e_start_down = pool[3 * M + 1];
+  // Same staging buffers as the round before (the steady state of a worker): the first uploads and results wait only
+  // for the predecessor's last use of the very buffer, so the rounds overlap like the micro-batches inside one.
+  bool chained = ctx->prev_round;
+  for (int b = 0; b < 2 && chained; ++b)
+    chained = io->x_dev[b] == ctx->prev_x[b] && io->out_dev[b] == ctx->prev_out[b] && (!backward || io->dy_dev[b] == ctx->prev_dy[b]);
+
+  // transfer plans: the tensors of the next stage's weight blob and of the finished stage's gradient blob, M windows
+  std::vector<size_t> w_off, w_bytes, g_off, g_bytes;
+  std::vector<rp_piece> w_plan, g_plan;
+  if (up) { blob_items(ctx->cfg, ctx->wl, 2, w_off, w_bytes); w_plan = plan_transfers(w_bytes.data(), (int)w_bytes.size(), M, max_piece); }
+  if (down) { blob_items(ctx->cfg, ctx->gl, 4, g_off, g_bytes); g_plan = plan_transfers(g_bytes.data(), (int)g_bytes.size(), M, max_piece); }
+
+  const size_t act_bytes = (size_t)batch * seq * ctx->cfg.hidden * 2;
+  // work enqueued before this call may still use the staging buffers: the first uploads wait for the compute stream as
+  // it stands now, the first results for the activation-download stream as it stands now
+  HIP_TRY(ctx, hipEventRecord(e_start, ctx->compute));
+  if (!chained) {
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->act_up, e_start, 0));
+    HIP_TRY(ctx, hipEventRecord(e_start_down, ctx->act_down));
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->compute, e_start_down, 0));
+  }
+  if (down) HIP_TRY(ctx, hipStreamWaitEvent(ctx->grad_down, e_start, 0));   // the finished gradients were written on the compute stream
+  if (up) {
+    Slot& nx = ctx->slots[io->next_slot];
+    if (nx.used) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, nx.free_ev, 0));
+  }
+  auto upload = [&](int j) -> rp_status {
+    const int b = j & 1;
+    if (j >= 2) HIP_TRY(ctx, hipStreamWaitEvent(ctx->act_up, e_done[j - 2], 0));   // the staging buffer's last reader
+    else if (chained && ctx->prev_done[b]) HIP_TRY(ctx, hipStreamWaitEvent(ctx->act_up, ctx->prev_done[b], 0));
+    HIP_TRY(ctx, hipMemcpyAsync(io->x_dev[b], io->x_host[j], act_bytes, hipMemcpyHostToDevice, ctx->act_up));
+    if (backward) HIP_TRY(ctx, hipMemcpyAsync(io->dy_dev[b], io->dy_host[j], act_bytes, hipMemcpyHostToDevice, ctx->act_up));
+    HIP_TRY(ctx, hipEventRecord(e_up[j], ctx->act_up));
+    return RP_OK;
+  };
+  s = upload(0);
+  if (s != RP_OK) return s;
+  for (int j = 0; j < M; ++j) {
+    const int b = j & 1;
+    // window j opens: the next micro-batch's activations go up while this one computes (one micro-batch early)
+    if (j + 1 < M) { s = upload(j + 1); if (s != RP_OK) return s; }
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->compute, e_up[j], 0));
+    if (j >= 2) HIP_TRY(ctx, hipStreamWaitEvent(ctx->compute, e_down[j - 2], 0));   // out_dev[b] has been sent home
+    else if (chained && ctx->prev_down[b]) HIP_TRY(ctx, hipStreamWaitEvent(ctx->compute, ctx->prev_down[b], 0));
+    if (backward)
+      s = rp_stage_backward(ctx, slot_id, RP_PHASE_BOTH, io->x_dev[b], io->dy_dev[b], io->out_dev[b], nullptr, grads, nullptr, nullptr,
+                            batch, seq, workspace, workspace_bytes_in);
+    else
+      s = rp_stage_forward(ctx, slot_id, io->x_dev[b], io->out_dev[b], nullptr, nullptr, batch, seq, workspace, workspace_bytes_in);
+    if (s != RP_OK) return s;
+    HIP_TRY(ctx, hipEventRecord(e_done[j], ctx->compute));
+    // the result goes home while the next micro-batch computes (one micro-batch late)
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->act_down, e_done[j], 0));
+    HIP_TRY(ctx, hipMemcpyAsync(io->out_host[j], io->out_dev[b], act_bytes, hipMemcpyDeviceToHost, ctx->act_down));
+    HIP_TRY(ctx, hipEventRecord(e_down[j], ctx->act_down));
+    // window j's chunk of the next stage's parameters: not before the window opens, and behind its activation upload
+    if (up) {
+      if (j >= 1) HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, e_done[j - 1], 0));
+      HIP_TRY(ctx, hipStreamWaitEvent(ctx->copy, e_up[j + 1 < M ? j + 1 : j], 0));
+      for (const rp_piece& pc : w_plan)
+        if (pc.window == j) {
+          const size_t o = w_off[pc.item] + pc.offset;
+          HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(io->next_dev_slot) + o, static_cast<const char*>(io->next_host_blob) + o, pc.bytes,
+                                      hipMemcpyHostToDevice, ctx->copy));
+        }
+    }
+    // window j's chunk of the finished stage's gradients: behind the activation download that falls into this window
+    if (down) {
+      if (j >= 1) HIP_TRY(ctx, hipStreamWaitEvent(ctx->grad_down, e_down[j - 1], 0));
+      for (const rp_piece& pc : g_plan)
+        if (pc.window == j) {
+          const size_t o = g_off[pc.item] + pc.offset;
+          HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(io->done_grads_host) + o, static_cast<const char*>(io->done_grads_dev) + o, pc.bytes,
+                                      hipMemcpyDeviceToHost, ctx->grad_down));
+        }
+    }
+  }
+  for (int b = 0; b < 2; ++b) {
+    // last micro-batch that used staging buffer b.  With one micro-batch buffer 1 was not touched: whoever used it
+    // earlier is already ordered before this round's transfers, which waited for later work on the same streams
+    const int j = ((M - 1) & 1) == b ? M - 1 : M - 2;
+    ctx->prev_done[b] = j >= 0 ? e_done[j] : nullptr;
+    ctx->prev_down[b] = j >= 0 ? e_down[j] : nullptr;
+    ctx->prev_x[b] = io->x_dev[b]; ctx->prev_out[b] = io->out_dev[b]; ctx->prev_dy[b] = backward ? io->dy_dev[b] : ctx->prev_dy[b];
+  }
+  ctx->prev_round = true;
+  ctx->round_parity ^= 1;
+  if (up) {   // every chunk of the next slot is complete once the copy stream gets here
+    Slot& nx = ctx->slots[io->next_slot];
+    for (int l = 0; l <= ctx->cfg.n_layers; ++l) HIP_TRY(ctx, hipEventRecord(nx.ev[l], ctx->copy));
+    nx.dev = io->next_dev_slot; nx.bytes = ctx->wl.total; nx.valid = true; nx.gated = true; nx.used = false;
+  }
+  return RP_OK;
+}
+
+}  // namespace
+
+rp_status rp_round_forward(rp_ctx* ctx, int slot_id, const rp_round_io* io, int batch, int seq, void* workspace, size_t workspace_bytes) {
+  return round_run(ctx, slot_id, io, false, nullptr, batch, seq, workspace, workspace_bytes);
+}
+rp_status rp_round_backward(rp_ctx* ctx, int slot_id, const rp_round_io* io, void* grads, int batch, int seq, void* workspace,
+                            size_t workspace_bytes) {
+  return round_run(ctx, slot_id, io, true, grads, batch, seq, workspace, workspace_bytes);
 }
 
 }  // extern "C"

@@ -190,6 +190,37 @@ class StageRunner:
                                grad_scale, self.batch, self.seq, self.ws_head, self.wsbytes)
         return loss, dx
 
+    def enable_rounds(self, streams_per_direction=1):
+        """Sets up the transfer streams of the multi-stream worker.  streams_per_direction = 2: activations and
+        parameters / gradients on streams of their own (five streams with compute, as in the paper); 1: one stream per
+        direction -- activation uploads share the parameter-upload stream, gradient downloads the activation-download
+        stream -- which keeps the process within the runtime's default of four hardware queues."""
+        self.act_down = torch.cuda.Stream(device=self.device)
+        if streams_per_direction == 2:
+            self.act_up = torch.cuda.Stream(device=self.device)
+            self.grad_down = torch.cuda.Stream(device=self.device)
+        else:
+            self.act_up, self.grad_down = self.copy, self.act_down
+        B.rp_ctx_set_transfer_streams(self.ctx, self.act_up.cuda_stream, self.act_down.cuda_stream, self.grad_down.cuda_stream)
+        shape = (self.T, self.cfg.hidden)
+        mk = lambda: [torch.empty(shape, dtype=torch.bfloat16, device=self.device) for _ in range(2)]
+        self.x_stage, self.dy_stage, self.out_stage = mk(), mk(), mk()
+
+    def round(self, x_host, out_host, slot=0, dy_host=None, next_slot=-1, next_host_blob=None, done_grads_dev=None,
+              done_grads_host=None, max_piece_bytes=0):
+        """One stage over len(x_host) micro-batches with host-resident activations; backward round when dy_host is given."""
+        io = B.make_round_io(x_host, out_host, self.x_stage, self.out_stage, dy_host, self.dy_stage if dy_host is not None else None,
+                             next_slot, self.slots[next_slot] if next_slot >= 0 else None, next_host_blob, done_grads_dev,
+                             done_grads_host, max_piece_bytes)
+        if dy_host is None:
+            B.rp_round_forward(self.ctx, slot, io, self.batch, self.seq, self.ws, self.wsbytes)
+        else:
+            B.rp_round_backward(self.ctx, slot, io, self.grads if self.gbytes else None, self.batch, self.seq, self.ws, self.wsbytes)
+        return io
+
     def sync(self):
         self.compute.synchronize()
         self.copy.synchronize()
+        for name in ("act_up", "act_down", "grad_down"):
+            if hasattr(self, name):
+                getattr(self, name).synchronize()
