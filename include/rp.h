@@ -257,6 +257,27 @@ RP_API rp_status rp_round_forward(rp_ctx* ctx, int slot_id, const rp_round_io* i
 RP_API rp_status rp_round_backward(rp_ctx* ctx, int slot_id, const rp_round_io* io, void* grads, int batch, int seq,
                             void* workspace, size_t workspace_bytes);
 
+/* ---- automatic stage partitioning (Sec. 4.4) ---------------------------------------------------------------- */
+
+/* Splits n_layers consecutive layers (the LM head counts as the last one) into forward stages F_1..F_Sf over the front
+ * layers and backward stages B_1..B_Sb over all layers, B_1 being the fused stage of the last layers whose forward
+ * doubles as the recomputation (Sec. 3.2, asymmetric stage splitting: sum F_i + B_1 = sum B_j = n_layers), so that
+ * (n_micro * (Sf + Sb) + n_gpus * (n_gpus - 1)) * t_max is smallest (the GPU time of Sec. 3.3, bubble analysis; t_max =
+ * the longest stage) while no stage's memory exceeds mem_limit.  t_fwd[l]: forward time of layer l; t_bwd[l]: its
+ * backward time including recomputation (also its time inside the fused stage); mem_fwd / mem_bwd: what layer l adds to
+ * a forward / backward stage's footprint.  Algorithm as in the paper: every contiguous run of forward or of backward
+ * times is a candidate for t_max; for a candidate the stages are packed greedily -- the fused stage first, as full as
+ * possible, then the other backward stages towards the front, then the forward stages from the front -- which gives
+ * the fewest stages for that bound; O(n_layers^3) in all.  Ties in cost: fewer stages, then the candidate met first
+ * (forward runs before backward runs, by start then end).
+ * fwd_layers, bwd_layers [host, n_layers entries each] receive the stage sizes, *n_fwd / *n_bwd their counts
+ * (bwd_layers[0] = B_1, the last layers); t_max, cost may be NULL.  Pure host function.
+ * Errors: RP_EINVAL (NULL, non-positive counts, negative or NaN inputs), RP_EUNSUPPORTED (a layer alone exceeds
+ * mem_limit). */
+RP_API rp_status rp_partition_stages(int n_layers, const double* t_fwd, const double* t_bwd, const double* mem_fwd,
+                              const double* mem_bwd, double mem_limit, int n_gpus, int n_micro, int* fwd_layers, int* n_fwd,
+                              int* bwd_layers, int* n_bwd, double* t_max, double* cost);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,6 +84,9 @@ _SIGS = {
     "rp_stage_backward": [_vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _vp, _sz],
     "rp_lmhead_ce_fwd_bwd": [_vp, _i, _vp, _vp, _vp, _vp, _vp, _f, _i, _i, _vp, _sz],
     "rp_plan_transfers": [_psz, _i, _i, _sz, C.POINTER(Piece), _i, C.POINTER(_i)],
+    "rp_partition_stages": [_i, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
+                            C.c_double, _i, _i, C.POINTER(_i), C.POINTER(_i), C.POINTER(_i), C.POINTER(_i),
+                            C.POINTER(C.c_double), C.POINTER(C.c_double)],
     "rp_ctx_set_transfer_streams": [_vp, _vp, _vp, _vp],
     "rp_round_forward": [_vp, _i, C.POINTER(RoundIO), _i, _i, _vp, _sz],
     "rp_round_backward": [_vp, _i, C.POINTER(RoundIO), _vp, _i, _i, _vp, _sz],
@@ -212,6 +215,19 @@ def rp_plan_transfers(item_bytes, n_windows, max_piece_bytes):
     if code != RP_OK:
         raise RpError(code, "rp_plan_transfers failed")
     return [(buf[i].item, buf[i].window, buf[i].offset, buf[i].bytes) for i in range(cnt.value)]
+
+
+def rp_partition_stages(t_fwd, t_bwd, mem_fwd, mem_bwd, mem_limit, n_gpus, n_micro):
+    """Returns (forward stage sizes, backward stage sizes with B_1 first, t_max, cost)."""
+    n = len(t_fwd)
+    arr = lambda v: (C.c_double * n)(*[float(x) for x in v])
+    fl, bl = (C.c_int * n)(), (C.c_int * n)()
+    nf, nb, tm, cost = C.c_int(), C.c_int(), C.c_double(), C.c_double()
+    code = lib.rp_partition_stages(n, arr(t_fwd), arr(t_bwd), arr(mem_fwd), arr(mem_bwd), float(mem_limit), n_gpus, n_micro,
+                                   fl, C.byref(nf), bl, C.byref(nb), C.byref(tm), C.byref(cost))
+    if code != RP_OK:
+        raise RpError(code, "rp_partition_stages failed")
+    return list(fl[:nf.value]), list(bl[:nb.value]), tm.value, cost.value
 
 
 def rp_ctx_set_transfer_streams(ctx, act_up, act_down, grad_down):
