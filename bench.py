@@ -93,7 +93,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2")
     ap.add_argument("--cpu-seq", type=int, default=4096, help="sequence length of the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--no-upload-leg", action="store_true")
+    ap.add_argument("--no-upload-leg", "--core-only", dest="no_upload_leg", action="store_true",
+                    help="only the timed steps and the timeline steps: no forward-stage, upload or round legs (profiling runs)")
     ap.add_argument("--round-streams", type=int, default=1, help="transfer streams per direction in that leg (1 or 2)")
     ap.add_argument("--round-micro", type=int, default=4, help="micro-batches per round in the multi-stream leg")
     args = ap.parse_args()
@@ -213,7 +214,7 @@ def main():
 
     # ---- forward stage alone (the F_i stages of Sec. 3.2: no internals kept, smaller workspace plan)
     fwd_stage = None
-    if c["n_layers"] > 0:
+    if c["n_layers"] > 0 and not args.no_upload_leg:
         for _ in range(2):
             B.rp_stage_forward(R.ctx, 0, x, out, None, router, R.batch, R.seq, R.ws, R.wsbytes)
         torch.cuda.synchronize()
