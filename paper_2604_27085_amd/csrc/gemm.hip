@@ -428,10 +428,12 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
     const long tiles = (long)((a.M + 255) / 256) * ((a.N + bn - 1) / bn);
     const int nk = (a.K + 63) / 64 + (a.K2 + 63) / 64;
     int sp = (int)(256 / tiles);
-    // a skinny output is bound by reading the other operand once: short slices are fine, idle CUs are not
-    const int min_slice = a.N <= 64 ? 4 : 16;
+    // a skinny output (few rows or few columns) is bound by reading the other operand once: short slices are fine,
+    // idle CUs are not
+    const bool skinny = a.N <= 64 || a.M <= 64;
+    const int min_slice = skinny ? 4 : 16;
     while (sp > 1 && nk / sp < min_slice) --sp;
-    if (sp > 8) sp = 8;
+    if (sp > (skinny ? 16 : 8)) sp = skinny ? 16 : 8;
     if (sp > 1) { a.splits = sp; a.epi = EPI_F32_ATOMIC; }
   }
   switch (layout) {
