@@ -1,0 +1,55 @@
+"""Parity at the full widths of the larger workloads (hidden size, head counts, FFN width, LoRA on every projection,
+expert shapes), on shorter sequences so that the CPU oracle finishes in seconds: the template instantiations and tile
+tails these widths select (8-chunk rows in the normalisation kernels, 64 query heads over 4 or 8 kv heads, GEMM N of
+24576 / 51200, the wide MoE combine) are the ones bench.py times on C3, C4 and C5.  The oracle runs in fp32 (its
+rounding is three orders of magnitude below the bf16 bound)."""
+import numpy as np
+import pytest
+
+import parity_util as pu
+import synth
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+CASES = {
+    # Qwen3-8B-shaped layer, LoRA r=16 on all seven projections, frozen base, 4096 tokens
+    "c3_width": ("C3", dict(n_layers=1, seq=4096), 3100),
+    # Qwen3-32B-shaped layer (a*d = 8192 != h = 5120, FFN 25600) + final norm and LM head with two vocabulary chunks
+    "c4_width": ("C4", dict(n_layers=1, seq=1024, vocab=32768), 3200),
+    # Qwen3-235B-A22B-shaped MoE layer: 64 query heads on 4 kv heads, experts of 1536, top-8 (of 16 here: the expert
+    # count only sets the size of the weights, 128 experts are covered at small width)
+    "c5_width": ("C5", dict(seq=512, n_experts=16), 3300),
+}
+
+
+@pytest.fixture(scope="module")
+def hz():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2604_27085_amd import harness
+    return harness
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_full_width_stage_matches_oracle(hz, name, capsys):
+    base, over, seed = CASES[name]
+
+    def say(msg):
+        with capsys.disabled():
+            print("[%s] %s" % (name, msg), flush=True)
+
+    c = synth.shrink(synth.CONFIGS[base], **over)
+    say("generating the workload")
+    wl = synth.make_workload(c, seed, gains_random=True)
+    say("HIP path")
+    got = pu.gpu_chain(c, wl, hz)
+    say("oracle (fp32)")
+    ref = pu.oracle_chain(c, wl, dtype=np.float32)
+    errs = pu.compare_chain(ref, got, c)
+    worst = max((v, k) for k, v in errs.items() if k != "loss")
+    say("worst relative error %.2e (%s)%s" % (worst + (", loss error %.1e" % errs["loss"] if "loss" in errs else "",)))
+    n_lora = 2 * len(c["lora"])
+    want = 2 + c["n_layers"] * (n_lora + (1 if c["n_experts"] else 0)) + (2 if c["vocab"] else 0)
+    assert len(errs) == want, sorted(errs)
