@@ -50,9 +50,11 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
 // idx [T, top_k] = experts with the largest logits (descending, ties -> lower index), w = softmax over those logits.
 hipError_t k_moe_route(hipStream_t st, const float* logits, int* idx, float* w, int T, int E, int top_k);
 // counts [E], seg [E+1] (first slot of every expert), tile_tab (int4 {expert, first row, rows, 0} per 256-row tile, at
-// most T*top_k/256 + E of them), *ntiles, slot_of [T*top_k], row_tok [T*top_k] (token of every slot).
+// most T*top_k/256 + E of them), *ntiles, slot_of [T*top_k], row_tok [T*top_k] (token of every slot);
+// hist: scratch, ceil(T*top_k / RP_MOE_RUN) * E ints (per-run histograms, then their prefix sums).
+#define RP_MOE_RUN 512
 hipError_t k_moe_plan(hipStream_t st, const int* idx, int T, int E, int top_k, int* counts, int* seg, void* tile_tab,
-                      int* ntiles, int* slot_of, int* row_tok);
+                      int* ntiles, int* slot_of, int* row_tok, int* hist);
 // out[t] = (res[t] if res) + sum_j (w[t,j] if w else 1) * src[slot_of[t,j]];  src bf16 [T*top_k, h], out bf16 [T, h].
 hipError_t k_moe_combine(hipStream_t st, const void* src, const int* slot_of, const float* w, const void* res, void* out,
                          int T, int h, int top_k);

@@ -93,7 +93,7 @@ struct LayerBuf {   // byte offsets of one layer's saved internals
   size_t z, rstd1, n1, qkv, rstd_q, rstd_k, qr, kr, o, lse, y, rstd2, n2, gu, act, u1, u2, u3, u4;
   // mixture of experts: routing (expert and weight per (token, choice)), the slot of every entry, the token of every
   // slot, per-expert counts and first slots, the tile table of the grouped GEMMs and its length
-  size_t m_idx, m_w, m_slot, m_tok, m_cnt, m_seg, m_tab, m_ntiles;
+  size_t m_idx, m_w, m_slot, m_tok, m_cnt, m_seg, m_tab, m_ntiles, m_hist;
   size_t end;
 };
 
@@ -136,6 +136,7 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
     b.m_idx = take(Tk * 4); b.m_w = take(Tk * 4); b.m_slot = take(Tk * 4); b.m_tok = take(Tk * 4);
     b.m_cnt = take((size_t)D.E * 4); b.m_seg = take((size_t)(D.E + 1) * 4); b.m_tab = take(max_tiles * 16);
     b.m_ntiles = take(4);
+    b.m_hist = take((Tk + RP_MOE_RUN - 1) / RP_MOE_RUN * (size_t)D.E * 4);
   }
   b.end = o;
   const size_t set = o;

@@ -4,8 +4,8 @@
 //   plan     : a stable counting sort of the T*top_k (token, choice) entries by expert.  Entry i = t*top_k + j gets slot
 //              seg[e] + (number of earlier entries of the same expert); the grouped GEMMs work on slot-ordered rows, so
 //              every expert owns a contiguous row range.  Also writes the table of 256-row tiles the GEMM grid walks.
-//              Three small kernels (count, scan + tile table, assign), no atomics: the order is a function of the
-//              logits alone.
+//              Four small kernels (per-run histograms, their prefix per expert, scan + tile table, assign); the
+//              order is a function of the logits alone.
 //   combine  : out[t] = (res[t]) + sum_j (w[t,j]) * src[slot_of[t,j]], j in order -- the weighted sum of the expert
 //              outputs in the forward pass, the plain sum of the expert input gradients in the backward pass
 //   swiglu backward for slot rows: the routing weight scales the incoming gradient, and the gradient of the routing
@@ -70,17 +70,49 @@ __global__ void __launch_bounds__(256) moe_route_kernel(const float* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------------ plan
-// counts[e] = number of entries routed to expert e.  One block per expert.
-__global__ void __launch_bounds__(256) moe_count_kernel(const int* __restrict__ idx, long n, int* __restrict__ counts) {
-  __shared__ int red[4];
-  const int e = blockIdx.x;
-  int c = 0;
-  for (long i = threadIdx.x; i < n; i += 256) c += idx[i] == e;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off, 64);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
+// The entries are cut into runs of RP_MOE_RUN consecutive entries, one wave per run.
+// hist[run][e] = number of entries of run `run` routed to expert e.
+__global__ void __launch_bounds__(256) moe_hist_kernel(const int* __restrict__ idx, long n, int E, int* __restrict__ hist) {
+  extern __shared__ int s_hist[];   // [4][E]
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  int* const h = s_hist + wv * E;
+  for (int e = lane; e < E; e += 64) h[e] = 0;
   __syncthreads();
-  if (threadIdx.x == 0) counts[e] = red[0] + red[1] + red[2] + red[3];
+  const long run = (long)blockIdx.x * 4 + wv;
+  const long i0 = run * RP_MOE_RUN;
+  for (int k = lane; k < RP_MOE_RUN; k += 64)
+    if (i0 + k < n) atomicAdd(&h[idx[i0 + k]], 1);
+  __syncthreads();
+  if (i0 < n)
+    for (int e = lane; e < E; e += 64) hist[run * E + e] = h[e];
+}
+
+// Per expert (one block each): hist[run][e] becomes the number of entries of expert e in earlier runs; counts[e] = total.
+__global__ void __launch_bounds__(256) moe_prefix_kernel(int* __restrict__ hist, long nruns, int E, int* __restrict__ counts) {
+  __shared__ int s_part[256];
+  __shared__ int s_carry;
+  const int e = blockIdx.x, tid = threadIdx.x;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (long r0 = 0; r0 < nruns; r0 += 256) {
+    const long r = r0 + tid;
+    const int v = r < nruns ? hist[r * E + e] : 0;
+    s_part[tid] = v;
+    __syncthreads();
+    // inclusive scan of 256 values
+    for (int off = 1; off < 256; off <<= 1) {
+      const int add = tid >= off ? s_part[tid - off] : 0;
+      __syncthreads();
+      s_part[tid] += add;
+      __syncthreads();
+    }
+    const int carry = s_carry;
+    if (r < nruns) hist[r * E + e] = carry + s_part[tid] - v;
+    __syncthreads();
+    if (tid == 255) s_carry = carry + s_part[255];
+    __syncthreads();
+  }
+  if (tid == 0) counts[e] = s_carry;
 }
 
 // seg[e] = first slot of expert e (seg[E] = n); tile table entries {expert, first row, rows, 0} for every 256-row tile
@@ -102,31 +134,39 @@ __global__ void __launch_bounds__(1024) moe_scan_kernel(const int* __restrict__ 
 }
 
 // slot_of[i] = seg[e] + rank of entry i among the entries of its expert (entry order); row_tok[slot] = token of the
-// entry.  One block per expert walks all entries in order, 256 at a time.
-__global__ void __launch_bounds__(256) moe_assign_kernel(const int* __restrict__ idx, long n, int top_k,
-                                                         const int* __restrict__ seg, int* __restrict__ slot_of,
-                                                         int* __restrict__ row_tok) {
-  __shared__ int wsum[4];
-  const int e = blockIdx.x;
+// entry.  Every wave walks its own run 64 entries at a time; inside such a group the lanes of one expert are found with
+// a ballot per distinct expert, and the wave's running position per expert lives in LDS.
+__global__ void __launch_bounds__(256) moe_assign_kernel(const int* __restrict__ idx, long n, int E, int top_k,
+                                                         const int* __restrict__ seg, const int* __restrict__ hist,
+                                                         int* __restrict__ slot_of, int* __restrict__ row_tok) {
+  extern __shared__ int s_pos[];   // [4][E]
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  int running = seg[e];
-  for (long base = 0; base < n; base += 256) {
-    const long i = base + threadIdx.x;
-    const bool hit = i < n && idx[i] == e;
-    const unsigned long long mask = __builtin_amdgcn_ballot_w64(hit);
-    const int rank = __builtin_popcountll(mask & ((1ull << lane) - 1ull));
-    if (lane == 0) wsum[wv] = __builtin_popcountll(mask);
-    __syncthreads();
-    int before = 0, total = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { before += k < wv ? wsum[k] : 0; total += wsum[k]; }
-    if (hit) {
-      const int slot = running + before + rank;
+  int* const pos = s_pos + wv * E;
+  const long run = (long)blockIdx.x * 4 + wv;
+  const long i0 = run * RP_MOE_RUN;
+  if (i0 >= n) return;   // no barriers below: the waves are independent
+  for (int e = lane; e < E; e += 64) pos[e] = seg[e] + hist[run * E + e];
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  for (int k0 = 0; k0 < RP_MOE_RUN && i0 + k0 < n; k0 += 64) {
+    const long i = i0 + k0 + lane;
+    const bool live = i < n;
+    const int e = live ? idx[i] : -1;
+    int slot = 0;
+    unsigned long long todo = __builtin_amdgcn_ballot_w64(live);
+    while (todo) {
+      const int first = __builtin_ctzll(todo);
+      const int e0 = __builtin_amdgcn_readlane(e, first);
+      const unsigned long long m = __builtin_amdgcn_ballot_w64(e == e0);
+      const int base = pos[e0];                       // wave-uniform address
+      if (e == e0) slot = base + __builtin_popcountll(m & lt);
+      // every lane has read pos[e0] before it is advanced: LDS operations of one wave execute in order
+      if (lane == first) pos[e0] = base + __builtin_popcountll(m);
+      todo &= ~m;
+    }
+    if (live) {
       slot_of[i] = slot;
       row_tok[slot] = (int)(i / top_k);
     }
-    running += total;
-    __syncthreads();
   }
 }
 
@@ -250,13 +290,17 @@ hipError_t k_moe_route(hipStream_t st, const float* logits, int* idx, float* w, 
 }
 
 hipError_t k_moe_plan(hipStream_t st, const int* idx, int T, int E, int top_k, int* counts, int* seg, void* tile_tab,
-                      int* ntiles, int* slot_of, int* row_tok) {
+                      int* ntiles, int* slot_of, int* row_tok, int* hist) {
   if (T == 0) return hipSuccess;
   if (E > 1024) return hipErrorInvalidValue;
   const long n = (long)T * top_k;
-  RP_LAUNCH(moe_count_kernel, dim3(E), dim3(256), 0, st, idx, n, counts);
+  const long nruns = (n + RP_MOE_RUN - 1) / RP_MOE_RUN;
+  const unsigned blocks = (unsigned)((nruns + 3) / 4);
+  const size_t lds = (size_t)4 * E * sizeof(int);
+  RP_LAUNCH(moe_hist_kernel, dim3(blocks), dim3(256), lds, st, idx, n, E, hist);
+  RP_LAUNCH(moe_prefix_kernel, dim3(E), dim3(256), 0, st, hist, nruns, E, counts);
   RP_LAUNCH(moe_scan_kernel, dim3(1), dim3(1024), 0, st, (const int*)counts, E, seg, (int4*)tile_tab, ntiles);
-  RP_LAUNCH(moe_assign_kernel, dim3(E), dim3(256), 0, st, idx, n, top_k, (const int*)seg, slot_of, row_tok);
+  RP_LAUNCH(moe_assign_kernel, dim3(blocks), dim3(256), lds, st, idx, n, E, top_k, (const int*)seg, (const int*)hist, slot_of, row_tok);
   return hipGetLastError();
 }
 
@@ -267,6 +311,8 @@ hipError_t k_moe_combine(hipStream_t st, const void* src, const int* slot_of, co
   const int grid = (T + 3) / 4;
   if (h <= 2048)
     RP_LAUNCH(moe_combine_kernel<4>, dim3(grid), dim3(256), 0, st, (const bf16*)src, slot_of, w, (const bf16*)res, (bf16*)out, T, h, top_k);
+  else if (h <= 4096)   // half the accumulator registers of the widest variant: more waves, more loads in flight
+    RP_LAUNCH(moe_combine_kernel<8>, dim3(grid), dim3(256), 0, st, (const bf16*)src, slot_of, w, (const bf16*)res, (bf16*)out, T, h, top_k);
   else
     RP_LAUNCH(moe_combine_kernel<16>, dim3(grid), dim3(256), 0, st, (const bf16*)src, slot_of, w, (const bf16*)res, (bf16*)out, T, h, top_k);
   return hipGetLastError();

@@ -331,8 +331,8 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z, 
     // router in the stage: logits = n2 Wr^T in fp32 (bf16 operands), so that the selection is a function of n2 alone
     if (c.moe_router) X.gemm_f32_nt(S(b.n2), D.h, W.t(RP_T_WR), D.h, X.router, D.E, T, D.E, D.h);
     RUN(X, "moe_route", 0, 4.0 * Td * D.E + 8.0 * Tkd, k_moe_route(X.st, X.router, idx, w, T, D.E, D.topk));
-    RUN(X, "moe_plan", 0, 8.0 * Tkd * D.E, k_moe_plan(X.st, idx, T, D.E, D.topk, (int*)S(b.m_cnt), (int*)S(b.m_seg), S(b.m_tab),
-                                                     (int*)S(b.m_ntiles), slot_of, (int*)S(b.m_tok)));
+    RUN(X, "moe_plan", 0, 16.0 * Tkd, k_moe_plan(X.st, idx, T, D.E, D.topk, (int*)S(b.m_cnt), (int*)S(b.m_seg), S(b.m_tab),
+                                                     (int*)S(b.m_ntiles), slot_of, (int*)S(b.m_tok), (int*)S(b.m_hist)));
     X.gemm_grouped(GEMM_NT, set, S(b.n2), D.h, T, true, W.t(RP_T_WGU), D.h, (long)2 * D.m * D.h, S(b.gu), 2 * D.m, 2 * D.m, D.h);
     RUN(X, "swiglu_fwd", 0, 6.0 * Tkd * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), Tk, D.m));
     X.gemm_grouped(GEMM_NT, set, S(b.act), D.m, (int)Tk, false, W.t(RP_T_WD), D.m, (long)D.h * D.m, f, D.h, D.h, D.m);
