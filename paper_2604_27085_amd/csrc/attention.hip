@@ -107,6 +107,19 @@ RP_DEV uint4 pack_frag(const f32x16& s, int off) {
 
 RP_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// x as the sum of three bf16 numbers (most significant first) in the first three slots of an MFMA operand chunk, zeros
+// in the other five: 24 mantissa bits survive, so an MFMA step against ones adds x to an fp32 accumulator exactly
+// enough for a softmax exponent.
+RP_DEV uint4 split3(float x) {
+  const uint32_t h = f32_to_bf16_bits(x);
+  const float r1 = x - bf16_bits_to_f32(h);
+  const uint32_t m = f32_to_bf16_bits(r1);
+  const uint32_t l = f32_to_bf16_bits(r1 - bf16_bits_to_f32(m));
+  return make_uint4(h | (m << 16), l, 0u, 0u);
+}
+// The other operand of that step: ones in the same three slots for the lanes that hold reduction indices 0..7.
+RP_DEV uint4 ones3(int lk) { return lk == 0 ? make_uint4(0x3F803F80u, 0x00003F80u, 0u, 0u) : make_uint4(0u, 0u, 0u, 0u); }
+
 // Writes a wave's 32 x D transposed accumulator (columns = the wave's 32 rows of the output) through LDS to global.
 template <int D>
 RP_DEV void store_acc_T(const f32x16 (&acc)[D / 32], float mul, bf16* stage /* [32][D+8] */, bf16* __restrict__ out,
@@ -477,8 +490,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
   bf16* const dOs = smem + 64 * LDK;
   bf16* const Qt = smem + 2 * 64 * LDK;
   bf16* const dOt = Qt + 64 * LDT;
-  float* const lse_s = stats;
-  float* const dl_s = stats + 64;
+  (void)stats;
 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -519,6 +531,11 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
   const bf16* dofrag = dOs + lr * LDK + 8 * lk;
   const bf16* qtfrag = Qt + tr_base<LDT>(lane);
   const bf16* dotfrag = dOt + tr_base<LDT>(lane);
+  // -lse/scale and -delta ride in the pad chunks of the Q and dO rows and enter through one extra MFMA step each (see
+  // the two-kernel version below)
+  const bf16* qx = Qs + lr * LDK + D;
+  const bf16* dox = dOs + lr * LDK + D;
+  const uint4 one_f = ones3(lk);
 
   uint4 qreg[T64::NREG], doreg[T64::NREG];
   float st_reg = 0.f;
@@ -531,8 +548,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
     if (tid < 128) {
       const int qi = q0 + (tid & 63);
       const long sidx = ((long)b * p.a + hq) * p.seq + (qi < p.seq ? qi : 0);
-      const float v = tid < 64 ? p.lse_in[sidx] * 1.4426950408889634f : p.delta[sidx];
-      st_reg = qi < p.seq ? v : (tid < 64 ? INFINITY : 0.f);   // padded query rows get P = 0
+      const float v = tid < 64 ? -p.lse_in[sidx] / p.scale : -p.delta[sidx];
+      st_reg = qi < p.seq ? v : (tid < 64 ? -3.0e4f : 0.f);   // padded query rows get P = exp(-3e4 scale) = 0
     }
   };
   if (niter > 0) prefetch(0);
@@ -543,7 +560,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
     T64::template store<LDT>(qreg, Qt, tid);
     T64::template store<LDK>(doreg, dOs, tid);
     T64::template store<LDT>(doreg, dOt, tid);
-    if (tid < 128) stats[tid] = st_reg;
+    if (tid < 64) *reinterpret_cast<uint4*>(Qs + tid * LDK + D) = split3(st_reg);
+    else if (tid < 128) *reinterpret_cast<uint4*>(dOs + (tid - 64) * LDK + D) = split3(st_reg);
     __syncthreads();
     if (it + 1 < niter) prefetch(it + 1);
     const int q0 = (qt0 + it) * 64;
@@ -561,20 +579,25 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
           s = mfma32(aq, kf[ks], ks == 0 ? zero16 : s);
           dp = mfma32(ad, vf[ks], ks == 0 ? zero16 : dp);
         }
+        s = mfma32(*reinterpret_cast<const uint4*>(qx + 32 * t2 * LDK), one_f, s);
+        dp = mfma32(*reinterpret_cast<const uint4*>(dox + 32 * t2 * LDK), one_f, dp);
         // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
+        // the branch is taken per tile, not per element: away from the diagonal nothing below compares positions
+        if (need_mask) {
 #pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-          const int ql = 32 * t2 + 8 * vg + 4 * lk;
-          const float4 l4 = *reinterpret_cast<const float4*>(lse_s + ql);
-          const float4 d4 = *reinterpret_cast<const float4*>(dl_s + ql);
-          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int v = 4 * vg + e;
-            float pr = fast_exp2(__builtin_fmaf(s[v], p.scale_log2e, -lv[e]));
-            if (need_mask) pr = (kpos > q0 + ql + e || !kok) ? 0.f : pr;
+          for (int v = 0; v < 16; ++v) {
+            const int qpos = q0 + 32 * t2 + 8 * (v >> 2) + 4 * lk + (v & 3);
+            float pr = fast_exp2(s[v] * p.scale_log2e);
+            pr = (kpos > qpos || !kok) ? 0.f : pr;
             s[v] = pr;                         // P
-            dp[v] = pr * (dp[v] - dv4[e]);     // dS
+            dp[v] = pr * dp[v];                // dS
+          }
+        } else {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const float pr = fast_exp2(s[v] * p.scale_log2e);
+            s[v] = pr;
+            dp[v] = pr * dp[v];
           }
         }
 #pragma unroll
@@ -623,8 +646,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) 
   bf16* const Qs = smem;
   bf16* const dOs = smem + 64 * LDK;                     // dK only
   bf16* const Tt = smem + (DV ? 1 : 2) * 64 * LDK;       // the transposed-read tile: dO (dV) or Q (dK)
-  float* const lse_s = stats;
-  float* const dl_s = stats + 64;
+  (void)stats;
 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -664,6 +686,13 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) 
   const bf16* qfrag = Qs + lr * LDK + 8 * lk;
   const bf16* dofrag = dOs + lr * LDK + 8 * lk;
   const bf16* tfrag = Tt + tr_base<LDT>(lane);
+  // The per-query terms of the softmax recomputation ride along in the products: the pad chunk of a Q row holds
+  // -lse/scale split into three bf16 numbers, that of a dO row -delta, and one extra MFMA step against ones3() adds
+  // them, so the score tile comes out as q.k - lse/scale and the dP tile as dO.v - delta.  (Rows of the score tile are
+  // queries here: without this every lane would need sixteen different lse and delta values per tile.)
+  const bf16* qx = Qs + lr * LDK + D;
+  const bf16* dox = dOs + lr * LDK + D;
+  const uint4 one_f = ones3(lk);
 
   uint4 qreg[T64::NREG], doreg[T64::NREG];
   float st_reg = 0.f;
@@ -676,8 +705,8 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) 
     if (tid < (DV ? 64 : 128)) {
       const int qi = q0 + (tid & 63);
       const long sidx = ((long)b * p.a + hq) * p.seq + (qi < p.seq ? qi : 0);
-      const float v = tid < 64 ? p.lse_in[sidx] * 1.4426950408889634f : p.delta[sidx];
-      st_reg = qi < p.seq ? v : (tid < 64 ? INFINITY : 0.f);   // padded query rows get P = 0
+      const float v = tid < 64 ? -p.lse_in[sidx] / p.scale : -p.delta[sidx];
+      st_reg = qi < p.seq ? v : (tid < 64 ? -3.0e4f : 0.f);   // padded query rows get P = exp(-3e4 scale) = 0
     }
   };
   if (niter > 0) prefetch(0);
@@ -691,7 +720,8 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) 
       T64::template store<LDK>(doreg, dOs, tid);
       T64::template store<LDT>(qreg, Tt, tid);
     }
-    if (tid < (DV ? 64 : 128)) stats[tid] = st_reg;
+    if (tid < 64) *reinterpret_cast<uint4*>(Qs + tid * LDK + D) = split3(st_reg);
+    else if (!DV && tid < 128) *reinterpret_cast<uint4*>(dOs + (tid - 64) * LDK + D) = split3(st_reg);
     __syncthreads();
     if (it + 1 < niter) prefetch(it + 1);
     const int q0 = (qt0 + it) * 64;
@@ -711,24 +741,25 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) 
           dp = mfma32(ad, vf[ks], ks == 0 ? zero16 : dp);
         }
       }
+      s = mfma32(*reinterpret_cast<const uint4*>(qx + 32 * t2 * LDK), one_f, s);
+      if constexpr (!DV) dp = mfma32(*reinterpret_cast<const uint4*>(dox + 32 * t2 * LDK), one_f, dp);
       // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
+      // the branch is taken per tile, not per element: away from the diagonal nothing below compares positions
+      if (need_mask) {
 #pragma unroll
-      for (int vg = 0; vg < 4; ++vg) {
-        const int ql = 32 * t2 + 8 * vg + 4 * lk;
-        const float4 l4 = *reinterpret_cast<const float4*>(lse_s + ql);
-        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-        float dv4[4] = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (!DV) {
-          const float4 d4 = *reinterpret_cast<const float4*>(dl_s + ql);
-          dv4[0] = d4.x; dv4[1] = d4.y; dv4[2] = d4.z; dv4[3] = d4.w;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int v = 4 * vg + e;
-          float pr = fast_exp2(__builtin_fmaf(s[v], p.scale_log2e, -lv[e]));
-          if (need_mask) pr = (kpos > q0 + ql + e || !kok) ? 0.f : pr;
+        for (int v = 0; v < 16; ++v) {
+          const int qpos = q0 + 32 * t2 + 8 * (v >> 2) + 4 * lk + (v & 3);
+          float pr = fast_exp2(s[v] * p.scale_log2e);
+          pr = (kpos > qpos || !kok) ? 0.f : pr;
           if constexpr (DV) s[v] = pr;                         // P
-          else s[v] = pr * (dp[v] - dv4[e]);                   // dS
+          else s[v] = pr * dp[v];                              // dS
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float pr = fast_exp2(s[v] * p.scale_log2e);
+          if constexpr (DV) s[v] = pr;
+          else s[v] = pr * dp[v];
         }
       }
 #pragma unroll
