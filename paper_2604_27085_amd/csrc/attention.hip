@@ -272,14 +272,22 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
         // maximum grows) makes the compiler carry a second copy of the accumulator through the loop, which costs more
         // than the multiplies.  The first key tile contains key 0 <= qpos, so m_run is finite from then on.
         {
-          const float m_new = fmaxf(m_run[t], mx);
-          const float alpha = fast_exp2(m_run[t] - m_new);
-          l_run[t] *= alpha;
-          m_run[t] = m_new;
+          // m_run is a reference exponent, not the exact running maximum: it moves only when a row's maximum outgrows
+          // it by 2^8 (the probabilities stay below 256, harmless in fp32 sums and bf16 operands), so after the first
+          // few key tiles almost every tile skips the rescale of the accumulator.  The skip is a wave-uniform branch,
+          // and alpha passes through an empty asm statement so that the multiplies cannot be hoisted out of it.
+          const bool grow = mx > m_run[t] + 8.f;
+          if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+            const float m_new = grow ? mx : m_run[t];
+            float alpha = fast_exp2(m_run[t] - m_new);
+            asm volatile("" : "+v"(alpha));
+            l_run[t] *= alpha;
+            m_run[t] = m_new;
 #pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[t][dt][v] *= alpha;
+              for (int v = 0; v < 16; ++v) oacc[t][dt][v] *= alpha;
+          }
         }
         float psum = 0.f;
 #pragma unroll
