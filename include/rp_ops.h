@@ -44,6 +44,17 @@ RP_API rp_status rp_op_qknorm_rope(void* stream, int bwd, int d, const void* in_
 RP_API rp_status rp_op_swiglu_fwd(void* stream, const void* gu, void* act, long T, int m);
 RP_API rp_status rp_op_swiglu_bwd(void* stream, const void* dact, const void* gu, void* dgu, long T, int m);
 
+/* Routing of a top-k mixture of experts (the MoE layer of App. B.2) and the plan of its grouped products.
+ * logits [dev] fp32 [T, E].  idx [dev] int32 [T, top_k]: the top_k largest logits of every token, descending, ties to the
+ * lower expert; w [dev] fp32 [T, top_k]: the softmax over them.  counts [dev] int32 [E]: entries per expert; seg [dev]
+ * int32 [E + 1]: first slot of every expert (seg[E] = T * top_k); slot_of [dev] int32 [T * top_k]: slot of entry
+ * t * top_k + j = seg[e] + number of earlier entries of the same expert (a stable counting sort); row_tok [dev] int32
+ * [T * top_k]: token of every slot; tile_tab [dev] 16 bytes x (T * top_k / 256 + E + 1): {expert, first row, rows, 0} of
+ * every 256-row tile in expert order, *ntiles [dev] their number; hist [dev] scratch, ceil(T * top_k / 512) * E int32.
+ * E <= 1024, top_k <= min(E, 64). */
+RP_API rp_status rp_op_moe_route_plan(void* stream, const float* logits, int T, int E, int top_k, int* idx, float* w,
+                               int* counts, int* seg, void* tile_tab, int* ntiles, int* slot_of, int* row_tok, int* hist);
+
 /* Causal grouped-query attention (the attention term of App. B.2), flash style.  q, o [T, a, d]; k, v [T, kh, d];
  * row strides ld* in elements; lse fp32 [batch, a, seq] (natural log). */
 RP_API rp_status rp_op_attn_fwd(void* stream, const void* q, const void* k, const void* v, void* o, float* lse, long ldq, long ldk,

@@ -100,6 +100,7 @@ _SIGS = {
                           _vp, _vp, _i, _i, _i, _i, _i, _f],
     "rp_op_swiglu_fwd": [_vp, _vp, _vp, _l, _i],
     "rp_op_swiglu_bwd": [_vp, _vp, _vp, _vp, _l, _i],
+    "rp_op_moe_route_plan": [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "rp_op_attn_fwd": [_vp, _vp, _vp, _vp, _vp, _vp, _l, _l, _l, _l, _i, _i, _i, _i, _i],
     "rp_op_attn_bwd": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _l, _l, _l, _l, _l, _l, _l, _l, _i, _i, _i,
                        _i, _i],
@@ -315,6 +316,11 @@ def rp_op_swiglu_fwd(stream, gu, act, T_, m):
 
 def rp_op_swiglu_bwd(stream, dact, gu, dgu, T_, m):
     _check(lib.rp_op_swiglu_bwd(stream, _ptr(dact), _ptr(gu), _ptr(dgu), T_, m))
+
+
+def rp_op_moe_route_plan(stream, logits, T_, E, top_k, idx, w, counts, seg, tile_tab, ntiles, slot_of, row_tok, hist):
+    _check(lib.rp_op_moe_route_plan(stream, _ptr(logits), T_, E, top_k, _ptr(idx), _ptr(w), _ptr(counts), _ptr(seg),
+                                    _ptr(tile_tab), _ptr(ntiles), _ptr(slot_of), _ptr(row_tok), _ptr(hist)))
 
 
 def rp_op_attn_fwd(stream, q, k, v, o, lse, ldq, ldk, ldv, ldo, batch, seq, a, kh, d):

@@ -821,6 +821,17 @@ rp_status rp_op_swiglu_bwd(void* stream, const void* dact, const void* gu, void*
   OP_RET(e);
 }
 
+rp_status rp_op_moe_route_plan(void* stream, const float* logits, int T, int E, int top_k, int* idx, float* w, int* counts,
+                               int* seg, void* tile_tab, int* ntiles, int* slot_of, int* row_tok, int* hist) {
+  if (!logits || !idx || !w || !counts || !seg || !tile_tab || !ntiles || !slot_of || !row_tok || !hist || T < 0 || E <= 0 ||
+      E > 1024 || top_k <= 0 || top_k > E || top_k > 64)
+    return fail(nullptr, RP_EINVAL, "rp_op_moe_route_plan: bad arguments");
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e = k_moe_route(st, logits, idx, w, T, E, top_k);
+  if (e == hipSuccess) e = k_moe_plan(st, idx, T, E, top_k, counts, seg, tile_tab, ntiles, slot_of, row_tok, hist);
+  OP_RET(e);
+}
+
 rp_status rp_op_attn_fwd(void* stream, const void* q, const void* k, const void* v, void* o, float* lse, long ldq, long ldk,
                          long ldv, long ldo, int batch, int seq, int a, int kh, int d) {
   if (!q || !k || !v || !o || !lse || (d != 64 && d != 128) || a <= 0 || kh <= 0 || a % kh || ldq % 8 || ldk % 8 || ldv % 8 || ldo % 8)

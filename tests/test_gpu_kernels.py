@@ -251,3 +251,48 @@ def test_attention_fwd_bwd(rp, d, a, kh, batch, seq):
     assert rel_l2(H.to_f32(dq).reshape(T, a, d), dq_ref) < 1e-2
     assert rel_l2(dkv_h[:, : kh * d].reshape(T, kh, d), dk_ref) < 1e-2
     assert rel_l2(dkv_h[:, kh * d:].reshape(T, kh, d), dv_ref) < 1e-2
+
+
+# ----------------------------------------------------------------------------------------------- MoE routing and plan
+@pytest.mark.parametrize("T,E,k", [(1, 8, 2), (200, 8, 2), (1064, 128, 8), (3000, 32, 4), (77, 6, 6), (520, 1024, 3)])
+def test_moe_route_and_plan_are_exact(rp, T, E, k):
+    """Index work, compared bit for bit: the selected experts (with planted exact ties), the stable counting sort of
+    the (token, choice) entries, the per-expert segments and the table of 256-row tiles.  The routing weights are
+    floating point and compared to fp32 rounding."""
+    B, H = rp
+    rng = np.random.default_rng(9000 + T + E)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    if T > 3 and E >= 4:                       # exact ties: the lower expert index must win
+        logits[1, :] = 0.25
+        logits[2, E - 1] = logits[2, 0] = 3.0
+    n = T * k
+    dv = "cuda:0"
+    d_logits = torch.from_numpy(logits).to(dv)
+    i32 = lambda m: torch.full((max(m, 1),), -7, dtype=torch.int32, device=dv)
+    idx, counts, seg, ntiles, slot_of, row_tok = i32(n), i32(E), i32(E + 1), i32(1), i32(n), i32(n)
+    max_tiles = n // 256 + E + 1
+    tab = torch.full((max_tiles, 4), -7, dtype=torch.int32, device=dv)
+    hist = i32((n + 511) // 512 * E)
+    w = torch.zeros(n, dtype=torch.float32, device=dv)
+    B.rp_op_moe_route_plan(stream(), d_logits, T, E, k, idx, w, counts, seg, tab, ntiles, slot_of, row_tok, hist)
+    torch.cuda.synchronize()
+    ref_idx, ref_w = L.moe_route(logits.astype(np.float64), k)
+    got_idx = idx.cpu().numpy()[:n].reshape(T, k)
+    assert np.array_equal(got_idx, ref_idx)
+    assert np.max(np.abs(w.cpu().numpy()[:n].reshape(T, k) - ref_w)) < 1e-6
+    flat = ref_idx.reshape(-1)
+    ref_counts = np.bincount(flat, minlength=E)
+    ref_seg = np.concatenate([[0], np.cumsum(ref_counts)])
+    order = np.argsort(flat, kind="stable")           # slot -> entry
+    ref_slot = np.empty(n, dtype=np.int64)
+    ref_slot[order] = np.arange(n)
+    assert np.array_equal(counts.cpu().numpy(), ref_counts)
+    assert np.array_equal(seg.cpu().numpy(), ref_seg)
+    assert np.array_equal(slot_of.cpu().numpy()[:n], ref_slot)
+    assert np.array_equal(row_tok.cpu().numpy()[:n], order // k)
+    tiles = []
+    for e in range(E):
+        for r0 in range(0, int(ref_counts[e]), 256):
+            tiles.append((e, int(ref_seg[e]) + r0, min(256, int(ref_counts[e]) - r0), 0))
+    assert int(ntiles.item()) == len(tiles) <= max_tiles
+    assert np.array_equal(tab.cpu().numpy()[:len(tiles)], np.array(tiles, dtype=np.int32).reshape(-1, 4))
