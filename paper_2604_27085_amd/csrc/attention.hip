@@ -492,13 +492,11 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
   constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32;
   using T64 = Tile64<D, 256>;
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-  float* const stats = reinterpret_cast<float*>(dyn_smem);          // 128 floats: lse (log2 units), delta
-  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem + 512);       // 2*64*LDK + 2*64*LDT elements
+  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);             // 2*64*LDK + 2*64*LDT elements
   bf16* const Qs = smem;
   bf16* const dOs = smem + 64 * LDK;
   bf16* const Qt = smem + 2 * 64 * LDK;
   bf16* const dOt = Qt + 64 * LDT;
-  (void)stats;
 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -648,13 +646,11 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) 
   constexpr bool DV = WHAT == 0;
   using T64 = Tile64<D, 256>;
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-  float* const stats = reinterpret_cast<float*>(dyn_smem);          // 128 floats: lse (log2 units), delta
-  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem + 512);
+  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);
   // dV: Qs [64][LDK] | dOt [64][LDT];   dK: Qs | dOs [64][LDK] | Qt [64][LDT]
   bf16* const Qs = smem;
   bf16* const dOs = smem + 64 * LDK;                     // dK only
   bf16* const Tt = smem + (DV ? 1 : 2) * 64 * LDK;       // the transposed-read tile: dO (dV) or Q (dK)
-  (void)stats;
 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -822,12 +818,12 @@ __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __res
 }
 
 constexpr int dq_smem_bytes(int d) { return (2 * 64 * (d + 8) + 64 * (d + 32)) * 2; }
-constexpr int dkv_fused_smem_bytes(int d) { return 512 + (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
+constexpr int dkv_fused_smem_bytes(int d) { return (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
 // operand tiles of the loop, or the four waves' fp32 staging of the epilogue, whichever is larger
 constexpr int dkv_smem_bytes(int d, int what) {
   const int loop = ((what == 0 ? 1 : 2) * 64 * (d + 8) + 64 * (d + 32)) * 2;
   const int stage = 4 * 32 * (d + 4) * 4;
-  return 512 + (loop > stage ? loop : stage);
+  return loop > stage ? loop : stage;
 }
 
 void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
