@@ -96,6 +96,7 @@ def main():
     ap.add_argument("--no-upload-leg", "--core-only", dest="no_upload_leg", action="store_true",
                     help="only the timed steps and the timeline steps: no forward-stage, upload or round legs (profiling runs)")
     ap.add_argument("--round-streams", type=int, default=1, help="transfer streams per direction in that leg (1 or 2)")
+    ap.add_argument("--round-piece-mib", type=int, default=0, help="largest transfer piece in that leg (0 = the library's default)")
     ap.add_argument("--round-micro", type=int, default=4, help="micro-batches per round in the multi-stream leg")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -285,7 +286,8 @@ def main():
 
         def rnd(i):
             R.round(xh, oh, slot=i & 1, dy_host=dyh, next_slot=(i + 1) & 1, next_host_blob=host,
-                    done_grads_dev=R.grads if R.gbytes else None, done_grads_host=g_host)
+                    done_grads_dev=R.grads if R.gbytes else None, done_grads_host=g_host,
+                    max_piece_bytes=args.round_piece_mib << 20)
 
         R.upload(host, slot=0)
         plain()
