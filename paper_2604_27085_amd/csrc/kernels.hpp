@@ -68,5 +68,17 @@ hipError_t k_moe_dlogits(hipStream_t st, const int* idx, const float* w, const i
 
 // Cross-entropy helpers.  part [P, T] (max, sumexp) partials -> lse[T]; then loss / coef from lse, label logits, labels.
 hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, float* lse, int T);
+// Frozen head, one sweep over the vocabulary: per chunk, z [vc, T] fp32 -> p = exp(z - m_t) [vc, T] bf16 against the
+// per-token reference exponent m (moved, with l rescaled and alpha set, when the chunk outgrows it), l += row sums,
+// zlab[t] = z at the label when it lies in the chunk (labels are global, v0 = first vocabulary row of the chunk).
+// pmax: scratch, ceil(vc / 256) * T floats.
+hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, int v0, const int* labels, float* pmax, float* zlab,
+                             int first, float* m, float* l, float* alpha, void* p);
+// acc[t, :] *= alpha[t] where alpha[t] != 1.
+hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int T, int h);
+hipError_t k_ce_lse_from_ref(hipStream_t st, const float* m, const float* l, float* lse, int T);
+// acc[t, :] = coef[t] * (acc[t, :] / l[t] - W[labels[t], :]) (zero where coef is zero).
+hipError_t k_ce_frozen_dx(hipStream_t st, float* acc, const float* l, const float* coef, const int* labels, const void* W, int T, int h,
+                          int V);
 hipError_t k_ce_finalize(hipStream_t st, const float* lse, const float* zlab, const int* labels, float grad_scale,
                          float* coef, float* loss_out, int T);

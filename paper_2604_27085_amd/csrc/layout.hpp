@@ -110,6 +110,7 @@ struct Plan {
   size_t fwd_bytes, bwd_bytes;
   // head
   size_t h_xf, h_rstd, h_part, h_zlab, h_lse, h_coef, h_dzt, h_dxacc, h_partials, head_bytes;
+  size_t h_z, h_m, h_l, h_alpha;   // frozen head: fp32 logits of one chunk, reference exponent, normaliser, rescale factor
   int head_chunk, head_parts;
   LayerBuf lb;                                    // offsets relative to a layer set
 };
@@ -177,6 +178,10 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
     P.h_zlab = take(T * 4); P.h_lse = take(T * 4); P.h_coef = take(T * 4);
     P.h_dzt = take((size_t)P.head_chunk * T * 2); P.h_dxacc = take(T * D.h * 4);
     P.h_partials = take((size_t)RP_PARTIAL_BLOCKS * D.h * 4);
+    if (!c.train_base) {
+      P.h_z = take((size_t)P.head_chunk * T * 4);
+      P.h_m = take(T * 4); P.h_l = take(T * 4); P.h_alpha = take(T * 4);
+    }
   }
   P.head_bytes = o;
   return P;

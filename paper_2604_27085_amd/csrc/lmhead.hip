@@ -67,7 +67,142 @@ __global__ void __launch_bounds__(1024) ce_finalize_kernel(const float* __restri
   for (int t = tid; t < T; t += 1024) coef[t] = labels[t] != -100 ? c : 0.f;
 }
 
+// ---- frozen head: one sweep over the vocabulary (no dW, so the softmax normaliser is only needed at the end) ---------
+// Per vocabulary chunk the logits Z^T [vc, T] (fp32) are turned into p = exp(z - m_t) against a per-token reference
+// exponent m_t, and acc_t = sum_v p_tv W_v, l_t = sum_v p_tv are carried from chunk to chunk; when a chunk's maximum
+// outgrows the reference by more than 2^8 (in e-units: 8), the reference moves and acc_t, l_t are rescaled.  At the end
+// lse_t = m_t + log l_t and dx_t = coef_t (acc_t / l_t - W[y_t]).
+
+constexpr int CE_SLAB = 256;    // rows per partial maximum
+constexpr int CE_PROB_ROWS = 512;
+
+// pmax[slab][t] = max over the slab's rows of z[r][t]; zlab[t] = z[label_t - v0][t] when the label is in this chunk.
+__global__ void __launch_bounds__(256) ce_chunk_max_kernel(const float* __restrict__ z, int vc, int T, int v0,
+                                                           const int* __restrict__ labels, float* __restrict__ pmax,
+                                                           float* __restrict__ zlab) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int r0 = blockIdx.y * CE_SLAB, r1 = min(r0 + CE_SLAB, vc);
+  float m = -INFINITY;
+  for (int r = r0; r < r1; ++r) m = fmaxf(m, z[(long)r * T + t]);
+  pmax[(long)blockIdx.y * T + t] = m;
+  const int lab = labels[t] - v0;
+  if (lab >= r0 && lab < r1) zlab[t] = z[(long)lab * T + t];
+}
+
+// Moves the reference exponent of every token if this chunk needs it and rescales l; alpha[t] is the factor acc_t must
+// be multiplied with (1 for most tokens and chunks).
+__global__ void __launch_bounds__(256) ce_chunk_ref_kernel(const float* __restrict__ pmax, int nslab, int T, int first,
+                                                           float* __restrict__ m, float* __restrict__ l,
+                                                           float* __restrict__ alpha) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  float cm = -INFINITY;
+  for (int i = 0; i < nslab; ++i) cm = fmaxf(cm, pmax[(long)i * T + t]);
+  if (first) { m[t] = cm; l[t] = 0.f; alpha[t] = 1.f; return; }
+  const float mo = m[t];
+  if (cm > mo + 8.f) {
+    const float a = __expf(mo - cm);
+    m[t] = cm; l[t] *= a; alpha[t] = a;
+  } else {
+    alpha[t] = 1.f;
+  }
+}
+
+// p[r][t] = exp(z[r][t] - m[t]) as bf16, l[t] += the fp32 sum over the block's rows.  Two tokens per thread.
+__global__ void __launch_bounds__(256) ce_chunk_prob_kernel(const float* __restrict__ z, int vc, int T,
+                                                            const float* __restrict__ m, bf16* __restrict__ p,
+                                                            float* __restrict__ l) {
+  const int t = (blockIdx.x * 256 + threadIdx.x) * 2;
+  if (t >= T) return;
+  const int r0 = blockIdx.y * CE_PROB_ROWS, r1 = min(r0 + CE_PROB_ROWS, vc);
+  const float m0 = m[t], m1 = m[t + 1];
+  float s0 = 0.f, s1 = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    const float2 zz = *reinterpret_cast<const float2*>(z + (long)r * T + t);
+    const float p0 = __expf(zz.x - m0), p1 = __expf(zz.y - m1);
+    s0 += p0; s1 += p1;
+    *reinterpret_cast<uint32_t*>(p + (long)r * T + t) = pack_bf16x2(p0, p1);
+  }
+  atomicAdd(l + t, s0);
+  atomicAdd(l + t + 1, s1);
+}
+
+// acc[t, :] *= alpha[t] for the rows whose reference moved.  One wave per row.
+__global__ void __launch_bounds__(256) ce_rescale_rows_kernel(float* __restrict__ acc, const float* __restrict__ alpha, int T, int h) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= T) return;
+  const float a = alpha[t];
+  if (a == 1.f) return;
+  float4* row = reinterpret_cast<float4*>(acc + (long)t * h);
+  for (int c = lane; c < h / 4; c += 64) { float4 v = row[c]; v.x *= a; v.y *= a; v.z *= a; v.w *= a; row[c] = v; }
+}
+
+__global__ void __launch_bounds__(256) ce_lse_from_ref_kernel(const float* __restrict__ m, const float* __restrict__ l,
+                                                              float* __restrict__ lse, int T) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t < T) lse[t] = m[t] + logf(l[t]);
+}
+
+// acc[t, :] = coef[t] * (acc[t, :] / l[t] - W[label_t, :]); rows with coef 0 (ignored labels) become zero.
+__global__ void __launch_bounds__(256) ce_frozen_dx_kernel(float* __restrict__ acc, const float* __restrict__ l,
+                                                           const float* __restrict__ coef, const int* __restrict__ labels,
+                                                           const bf16* __restrict__ W, int T, int h, int V) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= T) return;
+  const float c = coef[t];
+  float4* row = reinterpret_cast<float4*>(acc + (long)t * h);
+  if (c == 0.f) {
+    for (int q = lane; q < h / 4; q += 64) row[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
+  const float il = c / l[t];
+  const int lab = labels[t];
+  const bool has = lab >= 0 && lab < V;          // a label outside the vocabulary has no logit to subtract
+  const uint2* wr = reinterpret_cast<const uint2*>(W + (long)(has ? lab : 0) * h);
+  for (int q = lane; q < h / 4; q += 64) {
+    float4 v = row[q];
+    const uint2 w2 = has ? wr[q] : make_uint2(0u, 0u);
+    v.x = v.x * il - c * bf16_lo(w2.x); v.y = v.y * il - c * bf16_hi(w2.x);
+    v.z = v.z * il - c * bf16_lo(w2.y); v.w = v.w * il - c * bf16_hi(w2.y);
+    row[q] = v;
+  }
+}
+
 }  // namespace
+
+hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, int v0, const int* labels, float* pmax, float* zlab,
+                             int first, float* m, float* l, float* alpha, void* p) {
+  if (T == 0 || vc == 0) return hipSuccess;
+  if (T % 2) return hipErrorInvalidValue;
+  const int nslab = (vc + CE_SLAB - 1) / CE_SLAB;
+  RP_LAUNCH(ce_chunk_max_kernel, dim3((T + 255) / 256, nslab), dim3(256), 0, st, z, vc, T, v0, labels, pmax, zlab);
+  RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float*)pmax, nslab, T, first, m, l, alpha);
+  RP_LAUNCH(ce_chunk_prob_kernel, dim3((T / 2 + 255) / 256, (vc + CE_PROB_ROWS - 1) / CE_PROB_ROWS), dim3(256), 0, st, z, vc, T,
+            (const float*)m, (bf16*)p, l);
+  return hipGetLastError();
+}
+
+hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int T, int h) {
+  if (T == 0) return hipSuccess;
+  if (h % 4) return hipErrorInvalidValue;
+  RP_LAUNCH(ce_rescale_rows_kernel, dim3((T + 3) / 4), dim3(256), 0, st, acc, alpha, T, h);
+  return hipGetLastError();
+}
+
+hipError_t k_ce_lse_from_ref(hipStream_t st, const float* m, const float* l, float* lse, int T) {
+  if (T == 0) return hipSuccess;
+  RP_LAUNCH(ce_lse_from_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, m, l, lse, T);
+  return hipGetLastError();
+}
+
+hipError_t k_ce_frozen_dx(hipStream_t st, float* acc, const float* l, const float* coef, const int* labels, const void* W, int T, int h,
+                          int V) {
+  if (T == 0) return hipSuccess;
+  if (h % 4) return hipErrorInvalidValue;
+  RP_LAUNCH(ce_frozen_dx_kernel, dim3((T + 3) / 4), dim3(256), 0, st, acc, l, coef, labels, (const bf16*)W, T, h, V);
+  return hipGetLastError();
+}
 
 hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, float* lse, int T) {
   if (T == 0) return hipSuccess;

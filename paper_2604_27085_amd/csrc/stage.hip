@@ -422,6 +422,13 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
       k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, x, W.t(RP_T_G1), (const float*)S(b.rstd1), dy, dx_out, G.t(RP_T_G1), X.at<float>(X.P.partials), T, D.h));
 }
 
+// RP_HEAD_ONE_SWEEP=0 keeps the two-sweep schedule for a frozen head as well (comparison runs)
+bool env_head_one_sweep() {
+  static int v = -1;
+  if (v < 0) { const char* e = getenv("RP_HEAD_ONE_SWEEP"); v = e ? atoi(e) != 0 : 1; }
+  return v != 0;
+}
+
 rp_status check_call(rp_ctx* ctx, int slot_id, int batch, int seq, const void* ws, size_t ws_bytes, size_t need) {
   if (!ctx) return fail(nullptr, RP_EINVAL, "ctx is NULL");
   if (slot_id < 0 || slot_id >= RP_MAX_SLOTS) return fail(ctx, RP_EINVAL, "slot_id %d out of range", slot_id);
@@ -680,6 +687,41 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
   const double Td = (double)T;
   RUN(X, "rmsnorm_fwd", 0, 4.0 * Td * D.h, k_rmsnorm_fwd(X.st, x, W.t(RP_T_GF), X.at<void>(P.h_xf), X.at<float>(P.h_rstd), T, D.h, ctx->cfg.rms_eps));
   RUN(X, "fill", 0, 4.0 * Td, k_fill_u32(X.st, X.at<void>(P.h_zlab), T, 0u));
+  if (!train && !ctx->cfg.train_base && env_head_one_sweep()) {
+    // Frozen head: without dW the softmax normaliser is only needed at the very end, so one sweep over the vocabulary
+    // suffices (two logit-sized products instead of three).  Per chunk: logits (fp32) -> p = exp(z - m_t) against a
+    // per-token reference exponent that moves (and rescales what has been accumulated) only when a chunk outgrows it
+    // -> acc_t += p W_c;  finally lse_t = m_t + log l_t and dx_t = coef_t (acc_t / l_t - W[y_t]).
+    float* const zc = X.at<float>(P.h_z);
+    float* const acc = X.at<float>(P.h_dxacc);
+    RUN(X, "fill", 0, 4.0 * Td * D.h, k_fill_u32(X.st, acc, (long)T * D.h, 0u));
+    for (int v0 = 0, ci = 0; v0 < D.V; v0 += P.head_chunk, ++ci) {
+      const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
+      const bf16_t* Wc = Wv + (size_t)v0 * D.h;
+      GemmArgs g; gemm_zero_args(g);
+      g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h; g.epi = EPI_F32;
+      g.C = zc; g.ldc = T;
+      X.mark_gemm(GEMM_NT, g);
+      X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head logits");
+      RUN(X, "ce_chunk_update", 0, 10.0 * vc * Td,
+          k_ce_chunk_update(X.st, zc, vc, T, v0, labels, X.at<float>(P.h_part), X.at<float>(P.h_zlab), ci == 0, X.at<float>(P.h_m),
+                            X.at<float>(P.h_l), X.at<float>(P.h_alpha), X.at<void>(P.h_dzt)));
+      if (ci > 0) RUN(X, "ce_rescale", 0, 4.0 * Td, k_ce_rescale_rows(X.st, acc, X.at<float>(P.h_alpha), T, D.h));
+      GemmArgs d; gemm_zero_args(d);   // acc[T, h] += p^T^T . W_c
+      d.A = X.at<void>(P.h_dzt); d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = acc;
+      d.ldc = D.h; d.beta = 1; d.epi = EPI_F32;
+      X.mark_gemm(GEMM_TN, d);
+      X.chk(gemm_launch(X.st, GEMM_TN, d), "lm head dX");
+    }
+    RUN(X, "ce_lse", 0, 12.0 * Td, k_ce_lse_from_ref(X.st, X.at<float>(P.h_m), X.at<float>(P.h_l), X.at<float>(P.h_lse), T));
+    RUN(X, "ce_finalize", 0, 16.0 * Td,
+        k_ce_finalize(X.st, X.at<float>(P.h_lse), X.at<float>(P.h_zlab), labels, grad_scale, X.at<float>(P.h_coef), loss_out, T));
+    RUN(X, "ce_frozen_dx", 0, 8.0 * Td * D.h + 2.0 * Td * D.h,
+        k_ce_frozen_dx(X.st, acc, X.at<float>(P.h_l), X.at<float>(P.h_coef), labels, Wv, T, D.h, D.V));
+    RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
+        k_rmsnorm_bwd(X.st, acc, 1, x, W.t(RP_T_GF), X.at<float>(P.h_rstd), nullptr, dx, nullptr, X.at<float>(P.h_partials), T, D.h));
+    return finish_call(ctx, sl, X);
+  }
   {  // sweep 1: logits tile by tile, reduced to per-token (max, sum exp) partials; nothing of size T x V is stored
     GemmArgs g; gemm_zero_args(g);
     g.A = Wv; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = D.V; g.N = T; g.K = D.h; g.epi = EPI_CE_STATS;

@@ -243,6 +243,29 @@ def test_head_only_stage_ragged_vocab_and_ignored_rows(hz):
     assert np.all(got["head_dx"][::5] == 0.0)
 
 
+def test_frozen_head_reference_moves_between_chunks(hz):
+    """Frozen head, one sweep over the vocabulary: the rows of later vocabulary chunks are scaled up so that their
+    logits outgrow everything seen before by far more than the 2^8 the reference exponent tolerates -- the accumulated
+    input gradient and normaliser must be rescaled; some labels ignored, some in the last (ragged) chunk, loss scaling."""
+    c = dict(n_layers=0, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=256, vocab=40008, n_experts=0, top_k=0,
+             lora_rank=0, lora=(), train_base=0, batch=1, seq=72, x_from="normal")
+    wl = synth.make_workload(c, 81, gains_random=True)
+    Wv = wl["head"]["Wv"]
+    Wv[16384:32768] *= 12.0          # second chunk: logits of order +-4 -> +-50
+    Wv[32768:] *= 40.0               # third chunk larger still
+    wl["head"]["Wv"] = synth.bf16_round(Wv)
+    wl["labels"][::7] = -100
+    wl["labels"][1::9] = 40007       # last row of the ragged last chunk
+    wl["labels"][2::9] = 3           # first chunk: its logit is tiny against the later ones
+    ref = pu.oracle_chain(c, wl, grad_scale=32.0)
+    got = pu.gpu_chain(c, wl, hz, grad_scale=32.0)
+    errs = pu.compare_chain(ref, got, c)
+    assert set(errs) == {"loss", "head_dx"}
+    ignored = wl["labels"] == -100
+    assert ignored.sum() >= 8 and np.all(got["head_dx"][ignored] == 0.0)
+    assert ref["loss"] > 20.0        # the loss is dominated by the large logits: the rescale path was exercised
+
+
 def test_head_multiple_vocab_chunks_frozen(hz):
     """Vocabulary larger than one chunk of the second sweep (16384 rows) with a frozen head: only loss and dx."""
     c = dict(n_layers=0, hidden=128, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=256, vocab=40000, n_experts=0, top_k=0,
