@@ -384,7 +384,7 @@ void gemm_zero_args(GemmArgs& a) {
 int gemm_ce_stats_partials(int M) { return 2 * ((M + 255) / 256); }
 
 int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
-  if (a.epi == EPI_CE_STATS) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
+  if (a.epi == EPI_CE_STATS || a.epi == EPI_F32_COLMAX) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
   if (tile_hint) return tile_hint;
   // the eight-wave 256x128 tile supports the epilogues whose barrier pattern epilogue_barriers() knows
   const bool plain = a.epi == EPI_BF16 || a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC;
@@ -397,7 +397,8 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   if (layout < GEMM_NT || layout > GEMM_TN) return hipErrorInvalidValue;
   GemmArgs a = a_in;
   // 16-byte accesses everywhere: the output width and every leading dimension must keep rows aligned
-  const bool out_f32 = a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC;
+  const bool out_f32 = a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC || a.epi == EPI_F32_COLMAX;
+  if (a.epi == EPI_F32_COLMAX && (a.beta || !a.part || !a.labels || !a.zlab)) return hipErrorInvalidValue;
   if (a.N % 8 || a.K % 8 || a.lda % 8 || a.ldb % 8) return hipErrorInvalidValue;
   if (a.epi != EPI_CE_STATS && a.ldc % (out_f32 ? 4 : 8)) return hipErrorInvalidValue;
   if (a.R && a.ldr % 4) return hipErrorInvalidValue;

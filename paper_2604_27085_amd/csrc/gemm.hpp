@@ -15,7 +15,8 @@ enum {
   EPI_F32 = 1,       // C fp32 = alpha*acc (+ C if beta)
   EPI_F32_ATOMIC = 2,// C fp32 atomically += alpha*acc
   EPI_CE_STATS = 3,  // rows = vocab, cols = tokens: per-column (max, sum exp) partials + label logit
-  EPI_CE_DZ = 4      // C bf16 [rows, cols] = (exp(acc - lse[col]) - (row == label[col])) * coef[col]
+  EPI_CE_DZ = 4,     // C bf16 [rows, cols] = (exp(acc - lse[col]) - (row == label[col])) * coef[col]
+  EPI_F32_COLMAX = 5 // C fp32 = acc, plus per-column maximum partials (part[...].x, one per 128 rows) and the label logit
 };
 
 struct GemmArgs {

@@ -81,7 +81,7 @@ RP_DEV void tile_of_block(int M, int N, int BM, int BN, int& tile_m, int& tile_n
 RP_DEV void epilogue_barriers(const GemmArgs& p) {
   if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ) {
     __syncthreads();
-  } else if (p.epi == EPI_BF16 || p.epi == EPI_F32) {
+  } else if (p.epi == EPI_BF16 || p.epi == EPI_F32 || p.epi == EPI_F32_COLMAX) {
 #pragma unroll
     for (int j = 0; j < 2 * TN - 1; ++j) __syncthreads();
   }
@@ -136,7 +136,30 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
       if (grow < M && gcol < p.N)
         *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + gcol) = *reinterpret_cast<const uint4*>(s16 + row * STG_LD + cc * 8);
     }
-  } else if (p.epi == EPI_BF16 || p.epi == EPI_F32) {
+  } else if (p.epi == EPI_BF16 || p.epi == EPI_F32 || p.epi == EPI_F32_COLMAX) {
+    if (p.epi == EPI_F32_COLMAX) {
+      // rows are vocabulary entries, columns tokens: the maximum of every column over the wave's 128 rows, from the
+      // registers, before the tile goes out
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = wcol0 + j * 32 + lr;
+        const bool colok = col < p.N;
+        const int lab = colok ? p.labels[col] - p.row_offset : -1;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (row < M) {
+              mx = fmaxf(mx, acc[i][j][v]);
+              if (row == lab) p.zlab[col] = acc[i][j][v];
+            }
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        if (lk == 0 && colok) p.part[(long)part_row * p.part_ld + col] = make_float2(mx, 0.f);
+      }
+    }
     // fp32 staging, one 32-column half at a time: [128][36] floats (144-byte rows)
     float* s32 = reinterpret_cast<float*>(stg);
 #pragma unroll
@@ -153,7 +176,7 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
         const int row = t * 8 + rr, grow = wrow0 + row;
         if (grow < M && gcol < p.N) {
           float4 x = *reinterpret_cast<const float4*>(s32 + row * (STG_LD / 2) + cc * 4);
-          if (p.epi == EPI_F32) {
+          if (p.epi != EPI_BF16) {
             float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (long)grow * p.ldc + gcol);
             if (p.beta) { const float4 o = *dst; x.x += o.x; x.y += o.y; x.z += o.z; x.w += o.w; }
             *dst = x;

@@ -73,32 +73,17 @@ __global__ void __launch_bounds__(1024) ce_finalize_kernel(const float* __restri
 // outgrows the reference by more than 2^8 (in e-units: 8), the reference moves and acc_t, l_t are rescaled.  At the end
 // lse_t = m_t + log l_t and dx_t = coef_t (acc_t / l_t - W[y_t]).
 
-constexpr int CE_SLAB = 256;    // rows per partial maximum
-constexpr int CE_PROB_ROWS = 512;
-
-// pmax[slab][t] = max over the slab's rows of z[r][t]; zlab[t] = z[label_t - v0][t] when the label is in this chunk.
-__global__ void __launch_bounds__(256) ce_chunk_max_kernel(const float* __restrict__ z, int vc, int T, int v0,
-                                                           const int* __restrict__ labels, float* __restrict__ pmax,
-                                                           float* __restrict__ zlab) {
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  if (t >= T) return;
-  const int r0 = blockIdx.y * CE_SLAB, r1 = min(r0 + CE_SLAB, vc);
-  float m = -INFINITY;
-  for (int r = r0; r < r1; ++r) m = fmaxf(m, z[(long)r * T + t]);
-  pmax[(long)blockIdx.y * T + t] = m;
-  const int lab = labels[t] - v0;
-  if (lab >= r0 && lab < r1) zlab[t] = z[(long)lab * T + t];
-}
+constexpr int CE_PROB_ROWS = 128;
 
 // Moves the reference exponent of every token if this chunk needs it and rescales l; alpha[t] is the factor acc_t must
 // be multiplied with (1 for most tokens and chunks).
-__global__ void __launch_bounds__(256) ce_chunk_ref_kernel(const float* __restrict__ pmax, int nslab, int T, int first,
+__global__ void __launch_bounds__(256) ce_chunk_ref_kernel(const float2* __restrict__ pmax, int nslab, int T, int first,
                                                            float* __restrict__ m, float* __restrict__ l,
                                                            float* __restrict__ alpha) {
   const int t = blockIdx.x * 256 + threadIdx.x;
   if (t >= T) return;
   float cm = -INFINITY;
-  for (int i = 0; i < nslab; ++i) cm = fmaxf(cm, pmax[(long)i * T + t]);
+  for (int i = 0; i < nslab; ++i) cm = fmaxf(cm, pmax[(long)i * T + t].x);
   if (first) { m[t] = cm; l[t] = 0.f; alpha[t] = 1.f; return; }
   const float mo = m[t];
   if (cm > mo + 8.f) {
@@ -118,7 +103,19 @@ __global__ void __launch_bounds__(256) ce_chunk_prob_kernel(const float* __restr
   const int r0 = blockIdx.y * CE_PROB_ROWS, r1 = min(r0 + CE_PROB_ROWS, vc);
   const float m0 = m[t], m1 = m[t + 1];
   float s0 = 0.f, s1 = 0.f;
-  for (int r = r0; r < r1; ++r) {
+  int r = r0;
+  for (; r + 8 <= r1; r += 8) {          // eight rows in flight per thread
+    float2 zz[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) zz[k] = *reinterpret_cast<const float2*>(z + (long)(r + k) * T + t);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float p0 = __expf(zz[k].x - m0), p1 = __expf(zz[k].y - m1);
+      s0 += p0; s1 += p1;
+      *reinterpret_cast<uint32_t*>(p + (long)(r + k) * T + t) = pack_bf16x2(p0, p1);
+    }
+  }
+  for (; r < r1; ++r) {
     const float2 zz = *reinterpret_cast<const float2*>(z + (long)r * T + t);
     const float p0 = __expf(zz.x - m0), p1 = __expf(zz.y - m1);
     s0 += p0; s1 += p1;
@@ -171,13 +168,11 @@ __global__ void __launch_bounds__(256) ce_frozen_dx_kernel(float* __restrict__ a
 
 }  // namespace
 
-hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, int v0, const int* labels, float* pmax, float* zlab,
-                             int first, float* m, float* l, float* alpha, void* p) {
+hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, const float2* pmax, int nparts, int first, float* m,
+                             float* l, float* alpha, void* p) {
   if (T == 0 || vc == 0) return hipSuccess;
   if (T % 2) return hipErrorInvalidValue;
-  const int nslab = (vc + CE_SLAB - 1) / CE_SLAB;
-  RP_LAUNCH(ce_chunk_max_kernel, dim3((T + 255) / 256, nslab), dim3(256), 0, st, z, vc, T, v0, labels, pmax, zlab);
-  RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float*)pmax, nslab, T, first, m, l, alpha);
+  RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, pmax, nparts, T, first, m, l, alpha);
   RP_LAUNCH(ce_chunk_prob_kernel, dim3((T / 2 + 255) / 256, (vc + CE_PROB_ROWS - 1) / CE_PROB_ROWS), dim3(256), 0, st, z, vc, T,
             (const float*)m, (bf16*)p, l);
   return hipGetLastError();

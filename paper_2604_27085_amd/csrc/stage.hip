@@ -699,12 +699,13 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
       const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
       const bf16_t* Wc = Wv + (size_t)v0 * D.h;
       GemmArgs g; gemm_zero_args(g);
-      g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h; g.epi = EPI_F32;
-      g.C = zc; g.ldc = T;
+      g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h; g.epi = EPI_F32_COLMAX;
+      g.C = zc; g.ldc = T; g.labels = labels; g.zlab = X.at<float>(P.h_zlab); g.part = X.at<float2>(P.h_part); g.part_ld = T;
+      g.row_offset = v0;
       X.mark_gemm(GEMM_NT, g);
       X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head logits");
-      RUN(X, "ce_chunk_update", 0, 10.0 * vc * Td,
-          k_ce_chunk_update(X.st, zc, vc, T, v0, labels, X.at<float>(P.h_part), X.at<float>(P.h_zlab), ci == 0, X.at<float>(P.h_m),
+      RUN(X, "ce_chunk_update", 0, 6.0 * vc * Td,
+          k_ce_chunk_update(X.st, zc, vc, T, X.at<float2>(P.h_part), gemm_ce_stats_partials(vc), ci == 0, X.at<float>(P.h_m),
                             X.at<float>(P.h_l), X.at<float>(P.h_alpha), X.at<void>(P.h_dzt)));
       if (ci > 0) RUN(X, "ce_rescale", 0, 4.0 * Td, k_ce_rescale_rows(X.st, acc, X.at<float>(P.h_alpha), T, D.h));
       GemmArgs d; gemm_zero_args(d);   // acc[T, h] += p^T^T . W_c
