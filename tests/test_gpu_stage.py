@@ -266,6 +266,19 @@ def test_frozen_head_reference_moves_between_chunks(hz):
     assert ref["loss"] > 20.0        # the loss is dominated by the large logits: the rescale path was exercised
 
 
+def test_frozen_head_single_ragged_chunk(hz):
+    """Frozen head whose vocabulary fits one chunk and is not a multiple of any tile; ragged token count."""
+    c = dict(n_layers=0, hidden=128, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=256, vocab=1000, n_experts=0, top_k=0,
+             lora_rank=0, lora=(), train_base=0, batch=1, seq=136, x_from="normal")
+    wl = synth.make_workload(c, 83, gains_random=True)
+    wl["x"] = synth.bf16_round(wl["x"] * 4.0)
+    wl["labels"][5::11] = -100
+    ref = pu.oracle_chain(c, wl)
+    got = pu.gpu_chain(c, wl, hz)
+    errs = pu.compare_chain(ref, got, c)
+    assert set(errs) == {"loss", "head_dx"}
+
+
 def test_head_multiple_vocab_chunks_frozen(hz):
     """Vocabulary larger than one chunk of the second sweep (16384 rows) with a frozen head: only loss and dx."""
     c = dict(n_layers=0, hidden=128, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=256, vocab=40000, n_experts=0, top_k=0,
