@@ -278,6 +278,7 @@ def main():
         for t in dyh:
             t.copy_(dy_in)
         g_host = torch.empty(max(R.gbytes, 4) // 4, dtype=torch.float32).pin_memory() if R.gbytes else None
+        g_done = torch.zeros_like(R.grads) if R.gbytes else None     # a finished stage's gradients, not the ones being accumulated
 
         def plain():
             for _ in range(m_r):
@@ -286,7 +287,7 @@ def main():
 
         def rnd(i):
             R.round(xh, oh, slot=i & 1, dy_host=dyh, next_slot=(i + 1) & 1, next_host_blob=host,
-                    done_grads_dev=R.grads if R.gbytes else None, done_grads_host=g_host,
+                    done_grads_dev=g_done, done_grads_host=g_host,
                     max_piece_bytes=args.round_piece_mib << 20)
 
         R.upload(host, slot=0)
