@@ -2,6 +2,7 @@
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include "../../include/rp.h"
 #include "kernels.hpp"   // RP_PARTIAL_BLOCKS
 
@@ -171,7 +172,10 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   // head
   o = 0;
   if (D.V > 0) {
-    P.head_chunk = 16384;
+    // vocabulary rows per pass: 32768 while the transposed dZ chunk stays within 2^27 elements, else 16384
+    // (RP_HEAD_CHUNK, a multiple of 256, overrides: the tests use it to put several chunks into a small vocabulary)
+    P.head_chunk = (T * 32768 <= ((size_t)1 << 27)) ? 32768 : 16384;
+    if (const char* e = getenv("RP_HEAD_CHUNK")) { const int v = atoi(e); if (v >= 256 && v % 256 == 0) P.head_chunk = v; }
     if (P.head_chunk > D.V) P.head_chunk = (int)align_up(D.V, 8);
     P.head_parts = 2 * ((D.V + 255) / 256);
     P.h_xf = take(T * D.h * 2); P.h_rstd = take(T * 4); P.h_part = take((size_t)P.head_parts * T * 8);

@@ -33,8 +33,9 @@ def hz():
 
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("name", sorted(CASES))
-def test_full_width_stage_matches_oracle(hz, name, capsys):
+def test_full_width_stage_matches_oracle(hz, name, capsys, monkeypatch):
     base, over, seed = CASES[name]
+    monkeypatch.setenv("RP_HEAD_CHUNK", "16384")     # c4_width: two chunks in a vocabulary of 32768
 
     def say(msg):
         with capsys.disabled():

@@ -34,7 +34,7 @@ def test_c1_chain_matches_oracle(hz):
 @pytest.mark.timeout(900)
 def test_c2_full_size_every_stage_call_matches_oracle(hz, capsys):
     """The benchmark's workload at its full size and in the launch configuration bench.py times (Qwen3-1.7B-shaped
-    layers, 4096 tokens, vocabulary 151936, 256x256 GEMM tiles, 16384-row vocabulary chunks).  Every call is checked
+    layers, 4096 tokens, vocabulary 151936, 256x256 GEMM tiles, 32768-row vocabulary chunks).  Every call is checked
     against the oracle ON THE SAME INPUTS: the 4-layer forward produces the layer inputs, the head runs on the stage
     output the GPU produced, and each layer's backward stage (recomputation + backward, one layer per call) gets the
     GPU's own layer input and incoming gradient, so the bound applies to each call and not to a sum of their
@@ -243,10 +243,11 @@ def test_head_only_stage_ragged_vocab_and_ignored_rows(hz):
     assert np.all(got["head_dx"][::5] == 0.0)
 
 
-def test_frozen_head_reference_moves_between_chunks(hz):
+def test_frozen_head_reference_moves_between_chunks(hz, monkeypatch):
     """Frozen head, one sweep over the vocabulary: the rows of later vocabulary chunks are scaled up so that their
     logits outgrow everything seen before by far more than the 2^8 the reference exponent tolerates -- the accumulated
     input gradient and normaliser must be rescaled; some labels ignored, some in the last (ragged) chunk, loss scaling."""
+    monkeypatch.setenv("RP_HEAD_CHUNK", "16384")
     c = dict(n_layers=0, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=256, vocab=40008, n_experts=0, top_k=0,
              lora_rank=0, lora=(), train_base=0, batch=1, seq=72, x_from="normal")
     wl = synth.make_workload(c, 81, gains_random=True)
@@ -280,7 +281,7 @@ def test_frozen_head_single_ragged_chunk(hz):
 
 
 def test_head_multiple_vocab_chunks_frozen(hz):
-    """Vocabulary larger than one chunk of the second sweep (16384 rows) with a frozen head: only loss and dx."""
+    """Vocabulary larger than one chunk (32768 rows at this token count) with a frozen head: only loss and dx."""
     c = dict(n_layers=0, hidden=128, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=256, vocab=40000, n_experts=0, top_k=0,
              lora_rank=0, lora=(), train_base=0, batch=1, seq=64, x_from="normal")
     wl = synth.make_workload(c, 78)
