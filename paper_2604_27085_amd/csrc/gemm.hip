@@ -16,8 +16,9 @@
 // barrier sits before the last four MFMAs of a tile and the first fragments of the next tile are read under them.
 // Measured on MI355X the 256x256 tile asks L2 for one byte per 128 FLOP; the chip runs power-limited near 1.8 GHz
 // under this kernel.  Tried and dropped: direct HBM -> LDS loads with a four-deep ring, touching lines two tiles
-// ahead to pull them into L2, staggered K-loop starts, a reduction split merged through scratch memory, a 128x128
-// wave tile with one wave per SIMD.  Outputs too small to fill the chip with 256x256 tiles use a 256x128 tile worked
+// ahead to pull them into L2, touching the first lines of the workgroup's successor tile before the epilogue,
+// staggered K-loop starts, a reduction split merged through scratch memory, a 128x128 wave tile with one wave per
+// SIMD.  Outputs too small to fill the chip with 256x256 tiles use a 256x128 tile worked
 // on by two wave groups that split every K tile (merged through LDS); GEMMs that accumulate into an fp32 output and
 // would still leave CUs idle are split along the reduction and merged with fp32 atomics.
 //

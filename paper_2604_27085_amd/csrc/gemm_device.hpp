@@ -87,6 +87,43 @@ RP_DEV void epilogue_barriers(const GemmArgs& p) {
   }
 }
 
+// Local row (relative to the wave's block, minus the lane's 4*lk) of accumulator register v of MFMA tile row i.
+RP_DEV constexpr int acc_row(int i, int v) { return i * 32 + 8 * (v >> 2) + (v & 3); }
+
+// max(a, b, c) as one instruction (the accumulators need no NaN canonicalisation)
+RP_DEV float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// Maximum of a lane's 64 accumulators of tile column j (all of the wave's 128 rows after the exchange between the
+// half-waves).
+RP_DEV float column_max(const f32x16 (&acc)[TM][TN], int j) {
+  float mx = acc[0][j][0];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int v = (i == 0 ? 1 : 0); v + 1 < 16; v += 2) mx = max3(mx, acc[i][j][v], acc[i][j][v + 1]);
+  mx = fmaxf(mx, acc[0][j][15]);
+  return fmaxf(mx, __shfl_xor(mx, 32, 64));
+}
+
+// The accumulator of tile column j whose local row is lab_local (= label row - first row of the wave's block - 4*lk),
+// if this lane holds it.  Called only when some lane of the wave has its label inside the block.
+RP_DEV bool label_logit(const f32x16 (&acc)[TM][TN], int j, int lab_local, float& z) {
+  bool found = false;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const bool hit = lab_local == acc_row(i, v);
+      z = hit ? acc[i][j][v] : z;
+      found |= hit;
+    }
+  return found;
+}
+
 // Epilogue.  acc[i][j][v] is element (i*32 + 8*(v/4) + 4*lk + v%4, j*32 + lr) of the wave's 128x64 block whose top
 // left corner is (wrow0, wcol0).  Every wave stages its block through its own 18 KB of LDS (all waves must have
 // finished the K loop) so that global accesses are 16 bytes per lane and cover whole 128-byte lines.
@@ -100,31 +137,52 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
 
   if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ) {
     bf16* s16 = reinterpret_cast<bf16*>(stg);
+    unsigned short* const h16 = reinterpret_cast<unsigned short*>(stg);
+    // two rows of a column are converted by one instruction and go out as the halves of its result
+    auto stage2 = [&](int i, int j, int v, float x0, float x1) {
+      const uint32_t pk = pack_bf16x2(x0, x1);
+      unsigned short* const d = h16 + (acc_row(i, v) + 4 * lk) * STG_LD + j * 32 + lr;
+      d[0] = (unsigned short)pk;
+      d[STG_LD] = (unsigned short)(pk >> 16);
+    };
     if (p.epi == EPI_BF16) {
+      if (p.alpha == 1.f) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+          for (int j = 0; j < TN; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v)
-            s16[(i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3)) * STG_LD + j * 32 + lr] = (bf16)(p.alpha * acc[i][j][v]);
+            for (int v = 0; v < 16; v += 2) stage2(i, j, v, acc[i][j][v], acc[i][j][v + 1]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) stage2(i, j, v, p.alpha * acc[i][j][v], p.alpha * acc[i][j][v + 1]);
+      }
     } else {
-      // dZ^T = (softmax - onehot) * coef: rows are vocabulary entries, columns tokens
+      // dZ^T = (softmax - onehot) * coef: rows are vocabulary entries, columns tokens.  Every element gets
+      // exp(z - lse) * coef (rows past the end of the vocabulary are never stored); the one element per column that
+      // is the label is fixed up in the staging buffer afterwards.
+      constexpr float LOG2E = 1.4426950408889634f;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int col = wcol0 + j * 32 + lr;
         const bool colok = col < p.N;
-        const int lab = colok ? p.labels[col] - p.row_offset : -1;
-        const float lse = colok ? p.lse[col] : 0.f, cf = colok ? p.coef[col] : 0.f;
+        const int lab = colok ? p.labels[col] - p.row_offset - wrow0 : -1;
+        const float nl = colok ? -LOG2E * p.lse[col] : 0.f, cf = colok ? p.coef[col] : 0.f;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-            float g = __expf(acc[i][j][v] - lse);
-            if (wrow0 + row == lab) g -= 1.f;
-            s16[row * STG_LD + j * 32 + lr] = (bf16)(g * cf);
-          }
+          for (int v = 0; v < 16; v += 2)
+            stage2(i, j, v, __builtin_amdgcn_exp2f(fmaf(acc[i][j][v], LOG2E, nl)) * cf,
+                   __builtin_amdgcn_exp2f(fmaf(acc[i][j][v + 1], LOG2E, nl)) * cf);
+        if (__ballot(lab >= 0 && lab < WAVE_M)) {   // wave-uniform, rare
+          float z = 0.f;
+          if (label_logit(acc, j, lab - 4 * lk, z))
+            s16[lab * STG_LD + j * 32 + lr] = (bf16)((__builtin_amdgcn_exp2f(fmaf(z, LOG2E, nl)) - 1.f) * cf);
+        }
       }
     }
     __syncthreads();
@@ -145,18 +203,27 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
         const int col = wcol0 + j * 32 + lr;
         const bool colok = col < p.N;
         const int lab = colok ? p.labels[col] - p.row_offset : -1;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-            if (row < M) {
-              mx = fmaxf(mx, acc[i][j][v]);
-              if (row == lab) p.zlab[col] = acc[i][j][v];
-            }
+        float mx;
+        if (wrow0 + WAVE_M <= M) {   // wave-uniform: no row of the block is past the end
+          mx = column_max(acc, j);
+          if (__ballot(lab >= wrow0 && lab < wrow0 + WAVE_M)) {
+            float z = 0.f;
+            if (label_logit(acc, j, lab - wrow0 - 4 * lk, z)) p.zlab[col] = z;
           }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        } else {
+          mx = -INFINITY;
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+              if (row < M) {
+                mx = fmaxf(mx, acc[i][j][v]);
+                if (row == lab) p.zlab[col] = acc[i][j][v];
+              }
+            }
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        }
         if (lk == 0 && colok) p.part[(long)part_row * p.part_ld + col] = make_float2(mx, 0.f);
       }
     }
@@ -205,32 +272,51 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
     }
   } else if (p.epi == EPI_CE_STATS) {
     // rows are vocabulary entries, columns are tokens: every lane reduces its own column over the wave's 128 rows
+    constexpr float LOG2E = 1.4426950408889634f;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = wcol0 + j * 32 + lr;
       const bool colok = col < p.N;
       const int lab = colok ? p.labels[col] - p.row_offset : -1;
-      float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-          if (row < M) {
-            mx = fmaxf(mx, acc[i][j][v]);
-            if (row == lab) p.zlab[col] = acc[i][j][v];
-          }
+      float mx, s = 0.f;
+      if (wrow0 + WAVE_M <= M) {   // wave-uniform: no row of the block is past the end
+        mx = column_max(acc, j);
+        if (__ballot(lab >= wrow0 && lab < wrow0 + WAVE_M)) {
+          float z = 0.f;
+          if (label_logit(acc, j, lab - wrow0 - 4 * lk, z)) p.zlab[col] = z;
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      float s = 0.f;
-      if (mx > -INFINITY) {
+        const float nm = -LOG2E * mx;
+        float s2 = 0.f;   // two chains
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; v += 2) {
+            s += __builtin_amdgcn_exp2f(fmaf(acc[i][j][v], LOG2E, nm));
+            s2 += __builtin_amdgcn_exp2f(fmaf(acc[i][j][v + 1], LOG2E, nm));
+          }
+        s += s2;
+      } else {
+        mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-            if (row < M) s += __expf(acc[i][j][v] - mx);
+            if (row < M) {
+              mx = fmaxf(mx, acc[i][j][v]);
+              if (row == lab) p.zlab[col] = acc[i][j][v];
+            }
           }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        if (mx > -INFINITY) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+              if (row < M) s += __expf(acc[i][j][v] - mx);
+            }
+        }
       }
       s += __shfl_xor(s, 32, 64);
       if (lk == 0 && colok) p.part[(long)part_row * p.part_ld + col] = make_float2(mx, s);
