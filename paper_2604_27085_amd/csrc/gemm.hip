@@ -292,10 +292,7 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
         }
         __syncthreads();
       }
-    if (kg != 0) {   // wave-uniform: only the barriers of the epilogue
-      epilogue_barriers(p);
-      return;
-    }
+    if (kg != 0) return;   // wave-uniform; the epilogue has no workgroup barrier
   }
   epilogue(p, Mlim, acc, smem, wmn, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
 }
@@ -387,7 +384,7 @@ int gemm_ce_stats_partials(int M) { return 2 * ((M + 255) / 256); }
 int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
   if (a.epi == EPI_CE_STATS || a.epi == EPI_F32_COLMAX) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
   if (tile_hint) return tile_hint;
-  // the eight-wave 256x128 tile supports the epilogues whose barrier pattern epilogue_barriers() knows
+  // the eight-wave 256x128 tile is used for the plain epilogues
   const bool plain = a.epi == EPI_BF16 || a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC;
   const int atomic_nk = (a.epi == EPI_F32 && a.beta && env_splitk()) ? (a.K + 63) / 64 + (a.K2 + 63) / 64 : 0;
   return env_tile() ? env_tile() : choose_tile(a.M, a.N, plain, atomic_nk);

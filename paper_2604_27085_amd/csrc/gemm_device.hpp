@@ -77,14 +77,12 @@ RP_DEV void tile_of_block(int M, int N, int BM, int BN, int& tile_m, int& tile_n
   tile_n = in_group / gm;
 }
 
-// The barriers epilogue() executes for these arguments, for waves of the workgroup that hold no part of the result.
-RP_DEV void epilogue_barriers(const GemmArgs& p) {
-  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ) {
-    __syncthreads();
-  } else if (p.epi == EPI_BF16 || p.epi == EPI_F32 || p.epi == EPI_F32_COLMAX) {
-#pragma unroll
-    for (int j = 0; j < 2 * TN - 1; ++j) __syncthreads();
-  }
+// A wave stages its block through LDS that no other wave touches: the LDS executes one wave's accesses in order, so
+// the read-back only has to stay behind the writes in the instruction stream.
+RP_DEV void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Local row (relative to the wave's block, minus the lane's 4*lk) of accumulator register v of MFMA tile row i.
@@ -126,7 +124,8 @@ RP_DEV bool label_logit(const f32x16 (&acc)[TM][TN], int j, int lab_local, float
 
 // Epilogue.  acc[i][j][v] is element (i*32 + 8*(v/4) + 4*lk + v%4, j*32 + lr) of the wave's 128x64 block whose top
 // left corner is (wrow0, wcol0).  Every wave stages its block through its own 18 KB of LDS (all waves must have
-// finished the K loop) so that global accesses are 16 bytes per lane and cover whole 128-byte lines.
+// finished the K loop) so that global accesses are 16 bytes per lane and cover whole 128-byte lines; no workgroup
+// barrier inside.
 // part_row: row of the cross-entropy partial array this wave writes (EPI_CE_STATS).
 // M: rows of C that exist (the end of the group's rows in grouped mode).
 RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsigned char* smem, int wave, int lane,
@@ -185,7 +184,7 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
         }
       }
     }
-    __syncthreads();
+    wave_lds_fence();
     bf16* Cp = reinterpret_cast<bf16*>(p.C);
     const int gcol = wcol0 + cc * 8;
 #pragma unroll
@@ -229,14 +228,22 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
     }
     // fp32 staging, one 32-column half at a time: [128][36] floats (144-byte rows)
     float* s32 = reinterpret_cast<float*>(stg);
+    const bool unit = p.alpha == 1.f;   // uniform
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      if (j) __syncthreads();
+      if (j) wave_lds_fence();
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i) {
+        float* const d = s32 + (i * 32 + 4 * lk) * (STG_LD / 2) + lr;
+        if (unit) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s32[(i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3)) * (STG_LD / 2) + lr] = p.alpha * acc[i][j][v];
-      __syncthreads();
+          for (int v = 0; v < 16; ++v) d[acc_row(0, v) * (STG_LD / 2)] = acc[i][j][v];
+        } else {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) d[acc_row(0, v) * (STG_LD / 2)] = p.alpha * acc[i][j][v];
+        }
+      }
+      wave_lds_fence();
       const int gcol = wcol0 + j * 32 + cc * 4;
 #pragma unroll
       for (int t = 0; t < WAVE_M / 8; ++t) {
