@@ -245,20 +245,49 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
       }
       wave_lds_fence();
       const int gcol = wcol0 + j * 32 + cc * 4;
+      const bool colok = gcol < p.N;
+      // What is added from memory (the fp32 output itself when it accumulates, the bf16 residual) is loaded for eight
+      // row groups at a time before anything is stored: the compiler cannot tell that the stores leave the later
+      // loads alone, and one load-add-store round trip after the other costs 16-20 us per tile.
+      constexpr int NB = 8;
 #pragma unroll
-      for (int t = 0; t < WAVE_M / 8; ++t) {
-        const int row = t * 8 + rr, grow = wrow0 + row;
-        if (grow < M && gcol < p.N) {
-          float4 x = *reinterpret_cast<const float4*>(s32 + row * (STG_LD / 2) + cc * 4);
-          if (p.epi != EPI_BF16) {
-            float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(p.C) + (long)grow * p.ldc + gcol);
-            if (p.beta) { const float4 o = *dst; x.x += o.x; x.y += o.y; x.z += o.z; x.w += o.w; }
-            *dst = x;
+      for (int t0 = 0; t0 < WAVE_M / 8; t0 += NB) {
+        if (p.epi != EPI_BF16) {
+          float* const Cf = reinterpret_cast<float*>(p.C);
+          float4 o[NB];
+          if (p.beta) {
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+              const int grow = wrow0 + (t0 + u) * 8 + rr;
+              o[u] = (grow < M && colok) ? *reinterpret_cast<const float4*>(Cf + (long)grow * p.ldc + gcol) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
           } else {
-            const uint2 r2 = *reinterpret_cast<const uint2*>(reinterpret_cast<const bf16*>(p.R) + (long)grow * p.ldr + gcol);
-            x.x += bf16_lo(r2.x); x.y += bf16_hi(r2.x); x.z += bf16_lo(r2.y); x.w += bf16_hi(r2.y);
-            *reinterpret_cast<uint2*>(reinterpret_cast<bf16*>(p.C) + (long)grow * p.ldc + gcol) =
-                make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+#pragma unroll
+            for (int u = 0; u < NB; ++u) o[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+          }
+#pragma unroll
+          for (int u = 0; u < NB; ++u) {
+            const int row = (t0 + u) * 8 + rr, grow = wrow0 + row;
+            float4 x = *reinterpret_cast<const float4*>(s32 + row * (STG_LD / 2) + cc * 4);
+            x.x += o[u].x; x.y += o[u].y; x.z += o[u].z; x.w += o[u].w;
+            if (grow < M && colok) *reinterpret_cast<float4*>(Cf + (long)grow * p.ldc + gcol) = x;
+          }
+        } else {
+          uint2 r2[NB];
+#pragma unroll
+          for (int u = 0; u < NB; ++u) {
+            const int grow = wrow0 + (t0 + u) * 8 + rr;
+            r2[u] = (grow < M && colok) ? *reinterpret_cast<const uint2*>(reinterpret_cast<const bf16*>(p.R) + (long)grow * p.ldr + gcol)
+                                        : make_uint2(0u, 0u);
+          }
+#pragma unroll
+          for (int u = 0; u < NB; ++u) {
+            const int row = (t0 + u) * 8 + rr, grow = wrow0 + row;
+            float4 x = *reinterpret_cast<const float4*>(s32 + row * (STG_LD / 2) + cc * 4);
+            x.x += bf16_lo(r2[u].x); x.y += bf16_hi(r2[u].x); x.z += bf16_lo(r2[u].y); x.w += bf16_hi(r2[u].y);
+            if (grow < M && colok)
+              *reinterpret_cast<uint2*>(reinterpret_cast<bf16*>(p.C) + (long)grow * p.ldc + gcol) =
+                  make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
           }
         }
       }
