@@ -63,6 +63,16 @@ def test_gemm_layouts_ragged(rp, layout, tile):
     B.rp_op_gemm(stream(), layout, 1, A, Bm, C32, M, N, K, lda, ldb, N, alpha=0.25, beta=1, tile=tile)
     torch.cuda.synchronize()
     assert rel_l2(C32.cpu().numpy(), 0.25 * ref + 0.5) < 1e-5
+    # fp32 output that overwrites what the buffer held (no accumulation, unit scale)
+    C32.fill_(float("nan"))
+    B.rp_op_gemm(stream(), layout, 1, A, Bm, C32, M, N, K, lda, ldb, N, beta=0, tile=tile)
+    torch.cuda.synchronize()
+    assert rel_l2(C32.cpu().numpy(), ref) < 1e-5
+    # bf16 output with a scale
+    Cm.fill_(float("nan"))
+    B.rp_op_gemm(stream(), layout, 0, A, Bm, Cm, M, N, K, lda, ldb, N, alpha=-0.5, tile=tile)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(Cm), -0.5 * ref) < 4e-3
 
 
 def test_gemm_second_pair_residual_and_atomic(rp):
@@ -79,6 +89,12 @@ def test_gemm_second_pair_residual_and_atomic(rp):
                      lda2=K2, ldb2=K2, R=dev(H, res), ldr=N, tile=tile)
         torch.cuda.synchronize()
         assert rel_l2(H.to_f32(Cm), ref) < 4e-3, tile
+    # the same with a scale on the product (the residual is not scaled)
+    Cm = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
+    B.rp_op_gemm(stream(), 0, 0, dev(H, x), dev(H, w), Cm, M, N, K, K, K, N, alpha=0.5, A2=dev(H, u), B2=dev(H, bl), K2=K2,
+                 lda2=K2, ldb2=K2, R=dev(H, res), ldr=N, tile=1)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(Cm), 0.5 * (ref - res) + res) < 4e-3
     # NN with a second pair (activation gradient of a LoRA linear): dx = dy W + ud A
     dy, ud, a_l = rnd(rng, (M, N)), rnd(rng, (M, K2)), rnd(rng, (K2, K), 0.1)
     ref2 = dy.astype(np.float64) @ w.astype(np.float64) + ud.astype(np.float64) @ a_l.astype(np.float64)
