@@ -449,18 +449,26 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_bwd_dq_kernel(c
             dpT[t] = mfma32(av, dof[t][ks], ks == 0 ? zero16 : dpT[t]);
           }
         }
+        // one wave-uniform branch per half tile around two whole element loops (a test per element would be
+        // compiled into a branch per element)
+        if (need_mask) {
 #pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          const int qpos = qw0 + 32 * t + lr;
+          for (int t = 0; t < QT; ++t) {
+            const int qpos = qw0 + 32 * t + lr;
+            const int klim = (qpos < p.seq - 1 ? qpos : p.seq - 1) - (kv0 + 32 * kt + 4 * lk);   // local key index <= klim
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            float pr = fast_exp2(__builtin_fmaf(sT[t][v], p.scale_log2e, -lse2[t]));
-            if (need_mask) {
-              const int kpos = kv0 + 32 * kt + 8 * (v >> 2) + 4 * lk + (v & 3);
-              pr = (kpos > qpos || kpos >= p.seq) ? 0.f : pr;
+            for (int v = 0; v < 16; ++v) {
+              float pr = fast_exp2(__builtin_fmaf(sT[t][v], p.scale_log2e, -lse2[t]));
+              pr = (8 * (v >> 2) + (v & 3) > klim) ? 0.f : pr;
+              sT[t][v] = pr * (dpT[t][v] - dl[t]);   // dS^T
             }
-            sT[t][v] = pr * (dpT[t][v] - dl[t]);   // dS^T
           }
+        } else {
+#pragma unroll
+          for (int t = 0; t < QT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              sT[t][v] = fast_exp2(__builtin_fmaf(sT[t][v], p.scale_log2e, -lse2[t])) * (dpT[t][v] - dl[t]);   // dS^T
         }
 #pragma unroll
         for (int g2 = 0; g2 < 2; ++g2) {
