@@ -585,16 +585,40 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
       // the two 32-query halves of the tile one after the other: half as many score registers live at a time
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2) {
-        f32x16 s, dp;
+        f32x16 s = zero16, dp = zero16;
+        // One wave per SIMD: nothing else covers the LDS latency, so every fragment is requested AHEAD MFMAs before
+        // the one that consumes it.  Score phase: 2*(KS+1) products, alternately S and dP; the last pair are the
+        // extra steps that bring in -lse/scale and -delta.
+        constexpr int AHEAD = 4;
+        {
+          constexpr int NS = 2 * (KS + 1);
+          auto sfrag_at = [&](int n) {
+            const int ks = n >> 1;
+            const bf16* src = ks < KS ? ((n & 1) ? dofrag : qfrag) + 16 * ks : ((n & 1) ? dox : qx);
+            return *reinterpret_cast<const uint4*>(src + 32 * t2 * LDK);
+          };
+          uint4 ring[AHEAD];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const uint4 aq = *reinterpret_cast<const uint4*>(qfrag + 32 * t2 * LDK + 16 * ks);
-          const uint4 ad = *reinterpret_cast<const uint4*>(dofrag + 32 * t2 * LDK + 16 * ks);
-          s = mfma32(aq, kf[ks], ks == 0 ? zero16 : s);
-          dp = mfma32(ad, vf[ks], ks == 0 ? zero16 : dp);
+          for (int n = 0; n < AHEAD; ++n) ring[n] = sfrag_at(n);
+#pragma unroll
+          for (int n = 0; n < NS; ++n) {
+            const uint4 a = ring[n % AHEAD];
+            if (n + AHEAD < NS) ring[n % AHEAD] = sfrag_at(n + AHEAD);
+            const int ks = n >> 1;
+            if (n & 1) dp = mfma32(a, ks < KS ? vf[ks] : one_f, dp);
+            else s = mfma32(a, ks < KS ? kf[ks] : one_f, s);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
-        s = mfma32(*reinterpret_cast<const uint4*>(qx + 32 * t2 * LDK), one_f, s);
-        dp = mfma32(*reinterpret_cast<const uint4*>(dox + 32 * t2 * LDK), one_f, dp);
+        // the first fragments of the update phase are requested now, under the exponentials
+        constexpr int NU = 4 * DT;
+        auto ufrag_at = [&](int n) {   // n = (g2 * DT + dt) * 2 + which
+          return read_frag_tr<LDT>((n & 1) ? qtfrag : dotfrag, 2 * t2 + n / (2 * DT), 32 * ((n >> 1) % DT));
+        };
+        uint4 uring[AHEAD];
+#pragma unroll
+        for (int n = 0; n < AHEAD; ++n) uring[n] = ufrag_at(n);
+        __builtin_amdgcn_sched_barrier(0);
         // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
         // the branch is taken per tile, not per element: away from the diagonal nothing below compares positions
         if (need_mask) {
@@ -614,17 +638,18 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
             dp[v] = pr * dp[v];
           }
         }
+        // the 4*DT accumulator updates as one sequence, fragments AHEAD updates early
+        {
+          const uint4 pfg[2] = {pack_frag(s, 0), pack_frag(s, 8)};
+          const uint4 dfg[2] = {pack_frag(dp, 0), pack_frag(dp, 8)};
 #pragma unroll
-        for (int g2 = 0; g2 < 2; ++g2) {
-          const int gq = 2 * t2 + g2;
-          const uint4 pf = pack_frag(s, 8 * g2);
-          const uint4 df = pack_frag(dp, 8 * g2);
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            const uint4 ado = read_frag_tr<LDT>(dotfrag, gq, 32 * dt);
-            dvacc[dt] = mfma32(ado, pf, dvacc[dt]);
-            const uint4 aq = read_frag_tr<LDT>(qtfrag, gq, 32 * dt);
-            dkacc[dt] = mfma32(aq, df, dkacc[dt]);
+          for (int n = 0; n < NU; ++n) {
+            const uint4 a = uring[n % AHEAD];
+            if (n + AHEAD < NU) uring[n % AHEAD] = ufrag_at(n + AHEAD);
+            const int g2 = n / (2 * DT), dt = (n >> 1) % DT;
+            if (n & 1) dkacc[dt] = mfma32(a, dfg[g2], dkacc[dt]);
+            else dvacc[dt] = mfma32(a, pfg[g2], dvacc[dt]);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       }
