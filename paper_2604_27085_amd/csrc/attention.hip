@@ -241,14 +241,32 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
     {
       f32x16 sT[QT][2];
       const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      // every LDS fragment is requested AHEAD products before the one that consumes it, so that the MFMAs do not each
+      // wait out an LDS round trip
+      constexpr int AHEAD = 3;
+      {
+        constexpr int NS = 2 * KS;
+        auto sfrag_at = [&](int n) { return *reinterpret_cast<const uint4*>(kfrag + 32 * (n & 1) * LDK + 16 * (n >> 1)); };
+        uint4 ring[AHEAD];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
+        for (int n = 0; n < AHEAD; ++n) ring[n] = sfrag_at(n);
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-          const uint4 a = *reinterpret_cast<const uint4*>(kfrag + 32 * kt * LDK + 16 * ks);
+        for (int n = 0; n < NS; ++n) {
+          const uint4 a = ring[n % AHEAD];
+          if (n + AHEAD < NS) ring[n % AHEAD] = sfrag_at(n + AHEAD);
+          const int ks = n >> 1, kt = n & 1;
 #pragma unroll
           for (int t = 0; t < QT; ++t) sT[t][kt] = mfma32(a, qf[t][ks], ks == 0 ? zero16 : sT[t][kt]);
+          __builtin_amdgcn_sched_barrier(0);
         }
+      }
+      // the first V fragments are requested now, under the softmax arithmetic
+      constexpr int NU = 4 * DT;
+      auto ufrag_at = [&](int n) { return read_frag_tr<LDV>(vfrag, n / DT, 32 * (n % DT)); };
+      uint4 uring[AHEAD];
+#pragma unroll
+      for (int n = 0; n < AHEAD; ++n) uring[n] = ufrag_at(n);
+      __builtin_amdgcn_sched_barrier(0);
       const bool need_mask = (kv0 + 63 > qw0) || (kv0 + 64 > p.seq);   // wave-uniform
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
@@ -300,16 +318,19 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
           }
         l_run[t] += psum;
       }
+      {
+        uint4 pf[4][QT];
 #pragma unroll
-      for (int gk = 0; gk < 4; ++gk) {
-        uint4 pf[QT];
+        for (int gk = 0; gk < 4; ++gk)
 #pragma unroll
-        for (int t = 0; t < QT; ++t) pf[t] = pack_frag(sT[t][gk >> 1], 8 * (gk & 1));
+          for (int t = 0; t < QT; ++t) pf[gk][t] = pack_frag(sT[t][gk >> 1], 8 * (gk & 1));
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const uint4 a = read_frag_tr<LDV>(vfrag, gk, 32 * dt);
+        for (int n = 0; n < NU; ++n) {
+          const uint4 a = uring[n % AHEAD];
+          if (n + AHEAD < NU) uring[n % AHEAD] = ufrag_at(n + AHEAD);
 #pragma unroll
-          for (int t = 0; t < QT; ++t) oacc[t][dt] = mfma32(a, pf[t], oacc[t][dt]);
+          for (int t = 0; t < QT; ++t) oacc[t][n % DT] = mfma32(a, pf[n / DT][t], oacc[t][n % DT]);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
@@ -470,16 +491,24 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_bwd_dq_kernel(c
             for (int v = 0; v < 16; ++v)
               sT[t][v] = fast_exp2(__builtin_fmaf(sT[t][v], p.scale_log2e, -lse2[t])) * (dpT[t][v] - dl[t]);   // dS^T
         }
+        {   // the 2*DT accumulator updates as one sequence, K^T fragments requested AHEAD updates early
+          constexpr int NU = 2 * DT, AHEAD = 2;
+          uint4 df[2][QT];
 #pragma unroll
-        for (int g2 = 0; g2 < 2; ++g2) {
-          uint4 df[QT];
+          for (int g2 = 0; g2 < 2; ++g2)
 #pragma unroll
-          for (int t = 0; t < QT; ++t) df[t] = pack_frag(sT[t], 8 * g2);
+            for (int t = 0; t < QT; ++t) df[g2][t] = pack_frag(sT[t], 8 * g2);
+          auto ufrag_at = [&](int n) { return read_frag_tr<LDT>(ktfrag, 2 * kt + n / DT, 32 * (n % DT)); };
+          uint4 uring[AHEAD];
 #pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            const uint4 a = read_frag_tr<LDT>(ktfrag, 2 * kt + g2, 32 * dt);
+          for (int n = 0; n < AHEAD; ++n) uring[n] = ufrag_at(n);
 #pragma unroll
-            for (int t = 0; t < QT; ++t) dqacc[t][dt] = mfma32(a, df[t], dqacc[t][dt]);
+          for (int n = 0; n < NU; ++n) {
+            const uint4 a = uring[n % AHEAD];
+            if (n + AHEAD < NU) uring[n % AHEAD] = ufrag_at(n + AHEAD);
+#pragma unroll
+            for (int t = 0; t < QT; ++t) dqacc[t][n % DT] = mfma32(a, df[n / DT][t], dqacc[t][n % DT]);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       }
@@ -768,18 +797,38 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) 
     // the two 32-query halves of the tile one after the other: half as many score registers live at a time
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
-      f32x16 s, dp;
+      f32x16 s = zero16, dp = zero16;
+      // every LDS fragment is requested AHEAD MFMAs before the one that consumes it (see the one-kernel version); the
+      // dK kernel has no registers to spare for more than two
+      constexpr int AHEAD = DV ? 4 : 2;
+      {
+        constexpr int PER = DV ? 1 : 2, NS = PER * (KS + 1);   // products per reduction step: S (and dP)
+        auto sfrag_at = [&](int n) {
+          const int ks = n / PER;
+          const bool second = PER == 2 && (n & 1);
+          const bf16* src = ks < KS ? (second ? dofrag : qfrag) + 16 * ks : (second ? dox : qx);
+          return *reinterpret_cast<const uint4*>(src + 32 * t2 * LDK);
+        };
+        uint4 ring[AHEAD];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const uint4 aq = *reinterpret_cast<const uint4*>(qfrag + 32 * t2 * LDK + 16 * ks);
-        s = mfma32(aq, kf[ks], ks == 0 ? zero16 : s);
-        if constexpr (!DV) {
-          const uint4 ad = *reinterpret_cast<const uint4*>(dofrag + 32 * t2 * LDK + 16 * ks);
-          dp = mfma32(ad, vf[ks], ks == 0 ? zero16 : dp);
+        for (int n = 0; n < AHEAD; ++n) ring[n] = sfrag_at(n);
+#pragma unroll
+        for (int n = 0; n < NS; ++n) {
+          const uint4 a = ring[n % AHEAD];
+          if (n + AHEAD < NS) ring[n % AHEAD] = sfrag_at(n + AHEAD);
+          const int ks = n / PER;
+          if (PER == 2 && (n & 1)) dp = mfma32(a, ks < KS ? vf[DV ? 0 : ks] : one_f, dp);
+          else s = mfma32(a, ks < KS ? kf[ks] : one_f, s);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
-      s = mfma32(*reinterpret_cast<const uint4*>(qx + 32 * t2 * LDK), one_f, s);
-      if constexpr (!DV) dp = mfma32(*reinterpret_cast<const uint4*>(dox + 32 * t2 * LDK), one_f, dp);
+      // the first fragments of the update phase are requested now, under the exponentials
+      constexpr int NU = 2 * DT;
+      auto ufrag_at = [&](int n) { return read_frag_tr<LDT>(tfrag, 2 * t2 + n / DT, 32 * (n % DT)); };
+      uint4 uring[AHEAD];
+#pragma unroll
+      for (int n = 0; n < AHEAD; ++n) uring[n] = ufrag_at(n);
+      __builtin_amdgcn_sched_barrier(0);
       // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
       // the branch is taken per tile, not per element: away from the diagonal nothing below compares positions
       if (need_mask) {
@@ -799,13 +848,14 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) 
           else s[v] = pr * dp[v];
         }
       }
+      {
+        const uint4 bfg[2] = {pack_frag(s, 0), pack_frag(s, 8)};
 #pragma unroll
-      for (int g2 = 0; g2 < 2; ++g2) {
-        const uint4 bfrag = pack_frag(s, 8 * g2);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const uint4 at = read_frag_tr<LDT>(tfrag, 2 * t2 + g2, 32 * dt);
-          acc[dt] = mfma32(at, bfrag, acc[dt]);
+        for (int n = 0; n < NU; ++n) {
+          const uint4 at = uring[n % AHEAD];
+          if (n + AHEAD < NU) uring[n % AHEAD] = ufrag_at(n + AHEAD);
+          acc[n % DT] = mfma32(at, bfg[n / DT], acc[n % DT]);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
