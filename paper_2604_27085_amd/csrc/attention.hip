@@ -521,9 +521,10 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_bwd_dq_kernel(c
 }
 
 // ================================================================================================ dK, dV in one kernel
-// One wave per SIMD (the K and V fragments plus both accumulators take more than 256 registers per lane), four
-// recomputed/updated products per tile.  The better choice for short sequences, where the loops are short and the
-// second launch of the split version costs more than the lower occupancy.
+// One wave per SIMD at head dimension 128 (the K and V fragments plus both accumulators take more than 256 registers
+// per lane), two at 64; four recomputed/updated products per tile.  A version split into a dV and a dK kernel at two
+// waves per SIMD each (the scores recomputed in both) was as fast at best once the LDS reads here were issued ahead
+// of their MFMAs (sequence 8192 to 31744: 0 to 3 % slower; 16 % slower at head dimension 64) and is gone.
 template <int D>
 __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs p) {
   constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32;
@@ -574,8 +575,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
   const bf16* dofrag = dOs + lr * LDK + 8 * lk;
   const bf16* qtfrag = Qt + tr_base<LDT>(lane);
   const bf16* dotfrag = dOt + tr_base<LDT>(lane);
-  // -lse/scale and -delta ride in the pad chunks of the Q and dO rows and enter through one extra MFMA step each (see
-  // the two-kernel version below)
+  // The per-query terms of the softmax recomputation ride along in the products: the pad chunk of a Q row holds
+  // -lse/scale split into three bf16 numbers, that of a dO row -delta, and one extra MFMA step against ones3() adds
+  // them, so the score tile comes out as q.k - lse/scale and the dP tile as dO.v - delta.  (Rows of the score tile are
+  // queries here: without this every lane would need sixteen different lse and delta values per tile.)
   const bf16* qx = Qs + lr * LDK + D;
   const bf16* dox = dOs + lr * LDK + D;
   const uint4 one_f = ones3(lk);
@@ -696,182 +699,6 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
   }
 }
 
-// ================================================================================================ dK, dV
-// Two launches of one template, each at two waves per SIMD (one kernel holding K, V fragments and both accumulators
-// needs more than 256 registers per lane and runs alone on its SIMD; measured at long sequences that costs more than
-// the score recomputation that the split adds):
-//   WHAT = 0: dV^T += dO^T P      (S recomputed; K fragments in registers, Q and dO^T tiles in LDS)
-//   WHAT = 1: dK^T += Q^T dS      (S and dP recomputed; K and V fragments in registers, Q, dO and Q^T tiles in LDS)
-template <int D, int WHAT>
-__global__ void __launch_bounds__(256, 2) attn_bwd_dkv_kernel(const AttnArgs p) {
-  constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32;
-  constexpr bool DV = WHAT == 0;
-  using T64 = Tile64<D, 256>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);
-  // dV: Qs [64][LDK] | dOt [64][LDT];   dK: Qs | dOs [64][LDK] | Qt [64][LDT]
-  bf16* const Qs = smem;
-  bf16* const dOs = smem + 64 * LDK;                     // dK only
-  bf16* const Tt = smem + (DV ? 1 : 2) * 64 * LDK;       // the transposed-read tile: dO (dV) or Q (dK)
-
-  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nhb = p.a * p.batch;
-  const int kvt = (int)blockIdx.x / nhb;     // key tile 0 sees every query: heaviest first, for every head
-  const int hb = (int)blockIdx.x % nhb;
-  const int hq = hb % p.a, b = hb / p.a;
-  const int grp = p.a / p.kh;
-  const int g = hq / grp;
-  const int kv0 = kvt * 128, kw0 = kv0 + 32 * w;
-  const long tok0 = (long)b * p.seq;
-  const bf16* kb = p.k + tok0 * p.ldk + g * D;
-  const bf16* vb = p.v + tok0 * p.ldv + g * D;
-  const int kpos = kw0 + lr;
-  const bool kok = kpos < p.seq;
-
-  uint4 kf[KS], vf[DV ? 1 : KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    kf[ks] = make_uint4(0u, 0u, 0u, 0u);
-    if (kok) kf[ks] = *reinterpret_cast<const uint4*>(kb + (long)kpos * p.ldk + 16 * ks + 8 * lk);
-    if constexpr (!DV) {
-      vf[ks] = make_uint4(0u, 0u, 0u, 0u);
-      if (kok) vf[ks] = *reinterpret_cast<const uint4*>(vb + (long)kpos * p.ldv + 16 * ks + 8 * lk);
-    }
-  }
-  f32x16 acc[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
-
-  const int nQ = (p.seq + 63) / 64;
-  const int qt0 = kv0 / 64;
-  const int niter = nQ - qt0;
-
-  const bf16* qfrag = Qs + lr * LDK + 8 * lk;
-  const bf16* dofrag = dOs + lr * LDK + 8 * lk;
-  const bf16* tfrag = Tt + tr_base<LDT>(lane);
-  // The per-query terms of the softmax recomputation ride along in the products: the pad chunk of a Q row holds
-  // -lse/scale split into three bf16 numbers, that of a dO row -delta, and one extra MFMA step against ones3() adds
-  // them, so the score tile comes out as q.k - lse/scale and the dP tile as dO.v - delta.  (Rows of the score tile are
-  // queries here: without this every lane would need sixteen different lse and delta values per tile.)
-  const bf16* qx = Qs + lr * LDK + D;
-  const bf16* dox = dOs + lr * LDK + D;
-  const uint4 one_f = ones3(lk);
-
-  uint4 qreg[T64::NREG], doreg[T64::NREG];
-  float st_reg = 0.f;
-  const rsrc_t rq = seq_rsrc(p.q + tok0 * p.ldq + hq * D, p.ldq, p.seq, D);
-  const rsrc_t rdo = seq_rsrc(p.dout + tok0 * p.lddo + hq * D, p.lddo, p.seq, D);
-  auto prefetch = [&](int it) {
-    const int q0 = (qt0 + it) * 64;
-    T64::load(qreg, rq, p.ldq, q0, tid);
-    T64::load(doreg, rdo, p.lddo, q0, tid);
-    if (tid < (DV ? 64 : 128)) {
-      const int qi = q0 + (tid & 63);
-      const long sidx = ((long)b * p.a + hq) * p.seq + (qi < p.seq ? qi : 0);
-      const float v = tid < 64 ? -p.lse_in[sidx] / p.scale : -p.delta[sidx];
-      st_reg = qi < p.seq ? v : (tid < 64 ? -3.0e4f : 0.f);   // padded query rows get P = exp(-3e4 scale) = 0
-    }
-  };
-  if (niter > 0) prefetch(0);
-
-  for (int it = 0; it < niter; ++it) {
-    __syncthreads();
-    T64::template store<LDK>(qreg, Qs, tid);
-    if constexpr (DV) {
-      T64::template store<LDT>(doreg, Tt, tid);
-    } else {
-      T64::template store<LDK>(doreg, dOs, tid);
-      T64::template store<LDT>(qreg, Tt, tid);
-    }
-    if (tid < 64) *reinterpret_cast<uint4*>(Qs + tid * LDK + D) = split3(st_reg);
-    else if (!DV && tid < 128) *reinterpret_cast<uint4*>(dOs + (tid - 64) * LDK + D) = split3(st_reg);
-    __syncthreads();
-    if (it + 1 < niter) prefetch(it + 1);
-    const int q0 = (qt0 + it) * 64;
-    // a wave whose keys all follow this tile's queries runs it fully masked (see the forward kernel)
-    const bool need_mask = (q0 < kw0 + 31) || (kw0 + 32 > p.seq);   // wave-uniform
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    // the two 32-query halves of the tile one after the other: half as many score registers live at a time
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2) {
-      f32x16 s = zero16, dp = zero16;
-      // every LDS fragment is requested AHEAD MFMAs before the one that consumes it (see the one-kernel version); the
-      // dK kernel has no registers to spare for more than two
-      constexpr int AHEAD = DV ? 4 : 2;
-      {
-        constexpr int PER = DV ? 1 : 2, NS = PER * (KS + 1);   // products per reduction step: S (and dP)
-        auto sfrag_at = [&](int n) {
-          const int ks = n / PER;
-          const bool second = PER == 2 && (n & 1);
-          const bf16* src = ks < KS ? (second ? dofrag : qfrag) + 16 * ks : (second ? dox : qx);
-          return *reinterpret_cast<const uint4*>(src + 32 * t2 * LDK);
-        };
-        uint4 ring[AHEAD];
-#pragma unroll
-        for (int n = 0; n < AHEAD; ++n) ring[n] = sfrag_at(n);
-#pragma unroll
-        for (int n = 0; n < NS; ++n) {
-          const uint4 a = ring[n % AHEAD];
-          if (n + AHEAD < NS) ring[n % AHEAD] = sfrag_at(n + AHEAD);
-          const int ks = n / PER;
-          if (PER == 2 && (n & 1)) dp = mfma32(a, ks < KS ? vf[DV ? 0 : ks] : one_f, dp);
-          else s = mfma32(a, ks < KS ? kf[ks] : one_f, s);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-      // the first fragments of the update phase are requested now, under the exponentials
-      constexpr int NU = 2 * DT;
-      auto ufrag_at = [&](int n) { return read_frag_tr<LDT>(tfrag, 2 * t2 + n / DT, 32 * (n % DT)); };
-      uint4 uring[AHEAD];
-#pragma unroll
-      for (int n = 0; n < AHEAD; ++n) uring[n] = ufrag_at(n);
-      __builtin_amdgcn_sched_barrier(0);
-      // rows of the score tile are queries: q = q0 + 32*t2 + 8*(v/4) + 4*lk + v%4
-      // the branch is taken per tile, not per element: away from the diagonal nothing below compares positions
-      if (need_mask) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int qpos = q0 + 32 * t2 + 8 * (v >> 2) + 4 * lk + (v & 3);
-          float pr = fast_exp2(s[v] * p.scale_log2e);
-          pr = (kpos > qpos || !kok) ? 0.f : pr;
-          if constexpr (DV) s[v] = pr;                         // P
-          else s[v] = pr * dp[v];                              // dS
-        }
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float pr = fast_exp2(s[v] * p.scale_log2e);
-          if constexpr (DV) s[v] = pr;
-          else s[v] = pr * dp[v];
-        }
-      }
-      {
-        const uint4 bfg[2] = {pack_frag(s, 0), pack_frag(s, 8)};
-#pragma unroll
-        for (int n = 0; n < NU; ++n) {
-          const uint4 at = uring[n % AHEAD];
-          if (n + AHEAD < NU) uring[n % AHEAD] = ufrag_at(n + AHEAD);
-          acc[n % DT] = mfma32(at, bfg[n / DT], acc[n % DT]);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-    }
-  }
-  __syncthreads();
-  const float mul = DV ? 1.f : p.scale;
-  if (grp == 1) {
-    bf16* out = DV ? p.dv + tok0 * p.lddv + g * D : p.dk + tok0 * p.lddk + g * D;
-    store_acc_T<D>(acc, mul, smem + w * 32 * LDK, out, DV ? p.lddv : p.lddk, kw0, p.seq, lane);
-  } else {
-    float* const stage = reinterpret_cast<float*>(smem) + w * 32 * (D + 4);
-    const long ldp = (long)p.a * D;
-    store_acc_T_f32<D>(acc, mul, stage, (DV ? p.dv_part : p.dk_part) + tok0 * ldp + hq * D, ldp, kw0, p.seq, lane);
-  }
-}
-
 // dk[t, g, :] = sum over the query heads of group g of the fp32 partials, in head order; same for dv.
 template <int D>
 __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __restrict__ dk_part, const float* __restrict__ dv_part,
@@ -902,13 +729,6 @@ __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __res
 
 constexpr int dq_smem_bytes(int d) { return (2 * 64 * (d + 8) + 64 * (d + 32)) * 2; }
 constexpr int dkv_fused_smem_bytes(int d) { return (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
-// operand tiles of the loop, or the four waves' fp32 staging of the epilogue, whichever is larger
-constexpr int dkv_smem_bytes(int d, int what) {
-  const int loop = ((what == 0 ? 1 : 2) * 64 * (d + 8) + 64 * (d + 32)) * 2;
-  const int stage = 4 * 32 * (d + 4) * 4;
-  return loop > stage ? loop : stage;
-}
-
 void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
   p.batch = batch; p.seq = seq; p.a = a; p.kh = kh;
   p.scale = 1.0f / sqrtf((float)d);
@@ -923,13 +743,6 @@ hipError_t set_smem(K kern, int bytes, bool& done) {
   return e;
 }
 
-// Reads a 1/2 switch from the environment (RP_ATTN_DKV: 1 = one dK/dV kernel, 2 = two kernels).
-int env_shape(const char* name, int dflt) {
-  const char* s = getenv(name);
-  const int v = s ? atoi(s) : dflt;
-  return (v == 1 || v == 2) ? v : dflt;   // anything else: the default
-}
-
 template <int D, int QT, int NW>
 hipError_t launch_fwd(hipStream_t st, const AttnArgs& p) {
   constexpr int BQ = NW * 32 * QT;
@@ -937,15 +750,6 @@ hipError_t launch_fwd(hipStream_t st, const AttnArgs& p) {
   AttnArgs pf = p;
   pf.fold = grid > 256 && grid <= 512;
   RP_LAUNCH((attn_fwd_kernel<D, QT, NW>), dim3(grid), dim3(NW * 64), 0, st, pf);
-  return hipGetLastError();
-}
-
-template <int D, int WHAT>
-hipError_t launch_dkv(hipStream_t st, const AttnArgs& p, int grid) {
-  static bool done = false;
-  hipError_t e = set_smem(attn_bwd_dkv_kernel<D, WHAT>, dkv_smem_bytes(D, WHAT), done);
-  if (e != hipSuccess) return e;
-  RP_LAUNCH((attn_bwd_dkv_kernel<D, WHAT>), dim3(grid), dim3(256), dkv_smem_bytes(D, WHAT), st, p);
   return hipGetLastError();
 }
 
@@ -1024,13 +828,7 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
   }
   if (part == 0) {
     const int nk = ((seq + 127) / 128) * a * batch;   // one workgroup per 128 keys and query head
-    // one kernel for short sequences, two kernels at twice the occupancy for long ones (RP_ATTN_DKV: 1 / 2 forces)
-    static const int forced = env_shape("RP_ATTN_DKV", 0);
-    const bool split = forced ? forced == 2 : seq >= 8192;
-    if (!split) return d == 128 ? launch_dkv_fused<128>(st, p, nk) : launch_dkv_fused<64>(st, p, nk);
-    if (d == 128) { if ((e = launch_dkv<128, 0>(st, p, nk)) == hipSuccess) e = launch_dkv<128, 1>(st, p, nk); }
-    else { if ((e = launch_dkv<64, 0>(st, p, nk)) == hipSuccess) e = launch_dkv<64, 1>(st, p, nk); }
-    return e;
+    return d == 128 ? launch_dkv_fused<128>(st, p, nk) : launch_dkv_fused<64>(st, p, nk);
   } else {
     return d == 128 ? launch_dq<128, 1, 4>(st, p) : launch_dq<64, 1, 4>(st, p);
   }
