@@ -526,7 +526,8 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_bwd_dq_kernel(c
 // waves per SIMD each (the scores recomputed in both) was as fast at best once the LDS reads here were issued ahead
 // of their MFMAs (sequence 8192 to 31744: 0 to 3 % slower; 16 % slower at head dimension 64) and is gone.  Staggering
 // the two 32-query halves so that one half's exponentials sit in the slots of the other half's MFMAs was 12-20 % slower
-// (a wave issues in order: the dependent multiply-exp-multiply chains hold back the next MFMA).
+// (a wave issues in order: the dependent multiply-exp-multiply chains hold back the next MFMA).  Two sets of LDS tiles
+// at d = 128 (the next query tile stored during the updates, one barrier per tile instead of two) changed nothing.
 template <int D>
 __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs p) {
   constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32;
