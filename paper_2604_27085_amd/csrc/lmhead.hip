@@ -7,33 +7,32 @@
 namespace {
 
 // lse[t] = log sum_v exp(z[t, v]) from P partial (max, sum) pairs per token; part is [P][ld] so reads are coalesced
-// over tokens.  A block handles 16 tokens with 16 slices of the partials each, merged through LDS.
-__global__ void __launch_bounds__(256) ce_lse_kernel(const float2* __restrict__ part, int P, long ld, float* __restrict__ lse, int T) {
-  __shared__ float2 red[16][17];
+// over tokens.  A block handles 16 tokens with 64 slices of the partials each (a thread's chain of dependent
+// exponentials is P/64 long), merged through LDS in two steps.
+__global__ void __launch_bounds__(1024) ce_lse_kernel(const float2* __restrict__ part, int P, long ld, float* __restrict__ lse, int T) {
+  constexpr int NS = 64;
+  __shared__ float2 red[NS][17];
   const int tl = threadIdx.x & 15, sl = threadIdx.x >> 4;
   const int t = blockIdx.x * 16 + tl;
   float m = -INFINITY, s = 0.f;
-  if (t < T) {
-    for (int i = sl; i < P; i += 16) {
-      const float2 v = part[(long)i * ld + t];
-      if (v.x > -INFINITY) {
-        const float mn = fmaxf(m, v.x);
-        s = s * __expf(m - mn) + v.y * __expf(v.x - mn);
-        m = mn;
-      }
+  auto merge = [&](const float2 v) {
+    if (v.x > -INFINITY) {
+      const float mn = fmaxf(m, v.x);
+      s = s * __expf(m - mn) + v.y * __expf(v.x - mn);
+      m = mn;
     }
-  }
+  };
+  if (t < T)
+    for (int i = sl; i < P; i += NS) merge(part[(long)i * ld + t]);
   red[sl][tl] = make_float2(m, s);
   __syncthreads();
+  if (sl < 8) {   // slices sl, sl + 8, ..., in a fixed order
+    for (int i = sl + 8; i < NS; i += 8) merge(red[i][tl]);
+    red[sl][tl] = make_float2(m, s);
+  }
+  __syncthreads();
   if (sl == 0 && t < T) {
-    for (int i = 1; i < 16; ++i) {
-      const float2 v = red[i][tl];
-      if (v.x > -INFINITY) {
-        const float mn = fmaxf(m, v.x);
-        s = s * __expf(m - mn) + v.y * __expf(v.x - mn);
-        m = mn;
-      }
-    }
+    for (int i = 1; i < 8; ++i) merge(red[i][tl]);
     lse[t] = m + logf(s);
   }
 }
@@ -201,7 +200,7 @@ hipError_t k_ce_frozen_dx(hipStream_t st, float* acc, const float* l, const floa
 
 hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, float* lse, int T) {
   if (T == 0) return hipSuccess;
-  RP_LAUNCH(ce_lse_kernel, dim3((T + 15) / 16), dim3(256), 0, st, part, P, part_ld, lse, T);
+  RP_LAUNCH(ce_lse_kernel, dim3((T + 15) / 16), dim3(1024), 0, st, part, P, part_ld, lse, T);
   return hipGetLastError();
 }
 
