@@ -98,12 +98,12 @@ template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1>
 struct Cfg {
   static constexpr int BM = WGM * WAVE_M, BN = WGN * WAVE_N, NWT = WGM * WGN, NW = NWT * KG, NTHR = NW * 64;
   static_assert((BK / 16) % KG == 0, "the K tile does not divide over the wave groups");
-  static_assert(KG == 1 || NWT * (TM * 16 * 64 * 4) <= 160 * 1024, "accumulator exchange does not fit in LDS");
+  static_assert(KG == 1 || NW * (TM * 16 * 64 * 4) <= 160 * 1024, "accumulator exchange does not fit in LDS");
   using LA = TileLoader<BM, BK, NTHR, TA>;
   using LB = TileLoader<BN, BK, NTHR, TB>;
   static constexpr int MAIN_BYTES = 2 * (LA::S::ELEMS + LB::S::ELEMS) * 2;
-  static constexpr int XCH_BYTES = KG > 1 ? NWT * (TM * 16 * 64 * 4) : 0;   // one column of MFMA tiles per exchange
-  static constexpr int SMEM0 = MAIN_BYTES > NWT * STG_BYTES ? MAIN_BYTES : NWT * STG_BYTES;
+  static constexpr int XCH_BYTES = KG > 1 ? NW * (TM * 16 * 64 * 4) : 0;   // every wave hands over one column of MFMA tiles
+  static constexpr int SMEM0 = MAIN_BYTES > NW * STG_BYTES ? MAIN_BYTES : NW * STG_BYTES;   // every wave stages
   static constexpr int SMEM = SMEM0 > XCH_BYTES ? SMEM0 : XCH_BYTES;
   // waves per SIMD the register budget is set for
   static constexpr int WPS = (NW == 8) ? 2 : (SMEM * 2 <= 160 * 1024 ? 2 : 1);
@@ -270,29 +270,32 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   __syncthreads();   // every wave is done with the operand tiles: the epilogue reuses the LDS
 
   if constexpr (KG > 1) {
-    // the K loop ended with a barrier, so the operand tiles are dead: groups 1.. hand their accumulators to group 0,
-    // one column of MFMA tiles at a time, [wave][register][lane] (conflict-free)
-    float* const xch = reinterpret_cast<float*>(smem) + wmn * (TM * 16 * 64) + lane;
+    static_assert(KG == 2 && TN == 2, "the exchange pairs two wave groups with the two column halves of a block");
+    // The K loop ended with a barrier, so the operand tiles are dead.  The two groups hold partial sums of the same
+    // blocks: group 1 hands its left half (tile column 0) to group 0 and takes group 0's right half, in one exchange
+    // ([group][wave][register][lane], conflict-free), and each group finishes and writes its own half.
+    float* const mine = reinterpret_cast<float*>(smem) + (kg * C::NWT + wmn) * (TM * 16 * 64) + lane;
+    float* const theirs = reinterpret_cast<float*>(smem) + ((kg ^ 1) * C::NWT + wmn) * (TM * 16 * 64) + lane;
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < TN; ++j) {
+      if (j == kg) continue;   // wave-uniform: the half this wave gives away is j = 1 - kg
 #pragma unroll
-      for (int g = 1; g < KG; ++g) {
-        if (kg == g) {
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
+        for (int v = 0; v < 16; ++v) mine[(i * 16 + v) * 64] = acc[i][j][v];
+    }
+    __syncthreads();
 #pragma unroll
-            for (int v = 0; v < 16; ++v) xch[(i * 16 + v) * 64] = acc[i][j][v];
-        }
-        __syncthreads();
-        if (kg == 0) {
+    for (int j = 0; j < TN; ++j) {
+      if (j != kg) continue;
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] += xch[(i * 16 + v) * 64];
-        }
-        __syncthreads();
-      }
-    if (kg != 0) return;   // wave-uniform; the epilogue has no workgroup barrier
+        for (int v = 0; v < 16; ++v) acc[i][j][v] += theirs[(i * 16 + v) * 64];
+    }
+    __syncthreads();   // the staging of the epilogue overwrites the exchange area
+    epilogue(p, Mlim, acc, smem, wave, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm, kg, kg + 1);
+    return;
   }
   epilogue(p, Mlim, acc, smem, wmn, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
 }

@@ -128,8 +128,10 @@ RP_DEV bool label_logit(const f32x16 (&acc)[TM][TN], int j, int lab_local, float
 // barrier inside.
 // part_row: row of the cross-entropy partial array this wave writes (EPI_CE_STATS).
 // M: rows of C that exist (the end of the group's rows in grouped mode).
+// j0, j1 (wave-uniform): the 32-column halves [j0, j1) of the block this wave writes -- both, except in the plain
+// epilogues of the two-group tile, where the groups take one half each.
 RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsigned char* smem, int wave, int lane,
-                     int wrow0, int wcol0, int part_row) {
+                     int wrow0, int wcol0, int part_row, int j0 = 0, int j1 = TN) {
   const int lr = lane & 31, lk = lane >> 5;
   unsigned char* const stg = smem + wave * STG_BYTES;
   const int rr = lane >> 3, cc = lane & 7;   // read-back: 8 rows per pass, 8 chunks of 16 bytes per row
@@ -147,18 +149,22 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
     if (p.epi == EPI_BF16) {
       if (p.alpha == 1.f) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j) {
+          if (j < j0 || j >= j1) continue;
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
+          for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int v = 0; v < 16; v += 2) stage2(i, j, v, acc[i][j][v], acc[i][j][v + 1]);
+        }
       } else {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j) {
+          if (j < j0 || j >= j1) continue;
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
+          for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int v = 0; v < 16; v += 2) stage2(i, j, v, p.alpha * acc[i][j][v], p.alpha * acc[i][j][v + 1]);
+        }
       }
     } else {
       // dZ^T = (softmax - onehot) * coef: rows are vocabulary entries, columns tokens.  Every element gets
@@ -186,12 +192,22 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
     }
     wave_lds_fence();
     bf16* Cp = reinterpret_cast<bf16*>(p.C);
-    const int gcol = wcol0 + cc * 8;
+    if (j1 - j0 == TN) {
+      const int gcol = wcol0 + cc * 8;
 #pragma unroll
-    for (int t = 0; t < WAVE_M / 8; ++t) {
-      const int row = t * 8 + rr, grow = wrow0 + row;
-      if (grow < M && gcol < p.N)
-        *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + gcol) = *reinterpret_cast<const uint4*>(s16 + row * STG_LD + cc * 8);
+      for (int t = 0; t < WAVE_M / 8; ++t) {
+        const int row = t * 8 + rr, grow = wrow0 + row;
+        if (grow < M && gcol < p.N)
+          *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + gcol) = *reinterpret_cast<const uint4*>(s16 + row * STG_LD + cc * 8);
+      }
+    } else {   // one half: 16 rows per pass, 4 chunks of 16 bytes per row
+      const int lcol = j0 * 32 + (lane & 3) * 8, gcol = wcol0 + lcol;
+#pragma unroll
+      for (int t = 0; t < WAVE_M / 16; ++t) {
+        const int row = t * 16 + (lane >> 2), grow = wrow0 + row;
+        if (grow < M && gcol < p.N)
+          *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + gcol) = *reinterpret_cast<const uint4*>(s16 + row * STG_LD + lcol);
+      }
     }
   } else if (p.epi == EPI_BF16 || p.epi == EPI_F32 || p.epi == EPI_F32_COLMAX) {
     if (p.epi == EPI_F32_COLMAX) {
@@ -231,7 +247,8 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
     const bool unit = p.alpha == 1.f;   // uniform
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      if (j) wave_lds_fence();
+      if (j < j0 || j >= j1) continue;
+      if (j > j0) wave_lds_fence();
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         float* const d = s32 + (i * 32 + 4 * lk) * (STG_LD / 2) + lr;
@@ -297,7 +314,7 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = wcol0 + j * 32 + lr;
-      if (col >= p.N) continue;
+      if (col >= p.N || j < j0 || j >= j1) continue;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
