@@ -403,6 +403,7 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   if (a.N % 8 || a.K % 8 || a.lda % 8 || a.ldb % 8) return hipErrorInvalidValue;
   if (a.epi != EPI_CE_STATS && a.ldc % (out_f32 ? 4 : 8)) return hipErrorInvalidValue;
   if (a.R && a.ldr % 4) return hipErrorInvalidValue;
+  if (a.epi == EPI_SWIGLU_BWD && (!a.R || a.ldr % 8 || a.ldc % 8 || a.grp_tab)) return hipErrorInvalidValue;
   const bool ta = layout == GEMM_TN, tb = layout != GEMM_NT;
   if (ta && a.M % 8) return hipErrorInvalidValue;
   if (!a.A2 || !a.B2) a.K2 = 0;

@@ -16,7 +16,11 @@ enum {
   EPI_F32_ATOMIC = 2,// C fp32 atomically += alpha*acc
   EPI_CE_STATS = 3,  // rows = vocab, cols = tokens: per-column (max, sum exp) partials + label logit
   EPI_CE_DZ = 4,     // C bf16 [rows, cols] = (exp(acc - lse[col]) - (row == label[col])) * coef[col]
-  EPI_F32_COLMAX = 5 // C fp32 = acc, plus per-column maximum partials (part[...].x, one per 128 rows) and the label logit
+  EPI_F32_COLMAX = 5,// C fp32 = acc, plus per-column maximum partials (part[...].x, one per 128 rows) and the label logit
+  // The product is the gradient of act = silu(gate) * up ([M, N]); R holds gate | up ([M, 2N], row stride ldr) and
+  // C ([M, 2N], row stride ldc) receives d gate | d up.  The product itself is rounded to bf16 on the way (as if it
+  // had been stored) and never written.
+  EPI_SWIGLU_BWD = 6
 };
 
 struct GemmArgs {

@@ -136,7 +136,7 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
   unsigned char* const stg = smem + wave * STG_BYTES;
   const int rr = lane >> 3, cc = lane & 7;   // read-back: 8 rows per pass, 8 chunks of 16 bytes per row
 
-  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ) {
+  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ || p.epi == EPI_SWIGLU_BWD) {
     bf16* s16 = reinterpret_cast<bf16*>(stg);
     unsigned short* const h16 = reinterpret_cast<unsigned short*>(stg);
     // two rows of a column are converted by one instruction and go out as the halves of its result
@@ -146,7 +146,7 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
       d[0] = (unsigned short)pk;
       d[STG_LD] = (unsigned short)(pk >> 16);
     };
-    if (p.epi == EPI_BF16) {
+    if (p.epi != EPI_CE_DZ) {
       if (p.alpha == 1.f) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
@@ -192,7 +192,54 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
     }
     wave_lds_fence();
     bf16* Cp = reinterpret_cast<bf16*>(p.C);
-    if (j1 - j0 == TN) {
+    if (p.epi == EPI_SWIGLU_BWD) {
+      // a lane takes 8 columns of a row of the staged product d (the gradient of silu(gate) * up), reads gate and up
+      // there and writes  d_gate = d * up * s * (1 + gate * (1 - s)),  d_up = d * gate * s,  s = sigmoid(gate);
+      // the loads of four row groups are in flight before anything is stored
+      const bf16* Rp = reinterpret_cast<const bf16*>(p.R);
+      const int gcol = wcol0 + cc * 8;
+      constexpr int NB = 4;
+#pragma unroll
+      for (int t0 = 0; t0 < WAVE_M / 8; t0 += NB) {
+        uint4 gv[NB], uv[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          const int grow = wrow0 + (t0 + u) * 8 + rr;
+          gv[u] = make_uint4(0u, 0u, 0u, 0u);
+          uv[u] = gv[u];
+          if (grow < M && gcol < p.N) {
+            gv[u] = *reinterpret_cast<const uint4*>(Rp + (long)grow * p.ldr + gcol);
+            uv[u] = *reinterpret_cast<const uint4*>(Rp + (long)grow * p.ldr + p.N + gcol);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          const int row = (t0 + u) * 8 + rr, grow = wrow0 + row;
+          const uint4 dv = *reinterpret_cast<const uint4*>(s16 + row * STG_LD + cc * 8);
+          const uint32_t dw[4] = {dv.x, dv.y, dv.z, dv.w}, gw[4] = {gv[u].x, gv[u].y, gv[u].z, gv[u].w},
+                         uw[4] = {uv[u].x, uv[u].y, uv[u].z, uv[u].w};
+          uint32_t og[4], ou[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float dg2[2], du2[2];
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+              const float d = hh ? bf16_hi(dw[e]) : bf16_lo(dw[e]), g = hh ? bf16_hi(gw[e]) : bf16_lo(gw[e]),
+                          up = hh ? bf16_hi(uw[e]) : bf16_lo(uw[e]);
+              const float sg = 1.f / (1.f + __expf(-g));
+              dg2[hh] = d * up * sg * (1.f + g * (1.f - sg));
+              du2[hh] = d * g * sg;
+            }
+            og[e] = pack_bf16x2(dg2[0], dg2[1]);
+            ou[e] = pack_bf16x2(du2[0], du2[1]);
+          }
+          if (grow < M && gcol < p.N) {
+            *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + gcol) = make_uint4(og[0], og[1], og[2], og[3]);
+            *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + p.N + gcol) = make_uint4(ou[0], ou[1], ou[2], ou[3]);
+          }
+        }
+      }
+    } else if (j1 - j0 == TN) {
       const int gcol = wcol0 + cc * 8;
 #pragma unroll
       for (int t = 0; t < WAVE_M / 8; ++t) {

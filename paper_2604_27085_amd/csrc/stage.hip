@@ -154,20 +154,21 @@ struct Exec {
     static const char* til[6] = {"", "256x256", "256x128", "128x128", "128x64", "256x128k2"};
     char nm[40];
     snprintf(nm, sizeof(nm), "gemm_%s_%s", til[gemm_pick_tile(g)], lay[layout]);
-    const double out_b = (g.epi == EPI_BF16 || g.epi == EPI_CE_DZ) ? 2.0 : (g.epi == EPI_CE_STATS ? 0.0 : 4.0 * (1 + g.beta));
+    const double out_b = (g.epi == EPI_BF16 || g.epi == EPI_CE_DZ) ? 2.0
+                         : g.epi == EPI_SWIGLU_BWD ? 4.0 : (g.epi == EPI_CE_STATS ? 0.0 : 4.0 * (1 + g.beta));
     mark(nm, 2.0 * g.M * (double)g.N * ((double)g.K + g.K2),
          2.0 * ((double)g.M * g.K + (double)g.N * g.K + (double)g.M * g.K2 + (double)g.N * g.K2) + out_b * g.M * (double)g.N +
-             (g.R ? 2.0 * g.M * (double)g.N : 0.0));
+             (g.R ? (g.epi == EPI_SWIGLU_BWD ? 4.0 : 2.0) * g.M * (double)g.N : 0.0));
   }
   template <typename Tp> Tp* at(size_t off) const { return reinterpret_cast<Tp*>(ws + off); }
 
   // C[M,N] (bf16) = alpha * A * op(B) (+ second pair) (+ R)
   void gemm_bf16(int layout, const void* A, long lda, const void* B, long ldb, void* C, long ldc, int M, int N, int K,
                  float alpha = 1.f, const void* A2 = nullptr, long lda2 = 0, const void* B2 = nullptr, long ldb2 = 0,
-                 int K2 = 0, const void* R = nullptr, long ldr = 0) {
+                 int K2 = 0, const void* R = nullptr, long ldr = 0, int epi = EPI_BF16) {
     GemmArgs g; gemm_zero_args(g);
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
-    g.A2 = A2; g.lda2 = lda2; g.B2 = B2; g.ldb2 = ldb2; g.K2 = K2; g.R = R; g.ldr = ldr; g.epi = EPI_BF16;
+    g.A2 = A2; g.lda2 = lda2; g.B2 = B2; g.ldb2 = ldb2; g.K2 = K2; g.R = R; g.ldr = ldr; g.epi = epi;
     mark_gemm(layout, g);
     chk(gemm_launch(st, layout, g), "gemm_bf16");
   }
@@ -276,8 +277,10 @@ void linear_fwd(Exec& X, const LayerW& W, int w_id, const FusedLora& f, size_t b
 }
 
 // dX[T,K] = dY W (+ LoRA);  dW += dY^T X;  LoRA gradients.  u_buf = U saved by the forward, ud = scratch [T, n*r].
+// sw_gu (optional): x = silu(gate) * up of the [T, 2K] buffer sw_gu; instead of dx ([T, K]) the input-gradient GEMM
+// then writes d gate | d up into sw_dgu ([T, 2K]) from its epilogue.
 void linear_bwd(Exec& X, const LayerW& W, const LayerG& G, int w_id, const FusedLora& f, size_t bd_off, const void* dy,
-                int N, const void* x, int K, void* dx, const void* u_buf) {
+                int N, const void* x, int K, void* dx, const void* u_buf, const void* sw_gu = nullptr, void* sw_dgu = nullptr) {
   const int nr = f.n * X.D.r;
   void* ud = X.at<void>(X.P.ud);
   const void* Bm = nullptr;
@@ -285,8 +288,12 @@ void linear_bwd(Exec& X, const LayerW& W, const LayerG& G, int w_id, const Fused
     Bm = lora_b_matrix(X, W, f, N, bd_off);
     X.gemm_skinny_bf16(GEMM_NN, dy, N, Bm, nr, ud, (int)X.T, nr, N, X.ctx->cfg.lora_scale, X.P.skinny_bwd);
   }
-  X.gemm_bf16(GEMM_NN, dy, N, W.t(w_id), K, dx, K, (int)X.T, K, N, 1.f, f.n ? ud : nullptr, nr, f.n ? W.t(f.a_id[0]) : nullptr,
-              K, f.n ? nr : 0);
+  if (sw_gu)
+    X.gemm_bf16(GEMM_NN, dy, N, W.t(w_id), K, sw_dgu, 2 * K, (int)X.T, K, N, 1.f, f.n ? ud : nullptr, nr,
+                f.n ? W.t(f.a_id[0]) : nullptr, K, f.n ? nr : 0, sw_gu, 2 * K, EPI_SWIGLU_BWD);
+  else
+    X.gemm_bf16(GEMM_NN, dy, N, W.t(w_id), K, dx, K, (int)X.T, K, N, 1.f, f.n ? ud : nullptr, nr, f.n ? W.t(f.a_id[0]) : nullptr,
+                K, f.n ? nr : 0);
   X.gemm_wgrad(dy, N, x, K, G.t(w_id), K, N, K, (int)X.T);
   if (f.n) {
     // the adapted A matrices are adjacent in both blobs, so one product fills all of them
@@ -387,9 +394,9 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
     }
   } else {
     // z = y + down(act)
+    // the SwiGLU backward rides in the epilogue of the down projection's input-gradient GEMM
     linear_bwd(X, W, G, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, dz, D.h, S(b.act), D.m,
-               X.at<void>(X.P.dact), S(b.u4));
-    RUN(X, "swiglu_bwd", 0, 10.0 * Td * D.m, k_swiglu_bwd(X.st, X.at<void>(X.P.dact), S(b.gu), X.at<void>(X.P.dgu), T, D.m));
+               nullptr, S(b.u4), S(b.gu), X.at<void>(X.P.dgu));
     linear_bwd(X, W, G, RP_T_WGU, fused_gu(D), X.P.bd3, X.at<void>(X.P.dgu), 2 * D.m, S(b.n2), D.h, X.at<void>(X.P.dn), S(b.u3));
   }
   RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
