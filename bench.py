@@ -148,10 +148,7 @@ def main():
 
     def step(slot=0):
         if has_head:
-            R.recompute(x, out, slot)
-            loss, dy = R.head(out, labels, 1.0, slot, loss=loss_buf, dx=dy_head)
-            R.backward_only(x, dy, dx, slot)
-            return loss
+            return R.fused_last_stage(x, labels, out, dy_head, dx, loss_buf, 1.0, slot)
         B.rp_stage_backward(R.ctx, slot, B.PHASE_BOTH, x, dy_in, dx, out, R.grads if R.gbytes else None, router, d_router,
                             R.batch, R.seq, R.ws, R.wsbytes)
         return None

@@ -79,6 +79,12 @@ typedef struct {
   int32_t train_base;  /* 1: base weights and norm gains receive fp32 gradients; 0: frozen */
   int32_t moe_router;  /* MoE only.  1: the layer chunk holds the router Wr [E, h] and the stage computes the router
                           logits n2 Wr^T itself (fp32);  0: the caller supplies the logits */
+  int32_t head_chunk;  /* vocabulary rows per pass of the LM head (the logits of one pass are the largest buffer of its
+                          workspace); 0 = automatic (32768, or 16384 for more than 4096 tokens), else a multiple of 256.
+                          Enters rp_query_sizes like every other field. */
+  int32_t head_two_sweeps; /* 0: a frozen head (train_base = 0) makes one sweep over the vocabulary; 1: it runs the
+                          two-sweep schedule of a trainable head (statistics, then gradients) -- same results, for
+                          comparison runs */
 } rp_stage_cfg;
 
 /* Tensor ids inside one layer's chunk of the weight blob (and of the gradient blob). */

@@ -17,10 +17,15 @@ extern "C" {
  * (A2, B2, K2): optional second operand pair, same layout, appended to the reduction (LoRA up-projection).
  * K, K2 and all leading dimensions are multiples of 8; N (and M for layout 2) too when that operand is transposed.
  * tile 0 = automatic, 1..4 force 256x256, 256x128, 128x128, 128x64; 5 = 256x128 worked on by two wave groups that
- * split every K tile (for outputs too small to fill the chip with 256x256 tiles). */
+ * split every K tile (for outputs too small to fill the chip with 256x256 tiles).
+ * split_ws [dev, split_ws_bytes] or NULL: scratch for a reduction split.  An accumulating fp32 product (out_f32 1 with
+ * beta) whose 256x256 tiles would leave most compute units idle is cut into up to 16 slices along K when the scratch
+ * holds slices * M * N floats; the slices' partial products are added to C in slice order by a second kernel, so the
+ * result is reproducible run to run (the weight-gradient accumulation of Sec. 4.1.1).  out_f32 3: as 1, but the merged
+ * sum is written to C as bf16 [M, N] (overwritten; needs M * N floats of scratch; one direct pass when nothing splits). */
 RP_API rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const void* B, void* C, int M, int N, int K,
                      long lda, long ldb, long ldc, float alpha, int beta, const void* A2, const void* B2, int K2, long lda2,
-                     long ldb2, const void* R, long ldr, int tile);
+                     long ldb2, const void* R, long ldr, int tile, void* split_ws, size_t split_ws_bytes);
 
 /* RMSNorm: y = x * rstd * g, rstd_t = (mean_j x_tj^2 + eps)^(-1/2); rstd fp32 [T] (may be NULL). */
 RP_API rp_status rp_op_rmsnorm_fwd(void* stream, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps);

@@ -26,7 +26,7 @@ class StageCfg(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32),
                 ("n_experts", C.c_int32), ("top_k", C.c_int32), ("rope_base", C.c_float), ("rms_eps", C.c_float),
                 ("qk_norm", C.c_int32), ("lora_rank", C.c_int32), ("lora_scale", C.c_float), ("lora_mask", C.c_uint32),
-                ("train_base", C.c_int32), ("moe_router", C.c_int32)]
+                ("train_base", C.c_int32), ("moe_router", C.c_int32), ("head_chunk", C.c_int32), ("head_two_sweeps", C.c_int32)]
 
 
 class Piece(C.Structure):
@@ -92,7 +92,7 @@ _SIGS = {
     "rp_round_backward": [_vp, _i, C.POINTER(RoundIO), _vp, _i, _i, _vp, _sz],
     "rp_trace_start": [_vp, _i],
     "rp_trace_stop": [_vp, C.POINTER(TraceRecord), _i, C.POINTER(_i)],
-    "rp_op_gemm": [_vp, _i, _i, _vp, _vp, _vp, _i, _i, _i, _l, _l, _l, _f, _i, _vp, _vp, _i, _l, _l, _vp, _l, _i],
+    "rp_op_gemm": [_vp, _i, _i, _vp, _vp, _vp, _i, _i, _i, _l, _l, _l, _f, _i, _vp, _vp, _i, _l, _l, _vp, _l, _i, _vp, _sz],
     "rp_op_rmsnorm_fwd": [_vp, _vp, _vp, _vp, _vp, _i, _i, _f],
     "rp_op_rmsnorm_bwd": [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i],
     "rp_op_rope_table": [_vp, _vp, _i, _i, _f],
@@ -130,13 +130,14 @@ def _check(code, ctx=None):
 
 
 def make_cfg(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab=0, n_experts=0, top_k=0, rope_base=1.0e6,
-             rms_eps=1.0e-6, qk_norm=1, lora_rank=0, lora_scale=1.0, lora=(), train_base=1, moe_router=0):
+             rms_eps=1.0e-6, qk_norm=1, lora_rank=0, lora_scale=1.0, lora=(), train_base=1, moe_router=0, head_chunk=0,
+             head_two_sweeps=0):
     mask = 0
     for name in lora:
         mask |= LORA_BITS[name]
     return StageCfg(C.sizeof(StageCfg), n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, n_experts, top_k,
                     rope_base, rms_eps, int(qk_norm), lora_rank, lora_scale, mask if lora_rank > 0 else 0, int(train_base),
-                    int(moe_router))
+                    int(moe_router), int(head_chunk), int(head_two_sweeps))
 
 
 # ---- rp.h ---------------------------------------------------------------------------------------------------------
@@ -284,9 +285,10 @@ def rp_trace_stop(ctx, cap):
 
 
 def rp_op_gemm(stream, layout, out_f32, A, B, Cm, M, N, K, lda, ldb, ldc, alpha=1.0, beta=0, A2=None, B2=None, K2=0,
-               lda2=0, ldb2=0, R=None, ldr=0, tile=0):
+               lda2=0, ldb2=0, R=None, ldr=0, tile=0, split_ws=None):
     _check(lib.rp_op_gemm(stream, layout, out_f32, _ptr(A), _ptr(B), _ptr(Cm), M, N, K, lda, ldb, ldc, alpha, beta,
-                          _ptr(A2), _ptr(B2), K2, lda2, ldb2, _ptr(R), ldr, tile))
+                          _ptr(A2), _ptr(B2), K2, lda2, ldb2, _ptr(R), ldr, tile, _ptr(split_ws),
+                          split_ws.numel() * split_ws.element_size() if split_ws is not None else 0))
 
 
 def rp_op_rmsnorm_fwd(stream, x, g, y, rstd, T_, h, eps):

@@ -200,11 +200,8 @@ __global__ void __launch_bounds__(512) qknorm_rope_kernel(const bf16* __restrict
                                                           long ld_raw, float* __restrict__ part,
                                                           const float2* __restrict__ cs, int T, int seq, int a, int k,
                                                           int use_norm, float eps) {
-  __shared__ float dg_s[2 * D];
-  if (BWD && part) {
-    for (int i = threadIdx.x; i < 2 * D; i += (int)blockDim.x) dg_s[i] = 0.f;
-    __syncthreads();
-  }
+  constexpr int MAXW = 8;             // waves per block the gain-gradient merge is sized for
+  __shared__ float dg_s[BWD ? MAXW : 1][2 * D];
   constexpr int LPH = D / 8;          // lanes per head
   constexpr int HPW = 64 / LPH;       // heads per wave pass
   const int lane = threadIdx.x & 63;
@@ -307,16 +304,23 @@ __global__ void __launch_bounds__(512) qknorm_rope_kernel(const bf16* __restrict
   }
   if constexpr (BWD) {
     if (use_norm && part) {
-      // lanes with the same `sub` hold partial sums for the same 8 gain entries; waves merge in LDS, blocks via part[]
+      // lanes with the same `sub` hold partial sums for the same 8 gain entries; every wave leaves its sums in a row
+      // of its own, the rows are added in wave order (no atomics: the result does not depend on timing), blocks merge
+      // via part[]
+      const int wv = threadIdx.x >> 6, nwv = (int)blockDim.x >> 6;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float vq = dgq_acc[e], vk = dgk_acc[e];
 #pragma unroll
         for (int o = LPH; o < 64; o <<= 1) { vq += __shfl_xor(vq, o, 64); vk += __shfl_xor(vk, o, 64); }
-        if (hsel == 0) { atomicAdd(dg_s + sub * 8 + e, vq); atomicAdd(dg_s + D + sub * 8 + e, vk); }
+        if (hsel == 0) { dg_s[wv][sub * 8 + e] = vq; dg_s[wv][D + sub * 8 + e] = vk; }
       }
       __syncthreads();
-      for (int i = threadIdx.x; i < 2 * D; i += (int)blockDim.x) part[(long)blockIdx.x * 2 * D + i] = dg_s[i];
+      for (int i = threadIdx.x; i < 2 * D; i += (int)blockDim.x) {
+        float t = dg_s[0][i];
+        for (int k2 = 1; k2 < nwv; ++k2) t += dg_s[k2][i];
+        part[(long)blockIdx.x * 2 * D + i] = t;
+      }
     }
   }
 }

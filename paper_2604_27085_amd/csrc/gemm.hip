@@ -327,22 +327,29 @@ hipError_t launch_tile(hipStream_t st, const GemmArgs& a, int tile) {
   }
 }
 
-int env_splitk() {
-  static int v = -1;
-  if (v < 0) {
-    const char* s = getenv("RP_GEMM_SPLITK");
-    v = s ? atoi(s) : 1;
+// Merge of a reduction split: C (+)= sum over the slices, added in slice order (one thread per four columns).
+template <bool OUT_BF16>
+__global__ void __launch_bounds__(256) splitk_merge_kernel(const float* __restrict__ ws, int splits, long slice_stride,
+                                                           void* __restrict__ Cout, long ldc, int M, int N, int beta) {
+  const int n4 = N >> 2;
+  const long total = (long)M * n4;
+  for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
+    const long row = idx / n4;
+    const int c = (int)(idx - row * n4) * 4;
+    const float* src = ws + row * N + c;
+    float4 acc = *reinterpret_cast<const float4*>(src);
+    for (int s = 1; s < splits; ++s) {
+      const float4 v = *reinterpret_cast<const float4*>(src + (long)s * slice_stride);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    if constexpr (OUT_BF16) {
+      *reinterpret_cast<uint2*>(reinterpret_cast<bf16*>(Cout) + row * ldc + c) = make_uint2(pack_bf16x2(acc.x, acc.y), pack_bf16x2(acc.z, acc.w));
+    } else {
+      float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(Cout) + row * ldc + c);
+      if (beta) { const float4 o = *dst; acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w; }
+      *dst = acc;
+    }
   }
-  return v;
-}
-
-int env_tile() {
-  static int v = -1;
-  if (v < 0) {
-    const char* s = getenv("RP_GEMM_TILE");
-    v = s ? atoi(s) : 0;
-  }
-  return v;
 }
 
 // Picks the tile with the smallest modelled time: n = workgroups on the busiest CU, each costing its area divided by
@@ -389,8 +396,9 @@ int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
   if (tile_hint) return tile_hint;
   // the eight-wave 256x128 tile is used for the plain epilogues
   const bool plain = a.epi == EPI_BF16 || a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC;
-  const int atomic_nk = (a.epi == EPI_F32 && a.beta && env_splitk()) ? (a.K + 63) / 64 + (a.K2 + 63) / 64 : 0;
-  return env_tile() ? env_tile() : choose_tile(a.M, a.N, plain, atomic_nk);
+  const bool can_split = a.epi == EPI_F32 && (a.beta || a.split_out_bf16) && a.split_ws;
+  const int atomic_nk = can_split ? (a.K + 63) / 64 + (a.K2 + 63) / 64 : 0;
+  return choose_tile(a.M, a.N, plain, atomic_nk);
 }
 
 hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int tile_hint) {
@@ -423,10 +431,14 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
       if (a.bytesA == ~0u || a.row_map_rows <= 0) return hipErrorInvalidValue;
     }
   }
-  // Reduction split: only for outputs that accumulate in fp32 (the merge is an atomic add), when the 256x256 tiling
-  // would leave at least half of the CUs without work and every slice still gets a long K loop.
+  // Reduction split: only for outputs that accumulate in fp32 (or skinny products merged into bf16) and only when the
+  // caller gave scratch memory for the slices' partial products, when the 256x256 tiling would leave at least half of
+  // the CUs without work and every slice still gets a long K loop.  The slices are added in a fixed order by a second
+  // kernel: results are reproducible run to run.
   a.splits = 1;
-  if ((tile == 1 || tile == 5) && a.epi == EPI_F32 && a.beta && env_splitk()) {
+  a.c_slice_stride = 0;
+  if (a.split_out_bf16 && (a.epi != EPI_F32 || !a.split_ws || a.ldc % 4 || (size_t)a.M * a.N * 4 > a.split_ws_bytes)) return hipErrorInvalidValue;
+  if ((tile == 1 || tile == 5) && a.epi == EPI_F32 && (a.beta || a.split_out_bf16) && a.split_ws) {
     const int bn = tile == 1 ? 256 : 128;
     const long tiles = (long)((a.M + 255) / 256) * ((a.N + bn - 1) / bn);
     const int nk = (a.K + 63) / 64 + (a.K2 + 63) / 64;
@@ -437,11 +449,29 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
     const int min_slice = skinny ? 4 : 16;
     while (sp > 1 && nk / sp < min_slice) --sp;
     if (sp > (skinny ? 16 : 8)) sp = skinny ? 16 : 8;
-    if (sp > 1) { a.splits = sp; a.epi = EPI_F32_ATOMIC; }
+    while (sp > 1 && (size_t)sp * a.M * a.N * 4 > a.split_ws_bytes) --sp;
+    a.splits = sp;
   }
+  if (a.split_out_bf16 && a.splits == 1) { a.epi = EPI_BF16; a.split_out_bf16 = 0; }   // nothing to merge: one direct pass
+  void* const C_final = a.C;
+  const long ldc_final = a.ldc;
+  const int beta_final = a.beta;
+  const bool merged = a.splits > 1;
+  if (merged) {   // the slices write fp32 partials [slice][M][N]
+    a.C = a.split_ws; a.ldc = a.N; a.beta = 0; a.c_slice_stride = (long)a.M * a.N;
+  }
+  hipError_t e;
   switch (layout) {
-    case GEMM_NT: return launch_tile<false, false>(st, a, tile);
-    case GEMM_NN: return launch_tile<false, true>(st, a, tile);
-    default: return launch_tile<true, true>(st, a, tile);
+    case GEMM_NT: e = launch_tile<false, false>(st, a, tile); break;
+    case GEMM_NN: e = launch_tile<false, true>(st, a, tile); break;
+    default: e = launch_tile<true, true>(st, a, tile); break;
   }
+  if (e != hipSuccess || !merged) return e;
+  const long quads = (long)a.M * (a.N / 4);
+  const int grid = (int)((quads + 255) / 256 < 4096 ? (quads + 255) / 256 : 4096);
+  if (a.split_out_bf16)
+    RP_LAUNCH(splitk_merge_kernel<true>, dim3(grid), dim3(256), 0, st, a.split_ws, a.splits, a.c_slice_stride, C_final, ldc_final, a.M, a.N, 0);
+  else
+    RP_LAUNCH(splitk_merge_kernel<false>, dim3(grid), dim3(256), 0, st, a.split_ws, a.splits, a.c_slice_stride, C_final, ldc_final, a.M, a.N, beta_final);
+  return hipGetLastError();
 }

@@ -49,7 +49,16 @@ struct GemmArgs {
   int row_map_rows;            // rows of the A buffer that row_map indexes
   int splits;                  // reduction slices (grid.y), chosen by gemm_launch
   int part_row0;               // first partial row this launch writes (2 per M tile)
+  // Reduction split (EPI_F32 with beta): with a scratch buffer of at least splits * M * N floats the slices write
+  // their partial products there ([slice][M][N]) and a second kernel adds them to C in slice order, so the result does
+  // not depend on scheduling.  Without the buffer the GEMM is not split.  out_bf16: the merged sum is written to C
+  // as bf16 (overwritten, not accumulated) -- the skinny LoRA projections.
+  float* split_ws; size_t split_ws_bytes; int split_out_bf16;
+  long c_slice_stride;         // set by gemm_launch: elements between the partial outputs of consecutive slices
 };
+
+// Scratch that lets every reduction split gemm_launch would choose go ahead: splits * tiles <= 256 tiles of 256 x 256.
+#define RP_SPLITK_WS_BYTES ((size_t)64 << 20)
 
 // Enqueues one GEMM.  Returns hipSuccess or the launch error.  tile_hint: 0 = choose automatically.
 hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a, int tile_hint = 0);

@@ -317,7 +317,7 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
 #pragma unroll
       for (int t0 = 0; t0 < WAVE_M / 8; t0 += NB) {
         if (p.epi != EPI_BF16) {
-          float* const Cf = reinterpret_cast<float*>(p.C);
+          float* const Cf = reinterpret_cast<float*>(p.C) + (long)blockIdx.y * p.c_slice_stride;   // slice of a reduction split
           float4 o[NB];
           if (p.beta) {
 #pragma unroll

@@ -70,8 +70,9 @@ hipError_t k_moe_dlogits(hipStream_t st, const int* idx, const float* w, const i
 hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, float* lse, int T);
 // Frozen head, one sweep over the vocabulary: per chunk, z [vc, T] fp32 -> p = exp(z - m_t) [vc, T] bf16 against the
 // per-token reference exponent m (moved, with l rescaled and alpha set, when the chunk outgrows it by more than e^8),
-// l += row sums.  pmax [nparts][T]: the chunk's per-column maxima (.x), as the logits GEMM left them.
-hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, const float2* pmax, int nparts, int first, float* m,
+// l += row sums.  pmax [nparts][T]: the chunk's per-column maxima (.x), as the logits GEMM left them, one row per 128
+// vocabulary rows; the .y halves are overwritten (per-block row sums, added to l in row order: no atomics).
+hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, float2* pmax, int nparts, int first, float* m,
                              float* l, float* alpha, void* p);
 // acc[t, :] *= alpha[t] where alpha[t] != 1.
 hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int T, int h);

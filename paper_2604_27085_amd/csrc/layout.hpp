@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include "../../include/rp.h"
 #include "kernels.hpp"   // RP_PARTIAL_BLOCKS
+#include "gemm.hpp"      // RP_SPLITK_WS_BYTES
 
 namespace rp {
 
@@ -106,7 +107,7 @@ struct Plan {
   size_t moe_wslot, moe_dw;      // routing weight per slot, its gradient per slot (backward)
   size_t moe_dlog, moe_dlog16;   // router in the stage: gradient of the logits fp32 [T, E] and its bf16 copy
   int moe_max_tiles;             // capacity of the tile table
-  size_t skinny_fwd, skinny_bwd;   // fp32 [T, 3r]: a skinny LoRA product before its conversion to bf16
+  size_t split_fwd, split_bwd, h_split;   // partial products of a GEMM reduction split (RP_SPLITK_WS_BYTES each), per plan
   size_t dkvp;   // per-query-head dK/dV partials of grouped attention; shares memory with dact|dgu, dead by then
   size_t fwd_bytes, bwd_bytes;
   // head
@@ -153,8 +154,8 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
     size_t f = o + set;
     f = align_up(f + T * D.h * 2, 256);
     if (D.E > 0) { P.moe_f_fwd = f; f = align_up(f + Tk * D.h * 2, 256); }
-    P.skinny_fwd = f;
-    f = align_up(f + T * (size_t)(3 * D.r) * 4, 256);
+    P.split_fwd = f;
+    if (D.r > 0) f = align_up(f + RP_SPLITK_WS_BYTES, 256);   // only the skinny LoRA products split in a forward stage
     P.fwd_bytes = f;
   }
   o += set * (size_t)(D.L > 0 ? D.L : 0);
@@ -166,22 +167,23 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   P.dn = take(T * D.h * 2); P.dout = take(T * D.qd * 2); P.dqr = take(T * D.qd * 2); P.dkr = take(T * D.kd * 2);
   P.dqkv = take(T * D.n1 * 2); P.delta = take(T * D.a * 4);
   P.ud = take(T * (size_t)(3 * D.r) * 2);
-  P.skinny_bwd = take(T * (size_t)(3 * D.r) * 4);
+  P.split_bwd = take(RP_SPLITK_WS_BYTES);
   P.partials = take((size_t)RP_PARTIAL_BLOCKS * (size_t)(D.h > 2 * D.d ? D.h : 2 * D.d) * 4);
   P.bwd_bytes = o;
   // head
   o = 0;
   if (D.V > 0) {
-    // vocabulary rows per pass: 32768 while the transposed dZ chunk stays within 2^27 elements, else 16384
-    // (RP_HEAD_CHUNK, a multiple of 256, overrides: the tests use it to put several chunks into a small vocabulary)
+    // vocabulary rows per pass: 32768 while the transposed dZ chunk stays within 2^27 elements, else 16384, unless the
+    // configuration fixes it (the tests use that to put several chunks into a small vocabulary)
     P.head_chunk = (T * 32768 <= ((size_t)1 << 27)) ? 32768 : 16384;
-    if (const char* e = getenv("RP_HEAD_CHUNK")) { const int v = atoi(e); if (v >= 256 && v % 256 == 0) P.head_chunk = v; }
+    if (c.head_chunk > 0) P.head_chunk = c.head_chunk;
     if (P.head_chunk > D.V) P.head_chunk = (int)align_up(D.V, 8);
     P.head_parts = 2 * ((D.V + 255) / 256);
     P.h_xf = take(T * D.h * 2); P.h_rstd = take(T * 4); P.h_part = take((size_t)P.head_parts * T * 8);
     P.h_zlab = take(T * 4); P.h_lse = take(T * 4); P.h_coef = take(T * 4);
     P.h_dzt = take((size_t)P.head_chunk * T * 2); P.h_dxacc = take(T * D.h * 4);
     P.h_partials = take((size_t)RP_PARTIAL_BLOCKS * D.h * 4);
+    P.h_split = take(RP_SPLITK_WS_BYTES);
     if (!c.train_base) {
       P.h_z = take((size_t)P.head_chunk * T * 4);
       P.h_m = take(T * 4); P.h_l = take(T * 4); P.h_alpha = take(T * 4);

@@ -93,10 +93,13 @@ __global__ void __launch_bounds__(256) ce_chunk_ref_kernel(const float2* __restr
   }
 }
 
-// p[r][t] = exp(z[r][t] - m[t]) as bf16, l[t] += the fp32 sum over the block's rows.  Two tokens per thread.
+// p[r][t] = exp(z[r][t] - m[t]) as bf16; the fp32 sum over the block's CE_PROB_ROWS rows goes to the .y half of the
+// block's row of the partial array (whose .x half holds the column maxima the logits GEMM left there, one row of
+// partials per CE_PROB_ROWS vocabulary rows): no atomics, ce_chunk_sum_kernel adds the rows in order.  Two tokens per
+// thread.
 __global__ void __launch_bounds__(256) ce_chunk_prob_kernel(const float* __restrict__ z, int vc, int T,
                                                             const float* __restrict__ m, bf16* __restrict__ p,
-                                                            float* __restrict__ l) {
+                                                            float2* __restrict__ part) {
   const int t = (blockIdx.x * 256 + threadIdx.x) * 2;
   if (t >= T) return;
   const int r0 = blockIdx.y * CE_PROB_ROWS, r1 = min(r0 + CE_PROB_ROWS, vc);
@@ -120,8 +123,22 @@ __global__ void __launch_bounds__(256) ce_chunk_prob_kernel(const float* __restr
     s0 += p0; s1 += p1;
     *reinterpret_cast<uint32_t*>(p + (long)r * T + t) = pack_bf16x2(p0, p1);
   }
-  atomicAdd(l + t, s0);
-  atomicAdd(l + t + 1, s1);
+  part[(long)blockIdx.y * T + t].y = s0;
+  part[(long)blockIdx.y * T + t + 1].y = s1;
+}
+
+// l[t] += sum over the chunk's partial rows of part[i][t].y, in row order.
+__global__ void __launch_bounds__(256) ce_chunk_sum_kernel(const float2* __restrict__ part, int nslab, int T, float* __restrict__ l) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;   // four chains, merged in a fixed order
+  int i = 0;
+  for (; i + 4 <= nslab; i += 4) {
+    s0 += part[(long)i * T + t].y; s1 += part[(long)(i + 1) * T + t].y;
+    s2 += part[(long)(i + 2) * T + t].y; s3 += part[(long)(i + 3) * T + t].y;
+  }
+  for (; i < nslab; ++i) s0 += part[(long)i * T + t].y;
+  l[t] += (s0 + s1) + (s2 + s3);
 }
 
 // acc[t, :] *= alpha[t] for the rows whose reference moved.  One wave per row.
@@ -167,13 +184,14 @@ __global__ void __launch_bounds__(256) ce_frozen_dx_kernel(float* __restrict__ a
 
 }  // namespace
 
-hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, const float2* pmax, int nparts, int first, float* m,
+hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, float2* pmax, int nparts, int first, float* m,
                              float* l, float* alpha, void* p) {
   if (T == 0 || vc == 0) return hipSuccess;
-  if (T % 2) return hipErrorInvalidValue;
-  RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, pmax, nparts, T, first, m, l, alpha);
-  RP_LAUNCH(ce_chunk_prob_kernel, dim3((T / 2 + 255) / 256, (vc + CE_PROB_ROWS - 1) / CE_PROB_ROWS), dim3(256), 0, st, z, vc, T,
-            (const float*)m, (bf16*)p, l);
+  const int nblk = (vc + CE_PROB_ROWS - 1) / CE_PROB_ROWS;
+  if (T % 2 || nblk > nparts) return hipErrorInvalidValue;   // one partial row per CE_PROB_ROWS vocabulary rows
+  RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float2*)pmax, nparts, T, first, m, l, alpha);
+  RP_LAUNCH(ce_chunk_prob_kernel, dim3((T / 2 + 255) / 256, nblk), dim3(256), 0, st, z, vc, T, (const float*)m, (bf16*)p, pmax);
+  RP_LAUNCH(ce_chunk_sum_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float2*)pmax, nblk, T, l);
   return hipGetLastError();
 }
 

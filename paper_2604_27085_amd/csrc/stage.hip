@@ -86,6 +86,8 @@ rp_status validate_cfg(const rp_stage_cfg* c, rp_ctx* ctx) {
   if (c->n_layers < 0 || c->vocab < 0 || (c->n_layers == 0 && c->vocab == 0)) return fail(ctx, RP_EINVAL, "stage has neither layers nor a head");
   if (c->hidden <= 0 || c->hidden % 8 || c->hidden > 8192) return fail(ctx, RP_EUNSUPPORTED, "hidden must be a multiple of 8 in (0, 8192]");
   if (c->vocab % 8) return fail(ctx, RP_EUNSUPPORTED, "vocab must be a multiple of 8");
+  if (c->head_chunk < 0 || c->head_chunk % 256) return fail(ctx, RP_EINVAL, "head_chunk must be 0 or a positive multiple of 256");
+  if (c->head_two_sweeps != 0 && c->head_two_sweeps != 1) return fail(ctx, RP_EINVAL, "head_two_sweeps must be 0 or 1");
   if (c->n_layers > 0) {
     if (c->head_dim != 64 && c->head_dim != 128) return fail(ctx, RP_EUNSUPPORTED, "head_dim must be 64 or 128");
     if (c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads) return fail(ctx, RP_EINVAL, "n_q_heads must be a positive multiple of n_kv_heads");
@@ -134,6 +136,8 @@ struct Exec {
   hipError_t err = hipSuccess;
   const char* where = "";
   bool fwd_only = false;           // the forward-stage plan of the workspace is in use (rp_stage_forward)
+  size_t split_off = 0;            // scratch for the partial products of a GEMM reduction split, in the plan in use
+  bool has_split = false;
   float* router = nullptr;         // router logits of the layer being run, fp32 [T, E] (mixture of experts): read, or
                                    // written first when the stage holds the router weights
   float* d_router = nullptr;       // their gradient (optional)
@@ -161,6 +165,9 @@ struct Exec {
              (g.R ? (g.epi == EPI_SWIGLU_BWD ? 4.0 : 2.0) * g.M * (double)g.N : 0.0));
   }
   template <typename Tp> Tp* at(size_t off) const { return reinterpret_cast<Tp*>(ws + off); }
+  void give_split_ws(GemmArgs& g) const {
+    if (has_split) { g.split_ws = at<float>(split_off); g.split_ws_bytes = RP_SPLITK_WS_BYTES; }
+  }
 
   // C[M,N] (bf16) = alpha * A * op(B) (+ second pair) (+ R)
   void gemm_bf16(int layout, const void* A, long lda, const void* B, long ldb, void* C, long ldc, int M, int N, int K,
@@ -174,19 +181,14 @@ struct Exec {
   }
   // C[M,N] (bf16) = alpha * A * op(B) for a skinny N (the LoRA down-projections, N = a few ranks): the product is bound by
   // reading A once, and with so few output tiles only a reduction split puts enough workgroups on the chip.  The
-  // slices add into a zeroed fp32 buffer (tmp32, [M, N]), which is then converted.
-  void gemm_skinny_bf16(int layout, const void* A, long lda, const void* B, long ldb, void* C, int M, int N, int K, float alpha,
-                        size_t tmp32_off) {
-    float* tmp = at<float>(tmp32_off);
-    mark("fill", 0, 4.0 * M * N);
-    chk(k_fill_u32(st, tmp, (long)M * N, 0u), "fill");
+  // slices write fp32 partial products that are added in slice order and converted by the merge kernel.
+  void gemm_skinny_bf16(int layout, const void* A, long lda, const void* B, long ldb, void* C, int M, int N, int K, float alpha) {
     GemmArgs g; gemm_zero_args(g);
-    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = tmp; g.ldc = N; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
-    g.beta = 1; g.epi = EPI_F32;
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = N; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
+    g.epi = EPI_BF16;
+    if (has_split && (size_t)M * N * 4 <= RP_SPLITK_WS_BYTES) { g.epi = EPI_F32; g.split_out_bf16 = 1; give_split_ws(g); }
     mark_gemm(layout, g);
     chk(gemm_launch(st, layout, g), "gemm_skinny");
-    mark("cast", 0, 6.0 * M * N);
-    chk(k_cast_f32_bf16(st, tmp, C, (long)M * N), "cast");
   }
   // Grouped GEMM over expert-sorted slot rows: C[slot, N] = A[row_map ? row_map[slot] : slot, K] * op(B_e), B_e the
   // matrix of the expert that owns the slot.  set = the layer's saved internals (routing plan).
@@ -220,6 +222,7 @@ struct Exec {
     if (!C) return;
     GemmArgs g; gemm_zero_args(g);
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.beta = 1; g.epi = EPI_F32;
+    give_split_ws(g);
     mark_gemm(GEMM_TN, g);
     chk(gemm_launch(st, GEMM_TN, g), "gemm_wgrad");
   }
@@ -266,12 +269,11 @@ const void* lora_b_matrix(Exec& X, const LayerW& W, const FusedLora& f, int N, s
 // Y[T,N] = X W^T (+ LoRA) (+ R).  u_buf receives U = s * X A^T (kept for the backward).
 void linear_fwd(Exec& X, const LayerW& W, int w_id, const FusedLora& f, size_t bd_off, const void* x, int K, void* y,
                 int N, void* u_buf, const void* R) {
-  const size_t skinny_off = X.fwd_only ? X.P.skinny_fwd : X.P.skinny_bwd;
   const int nr = f.n * X.D.r;
   const void* Bm = nullptr;
   if (f.n) {
     Bm = lora_b_matrix(X, W, f, N, bd_off);
-    X.gemm_skinny_bf16(GEMM_NT, x, K, W.t(f.a_id[0]), K, u_buf, (int)X.T, nr, K, X.ctx->cfg.lora_scale, skinny_off);
+    X.gemm_skinny_bf16(GEMM_NT, x, K, W.t(f.a_id[0]), K, u_buf, (int)X.T, nr, K, X.ctx->cfg.lora_scale);
   }
   X.gemm_bf16(GEMM_NT, x, K, W.t(w_id), K, y, N, (int)X.T, N, K, 1.f, f.n ? u_buf : nullptr, nr, Bm, nr, f.n ? nr : 0, R, N);
 }
@@ -286,7 +288,7 @@ void linear_bwd(Exec& X, const LayerW& W, const LayerG& G, int w_id, const Fused
   const void* Bm = nullptr;
   if (f.n) {
     Bm = lora_b_matrix(X, W, f, N, bd_off);
-    X.gemm_skinny_bf16(GEMM_NN, dy, N, Bm, nr, ud, (int)X.T, nr, N, X.ctx->cfg.lora_scale, X.P.skinny_bwd);
+    X.gemm_skinny_bf16(GEMM_NN, dy, N, Bm, nr, ud, (int)X.T, nr, N, X.ctx->cfg.lora_scale);
   }
   if (sw_gu)
     X.gemm_bf16(GEMM_NN, dy, N, W.t(w_id), K, sw_dgu, 2 * K, (int)X.T, K, N, 1.f, f.n ? ud : nullptr, nr,
@@ -427,13 +429,6 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
   linear_bwd(X, W, G, RP_T_WQKV, fused_qkv(D), X.P.bd1, dqkv, D.n1, S(b.n1), D.h, X.at<void>(X.P.dn), S(b.u1));
   RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
       k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, x, W.t(RP_T_G1), (const float*)S(b.rstd1), dy, dx_out, G.t(RP_T_G1), X.at<float>(X.P.partials), T, D.h));
-}
-
-// RP_HEAD_ONE_SWEEP=0 keeps the two-sweep schedule for a frozen head as well (comparison runs)
-bool env_head_one_sweep() {
-  static int v = -1;
-  if (v < 0) { const char* e = getenv("RP_HEAD_ONE_SWEEP"); v = e ? atoi(e) != 0 : 1; }
-  return v != 0;
 }
 
 rp_status check_call(rp_ctx* ctx, int slot_id, int batch, int seq, const void* ws, size_t ws_bytes, size_t need) {
@@ -598,6 +593,7 @@ rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_o
   Slot& sl = ctx->slots[slot_id];
   Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
   X.fwd_only = true;
+  X.split_off = P.split_fwd; X.has_split = X.D.r > 0;
   const int L = ctx->cfg.n_layers;
   const size_t act_bytes = (size_t)X.T * X.D.h * 2;
   RUN(X, "rope_table", 0, 4.0 * seq * X.D.d, k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base));
@@ -636,18 +632,18 @@ rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_
   }
   Slot& sl = ctx->slots[slot_id];
   Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
+  X.split_off = P.split_bwd; X.has_split = true;
   const int L = ctx->cfg.n_layers;
   const size_t act_bytes = (size_t)X.T * X.D.h * 2;
   if (do_fwd) RUN(X, "rope_table", 0, 4.0 * seq * X.D.d, k_rope_table(X.st, X.at<float2>(P.rope), seq, X.D.d, ctx->cfg.rope_base));
   auto set_of = [&](int l) { return X.ws + P.layer0 + P.layer_stride * (size_t)l; };
-  for (int l = 0; l < L; ++l) {   // both phases read the weights
-    s = wait_chunk(ctx, sl, l);
-    if (s != RP_OK) return s;
-  }
   if (do_fwd) {
-    // recomputation: forward over the stage keeping every layer's internals
+    // recomputation: forward over the stage keeping every layer's internals; layer l starts as soon as its own chunk
+    // of the upload has landed (per-layer events, Sec. 4.3), so the recomputation overlaps the tail of the upload
     const void* x = x_in;
     for (int l = 0; l < L; ++l) {
+      s = wait_chunk(ctx, sl, l);
+      if (s != RP_OK) return s;
       const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
       void* z = set_of(l) + P.lb.z;
       if (router_logits) X.router = router_logits + (size_t)l * X.T * X.D.E;
@@ -659,6 +655,10 @@ rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_
   // backward in reverse layer order
   const void* dz = dy;
   for (int l = L - 1; do_bwd && l >= 0; --l) {
+    if (!do_fwd) {   // the backward phase alone: wait per layer, in the order the layers are run
+      s = wait_chunk(ctx, sl, l);
+      if (s != RP_OK) return s;
+    }
     const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
     const LayerG G{grads ? static_cast<char*>(grads) + ctx->gl.layer_bytes * (size_t)l : nullptr, &ctx->gl};
     const void* xl = l == 0 ? x_in : set_of(l - 1) + P.lb.z;
@@ -681,6 +681,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
   if (dx == x) return fail(ctx, RP_EINVAL, "dx must not alias x");
   Slot& sl = ctx->slots[slot_id];
   Exec X{ctx, ctx->compute, dims_of(ctx->cfg), batch, seq, (long)batch * seq, static_cast<char*>(workspace), P};
+  X.split_off = P.h_split; X.has_split = true;
   const Dims& D = X.D;
   const int T = (int)X.T, L = ctx->cfg.n_layers;
   s = wait_chunk(ctx, sl, L);
@@ -694,7 +695,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
   const double Td = (double)T;
   RUN(X, "rmsnorm_fwd", 0, 4.0 * Td * D.h, k_rmsnorm_fwd(X.st, x, W.t(RP_T_GF), X.at<void>(P.h_xf), X.at<float>(P.h_rstd), T, D.h, ctx->cfg.rms_eps));
   RUN(X, "fill", 0, 4.0 * Td, k_fill_u32(X.st, X.at<void>(P.h_zlab), T, 0u));
-  if (!train && !ctx->cfg.train_base && env_head_one_sweep()) {
+  if (!train && !ctx->cfg.train_base && !ctx->cfg.head_two_sweeps) {
     // Frozen head: without dW the softmax normaliser is only needed at the very end, so one sweep over the vocabulary
     // suffices (two logit-sized products instead of three).  Per chunk: logits (fp32) -> p = exp(z - m_t) against a
     // per-token reference exponent that moves (and rescales what has been accumulated) only when a chunk outgrows it
@@ -718,6 +719,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
       GemmArgs d; gemm_zero_args(d);   // acc[T, h] += p^T^T . W_c
       d.A = X.at<void>(P.h_dzt); d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = acc;
       d.ldc = D.h; d.beta = 1; d.epi = EPI_F32;
+      X.give_split_ws(d);
       X.mark_gemm(GEMM_TN, d);
       X.chk(gemm_launch(X.st, GEMM_TN, d), "lm head dX");
     }
@@ -754,12 +756,14 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
     GemmArgs d; gemm_zero_args(d);   // dXf[T, h] (+)= dZ^T^T . W_c   (reduction over the chunk's vocabulary rows)
     d.A = X.at<void>(P.h_dzt); d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = X.at<void>(P.h_dxacc);
     d.ldc = D.h; d.beta = 1; d.epi = EPI_F32;
+    X.give_split_ws(d);
     X.mark_gemm(GEMM_TN, d);
     X.chk(gemm_launch(X.st, GEMM_TN, d), "lm head dX");
     if (G.t(RP_T_WV)) {
       GemmArgs w; gemm_zero_args(w);  // dW_c[vc, h] += dZ^T . xf
       w.A = X.at<void>(P.h_dzt); w.lda = T; w.B = X.at<void>(P.h_xf); w.ldb = D.h; w.M = vc; w.N = D.h; w.K = T;
       w.C = G.t(RP_T_WV) + (size_t)v0 * D.h; w.ldc = D.h; w.beta = 1; w.epi = EPI_F32;
+      X.give_split_ws(w);
       X.mark_gemm(GEMM_NN, w);
       X.chk(gemm_launch(X.st, GEMM_NN, w), "lm head dW");
     }
@@ -815,7 +819,9 @@ rp_status rp_trace_stop(rp_ctx* ctx, rp_trace_record* out, int cap, int* n_out) 
 
 rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const void* B, void* C, int M, int N, int K,
                      long lda, long ldb, long ldc, float alpha, int beta, const void* A2, const void* B2, int K2, long lda2,
-                     long ldb2, const void* R, long ldr, int tile) {
+                     long ldb2, const void* R, long ldr, int tile, void* split_ws, size_t split_ws_bytes) {
+  if (out_f32 < 0 || out_f32 > 3 || (out_f32 == 3 && !split_ws) || (split_ws && reinterpret_cast<uintptr_t>(split_ws) % 16))
+    return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad out_f32 / split_ws");
   if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 5)
     return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad arguments");
   if ((layout != GEMM_NT) && (N % 8 || (layout == GEMM_TN && M % 8))) return fail(nullptr, RP_EINVAL, "rp_op_gemm: transposed operands need multiples of 8");
@@ -823,6 +829,7 @@ rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const
   g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.alpha = alpha; g.beta = beta;
   g.A2 = A2; g.B2 = B2; g.K2 = (A2 && B2) ? K2 : 0; g.lda2 = lda2; g.ldb2 = ldb2; g.R = R; g.ldr = ldr;
   g.epi = out_f32 == 2 ? EPI_F32_ATOMIC : (out_f32 ? EPI_F32 : EPI_BF16);
+  g.split_ws = static_cast<float*>(split_ws); g.split_ws_bytes = split_ws ? split_ws_bytes : 0; g.split_out_bf16 = out_f32 == 3;
   hipError_t e = gemm_launch(reinterpret_cast<hipStream_t>(stream), layout, g, tile);
   OP_RET(e);
 }

@@ -25,7 +25,8 @@ def cfg_from_dict(c, with_head=None, n_layers=None):
                       vocab=vocab, n_experts=c["n_experts"], top_k=c["top_k"], rope_base=c.get("rope_base", 1.0e6),
                       rms_eps=c.get("rms_eps", 1.0e-6), qk_norm=c.get("qk_norm", 1), lora_rank=c["lora_rank"],
                       lora_scale=c.get("lora_scale", 1.0), lora=c["lora"], train_base=c["train_base"],
-                      moe_router=c.get("moe_router", 0))
+                      moe_router=c.get("moe_router", 0), head_chunk=c.get("head_chunk", 0),
+                      head_two_sweeps=c.get("head_two_sweeps", 0))
 
 
 def _layer_tensors(p, cfg):
@@ -180,6 +181,15 @@ class StageRunner:
         """Second half: backward from the internals the recompute phase left in the workspace."""
         B.rp_stage_backward(self.ctx, slot, B.PHASE_BACKWARD, x, dy, dx, None, self.grads if self.gbytes else None, None,
                             None, self.batch, self.seq, self.ws, self.wsbytes)
+
+    def fused_last_stage(self, x, labels, out, dy_head, dx, loss, grad_scale=1.0, slot=0, train=True):
+        """The fused last stage (paper Sec. 3.2: its forward doubles as the recomputation), as three calls on caller-
+        owned buffers: forward keeping the internals -> LM head + loss on its own workspace (dy_head receives the
+        gradient of the stage output) -> backward from the kept internals.  This is the step bench.py times."""
+        self.recompute(x, out, slot)
+        self.head(out, labels, grad_scale, slot, train=train, loss=loss, dx=dy_head)
+        self.backward_only(x, dy_head, dx, slot)
+        return loss
 
     def head(self, x, labels, grad_scale=1.0, slot=0, train=True, loss=None, dx=None):
         if loss is None:

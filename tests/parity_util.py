@@ -51,7 +51,9 @@ def oracle_chain(c, wl, dtype=np.float64, grad_scale=1.0):
     return res
 
 
-def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True):
+def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True, fused=False):
+    """fused: a stage with a head runs as the fused last stage (recompute -> head on its own workspace -> backward
+    from the kept internals), the call sequence bench.py times, instead of forward stage -> head -> backward stage."""
     import torch
     cfg = harness.cfg_from_dict(c, with_head=wl["head"] is not None)
     R = harness.StageRunner(cfg, c["batch"], c["seq"])
@@ -73,6 +75,18 @@ def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True):
             d_router = torch.full_like(router, float("nan"))
         torch.cuda.synchronize()
         res = {}
+        if fused:
+            assert wl["head"] is not None and c["n_layers"] > 0 and router is None
+            labels = torch.from_numpy(wl["labels"]).to(R.device)
+            out, dy, dx = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+            loss = torch.empty(1, dtype=torch.float32, device=R.device)
+            torch.cuda.synchronize()
+            R.fused_last_stage(x, labels, out, dy, dx, loss, grad_scale, train=bool(c["train_base"]))
+            R.sync()
+            res.update(loss=float(loss.item()), head_dx=harness.to_f32(dy), out=harness.to_f32(out), dx=harness.to_f32(dx))
+            layer_g, head_g = harness.unpack_grads(cfg, R.grads)
+            res.update(grads=layer_g, head_grads=head_g)
+            return res
         if wl["head"] is not None:
             labels = torch.from_numpy(wl["labels"]).to(R.device)
             torch.cuda.synchronize()

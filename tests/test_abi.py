@@ -125,7 +125,7 @@ def test_argument_validation_returns_codes_without_gpu():
     assert B.lib.rp_stage_backward(None, 0, 3, None, None, None, None, None, None, None, 1, 8, None, 0) == B.RP_EINVAL
     assert B.lib.rp_lmhead_ce_fwd_bwd(None, 0, None, None, None, None, None, 1.0, 1, 8, None, 0) == B.RP_EINVAL
     assert B.lib.rp_stage_upload_weights(None, 0, None, None, 0) == B.RP_EINVAL
-    assert B.lib.rp_op_gemm(None, 9, 0, None, None, None, 1, 1, 8, 8, 8, 8, 1.0, 0, None, None, 0, 0, 0, None, 0, 0) == B.RP_EINVAL
+    assert B.lib.rp_op_gemm(None, 9, 0, None, None, None, 1, 1, 8, 8, 8, 8, 1.0, 0, None, None, 0, 0, 0, None, 0, 0, None, 0) == B.RP_EINVAL
 
 
 def test_workspace_covers_paper_activation_formula():

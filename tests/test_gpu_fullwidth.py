@@ -16,7 +16,7 @@ CASES = {
     # Qwen3-8B-shaped layer, LoRA r=16 on all seven projections, frozen base, 4096 tokens
     "c3_width": ("C3", dict(n_layers=1, seq=4096), 3100),
     # Qwen3-32B-shaped layer (a*d = 8192 != h = 5120, FFN 25600) + final norm and LM head with two vocabulary chunks
-    "c4_width": ("C4", dict(n_layers=1, seq=1024, vocab=32768), 3200),
+    "c4_width": ("C4", dict(n_layers=1, seq=1024, vocab=32768, head_chunk=16384), 3200),
     # Qwen3-235B-A22B-shaped MoE layer: 64 query heads on 4 kv heads, experts of 1536, top-8 (of 16 here: the expert
     # count only sets the size of the weights, 128 experts are covered at small width)
     "c5_width": ("C5", dict(seq=512, n_experts=16), 3300),
@@ -33,9 +33,8 @@ def hz():
 
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("name", sorted(CASES))
-def test_full_width_stage_matches_oracle(hz, name, capsys, monkeypatch):
+def test_full_width_stage_matches_oracle(hz, name, capsys):
     base, over, seed = CASES[name]
-    monkeypatch.setenv("RP_HEAD_CHUNK", "16384")     # c4_width: two chunks in a vocabulary of 32768
 
     def say(msg):
         with capsys.disabled():

@@ -110,6 +110,47 @@ def test_gemm_second_pair_residual_and_atomic(rp):
     assert rel_l2(C3.cpu().numpy(), dy.T.astype(np.float64) @ u.astype(np.float64) + 1.0) < 1e-5
 
 
+def test_gemm_reduction_split_merges_in_a_fixed_order(rp):
+    """Weight-gradient shapes whose 256x256 tiles would leave most of the chip idle are cut along the reduction; the
+    slices' partial products go through scratch memory and are added in slice order, so two runs agree bit for bit
+    (Sec. 4.1.1: gradients accumulate in place over micro-batches).  Ragged M and N, K long enough for 8 slices, the
+    skinny LoRA shapes with a bf16 result, and a scratch buffer too small for any split."""
+    B, H = rp
+    rng = np.random.default_rng(17)
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda:0")
+    for (M, N, K) in ((520, 392, 8200), (48, 1032, 4104), (1032, 16, 4104)):
+        a, b = rnd(rng, (K, M)), rnd(rng, (K, N))
+        ref = a.T.astype(np.float64) @ b.astype(np.float64)
+        A, Bm = dev(H, a), dev(H, b)
+        outs = []
+        for rep in range(2):
+            ws.fill_(0xFF)                                  # NaN patterns: every partial that is read was written first
+            C32 = torch.full((M, N), 2.0, dtype=torch.float32, device="cuda:0")
+            B.rp_op_gemm(stream(), 2, 1, A, Bm, C32, M, N, K, M, N, N, alpha=0.5, beta=1, split_ws=ws)
+            torch.cuda.synchronize()
+            outs.append(C32.clone())
+        assert torch.equal(outs[0], outs[1])
+        assert rel_l2(outs[0].cpu().numpy(), 0.5 * ref + 2.0) < 1e-5
+        # without scratch nothing is split: same product, one pass
+        C1 = torch.full((M, N), 2.0, dtype=torch.float32, device="cuda:0")
+        B.rp_op_gemm(stream(), 2, 1, A, Bm, C1, M, N, K, M, N, N, alpha=0.5, beta=1)
+        torch.cuda.synchronize()
+        assert rel_l2(C1.cpu().numpy(), 0.5 * ref + 2.0) < 1e-5
+        # a scratch buffer that holds one slice only: no split either
+        small = torch.empty(M * N * 4, dtype=torch.uint8, device="cuda:0")
+        C2 = torch.full((M, N), 2.0, dtype=torch.float32, device="cuda:0")
+        B.rp_op_gemm(stream(), 2, 1, A, Bm, C2, M, N, K, M, N, N, alpha=0.5, beta=1, split_ws=small)
+        torch.cuda.synchronize()
+        assert rel_l2(C2.cpu().numpy(), 0.5 * ref + 2.0) < 1e-5
+    # skinny product with a bf16 result (LoRA down-projection: [T, h] x [3r, h]^T), NT layout
+    T_, h, r3 = 2056, 1032, 48
+    x, am = rnd(rng, (T_, h)), rnd(rng, (r3, h), 0.05)
+    U = torch.full((T_, r3), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    B.rp_op_gemm(stream(), 0, 3, dev(H, x), dev(H, am), U, T_, r3, h, h, h, r3, alpha=2.0, split_ws=ws)
+    torch.cuda.synchronize()
+    assert rel_l2(H.to_f32(U), 2.0 * (x.astype(np.float64) @ am.T.astype(np.float64))) < 4e-3
+
+
 def test_gemm_submatrix_views_and_tiny(rp):
     B, H = rp
     rng = np.random.default_rng(8)
@@ -234,7 +275,7 @@ def test_swiglu_fwd_bwd(rp):
 
 
 # ----------------------------------------------------------------------------------------------- attention
-# the last two cases are long enough for the two-kernel dK/dV path (sequences of 8192 tokens and more)
+# the last two cases are long sequences (8192 tokens and more): many key tiles per query tile, fold order of the grid
 @pytest.mark.parametrize("d,a,kh,batch,seq", [(128, 4, 2, 1, 328), (64, 4, 2, 2, 136), (128, 8, 1, 1, 200), (128, 2, 2, 1, 8),
                                               (128, 2, 1, 1, 8264), (64, 1, 1, 1, 8192)])
 def test_attention_fwd_bwd(rp, d, a, kh, batch, seq):
