@@ -34,6 +34,17 @@ RP_API rp_status rp_op_rmsnorm_fwd(void* stream, const void* x, const void* g, v
 RP_API rp_status rp_op_rmsnorm_bwd(void* stream, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
                             const void* dres, void* dx, float* dg, float* scratch, int T, int h);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): rp_op_rmsnorm_bwd without the scratch argument.  The gain-gradient partials go through a 16 MiB
+ * array that is part of the library's code object (one copy per GPU, resident until the process ends); the call
+ * allocates and frees nothing.  Limit: h <= 4096 (RP_EINVAL beyond it, with a message; nothing is enqueued).  Same
+ * kernels and results as rp_op_rmsnorm_bwd.  All calls on one GPU share that array: calls that overlap on one GPU
+ * (different streams, or threads) race on it -- serialise them.  The array's address is looked up once per device, at
+ * rp_ctx_create on that device or else at the first call (with the stream's device current); do that first call
+ * outside a graph capture. */
+RP_API rp_status rp_op_rmsnorm_bwd_noalloc(void* stream, const void* dy, int dy_is_f32, const void* x, const void* g,
+                                    const float* rstd, const void* dres, void* dx, float* dg, int T, int h);
+
 /* cs: float2 [seq][d/2] = (cos, sin)(pos * base^(-2i/d)) */
 RP_API rp_status rp_op_rope_table(void* stream, void* cs, int seq, int d, float base);
 /* Per-head RMSNorm (optional) + rotary embedding with half-split pairs (i, i + d/2) on a query heads and k key heads.

@@ -95,6 +95,7 @@ _SIGS = {
     "rp_op_gemm": [_vp, _i, _i, _vp, _vp, _vp, _i, _i, _i, _l, _l, _l, _f, _i, _vp, _vp, _i, _l, _l, _vp, _l, _i, _vp, _sz],
     "rp_op_rmsnorm_fwd": [_vp, _vp, _vp, _vp, _vp, _i, _i, _f],
     "rp_op_rmsnorm_bwd": [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i],
+    "rp_op_rmsnorm_bwd_noalloc": [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i],
     "rp_op_rope_table": [_vp, _vp, _i, _i, _f],
     "rp_op_qknorm_rope": [_vp, _i, _i, _vp, _vp, _l, _l, _vp, _vp, _l, _l, _vp, _vp, _vp, _vp, _vp, _vp, _l, _vp, _vp,
                           _vp, _vp, _i, _i, _i, _i, _i, _f],
@@ -298,6 +299,11 @@ def rp_op_rmsnorm_fwd(stream, x, g, y, rstd, T_, h, eps):
 def rp_op_rmsnorm_bwd(stream, dy, dy_is_f32, x, g, rstd, dres, dx, dg, scratch, T_, h):
     _check(lib.rp_op_rmsnorm_bwd(stream, _ptr(dy), dy_is_f32, _ptr(x), _ptr(g), _ptr(rstd), _ptr(dres), _ptr(dx),
                                  _ptr(dg), _ptr(scratch), T_, h))
+
+
+def rp_op_rmsnorm_bwd_noalloc(stream, dy, dy_is_f32, x, g, rstd, dres, dx, dg, T_, h):
+    _check(lib.rp_op_rmsnorm_bwd_noalloc(stream, _ptr(dy), dy_is_f32, _ptr(x), _ptr(g), _ptr(rstd), _ptr(dres), _ptr(dx),
+                                         _ptr(dg), T_, h))
 
 
 def rp_op_rope_table(stream, cs, seq, d, base):

@@ -5,6 +5,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 
 #include "../../include/rp.h"
@@ -15,6 +16,11 @@
 #include "transfers.hpp"
 
 using namespace rp;
+
+// Scratch memory of the entry point that allocates nothing (rp_op_rmsnorm_bwd_noalloc): 16 MiB in the code object.
+constexpr int NOALLOC_MAX_H = 4096;                                  // widest row that entry point accepts
+constexpr size_t NOALLOC_FLOATS = (size_t)RP_PARTIAL_BLOCKS * NOALLOC_MAX_H;
+static __device__ __align__(256) float scratch[NOALLOC_FLOATS];
 
 namespace {
 
@@ -31,6 +37,31 @@ struct Slot {
 };
 
 char g_err[512];
+
+// ---- scratch memory for the entry point that allocates nothing -----------------------------------------------------
+// One array per GPU the library runs on, resident until the process ends.  In host code the array's name is only a
+// stand-in: its device address is looked up once per device (with that device current) and kept here; kernels, fills
+// and copies are always given that pointer.
+constexpr int MAX_DEVICES = 64;
+float* g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+// Device address of this GPU's copy of `scratch` (the current device).  No allocation: the symbol lives in the code
+// object.  Returns NULL and sets *err when the look-up fails.
+float* noalloc_scratch(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= MAX_DEVICES) { *err = hipErrorInvalidDevice; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = static_cast<float*>(ptr);
+  }
+  return g_scratch_ptr[dev];
+}
 
 }  // namespace
 
@@ -509,6 +540,10 @@ rp_status rp_ctx_create(rp_ctx** out, int device, void* compute_stream, void* co
   if (s != RP_OK) return s;
   if (!compute_stream || !copy_stream) return fail(nullptr, RP_EINVAL, "both streams must be non-NULL");
   HIP_TRY(nullptr, hipSetDevice(device));
+  {   // set-up of the no-allocation entry point for this device (rp_op_rmsnorm_bwd_noalloc)
+    hipError_t se = hipSuccess;
+    if (!noalloc_scratch(&se)) return fail(nullptr, RP_EHIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(se));
+  }
   rp_ctx* c = new (std::nothrow) rp_ctx();
   if (!c) return fail(nullptr, RP_ENOMEM, "out of host memory");
   c->cfg = *cfg; c->device = device;
@@ -844,6 +879,19 @@ rp_status rp_op_rmsnorm_bwd(void* stream, const void* dy, int dy_is_f32, const v
                             const void* dres, void* dx, float* dg, float* scratch, int T, int h) {
   if (!dy || !x || !g || !rstd || !dx || h % 8 || h > 8192 || (dg && !scratch)) return fail(nullptr, RP_EINVAL, "rp_op_rmsnorm_bwd: bad arguments");
   hipError_t e = k_rmsnorm_bwd(reinterpret_cast<hipStream_t>(stream), dy, dy_is_f32, x, g, rstd, dres, dx, dg, scratch, T, h);
+  OP_RET(e);
+}
+
+rp_status rp_op_rmsnorm_bwd_noalloc(void* stream, const void* dy, int dy_is_f32, const void* x, const void* g, const float* rstd,
+                                    const void* dres, void* dx, float* dg, int T, int h) {
+  if (!dy || !x || !g || !rstd || !dx || T < 0 || h <= 0 || h % 8) return fail(nullptr, RP_EINVAL, "rp_op_rmsnorm_bwd_noalloc: bad arguments");
+  if (h > NOALLOC_MAX_H)
+    return fail(nullptr, RP_EINVAL, "rp_op_rmsnorm_bwd_noalloc: h = %d exceeds the built-in scratch (h <= %d); use rp_op_rmsnorm_bwd with a caller-owned scratch", h, NOALLOC_MAX_H);
+  hipError_t e = hipSuccess;
+  float* const sp = noalloc_scratch(&e);
+  if (!sp) return fail(nullptr, RP_EHIP, "rp_op_rmsnorm_bwd_noalloc: scratch look-up failed: %s", hipGetErrorString(e));
+  // every partial row the column sum reads is written by the kernel before it: nothing has to start at zero
+  e = k_rmsnorm_bwd(reinterpret_cast<hipStream_t>(stream), dy, dy_is_f32, x, g, rstd, dres, dx, dg, sp, T, h);
   OP_RET(e);
 }
 

@@ -29,7 +29,7 @@ def declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
-    assert len(names) >= 19
+    assert len(names) >= 20
     for n in names:
         assert hasattr(B.lib, n), n
     assert sorted(B.EXPORTS) == names
@@ -126,6 +126,7 @@ def test_argument_validation_returns_codes_without_gpu():
     assert B.lib.rp_lmhead_ce_fwd_bwd(None, 0, None, None, None, None, None, 1.0, 1, 8, None, 0) == B.RP_EINVAL
     assert B.lib.rp_stage_upload_weights(None, 0, None, None, 0) == B.RP_EINVAL
     assert B.lib.rp_op_gemm(None, 9, 0, None, None, None, 1, 1, 8, 8, 8, 8, 1.0, 0, None, None, 0, 0, 0, None, 0, 0, None, 0) == B.RP_EINVAL
+    assert B.lib.rp_op_rmsnorm_bwd_noalloc(None, None, 0, None, None, None, None, None, None, 8, 8) == B.RP_EINVAL
 
 
 def test_workspace_covers_paper_activation_formula():
