@@ -165,6 +165,49 @@ def test_c2_full_size_every_stage_call_matches_oracle(hz, capsys):
     assert abs(loss_v - np.log(c["vocab"])) < 0.5
 
 
+@pytest.mark.timeout(900)
+def test_c2_full_size_fused_chain_against_the_never_rounding_oracle(hz, capsys):
+    """The benchmark's workload at full size through the call sequence bench.py times (fused last stage: recompute ->
+    head on its own workspace -> backward from the kept internals), compared AS ONE CHAIN with the oracle that never
+    rounds: errors of four layers and the head accumulate.  Bound per tensor: 2e-2 wherever 16-bit storage allows it.
+    On this workload it does not allow it everywhere: the residual stream is fed by an N(0, 0.02) embedding and is
+    carried by the branch outputs alone, so every stored bf16 tensor's rounding reaches the next layers in full, and
+    the attention backward multiplies what the forward left in q, k, v and the layer input (the gradients of Wq, Wk,
+    gq, gk collect four such factors).  storage_rounding.bf16_storage() measures that floor with the oracle itself
+    (its stored tensors rounded to bf16, nothing else changed, no HIP code involved); where the floor exceeds
+    2e-2 / 1.25 the HIP path must stay within 25 % of the floor and below 3e-2 in any case.  Local bounds (single
+    rows, blocks of 256 columns) apply with each tensor's bound."""
+    from storage_rounding import bf16_storage
+
+    def say(msg):
+        with capsys.disabled():
+            print("[c2 fused chain] " + msg, flush=True)
+
+    c = synth.CONFIGS["C2"]
+    say("generating the workload")
+    wl = synth.make_workload(c, synth.config_seed("C2"))
+    say("HIP path: fused last stage")
+    got = pu.gpu_chain(c, wl, hz, fused=True)
+    say("oracle (fp32), whole chain")
+    ref = pu.oracle_chain(c, wl, dtype=np.float32)
+    say("oracle with bf16 storage (the floor)")
+    with bf16_storage():
+        flo = pu.oracle_chain(c, wl, dtype=np.float32)
+    floor = {n: pu.rel_l2(g, r) for n, g, r in pu.chain_pairs(ref, flo)}
+    over = sorted(n for n, v in floor.items() if v > 2e-2)
+    say("storage floor above 2e-2 on %d of %d tensors (%s), worst %.2e (%s)"
+        % ((len(over), len(floor), " ".join(over)) + max((v, n) for n, v in floor.items())))
+    assert all(n.split(".")[-1] in ("Wq", "Wk", "gq", "gk") for n in over), over      # the q/k path only
+    tol_of = lambda n: min(3e-2, max(2e-2, 1.25 * floor[n]))
+    errs = pu.compare_chain(ref, got, c, tol_of=tol_of)
+    worst = max((v / tol_of(k), v, k) for k, v in errs.items() if k != "loss")
+    say("worst tensor %.2e (%s) = %.2f of its bound; over the plain 2e-2: %s; loss error %.1e"
+        % (worst[1], worst[2], worst[0], sorted(k for k, v in errs.items() if k != "loss" and v > 2e-2), errs["loss"]))
+    assert len(errs) == 4 + 2 + c["n_layers"] * 11, sorted(errs)
+    # everything off the q/k path meets the plain bound
+    assert all(v <= 2e-2 for k, v in errs.items() if k != "loss" and k.split(".")[-1] not in ("Wq", "Wk", "gq", "gk"))
+
+
 VARIANTS = {
     # ragged token count, every adapter on, frozen base, random gains
     "lora_all_frozen_ragged": dict(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=688, vocab=0,
