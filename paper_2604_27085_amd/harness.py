@@ -1,6 +1,9 @@
 """Thin harness around the binding: packs per-tensor arrays into the library's weight blob, owns the torch buffers
 (device memory, pinned host memory, streams) and unpacks gradient blobs.  Marshalling only -- no layer math here.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import torch
 
@@ -30,20 +33,36 @@ def cfg_from_dict(c, with_head=None, n_layers=None):
 
 
 def _layer_tensors(p, cfg):
-    """name -> ndarray in the library's fused order."""
-    out = {"G1": p["g1"], "WQKV": np.concatenate([p["Wq"], p["Wk"], p["Wv"]], axis=0), "WO": p["Wo"], "G2": p["g2"],
-           "WD": p["Wd"]}
+    """name -> list of ndarrays whose concatenation (flattened, in order) is the tensor in the library's fused order."""
+    out = {"G1": [p["g1"]], "WQKV": [p["Wq"], p["Wk"], p["Wv"]], "WO": [p["Wo"]], "G2": [p["g2"]], "WD": [p["Wd"]]}
     if cfg.qk_norm:
-        out["GQ"], out["GK"] = p["gq"], p["gk"]
+        out["GQ"], out["GK"] = [p["gq"]], [p["gk"]]
     if cfg.n_experts > 0:
-        out["WGU"] = np.concatenate([p["Wg"], p["Wu"]], axis=1)      # [E, 2m, h]
+        # [E, 2m, h]: per expert the gate rows, then the up rows
+        out["WGU"] = [a for e in range(cfg.n_experts) for a in (p["Wg"][e], p["Wu"][e])]
         if cfg.moe_router:
-            out["WR"] = p["Wr"]
+            out["WR"] = [p["Wr"]]
     else:
-        out["WGU"] = np.concatenate([p["Wg"], p["Wu"]], axis=0)      # [2m, h]
+        out["WGU"] = [p["Wg"], p["Wu"]]                               # [2m, h]
     for name, (A, Bm) in p.get("lora", {}).items():
-        out[_LA[name]], out[_LB[name]] = A, Bm
+        out[_LA[name]], out[_LB[name]] = [A], [Bm]
     return out
+
+
+_PACK_CHUNK = 1 << 22
+
+
+def _store_bf16(dst16, arr):
+    """dst16 (uint16 view of the blob) <- bf16 bits of arr, converted chunk by chunk on several threads."""
+    flat = np.ascontiguousarray(arr, dtype=np.float32).reshape(-1)
+    n = flat.size
+    if n <= _PACK_CHUNK:
+        dst16[:n] = f32_to_bf16_bits(flat)
+        return
+    def conv(i):
+        dst16[i:i + _PACK_CHUNK] = f32_to_bf16_bits(flat[i:i + _PACK_CHUNK])
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        list(ex.map(conv, range(0, n, _PACK_CHUNK)))
 
 
 def pack_weights(cfg, layers, head=None, out=None):
@@ -52,19 +71,22 @@ def pack_weights(cfg, layers, head=None, out=None):
     blob = np.zeros(wbytes, dtype=np.uint8) if out is None else out
     b16 = blob.view(np.uint16)
 
-    def put(layer, name, arr):
+    def put(layer, name, parts):
         off, n = B.rp_weight_layout(cfg, layer, B.T[name])
         if n == 0:
             return
-        assert arr.size == n, (name, arr.shape, n)
-        b16[off // 2: off // 2 + n] = f32_to_bf16_bits(arr).reshape(-1)
+        assert sum(a.size for a in parts) == n, (name, [a.shape for a in parts], n)
+        pos = off // 2
+        for a in parts:
+            _store_bf16(b16[pos:pos + a.size], a)
+            pos += a.size
 
     for li, p in enumerate(layers):
-        for name, arr in _layer_tensors(p, cfg).items():
-            put(li, name, arr)
+        for name, parts in _layer_tensors(p, cfg).items():
+            put(li, name, parts)
     if head is not None and cfg.vocab > 0:
-        put(cfg.n_layers, "GF", head["gf"])
-        put(cfg.n_layers, "WV", head["Wv"])
+        put(cfg.n_layers, "GF", [head["gf"]])
+        put(cfg.n_layers, "WV", [head["Wv"]])
     return blob
 
 

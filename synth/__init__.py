@@ -9,6 +9,9 @@ paper's Table "Model Configs": five Qwen3-shaped ones and a GPT-OSS-20B-shaped m
 whose router is part of the layer); weights N(0, 0.02), LoRA A N(0, 0.02), LoRA B N(0, 0.01), norm
 gains 1, token ids uniform, labels = next token.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 SEED_BASE = 27085
@@ -67,8 +70,31 @@ def bf16_round(x):
     return bits_to_f32(bf16_bits(x)).reshape(np.shape(x))
 
 
+_PAR_CHUNK = 1 << 22      # elements per independently drawn chunk of a large tensor
+
+
 def _normal(rng, shape, std):
-    return bf16_round(rng.standard_normal(shape, dtype=np.float32) * np.float32(std))
+    """N(0, std) rounded to bf16.  Tensors of more than one chunk are drawn chunk by chunk from child generators spawned
+    off rng (a fixed function of the seed and the shape, whatever the number of threads), several chunks at a time:
+    the larger workloads hold billions of parameters."""
+    n = int(np.prod(shape))
+    if n <= _PAR_CHUNK:
+        return bf16_round(rng.standard_normal(shape, dtype=np.float32) * np.float32(std))
+    out = np.empty(n, dtype=np.float32)
+    nchunk = -(-n // _PAR_CHUNK)
+    kids = rng.spawn(nchunk)
+
+    def fill(i):
+        sl = out[i * _PAR_CHUNK:(i + 1) * _PAR_CHUNK]
+        kids[i].standard_normal(out=sl, dtype=np.float32)
+        sl *= np.float32(std)
+        u = sl.view(np.uint32)                       # round to nearest even in place (no NaN among normal draws)
+        u += np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+        u &= np.uint32(0xFFFF0000)
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        list(ex.map(fill, range(nchunk)))
+    return out.reshape(shape)
 
 
 # ----------------------------------------------------------------------------- parameter / input draws
