@@ -308,6 +308,33 @@ def test_moe_router_in_stage_selection_is_topk_of_its_own_logits(hz):
     ref_sel = ref["grads"][0]["router_logits"] != 0.0
     assert np.array_equal(sel[decisive], ref_sel[decisive])
     assert pu.rel_l2(got["out"][decisive], ref["out"][decisive]) <= 2e-2
+    # The gradient side.  The gradient of the logits is local to a token: on the decisive tokens it must match.
+    assert pu.rel_l2(got["d_router"][0][decisive], ref["grads"][0]["router_logits"][decisive]) <= 2e-2
+    # The input gradient and the adapter gradients mix all tokens through the attention backward, so they can only be
+    # compared under one selection: the oracle is run again with its router's decision replaced, on the few tokens where
+    # the two sides differ, by the (valid) decision the stage took -- its own logits, softmax over the forced picks --
+    # and then everything is unique and compared in full.
+    differ = np.nonzero((sel != ref_sel).any(axis=1))[0]
+    assert 0 < len(differ) < 0.1 * sel.shape[0]          # near-ties exist on this input, and they are few
+    orig_route = OL.moe_route
+
+    def forced_route(logits, top_k):
+        order, w = orig_route(logits, top_k)
+        for t in differ:
+            picks = np.nonzero(sel[t])[0]
+            picks = picks[np.argsort(-logits[t, picks], kind="stable")]
+            z = logits[t, picks] - logits[t, picks].max()
+            order[t], w[t] = picks, np.exp(z) / np.exp(z).sum()
+        return order, w
+
+    OL.moe_route = forced_route
+    try:
+        ref2 = pu.oracle_chain(c, wl)
+    finally:
+        OL.moe_route = orig_route
+    assert np.array_equal(ref2["grads"][0]["router_logits"] != 0.0, sel)
+    errs = pu.compare_chain(ref2, got, c)
+    assert len(errs) == 2 + 2 + 2 * len(c["lora"]), sorted(errs)
 
 
 @pytest.mark.parametrize("name", sorted(VARIANTS))
