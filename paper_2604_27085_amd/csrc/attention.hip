@@ -107,6 +107,15 @@ RP_DEV uint4 pack_frag(const f32x16& s, int off) {
 
 RP_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Two waves share a SIMD in the forward kernel.  Left alone they fall into step: both issue their matrix products at
+// the same time (each at half rate) and then both do their exponentials, so the matrix pipeline idles while the vector
+// pipeline works and the other way round.  A wave raises its issue priority for its runs of MFMAs: whichever wave gets
+// there first keeps the matrix pipeline to itself, the other one falls behind by a phase, and from then on one wave's
+// exponentials run under the other wave's products (forward kernel +6 % at 8192 to 31744 tokens; the dQ kernel, whose
+// vector phase is short against its three products, does not change).
+#define MFMA_PHASE_BEGIN() __builtin_amdgcn_s_setprio(1)
+#define MFMA_PHASE_END() __builtin_amdgcn_s_setprio(0)
+
 // x as the sum of three bf16 numbers (most significant first) in the first three slots of an MFMA operand chunk, zeros
 // in the other five: 24 mantissa bits survive, so an MFMA step against ones adds x to an fp32 accumulator exactly
 // enough for a softmax exponent.
@@ -250,6 +259,7 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
         uint4 ring[AHEAD];
 #pragma unroll
         for (int n = 0; n < AHEAD; ++n) ring[n] = sfrag_at(n);
+        MFMA_PHASE_BEGIN();
 #pragma unroll
         for (int n = 0; n < NS; ++n) {
           const uint4 a = ring[n % AHEAD];
@@ -259,6 +269,7 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
           for (int t = 0; t < QT; ++t) sT[t][kt] = mfma32(a, qf[t][ks], ks == 0 ? zero16 : sT[t][kt]);
           __builtin_amdgcn_sched_barrier(0);
         }
+        MFMA_PHASE_END();
       }
       // the first V fragments are requested now, under the softmax arithmetic
       constexpr int NU = 4 * DT;
@@ -324,6 +335,7 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
         for (int gk = 0; gk < 4; ++gk)
 #pragma unroll
           for (int t = 0; t < QT; ++t) pf[gk][t] = pack_frag(sT[t][gk >> 1], 8 * (gk & 1));
+        MFMA_PHASE_BEGIN();
 #pragma unroll
         for (int n = 0; n < NU; ++n) {
           const uint4 a = uring[n % AHEAD];
@@ -332,6 +344,7 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
           for (int t = 0; t < QT; ++t) oacc[t][n % DT] = mfma32(a, pf[n / DT][t], oacc[t][n % DT]);
           __builtin_amdgcn_sched_barrier(0);
         }
+        MFMA_PHASE_END();
       }
     }
   }

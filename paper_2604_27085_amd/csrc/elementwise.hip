@@ -70,7 +70,10 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict_
                                                                const bf16* __restrict__ g, const float* __restrict__ rstd_in,
                                                                const bf16* __restrict__ dres, bf16* __restrict__ dx,
                                                                float* __restrict__ part, int T, int h) {
-  __shared__ float s_dot[2][4];
+  // Two rows per trip (rows r and r + gridDim.x): twice the loads in flight per thread -- at 4096 x 2048 the kernel is
+  // bound by memory latency, not bandwidth -- and one barrier for both rows.
+  constexpr int NR = 2;
+  __shared__ float s_dot[2][NR][4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nch = h >> 3;
   const uint4* gr = reinterpret_cast<const uint4*>(g);
@@ -83,51 +86,69 @@ __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict_
     if (c < nch) unpack8(gr[c], gg[i]);
   }
   int par = 0;
-  for (int row = blockIdx.x; row < T; row += gridDim.x, par ^= 1) {
-    const float rstd = rstd_in[row];
-    float dyv[MAXC][8], xf[MAXC][8];
-    float dot = 0.f;
+  for (int row0 = blockIdx.x; row0 < T; row0 += NR * gridDim.x, par ^= 1) {
+    float dyv[NR][MAXC][8], xf[NR][MAXC][8], rstd[NR], dot[NR];
+    uint4 rr[NR][MAXC];
 #pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-      const int c = (4 * i + wave) * 64 + lane;
+    for (int r = 0; r < NR; ++r) {
+      const int row = row0 + r * gridDim.x;
+      const bool rok = row < T;
+      rstd[r] = rok ? rstd_in[row] : 0.f;
+      dot[r] = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { dyv[i][e] = 0.f; xf[i][e] = 0.f; }
-      if (c < nch) {
-        unpack8(reinterpret_cast<const uint4*>(x + (long)row * h)[c], xf[i]);
-        if constexpr (sizeof(DyT) == 4) {
-          const float4* dr = reinterpret_cast<const float4*>(dy + (long)row * h) + 2 * c;
-          const float4 a = dr[0], b = dr[1];
-          dyv[i][0] = a.x; dyv[i][1] = a.y; dyv[i][2] = a.z; dyv[i][3] = a.w;
-          dyv[i][4] = b.x; dyv[i][5] = b.y; dyv[i][6] = b.z; dyv[i][7] = b.w;
-        } else {
-          unpack8(reinterpret_cast<const uint4*>(dy + (long)row * h)[c], dyv[i]);
-        }
+      for (int i = 0; i < MAXC; ++i) {
+        const int c = (4 * i + wave) * 64 + lane;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          dot += dyv[i][e] * gg[i][e] * xf[i][e];
-          dgacc[i][e] += dyv[i][e] * xf[i][e] * rstd;
+        for (int e = 0; e < 8; ++e) { dyv[r][i][e] = 0.f; xf[r][i][e] = 0.f; }
+        rr[r][i] = make_uint4(0u, 0u, 0u, 0u);
+        if (rok && c < nch) {
+          unpack8(reinterpret_cast<const uint4*>(x + (long)row * h)[c], xf[r][i]);
+          if constexpr (sizeof(DyT) == 4) {
+            const float4* dr = reinterpret_cast<const float4*>(dy + (long)row * h) + 2 * c;
+            const float4 a = dr[0], b = dr[1];
+            dyv[r][i][0] = a.x; dyv[r][i][1] = a.y; dyv[r][i][2] = a.z; dyv[r][i][3] = a.w;
+            dyv[r][i][4] = b.x; dyv[r][i][5] = b.y; dyv[r][i][6] = b.z; dyv[r][i][7] = b.w;
+          } else {
+            unpack8(reinterpret_cast<const uint4*>(dy + (long)row * h)[c], dyv[r][i]);
+          }
+          if (dres) rr[r][i] = reinterpret_cast<const uint4*>(dres + (long)row * h)[c];
         }
       }
     }
-    dot = wave_sum(dot);
-    if (lane == 0) s_dot[par][wave] = dot;
-    __syncthreads();   // the other parity's slots are rewritten only after the next barrier
-    dot = (s_dot[par][0] + s_dot[par][1]) + (s_dot[par][2] + s_dot[par][3]);
-    const float k2 = rstd * rstd * rstd * dot / (float)h;
 #pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-      const int c = (4 * i + wave) * 64 + lane;
-      if (c < nch) {
-        float o[8];
+    for (int r = 0; r < NR; ++r) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = rstd * dyv[i][e] * gg[i][e] - k2 * xf[i][e];
-        if (dres) {
-          float rr[8];
-          unpack8(reinterpret_cast<const uint4*>(dres + (long)row * h)[c], rr);
+      for (int i = 0; i < MAXC; ++i)
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] += rr[e];
+        for (int e = 0; e < 8; ++e) {
+          dot[r] += dyv[r][i][e] * gg[i][e] * xf[r][i][e];
+          dgacc[i][e] += dyv[r][i][e] * xf[r][i][e] * rstd[r];      // rows past the end contribute zeros
         }
-        reinterpret_cast<uint4*>(dx + (long)row * h)[c] = pack8(o);
+      dot[r] = wave_sum(dot[r]);
+      if (lane == 0) s_dot[par][r][wave] = dot[r];
+    }
+    __syncthreads();   // the other parity's slots are rewritten only after the next barrier
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      const int row = row0 + r * gridDim.x;
+      if (row >= T) continue;
+      const float d = (s_dot[par][r][0] + s_dot[par][r][1]) + (s_dot[par][r][2] + s_dot[par][r][3]);
+      const float k2 = rstd[r] * rstd[r] * rstd[r] * d / (float)h;
+#pragma unroll
+      for (int i = 0; i < MAXC; ++i) {
+        const int c = (4 * i + wave) * 64 + lane;
+        if (c < nch) {
+          float o[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = rstd[r] * dyv[r][i][e] * gg[i][e] - k2 * xf[r][i][e];
+          if (dres) {
+            float rv[8];
+            unpack8(rr[r][i], rv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += rv[e];
+          }
+          reinterpret_cast<uint4*>(dx + (long)row * h)[c] = pack8(o);
+        }
       }
     }
   }
@@ -228,76 +249,92 @@ __global__ void __launch_bounds__(512) qknorm_rope_kernel(const bf16* __restrict
 #pragma unroll
       for (int e = 0; e < 8; ++e) { const float2 v = row[e]; c8[e] = v.x; s8[e] = v.y; }
     }
-    for (int h0 = 0; h0 < a + k; h0 += HPW) {
-      const int head = h0 + hsel;
-      const bool ok = head < a + k;
-      const bool isq = head < a;
-      const int hh = isq ? head : head - a;
-      float f[8];
+    // NP passes of HPW heads at a time, all their loads issued before any arithmetic: a token's heads are the only
+    // work a wave has, so the loads in flight are what hides the memory latency
+    constexpr int NP = 4;
+    for (int h0 = 0; h0 < a + k; h0 += HPW * NP) {
+      uint4 in_v[NP], raw_v[NP];
+      float rs[NP];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] = 0.f;
-      if (ok) {
-        const bf16* src = isq ? in_q + (long)t * ld_in_q + hh * D : in_k + (long)t * ld_in_k + hh * D;
-        unpack8(reinterpret_cast<const uint4*>(src)[sub], f);
-      }
-      if constexpr (!BWD) {
-        if (use_norm) {
-          float ss = 0.f;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
-#pragma unroll
-          for (int o = LPH / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-          const float rstd = 1.0f / sqrtf(ss / (float)D + eps);
-          if (ok && sub == 0) {
-            if (isq) rstd_q[(long)t * a + hh] = rstd; else rstd_k[(long)t * k + hh] = rstd;
-          }
-#pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * (isq ? gqv[e] : gkv[e]);
-        }
-        float o8[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float partner = __shfl_xor(f[e], LPH / 2, 64);
-          o8[e] = first_half ? (f[e] * c8[e] - partner * s8[e]) : (f[e] * c8[e] + partner * s8[e]);
-        }
+      for (int u = 0; u < NP; ++u) {
+        const int head = h0 + u * HPW + hsel;
+        const bool ok = head < a + k, isq = head < a;
+        const int hh = isq ? head : head - a;
+        in_v[u] = make_uint4(0u, 0u, 0u, 0u);
+        raw_v[u] = in_v[u];
+        rs[u] = 0.f;
         if (ok) {
-          bf16* dst = isq ? out_q + (long)t * ld_out_q + hh * D : out_k + (long)t * ld_out_k + hh * D;
-          reinterpret_cast<uint4*>(dst)[sub] = pack8(o8);
-        }
-      } else {
-        // inverse rotation of the incoming gradient
-        float gr[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float partner = __shfl_xor(f[e], LPH / 2, 64);
-          gr[e] = first_half ? (f[e] * c8[e] + partner * s8[e]) : (f[e] * c8[e] - partner * s8[e]);
-        }
-        if (use_norm) {
-          float xr[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) xr[e] = 0.f;
-          float rstd = 0.f;
-          if (ok) {
+          const bf16* src = isq ? in_q + (long)t * ld_in_q + hh * D : in_k + (long)t * ld_in_k + hh * D;
+          in_v[u] = reinterpret_cast<const uint4*>(src)[sub];
+          if (BWD && use_norm) {
             const bf16* rsrc = (isq ? raw_q : raw_k) + (long)t * ld_raw + hh * D;
-            unpack8(reinterpret_cast<const uint4*>(rsrc)[sub], xr);
-            rstd = isq ? rstd_q[(long)t * a + hh] : rstd_k[(long)t * k + hh];
+            raw_v[u] = reinterpret_cast<const uint4*>(rsrc)[sub];
+            rs[u] = isq ? rstd_q[(long)t * a + hh] : rstd_k[(long)t * k + hh];
           }
-          float dot = 0.f;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NP; ++u) {
+        const int head = h0 + u * HPW + hsel;
+        if (h0 + u * HPW >= a + k) break;      // wave-uniform: no head left in this pass
+        const bool ok = head < a + k;
+        const bool isq = head < a;
+        const int hh = isq ? head : head - a;
+        float f[8];
+        unpack8(in_v[u], f);
+        if constexpr (!BWD) {
+          if (use_norm) {
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+#pragma unroll
+            for (int o = LPH / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+            const float rstd = 1.0f / sqrtf(ss / (float)D + eps);
+            if (ok && sub == 0) {
+              if (isq) rstd_q[(long)t * a + hh] = rstd; else rstd_k[(long)t * k + hh] = rstd;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = f[e] * rstd * (isq ? gqv[e] : gkv[e]);
+          }
+          float o8[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            const float gg = isq ? gqv[e] : gkv[e];
-            dot += gr[e] * gg * xr[e];
-            if (isq) dgq_acc[e] += gr[e] * xr[e] * rstd; else dgk_acc[e] += gr[e] * xr[e] * rstd;
+            const float partner = __shfl_xor(f[e], LPH / 2, 64);
+            o8[e] = first_half ? (f[e] * c8[e] - partner * s8[e]) : (f[e] * c8[e] + partner * s8[e]);
           }
+          if (ok) {
+            bf16* dst = isq ? out_q + (long)t * ld_out_q + hh * D : out_k + (long)t * ld_out_k + hh * D;
+            reinterpret_cast<uint4*>(dst)[sub] = pack8(o8);
+          }
+        } else {
+          // inverse rotation of the incoming gradient
+          float gr[8];
 #pragma unroll
-          for (int o = LPH / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
-          const float k2 = rstd * rstd * rstd * dot / (float)D;
+          for (int e = 0; e < 8; ++e) {
+            const float partner = __shfl_xor(f[e], LPH / 2, 64);
+            gr[e] = first_half ? (f[e] * c8[e] + partner * s8[e]) : (f[e] * c8[e] - partner * s8[e]);
+          }
+          if (use_norm) {
+            float xr[8];
+            unpack8(raw_v[u], xr);
+            const float rstd = rs[u];
+            float dot = 0.f;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) gr[e] = rstd * gr[e] * (isq ? gqv[e] : gkv[e]) - k2 * xr[e];
-        }
-        if (ok) {
-          bf16* dst = isq ? out_q + (long)t * ld_out_q + hh * D : out_k + (long)t * ld_out_k + hh * D;
-          reinterpret_cast<uint4*>(dst)[sub] = pack8(gr);
+            for (int e = 0; e < 8; ++e) {
+              const float gg = isq ? gqv[e] : gkv[e];
+              dot += gr[e] * gg * xr[e];
+              if (isq) dgq_acc[e] += gr[e] * xr[e] * rstd; else dgk_acc[e] += gr[e] * xr[e] * rstd;
+            }
+#pragma unroll
+            for (int o = LPH / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+            const float k2 = rstd * rstd * rstd * dot / (float)D;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) gr[e] = rstd * gr[e] * (isq ? gqv[e] : gkv[e]) - k2 * xr[e];
+          }
+          if (ok) {
+            bf16* dst = isq ? out_q + (long)t * ld_out_q + hh * D : out_k + (long)t * ld_out_k + hh * D;
+            reinterpret_cast<uint4*>(dst)[sub] = pack8(gr);
+          }
         }
       }
     }

@@ -95,36 +95,31 @@ __global__ void __launch_bounds__(256) ce_chunk_ref_kernel(const float2* __restr
 
 // p[r][t] = exp(z[r][t] - m[t]) as bf16; the fp32 sum over the block's CE_PROB_ROWS rows goes to the .y half of the
 // block's row of the partial array (whose .x half holds the column maxima the logits GEMM left there, one row of
-// partials per CE_PROB_ROWS vocabulary rows): no atomics, ce_chunk_sum_kernel adds the rows in order.  Two tokens per
-// thread.
+// partials per CE_PROB_ROWS vocabulary rows): no atomics, ce_chunk_sum_kernel adds the rows in order.
 __global__ void __launch_bounds__(256) ce_chunk_prob_kernel(const float* __restrict__ z, int vc, int T,
                                                             const float* __restrict__ m, bf16* __restrict__ p,
                                                             float2* __restrict__ part) {
-  const int t = (blockIdx.x * 256 + threadIdx.x) * 2;
+  const int t = (blockIdx.x * 256 + threadIdx.x) * 4;      // four tokens per thread: 16-byte loads, 8-byte stores
   if (t >= T) return;
   const int r0 = blockIdx.y * CE_PROB_ROWS, r1 = min(r0 + CE_PROB_ROWS, vc);
-  const float m0 = m[t], m1 = m[t + 1];
-  float s0 = 0.f, s1 = 0.f;
+  const float4 mm = *reinterpret_cast<const float4*>(m + t);
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto one = [&](const float4& zz, int r) {
+    const float p0 = __expf(zz.x - mm.x), p1 = __expf(zz.y - mm.y), p2 = __expf(zz.z - mm.z), p3 = __expf(zz.w - mm.w);
+    s.x += p0; s.y += p1; s.z += p2; s.w += p3;
+    *reinterpret_cast<uint2*>(p + (long)r * T + t) = make_uint2(pack_bf16x2(p0, p1), pack_bf16x2(p2, p3));
+  };
   int r = r0;
   for (; r + 8 <= r1; r += 8) {          // eight rows in flight per thread
-    float2 zz[8];
+    float4 zz[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) zz[k] = *reinterpret_cast<const float2*>(z + (long)(r + k) * T + t);
+    for (int k = 0; k < 8; ++k) zz[k] = *reinterpret_cast<const float4*>(z + (long)(r + k) * T + t);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const float p0 = __expf(zz[k].x - m0), p1 = __expf(zz[k].y - m1);
-      s0 += p0; s1 += p1;
-      *reinterpret_cast<uint32_t*>(p + (long)(r + k) * T + t) = pack_bf16x2(p0, p1);
-    }
+    for (int k = 0; k < 8; ++k) one(zz[k], r + k);
   }
-  for (; r < r1; ++r) {
-    const float2 zz = *reinterpret_cast<const float2*>(z + (long)r * T + t);
-    const float p0 = __expf(zz.x - m0), p1 = __expf(zz.y - m1);
-    s0 += p0; s1 += p1;
-    *reinterpret_cast<uint32_t*>(p + (long)r * T + t) = pack_bf16x2(p0, p1);
-  }
-  part[(long)blockIdx.y * T + t].y = s0;
-  part[(long)blockIdx.y * T + t + 1].y = s1;
+  for (; r < r1; ++r) one(*reinterpret_cast<const float4*>(z + (long)r * T + t), r);
+  float2* const row = part + (long)blockIdx.y * T + t;
+  row[0].y = s.x; row[1].y = s.y; row[2].y = s.z; row[3].y = s.w;
 }
 
 // l[t] += sum over the chunk's partial rows of part[i][t].y, in row order.
@@ -188,9 +183,9 @@ hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, floa
                              float* l, float* alpha, void* p) {
   if (T == 0 || vc == 0) return hipSuccess;
   const int nblk = (vc + CE_PROB_ROWS - 1) / CE_PROB_ROWS;
-  if (T % 2 || nblk > nparts) return hipErrorInvalidValue;   // one partial row per CE_PROB_ROWS vocabulary rows
+  if (T % 4 || nblk > nparts) return hipErrorInvalidValue;   // one partial row per CE_PROB_ROWS vocabulary rows
   RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float2*)pmax, nparts, T, first, m, l, alpha);
-  RP_LAUNCH(ce_chunk_prob_kernel, dim3((T / 2 + 255) / 256, nblk), dim3(256), 0, st, z, vc, T, (const float*)m, (bf16*)p, pmax);
+  RP_LAUNCH(ce_chunk_prob_kernel, dim3((T / 4 + 255) / 256, nblk), dim3(256), 0, st, z, vc, T, (const float*)m, (bf16*)p, pmax);
   RP_LAUNCH(ce_chunk_sum_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float2*)pmax, nblk, T, l);
   return hipGetLastError();
 }
