@@ -133,6 +133,11 @@ RP_API const char* rp_last_error(const rp_ctx* ctx);
 RP_API rp_status rp_query_sizes(const rp_stage_cfg* cfg, int batch, int seq, size_t* weight_blob_bytes,
                          size_t* grad_blob_bytes, size_t* workspace_bytes);
 
+/* Size of a device weight slot: the packed blob followed by the tensors the library derives from it when the weights
+ * arrive (the block-diagonal LoRA B matrices of the fused q|k|v and gate|up projections).  Equal to weight_blob_bytes
+ * for stages without such adapters. */
+RP_API rp_status rp_slot_bytes(const rp_stage_cfg* cfg, size_t* slot_bytes);
+
 /* Byte offset and element count of tensor `id` of layer `layer` (layer == n_layers addresses the head
  * chunk) inside the weight blob (bf16 elements).  n_elems == 0 when the tensor is absent. */
 RP_API rp_status rp_weight_layout(const rp_stage_cfg* cfg, int layer, int id, size_t* byte_offset, size_t* n_elems);
@@ -147,13 +152,15 @@ RP_API rp_status rp_weight_chunk(const rp_stage_cfg* cfg, int layer, size_t* beg
 
 /* Weight streaming (Sec. 4.2, parameter-upload stream).  Copies the packed stage weights from pinned host
  * memory into the caller-owned device slot, one hipMemcpyAsync per layer chunk on the copy stream, recording
- * one event per chunk so that layer l can start as soon as its own bytes have landed.  Before copying, the copy
- * stream waits for the last stage call that read this slot.  bytes must equal weight_blob_bytes.
- * host_blob [pinned], dev_slot [dev].  Errors: RP_EINVAL, RP_EHIP. */
+ * one event per chunk so that layer l can start as soon as its own bytes have landed; behind a chunk's copy and before
+ * its event, small kernels on the copy stream build the layer's derived tensors (see rp_slot_bytes) behind the blob.
+ * Before copying, the copy stream waits for the last stage call that read this slot.  bytes must equal
+ * weight_blob_bytes.  host_blob [pinned], dev_slot [dev, at least rp_slot_bytes].  Errors: RP_EINVAL, RP_EHIP. */
 RP_API rp_status rp_stage_upload_weights(rp_ctx* ctx, int slot_id, void* dev_slot, const void* host_blob, size_t bytes);
 
-/* Marks a device blob that already holds packed weights (written on the compute stream or before it) as slot
- * `slot_id` without copying; later stage calls on the slot wait for nothing. */
+/* Marks a device slot (at least rp_slot_bytes) whose first `bytes` = weight_blob_bytes already hold packed weights
+ * (written on the compute stream or before it) as slot `slot_id` without copying; the derived tensors are built on the
+ * compute stream; later stage calls on the slot wait for nothing. */
 RP_API rp_status rp_stage_bind_weights(rp_ctx* ctx, int slot_id, void* dev_slot, size_t bytes);
 
 /* Forward stage (Sec. 3.2): x_out = layers(x_in).  x_in, x_out [dev] bf16 [T, h] (may not alias).
@@ -233,7 +240,7 @@ typedef struct {
   void* dy_dev[2];             /* [dev] backward rounds */
   void* out_dev[2];            /* [dev] */
   int32_t next_slot;           /* slot that receives the next stage's weights during this round, or -1 */
-  void* next_dev_slot;         /* [dev]    as in rp_stage_upload_weights */
+  void* next_dev_slot;         /* [dev]    as in rp_stage_upload_weights (at least rp_slot_bytes) */
   const void* next_host_blob;  /* [pinned] */
   const void* done_grads_dev;  /* [dev] fp32 gradient blob of a stage that has finished, to be sent home, or NULL */
   void* done_grads_host;       /* [pinned] receives it */

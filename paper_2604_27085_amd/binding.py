@@ -75,6 +75,7 @@ _SIGS = {
     "rp_ctx_create": [C.POINTER(_vp), _i, _vp, _vp, _pcfg],
     "rp_ctx_destroy": [_vp],
     "rp_query_sizes": [_pcfg, _i, _i, _psz, _psz, _psz],
+    "rp_slot_bytes": [_pcfg, _psz],
     "rp_weight_layout": [_pcfg, _i, _i, _psz, _psz],
     "rp_grad_layout": [_pcfg, _i, _i, _psz, _psz],
     "rp_weight_chunk": [_pcfg, _i, _psz, _psz],
@@ -146,6 +147,12 @@ def rp_query_sizes(cfg, batch, seq):
     w, g, ws = C.c_size_t(), C.c_size_t(), C.c_size_t()
     _check(lib.rp_query_sizes(C.byref(cfg), batch, seq, C.byref(w), C.byref(g), C.byref(ws)))
     return w.value, g.value, ws.value
+
+
+def rp_slot_bytes(cfg):
+    n = C.c_size_t()
+    _check(lib.rp_slot_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
 
 
 def rp_weight_layout(cfg, layer, tensor_id):

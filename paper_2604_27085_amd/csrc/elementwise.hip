@@ -65,14 +65,14 @@ __global__ void __launch_bounds__(256) rmsnorm_fwd_kernel(const bf16* __restrict
 // One BLOCK per row: the four waves split the row's columns (chunk (4i + wave)*64 + lane, i < MAXC, so
 // h <= 2048*MAXC), the row's dot product crosses the waves through LDS (one barrier per row), and every lane owns its
 // columns for all the rows of the block, so the gain-gradient partial is written straight from registers.
-template <int MAXC, typename DyT>
+template <int MAXC, int NR, typename DyT>
 __global__ void __launch_bounds__(256) rmsnorm_bwd_kernel(const DyT* __restrict__ dy, const bf16* __restrict__ x,
                                                                const bf16* __restrict__ g, const float* __restrict__ rstd_in,
                                                                const bf16* __restrict__ dres, bf16* __restrict__ dx,
                                                                float* __restrict__ part, int T, int h) {
-  // Two rows per trip (rows r and r + gridDim.x): twice the loads in flight per thread -- at 4096 x 2048 the kernel is
-  // bound by memory latency, not bandwidth -- and one barrier for both rows.
-  constexpr int NR = 2;
+  // NR rows per trip (rows r, r + gridDim.x, ...): NR times the loads in flight per thread and one barrier for all of
+  // them, against NR times the registers (measured: two rows win at h = 5120, 145 against 181 us for 16384 rows, and
+  // lose at h = 4096, where they halve the waves per SIMD).
   __shared__ float s_dot[2][NR][4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nch = h >> 3;
@@ -462,12 +462,12 @@ hipError_t k_rmsnorm_bwd(hipStream_t st, const void* dy, int dy_is_f32, const vo
   if (dg && !scratch) return hipErrorInvalidValue;
   const int grid = T < RP_PARTIAL_BLOCKS ? T : RP_PARTIAL_BLOCKS;
   float* part = dg ? scratch : nullptr;
-#define RP_LAUNCH_RR(MAXC, DT) \
-  RP_LAUNCH((rmsnorm_bwd_kernel<MAXC, DT>), dim3(grid), dim3(256), 0, st, (const DT*)dy, (const bf16*)x, \
+#define RP_LAUNCH_RR(MAXC, NR, DT) \
+  RP_LAUNCH((rmsnorm_bwd_kernel<MAXC, NR, DT>), dim3(grid), dim3(256), 0, st, (const DT*)dy, (const bf16*)x, \
                      (const bf16*)g, rstd, (const bf16*)dres, (bf16*)dx, part, T, h)
-  if (h <= 2048) { if (dy_is_f32) RP_LAUNCH_RR(1, float); else RP_LAUNCH_RR(1, bf16); }
-  else if (h <= 4096) { if (dy_is_f32) RP_LAUNCH_RR(2, float); else RP_LAUNCH_RR(2, bf16); }
-  else { if (dy_is_f32) RP_LAUNCH_RR(4, float); else RP_LAUNCH_RR(4, bf16); }
+  if (h <= 2048) { if (dy_is_f32) RP_LAUNCH_RR(1, 2, float); else RP_LAUNCH_RR(1, 2, bf16); }
+  else if (h <= 4096) { if (dy_is_f32) RP_LAUNCH_RR(2, 1, float); else RP_LAUNCH_RR(2, 1, bf16); }
+  else { if (dy_is_f32) RP_LAUNCH_RR(4, 2, float); else RP_LAUNCH_RR(4, 2, bf16); }
 #undef RP_LAUNCH_RR
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && dg) {

@@ -90,6 +90,24 @@ inline BlobLayout blob_layout(const rp_stage_cfg& c, bool grads) {
   return B;
 }
 
+// Tensors the library derives from the uploaded blob and keeps behind it in the device slot, per layer: the
+// block-diagonal LoRA B of the fused q|k|v and gate|up projections ([n1, n_qkv*r] and [2m, n_gu*r]; the adapted
+// projections' B matrices on the diagonal, zeros elsewhere), built once when the weights arrive instead of in every call.
+struct DerivedLayout {
+  size_t bd1 = 0, bd3 = 0, layer_bytes = 0, total = 0;
+};
+
+inline DerivedLayout derived_layout(const rp_stage_cfg& c) {
+  const Dims D = dims_of(c);
+  DerivedLayout L;
+  size_t o = 0;
+  if (D.n_qkv > 0) { L.bd1 = o; o = align_up(o + (size_t)D.n1 * (size_t)(D.n_qkv * D.r) * 2, 256); }
+  if (D.n_gu > 0) { L.bd3 = o; o = align_up(o + (size_t)2 * D.m * (size_t)(D.n_gu * D.r) * 2, 256); }
+  L.layer_bytes = o;
+  L.total = o * (size_t)(c.n_layers > 0 ? c.n_layers : 0);
+  return L;
+}
+
 // ---- workspace plan ---------------------------------------------------------------------------------------------
 struct LayerBuf {   // byte offsets of one layer's saved internals
   size_t z, rstd1, n1, qkv, rstd_q, rstd_k, qr, kr, o, lse, y, rstd2, n2, gu, act, u1, u2, u3, u4;
@@ -100,7 +118,7 @@ struct LayerBuf {   // byte offsets of one layer's saved internals
 };
 
 struct Plan {
-  size_t rope, bd1, bd3;                          // RoPE table, block-diagonal LoRA B of the fused GEMMs
+  size_t rope;                                    // RoPE table
   size_t layer0, layer_stride;                    // saved internals, one set per layer (backward) or one set (forward)
   size_t tA, tB, dact, dgu, dn, dout, dqr, dkr, dqkv, delta, ud, partials;   // backward temporaries
   size_t moe_f_fwd, moe_f_bwd;   // expert outputs / expert input gradients per slot [T*top_k, h] (transient in a layer)
@@ -145,8 +163,6 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
   const size_t set = o;
   o = 0;
   P.rope = take((size_t)seq * (D.d / 2) * 8);
-  P.bd1 = take((size_t)D.n1 * (size_t)(D.n_qkv * D.r) * 2);
-  P.bd3 = take((size_t)2 * D.m * (size_t)(D.n_gu * D.r) * 2);
   P.layer0 = o;
   P.layer_stride = set;
   // forward-only: one set plus a second z buffer for ping-pong

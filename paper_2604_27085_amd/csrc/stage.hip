@@ -73,6 +73,7 @@ struct rp_ctx {
   hipStream_t compute, copy;
   Slot slots[RP_MAX_SLOTS];
   BlobLayout wl, gl;
+  DerivedLayout dl;
   char err[512];
   // optional per-kernel timeline: one event before every enqueued op, one after the last
   bool tracing = false;
@@ -148,6 +149,7 @@ rp_status validate_shape(rp_ctx* ctx, int batch, int seq) {
 struct LayerW {
   const char* base;
   const BlobLayout* L;
+  const char* derived = nullptr;    // this layer's derived tensors (block-diagonal LoRA B) behind the blob in the slot
   const bf16_t* t(int id) const { return L->elems[id] ? reinterpret_cast<const bf16_t*>(base + L->off[id]) : nullptr; }
 };
 struct LayerG {
@@ -287,15 +289,16 @@ FusedLora fused_single(bool on, int a_id, int b_id, int rows) {
   return f;
 }
 
-// Builds the block-diagonal B [N, n*r] of a fused projection in the workspace; returns it (or the plain B when n == 1).
-const void* lora_b_matrix(Exec& X, const LayerW& W, const FusedLora& f, int N, size_t bd_off) {
+// The B operand of a fused projection's LoRA product: the block-diagonal B [N, n*r] kept behind the blob in the slot
+// (derived_off = its offset in the layer's derived tensors), or the plain B when one adapter covers the whole output.
+const void* lora_b_matrix(const LayerW& W, const FusedLora& f, int N, size_t derived_off) {
   if (f.n == 0) return nullptr;
   if (f.n == 1 && f.row0[0] == 0 && f.row1[0] == N) return W.t(f.b_id[0]);
-  LoraSegs s{};
-  for (int i = 0; i < f.n; ++i) { s.src[i] = W.t(f.b_id[i]); s.row0[i] = f.row0[i]; s.row1[i] = f.row1[i]; s.col0[i] = i * X.D.r; }
-  RUN(X, "lora_blockdiag", 0, 2.0 * N * f.n * X.D.r + 2.0 * N * X.D.r, k_lora_blockdiag(X.st, X.at<void>(bd_off), N, f.n * X.D.r, s, X.D.r));
-  return X.at<void>(bd_off);
+  return W.derived + derived_off;
 }
+
+// Enqueues on `st` the kernels that build layer `l`'s derived tensors from the layer's chunk in the slot.
+hipError_t build_derived(const rp_ctx* ctx, hipStream_t st, char* slot, int l);
 
 // Y[T,N] = X W^T (+ LoRA) (+ R).  u_buf receives U = s * X A^T (kept for the backward).
 void linear_fwd(Exec& X, const LayerW& W, int w_id, const FusedLora& f, size_t bd_off, const void* x, int K, void* y,
@@ -303,7 +306,7 @@ void linear_fwd(Exec& X, const LayerW& W, int w_id, const FusedLora& f, size_t b
   const int nr = f.n * X.D.r;
   const void* Bm = nullptr;
   if (f.n) {
-    Bm = lora_b_matrix(X, W, f, N, bd_off);
+    Bm = lora_b_matrix(W, f, N, bd_off);
     X.gemm_skinny_bf16(GEMM_NT, x, K, W.t(f.a_id[0]), K, u_buf, (int)X.T, nr, K, X.ctx->cfg.lora_scale);
   }
   X.gemm_bf16(GEMM_NT, x, K, W.t(w_id), K, y, N, (int)X.T, N, K, 1.f, f.n ? u_buf : nullptr, nr, Bm, nr, f.n ? nr : 0, R, N);
@@ -318,7 +321,7 @@ void linear_bwd(Exec& X, const LayerW& W, const LayerG& G, int w_id, const Fused
   void* ud = X.at<void>(X.P.ud);
   const void* Bm = nullptr;
   if (f.n) {
-    Bm = lora_b_matrix(X, W, f, N, bd_off);
+    Bm = lora_b_matrix(W, f, N, bd_off);
     X.gemm_skinny_bf16(GEMM_NN, dy, N, Bm, nr, ud, (int)X.T, nr, N, X.ctx->cfg.lora_scale);
   }
   if (sw_gu)
@@ -348,7 +351,7 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z, 
 
   const double Td = (double)T;
   RUN(X, "rmsnorm_fwd", 0, 4.0 * Td * D.h, k_rmsnorm_fwd(X.st, x, W.t(RP_T_G1), S(b.n1), (float*)S(b.rstd1), T, D.h, c.rms_eps));
-  linear_fwd(X, W, RP_T_WQKV, fused_qkv(D), X.P.bd1, S(b.n1), D.h, qkv, D.n1, S(b.u1), nullptr);
+  linear_fwd(X, W, RP_T_WQKV, fused_qkv(D), X.ctx->dl.bd1, S(b.n1), D.h, qkv, D.n1, S(b.u1), nullptr);
   RUN(X, "qknorm_rope_fwd", 0, 4.0 * Td * (D.qd + D.kd),
       k_qknorm_rope(X.st, 0, D.d, qkv, qkv + D.qd, D.n1, D.n1, S(b.qr), S(b.kr), D.qd, D.kd, W.t(RP_T_GQ), W.t(RP_T_GK),
                     (float*)S(b.rstd_q), (float*)S(b.rstd_k), nullptr, nullptr, 0, nullptr, nullptr, nullptr,
@@ -379,7 +382,7 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z, 
     RUN(X, "moe_combine", 0, 2.0 * Tkd * D.h + 4.0 * Td * D.h, k_moe_combine(X.st, f, slot_of, w, S(b.y), z, T, D.h, D.topk));
     return;
   }
-  linear_fwd(X, W, RP_T_WGU, fused_gu(D), X.P.bd3, S(b.n2), D.h, S(b.gu), 2 * D.m, S(b.u3), nullptr);
+  linear_fwd(X, W, RP_T_WGU, fused_gu(D), X.ctx->dl.bd3, S(b.n2), D.h, S(b.gu), 2 * D.m, S(b.u3), nullptr);
   RUN(X, "swiglu_fwd", 0, 6.0 * Td * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), T, D.m));
   linear_fwd(X, W, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, S(b.act), D.m, z, D.h, S(b.u4), S(b.y));
 }
@@ -430,7 +433,7 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
     // the SwiGLU backward rides in the epilogue of the down projection's input-gradient GEMM
     linear_bwd(X, W, G, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, dz, D.h, S(b.act), D.m,
                nullptr, S(b.u4), S(b.gu), X.at<void>(X.P.dgu));
-    linear_bwd(X, W, G, RP_T_WGU, fused_gu(D), X.P.bd3, X.at<void>(X.P.dgu), 2 * D.m, S(b.n2), D.h, X.at<void>(X.P.dn), S(b.u3));
+    linear_bwd(X, W, G, RP_T_WGU, fused_gu(D), X.ctx->dl.bd3, X.at<void>(X.P.dgu), 2 * D.m, S(b.n2), D.h, X.at<void>(X.P.dn), S(b.u3));
   }
   RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
       k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, S(b.y), W.t(RP_T_G2), (const float*)S(b.rstd2), dz, dy, G.t(RP_T_G2), X.at<float>(X.P.partials), T, D.h));
@@ -457,9 +460,28 @@ void layer_backward(Exec& X, const LayerW& W, const LayerG& G, char* set, const 
       k_qknorm_rope(X.st, 1, D.d, X.at<void>(X.P.dqr), X.at<void>(X.P.dkr), D.qd, D.kd, dqkv, dqkv + D.qd, D.n1, D.n1,
                     W.t(RP_T_GQ), W.t(RP_T_GK), (float*)S(b.rstd_q), (float*)S(b.rstd_k), qkv, qkv + D.qd, D.n1,
                     G.t(RP_T_GQ), G.t(RP_T_GK), X.at<float>(X.P.partials), X.at<float2>(X.P.rope), T, X.seq, D.a, D.kh, c.qk_norm, c.rms_eps));
-  linear_bwd(X, W, G, RP_T_WQKV, fused_qkv(D), X.P.bd1, dqkv, D.n1, S(b.n1), D.h, X.at<void>(X.P.dn), S(b.u1));
+  linear_bwd(X, W, G, RP_T_WQKV, fused_qkv(D), X.ctx->dl.bd1, dqkv, D.n1, S(b.n1), D.h, X.at<void>(X.P.dn), S(b.u1));
   RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
       k_rmsnorm_bwd(X.st, X.at<void>(X.P.dn), 0, x, W.t(RP_T_G1), (const float*)S(b.rstd1), dy, dx_out, G.t(RP_T_G1), X.at<float>(X.P.partials), T, D.h));
+}
+
+hipError_t build_derived(const rp_ctx* ctx, hipStream_t st, char* slot, int l) {
+  const Dims D = dims_of(ctx->cfg);
+  if (ctx->dl.layer_bytes == 0 || l >= ctx->cfg.n_layers) return hipSuccess;
+  const LayerW W{slot + ctx->wl.layer_bytes * (size_t)l, &ctx->wl, nullptr};
+  char* const out = slot + ctx->wl.total + ctx->dl.layer_bytes * (size_t)l;
+  hipError_t e = hipSuccess;
+  const FusedLora groups[2] = {fused_qkv(D), fused_gu(D)};
+  const int width[2] = {D.n1, 2 * D.m};
+  const size_t off[2] = {ctx->dl.bd1, ctx->dl.bd3};
+  for (int gi = 0; gi < 2 && e == hipSuccess; ++gi) {
+    const FusedLora& f = groups[gi];
+    if (f.n == 0) continue;
+    LoraSegs sg{};
+    for (int i = 0; i < f.n; ++i) { sg.src[i] = W.t(f.b_id[i]); sg.row0[i] = f.row0[i]; sg.row1[i] = f.row1[i]; sg.col0[i] = i * D.r; }
+    e = k_lora_blockdiag(st, out + off[gi], width[gi], f.n * D.r, sg, D.r);
+  }
+  return e;
 }
 
 rp_status check_call(rp_ctx* ctx, int slot_id, int batch, int seq, const void* ws, size_t ws_bytes, size_t need) {
@@ -508,6 +530,14 @@ rp_status rp_query_sizes(const rp_stage_cfg* cfg, int batch, int seq, size_t* we
   return RP_OK;
 }
 
+rp_status rp_slot_bytes(const rp_stage_cfg* cfg, size_t* slot_bytes) {
+  rp_status s = validate_cfg(cfg, nullptr);
+  if (s != RP_OK) return s;
+  if (!slot_bytes) return fail(nullptr, RP_EINVAL, "slot_bytes is NULL");
+  *slot_bytes = blob_layout(*cfg, false).total + derived_layout(*cfg).total;
+  return RP_OK;
+}
+
 static rp_status layout_query(const rp_stage_cfg* cfg, bool grads, int layer, int id, size_t* off, size_t* n) {
   rp_status s = validate_cfg(cfg, nullptr);
   if (s != RP_OK) return s;
@@ -551,6 +581,7 @@ rp_status rp_ctx_create(rp_ctx** out, int device, void* compute_stream, void* co
   c->copy = reinterpret_cast<hipStream_t>(copy_stream);
   c->wl = blob_layout(*cfg, false);
   c->gl = blob_layout(*cfg, true);
+  c->dl = derived_layout(*cfg);
   c->err[0] = 0;
   const int nev = cfg->n_layers + 1;
   for (int i = 0; i < RP_MAX_SLOTS; ++i) {
@@ -599,6 +630,7 @@ rp_status rp_stage_upload_weights(rp_ctx* ctx, int slot_id, void* dev_slot, cons
     const size_t b0 = ctx->wl.layer_bytes * (size_t)l;
     const size_t n = l == L ? ctx->wl.head_bytes : ctx->wl.layer_bytes;
     if (n) HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(dev_slot) + b0, static_cast<const char*>(host_blob) + b0, n, hipMemcpyHostToDevice, ctx->copy));
+    HIP_TRY(ctx, build_derived(ctx, ctx->copy, static_cast<char*>(dev_slot), l));   // behind the chunk it reads, before its event
     HIP_TRY(ctx, hipEventRecord(sl.ev[l], ctx->copy));
   }
   sl.dev = dev_slot; sl.bytes = bytes; sl.valid = true; sl.gated = true; sl.used = false;
@@ -612,6 +644,7 @@ rp_status rp_stage_bind_weights(rp_ctx* ctx, int slot_id, void* dev_slot, size_t
   if (bytes != ctx->wl.total) return fail(ctx, RP_EINVAL, "bytes %zu != weight blob size %zu", bytes, ctx->wl.total);
   if (reinterpret_cast<uintptr_t>(dev_slot) % 256) return fail(ctx, RP_EINVAL, "dev_slot must be 256-byte aligned");
   Slot& sl = ctx->slots[slot_id];
+  for (int l = 0; l < ctx->cfg.n_layers; ++l) HIP_TRY(ctx, build_derived(ctx, ctx->compute, static_cast<char*>(dev_slot), l));
   sl.dev = dev_slot; sl.bytes = bytes; sl.valid = true; sl.gated = false; sl.used = false;
   return RP_OK;
 }
@@ -640,7 +673,8 @@ rp_status rp_stage_forward(rp_ctx* ctx, int slot_id, const void* x_in, void* x_o
     if (s != RP_OK) return s;
     if (layer_inputs_out && layer_inputs_out[l] && layer_inputs_out[l] != x) RUN(X, "copy", 0, 2.0 * act_bytes, k_copy16(X.st, x, layer_inputs_out[l], (long)act_bytes));
     void* z = (l == L - 1) ? x_out : pp[l & 1];
-    const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
+    const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl,
+                     static_cast<const char*>(sl.dev) + ctx->wl.total + ctx->dl.layer_bytes * (size_t)l};
     if (router_logits) X.router = router_logits + (size_t)l * X.T * X.D.E;
     layer_forward(X, W, set, x, z, P.moe_f_fwd);
     x = z;
@@ -679,7 +713,8 @@ rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_
     for (int l = 0; l < L; ++l) {
       s = wait_chunk(ctx, sl, l);
       if (s != RP_OK) return s;
-      const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
+      const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl,
+                     static_cast<const char*>(sl.dev) + ctx->wl.total + ctx->dl.layer_bytes * (size_t)l};
       void* z = set_of(l) + P.lb.z;
       if (router_logits) X.router = router_logits + (size_t)l * X.T * X.D.E;
       layer_forward(X, W, set_of(l), x, z, P.moe_f_bwd);
@@ -694,7 +729,8 @@ rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const void* x_
       s = wait_chunk(ctx, sl, l);
       if (s != RP_OK) return s;
     }
-    const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl};
+    const LayerW W{static_cast<const char*>(sl.dev) + ctx->wl.layer_bytes * (size_t)l, &ctx->wl,
+                     static_cast<const char*>(sl.dev) + ctx->wl.total + ctx->dl.layer_bytes * (size_t)l};
     const LayerG G{grads ? static_cast<char*>(grads) + ctx->gl.layer_bytes * (size_t)l : nullptr, &ctx->gl};
     const void* xl = l == 0 ? x_in : set_of(l - 1) + P.lb.z;
     void* dxl = l == 0 ? dx : X.at<void>(P.tB);
@@ -1129,6 +1165,7 @@ rp_status round_run(rp_ctx* ctx, int slot_id, const rp_round_io* io, bool backwa
   ctx->round_parity ^= 1;
   if (up) {   // every chunk of the next slot is complete once the copy stream gets here
     Slot& nx = ctx->slots[io->next_slot];
+    for (int l = 0; l < ctx->cfg.n_layers; ++l) HIP_TRY(ctx, build_derived(ctx, ctx->copy, static_cast<char*>(io->next_dev_slot), l));
     for (int l = 0; l <= ctx->cfg.n_layers; ++l) HIP_TRY(ctx, hipEventRecord(nx.ev[l], ctx->copy));
     nx.dev = io->next_dev_slot; nx.bytes = ctx->wl.total; nx.valid = true; nx.gated = true; nx.used = false;
   }

@@ -150,7 +150,8 @@ class StageRunner:
         self.copy = torch.cuda.Stream(device=self.device)
         self.wbytes, self.gbytes, self.wsbytes = B.rp_query_sizes(cfg, batch, seq)
         self.ctx = B.rp_ctx_create(self.device.index or 0, self.compute.cuda_stream, self.copy.cuda_stream, cfg)
-        self.slots = [torch.empty(self.wbytes, dtype=torch.uint8, device=self.device) for _ in range(n_slots)]
+        self.slot_bytes = B.rp_slot_bytes(cfg)      # the blob plus the tensors the library derives from it
+        self.slots = [torch.empty(self.slot_bytes, dtype=torch.uint8, device=self.device) for _ in range(n_slots)]
         self.ws = torch.empty(self.wsbytes, dtype=torch.uint8, device=self.device)
         # the head gets a workspace of its own so that it can run between the two phases of a fused last stage
         self.ws_head = self.ws

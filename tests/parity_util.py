@@ -98,7 +98,7 @@ def gpu_chain(c, wl, harness, grad_scale=1.0, use_upload=True, fused=False):
         if use_upload:
             R.upload(host)
         else:
-            R.slots[0].copy_(host)
+            R.slots[0][:R.wbytes].copy_(host)
             torch.cuda.synchronize()
             R.bind()
         x = harness.bf16_tensor(wl["x"], R.device)
