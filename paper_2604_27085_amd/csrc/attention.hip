@@ -38,6 +38,7 @@ struct AttnArgs {
   int batch, seq, a, kh;
   float scale_log2e, scale;
   int fold;   // see heavy_rank()
+  int kblock; // dK/dV kernel: key tiles per run of one head in an XCD's launch order (0: key-tile-major order over all heads)
 };
 
 // Launch position -> rank in the order "heaviest workgroup first".  A kernel that keeps two workgroups per CU and whose
@@ -47,6 +48,12 @@ struct AttnArgs {
 // tokens, while pairing neighbouring positions instead made it 20 % slower).  Larger grids are handed out as
 // workgroups finish, where heaviest-first is the right order.
 RP_DEV int heavy_rank(int pos, int n, int fold) { return (fold && pos >= 256) ? n - 1 - (pos - 256) : pos; }
+
+// Consecutive workgroups go to consecutive XCDs (eight, each with an L2 of its own).  The i-th of the nhb workgroups of a
+// query tile therefore takes head (i mod 8) * nhb/8 + i/8 instead of head i: an XCD then works on nhb/8 neighbouring query
+// heads, i.e. on one or two K/V heads with grouped queries, and its L2 fetches their K/V tiles once for all the workgroups
+// that stream them side by side -- instead of every XCD fetching every K/V head.
+RP_DEV int xcd_head(int i, int nhb) { return (nhb & 7) ? i : (i & 7) * (nhb >> 3) + (i >> 3); }
 
 RP_DEV rsrc_t seq_rsrc(const bf16* base, long ld, int seq, int D) {
   // covers rows 0..seq-1 of one head: later rows are out of range and read as zero
@@ -194,7 +201,7 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(cons
   const int nhb = p.a * p.batch;
   const int rank = heavy_rank((int)blockIdx.x, (int)gridDim.x, p.fold);
   const int qtile = nQ - 1 - rank / nhb;     // the heaviest query tiles of every head go first
-  const int hb = rank % nhb;
+  const int hb = xcd_head(rank % nhb, nhb);
   const int hq = hb % p.a, b = hb / p.a;
   const int g = hq / (p.a / p.kh);
   const int q0 = qtile * BQ, qw0 = q0 + w * 32 * QT;
@@ -408,7 +415,7 @@ __global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_bwd_dq_kernel(c
   const int nhb = p.a * p.batch;
   const int rank = heavy_rank((int)blockIdx.x, (int)gridDim.x, p.fold);
   const int qtile = nQ - 1 - rank / nhb;
-  const int hb = rank % nhb;
+  const int hb = xcd_head(rank % nhb, nhb);
   const int hq = hb % p.a, b = hb / p.a;
   const int g = hq / (p.a / p.kh);
   const int q0 = qtile * BQ, qw0 = q0 + w * 32 * QT;
@@ -555,8 +562,22 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nhb = p.a * p.batch;
-  const int kvt = (int)blockIdx.x / nhb;     // key tile 0 sees every query: heaviest first, for every head
-  const int hb = (int)blockIdx.x % nhb;
+  // Workgroups of one query head stream the same Q and dO tiles, a few tiles apart (key tile j starts at query tile 2j
+  // and all advance at the same pace).  Consecutive workgroups go to consecutive XCDs, so XCD x (launch positions x,
+  // x + 8, ...) takes nhb/8 neighbouring heads and walks them in runs of `kblock` key tiles: its 32 resident workgroups
+  // are two such runs, and the XCD's L2 fetches a Q/dO tile once for a whole run.  Key tile 0 sees every query, so the
+  // order is still heaviest first at the grain of a run; positions past the last key tile (ragged last run) exit.
+  int kvt, hb;
+  if (p.kblock) {
+    const int hp = nhb >> 3, per = hp * p.kblock;
+    const int s = (int)blockIdx.x >> 3, r = s % per;
+    hb = ((int)blockIdx.x & 7) * hp + r / p.kblock;
+    kvt = (s / per) * p.kblock + r % p.kblock;
+    if (kvt * 128 >= p.seq) return;          // uniform over the workgroup, before any barrier
+  } else {
+    kvt = (int)blockIdx.x / nhb;             // key tile 0 sees every query: heaviest first, for every head
+    hb = (int)blockIdx.x % nhb;
+  }
   const int hq = hb % p.a, b = hb / p.a;
   const int grp = p.a / p.kh;
   const int g = hq / grp;
@@ -843,7 +864,14 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
     return hipGetLastError();
   }
   if (part == 0) {
-    const int nk = ((seq + 127) / 128) * a * batch;   // one workgroup per 128 keys and query head
+    const int nkv = (seq + 127) / 128, nhb = a * batch;
+    int nk = nkv * nhb;                               // one workgroup per 128 keys and query head
+    // XCD-aware order (see the kernel) from 96 key tiles on: 5-7 % at 16-32 k tokens; below that the re-fetches it saves
+    // do not matter and the plain order balances the few rounds of workgroups better (4096 tokens: 10 % slower with it)
+    if (nhb % 8 == 0 && nkv >= 96) {
+      p.kblock = nkv >= 192 ? 32 : 16;
+      nk = ((nkv + p.kblock - 1) / p.kblock) * p.kblock * nhb;
+    }
     return d == 128 ? launch_dkv_fused<128>(st, p, nk) : launch_dkv_fused<64>(st, p, nk);
   } else {
     return d == 128 ? launch_dq<128, 1, 4>(st, p) : launch_dq<64, 1, 4>(st, p);

@@ -109,7 +109,8 @@ struct Cfg {
   static constexpr int WPS = (NW == 8) ? 2 : (SMEM * 2 <= 160 * 1024 ? 2 : 1);
 };
 
-template <int WGM, int WGN, int BK, bool TA, bool TB, int KG>
+// GATED: the conditional instance (a name of its own in profiles): returns at once unless *p.run_flag is set.
+template <int WGM, int WGN, int BK, bool TA, bool TB, int KG, bool GATED>
 __global__ void __launch_bounds__(WGM* WGN* KG * 64)
     __attribute__((amdgpu_waves_per_eu(Cfg<WGM, WGN, BK, TA, TB, KG>::WPS, Cfg<WGM, WGN, BK, TA, TB, KG>::WPS)))
     gemm_kernel(const GemmArgs p) {
@@ -124,6 +125,9 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   bf16* const sA1 = sB0 + LB::S::ELEMS;
   bf16* const sB1 = sA1 + LA::S::ELEMS;
 
+  if constexpr (GATED) {
+    if (*p.run_flag == 0) return;                      // uniform over the grid
+  }
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int kg = wave / C::NWT, wmn = wave % C::NWT;   // wave group, wave within the output tile
@@ -300,11 +304,11 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   epilogue(p, Mlim, acc, smem, wmn, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
 }
 
-template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1>
+template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1, bool GATED = false>
 hipError_t launch_one(hipStream_t st, const GemmArgs& a) {
   using C = Cfg<WGM, WGN, BK, TA, TB, KG>;
   static bool attr_done = false;
-  auto kern = gemm_kernel<WGM, WGN, BK, TA, TB, KG>;
+  auto kern = gemm_kernel<WGM, WGN, BK, TA, TB, KG, GATED>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return e;
@@ -318,6 +322,10 @@ hipError_t launch_one(hipStream_t st, const GemmArgs& a) {
 
 template <bool TA, bool TB>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& a, int tile) {
+  if (a.run_flag) {   // only the frozen head's conditional logits product: NT, 256x256 (checked by gemm_launch)
+    if constexpr (!TA && !TB) return launch_one<2, 4, 64, false, false, 1, true>(st, a);
+    return hipErrorInvalidValue;
+  }
   switch (tile) {
     case 1: return launch_one<2, 4, 64, TA, TB>(st, a);
     case 2: return launch_one<2, 2, 32, TA, TB>(st, a);
@@ -392,7 +400,7 @@ void gemm_zero_args(GemmArgs& a) {
 int gemm_ce_stats_partials(int M) { return 2 * ((M + 255) / 256); }
 
 int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
-  if (a.epi == EPI_CE_STATS || a.epi == EPI_F32_COLMAX) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
+  if (a.epi == EPI_CE_STATS || a.epi == EPI_F32_COLMAX || a.epi == EPI_CE_P) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
   if (tile_hint) return tile_hint;
   // the eight-wave 256x128 tile is used for the plain epilogues
   const bool plain = a.epi == EPI_BF16 || a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC;
@@ -408,6 +416,8 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   // 16-byte accesses everywhere: the output width and every leading dimension must keep rows aligned
   const bool out_f32 = a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC || a.epi == EPI_F32_COLMAX;
   if (a.epi == EPI_F32_COLMAX && (a.beta || !a.part || !a.labels || !a.zlab)) return hipErrorInvalidValue;
+  if (a.run_flag && (a.epi != EPI_F32_COLMAX || layout != GEMM_NT)) return hipErrorInvalidValue;
+  if (a.epi == EPI_CE_P && (!a.part || !a.labels || !a.zlab || !a.lse)) return hipErrorInvalidValue;
   if (a.N % 8 || a.K % 8 || a.lda % 8 || a.ldb % 8) return hipErrorInvalidValue;
   if (a.epi != EPI_CE_STATS && a.ldc % (out_f32 ? 4 : 8)) return hipErrorInvalidValue;
   if (a.R && a.ldr % 4) return hipErrorInvalidValue;

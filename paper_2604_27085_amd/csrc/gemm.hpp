@@ -20,8 +20,15 @@ enum {
   // The product is the gradient of act = silu(gate) * up ([M, N]); R holds gate | up ([M, 2N], row stride ldr) and
   // C ([M, 2N], row stride ldc) receives d gate | d up.  The product itself is rounded to bf16 on the way (as if it
   // had been stored) and never written.
-  EPI_SWIGLU_BWD = 6
+  EPI_SWIGLU_BWD = 6,
+  // rows = vocab, cols = tokens: C bf16 [rows, cols] = exp(min(acc - ref[col], CE_P_CLAMP)) against a per-token reference
+  // exponent (p.lse holds ref), plus per-column partials (maximum of acc in .x, fp32 sum of the exponentials in .y, one
+  // per 128 rows) and the label logit.  The frozen head's later vocabulary chunks: no logits go to memory.
+  EPI_CE_P = 7
 };
+// exp argument beyond which EPI_CE_P saturates; a chunk whose maximum exceeds ref + CE_P_LIMIT is redone the slow way
+#define RP_CE_P_CLAMP 64.0f
+#define RP_CE_P_LIMIT 60.0f
 
 struct GemmArgs {
   const void* A; const void* B;
@@ -47,6 +54,7 @@ struct GemmArgs {
   // 256x256 tiles, NT or NN, no second operand pair.
   const int4* grp_tab; const int* grp_ntiles; int grp_max_tiles; long grp_strideB; const int* row_map;
   int row_map_rows;            // rows of the A buffer that row_map indexes
+  const int* run_flag;         // optional [dev]: the kernel returns at once when *run_flag == 0 (conditional slow paths)
   int splits;                  // reduction slices (grid.y), chosen by gemm_launch
   int part_row0;               // first partial row this launch writes (2 per M tile)
   // Reduction split (EPI_F32 with beta): with a scratch buffer of at least splits * M * N floats the slices write

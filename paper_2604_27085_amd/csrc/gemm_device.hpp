@@ -136,7 +136,7 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
   unsigned char* const stg = smem + wave * STG_BYTES;
   const int rr = lane >> 3, cc = lane & 7;   // read-back: 8 rows per pass, 8 chunks of 16 bytes per row
 
-  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ || p.epi == EPI_SWIGLU_BWD) {
+  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ || p.epi == EPI_SWIGLU_BWD || p.epi == EPI_CE_P) {
     bf16* s16 = reinterpret_cast<bf16*>(stg);
     unsigned short* const h16 = reinterpret_cast<unsigned short*>(stg);
     // two rows of a column are converted by one instruction and go out as the halves of its result
@@ -146,7 +146,62 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
       d[0] = (unsigned short)pk;
       d[STG_LD] = (unsigned short)(pk >> 16);
     };
-    if (p.epi != EPI_CE_DZ) {
+    if (p.epi == EPI_CE_P) {
+      // p = exp(z - ref) for a frozen head's later vocabulary chunks: every lane owns token columns, so the chunk's
+      // per-token maximum and sum of exponentials over the wave's 128 rows come from the registers; rows past the end of
+      // the vocabulary are excluded from both (their staged values are never stored)
+      constexpr float LOG2E = 1.4426950408889634f;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = wcol0 + j * 32 + lr;
+        const bool colok = col < p.N;
+        const int lab = colok ? p.labels[col] - p.row_offset : -1;
+        const float nr = colok ? -LOG2E * p.lse[col] : 0.f;
+        const float cap = RP_CE_P_CLAMP * LOG2E;
+        float mx, sum = 0.f, sum2 = 0.f;
+        if (wrow0 + WAVE_M <= M) {   // wave-uniform: no row of the block is past the end
+          mx = column_max(acc, j);
+          if (__ballot(lab >= wrow0 && lab < wrow0 + WAVE_M)) {
+            float z = 0.f;
+            if (label_logit(acc, j, lab - wrow0 - 4 * lk, z)) p.zlab[col] = z;
+          }
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+              const float e0 = __builtin_amdgcn_exp2f(fminf(fmaf(acc[i][j][v], LOG2E, nr), cap));
+              const float e1 = __builtin_amdgcn_exp2f(fminf(fmaf(acc[i][j][v + 1], LOG2E, nr), cap));
+              sum += e0; sum2 += e1;
+              stage2(i, j, v, e0, e1);
+            }
+        } else {
+          mx = -INFINITY;
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+              const int row = wrow0 + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+              float e0 = 0.f, e1 = 0.f;
+              if (row < M) {
+                mx = fmaxf(mx, acc[i][j][v]);
+                if (row == lab) p.zlab[col] = acc[i][j][v];
+                e0 = __builtin_amdgcn_exp2f(fminf(fmaf(acc[i][j][v], LOG2E, nr), cap));
+              }
+              if (row + 1 < M) {
+                mx = fmaxf(mx, acc[i][j][v + 1]);
+                if (row + 1 == lab) p.zlab[col] = acc[i][j][v + 1];
+                e1 = __builtin_amdgcn_exp2f(fminf(fmaf(acc[i][j][v + 1], LOG2E, nr), cap));
+              }
+              sum += e0; sum2 += e1;
+              stage2(i, j, v, e0, e1);
+            }
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        }
+        sum += sum2;
+        sum += __shfl_xor(sum, 32, 64);
+        if (lk == 0 && colok) p.part[(long)part_row * p.part_ld + col] = make_float2(mx, sum);
+      }
+    } else if (p.epi != EPI_CE_DZ) {
       if (p.alpha == 1.f) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {

@@ -72,10 +72,14 @@ hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, flo
 // per-token reference exponent m (moved, with l rescaled and alpha set, when the chunk outgrows it by more than e^8),
 // l += row sums.  pmax [nparts][T]: the chunk's per-column maxima (.x), as the logits GEMM left them, one row per 128
 // vocabulary rows; the .y halves are overwritten (per-block row sums, added to l in row order: no atomics).
+// flag (optional, device): the reference and probability kernels return at once when *flag == 0 (the partial sums
+// already there are then added to l as they are).
 hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, float2* pmax, int nparts, int first, float* m,
-                             float* l, float* alpha, void* p);
-// acc[t, :] *= alpha[t] where alpha[t] != 1.
-hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int T, int h);
+                             float* l, float* alpha, void* p, const int* flag);
+// *flag = 1 when some token's maximum over the chunk (pmax .x) lies more than RP_CE_P_LIMIT above its reference m.
+hipError_t k_ce_chunk_check(hipStream_t st, const float2* pmax, int nparts, int T, const float* m, int* flag);
+// acc[t, :] *= alpha[t] where alpha[t] != 1 (nothing when flag is given and *flag == 0).
+hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int T, int h, const int* flag);
 hipError_t k_ce_lse_from_ref(hipStream_t st, const float* m, const float* l, float* lse, int T);
 // acc[t, :] = coef[t] * (acc[t, :] / l[t] - W[labels[t], :]) (zero where coef is zero).
 hipError_t k_ce_frozen_dx(hipStream_t st, float* acc, const float* l, const float* coef, const int* labels, const void* W, int T, int h,

@@ -130,7 +130,8 @@ struct Plan {
   size_t fwd_bytes, bwd_bytes;
   // head
   size_t h_xf, h_rstd, h_part, h_zlab, h_lse, h_coef, h_dzt, h_dxacc, h_partials, head_bytes;
-  size_t h_z, h_m, h_l, h_alpha;   // frozen head: fp32 logits of one chunk, reference exponent, normaliser, rescale factor
+  size_t h_z, h_m, h_l, h_alpha, h_flag;   // frozen head: fp32 logits of one chunk, reference exponent, normaliser, rescale
+                                           // factor, the flag that switches a chunk's slow path on
   int head_chunk, head_parts;
   LayerBuf lb;                                    // offsets relative to a layer set
 };
@@ -202,7 +203,7 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
     P.h_split = take(RP_SPLITK_WS_BYTES);
     if (!c.train_base) {
       P.h_z = take((size_t)P.head_chunk * T * 4);
-      P.h_m = take(T * 4); P.h_l = take(T * 4); P.h_alpha = take(T * 4);
+      P.h_m = take(T * 4); P.h_l = take(T * 4); P.h_alpha = take(T * 4); P.h_flag = take(4);
     }
   }
   P.head_bytes = o;

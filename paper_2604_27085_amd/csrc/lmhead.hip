@@ -3,6 +3,7 @@
 // per-token gradient coefficient.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "gemm.hpp"
 
 namespace {
 
@@ -71,6 +72,10 @@ __global__ void __launch_bounds__(1024) ce_finalize_kernel(const float* __restri
 // exponent m_t, and acc_t = sum_v p_tv W_v, l_t = sum_v p_tv are carried from chunk to chunk; when a chunk's maximum
 // outgrows the reference by more than 2^8 (in e-units: 8), the reference moves and acc_t, l_t are rescaled.  At the end
 // lse_t = m_t + log l_t and dx_t = coef_t (acc_t / l_t - W[y_t]).
+//
+// After the first chunk the logits GEMM writes p itself (EPI_CE_P) against the reference as it stands, together with the
+// chunk's column maxima and sums; only when some token's maximum outgrows its reference by more than RP_CE_P_LIMIT does
+// the chunk take the path above (a device flag switches those kernels on; they return at once otherwise).
 
 constexpr int CE_PROB_ROWS = 128;
 
@@ -78,7 +83,8 @@ constexpr int CE_PROB_ROWS = 128;
 // be multiplied with (1 for most tokens and chunks).
 __global__ void __launch_bounds__(256) ce_chunk_ref_kernel(const float2* __restrict__ pmax, int nslab, int T, int first,
                                                            float* __restrict__ m, float* __restrict__ l,
-                                                           float* __restrict__ alpha) {
+                                                           float* __restrict__ alpha, const int* __restrict__ run_flag) {
+  if (run_flag && *run_flag == 0) return;
   const int t = blockIdx.x * 256 + threadIdx.x;
   if (t >= T) return;
   float cm = -INFINITY;
@@ -98,7 +104,8 @@ __global__ void __launch_bounds__(256) ce_chunk_ref_kernel(const float2* __restr
 // partials per CE_PROB_ROWS vocabulary rows): no atomics, ce_chunk_sum_kernel adds the rows in order.
 __global__ void __launch_bounds__(256) ce_chunk_prob_kernel(const float* __restrict__ z, int vc, int T,
                                                             const float* __restrict__ m, bf16* __restrict__ p,
-                                                            float2* __restrict__ part) {
+                                                            float2* __restrict__ part, const int* __restrict__ run_flag) {
+  if (run_flag && *run_flag == 0) return;
   const int t = (blockIdx.x * 256 + threadIdx.x) * 4;      // four tokens per thread: 16-byte loads, 8-byte stores
   if (t >= T) return;
   const int r0 = blockIdx.y * CE_PROB_ROWS, r1 = min(r0 + CE_PROB_ROWS, vc);
@@ -122,6 +129,19 @@ __global__ void __launch_bounds__(256) ce_chunk_prob_kernel(const float* __restr
   row[0].y = s.x; row[1].y = s.y; row[2].y = s.z; row[3].y = s.w;
 }
 
+// Sets *flag when a token's maximum over the chunk (the .x halves of the partial rows) lies more than RP_CE_P_LIMIT
+// above its reference exponent: the probabilities EPI_CE_P wrote for this chunk are then replaced.
+__global__ void __launch_bounds__(256) ce_chunk_check_kernel(const float2* __restrict__ pmax, int nslab, int T,
+                                                             const float* __restrict__ m, int* __restrict__ flag) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int r0 = blockIdx.y * 8, r1 = min(r0 + 8, nslab);   // eight partial rows per thread
+  const float lim = m[t] + RP_CE_P_LIMIT;
+  bool over = false;
+  for (int i = r0; i < r1; ++i) over |= pmax[(long)i * T + t].x > lim;
+  if (over) *flag = 1;   // every writer stores the same value
+}
+
 // l[t] += sum over the chunk's partial rows of part[i][t].y, in row order.
 __global__ void __launch_bounds__(256) ce_chunk_sum_kernel(const float2* __restrict__ part, int nslab, int T, float* __restrict__ l) {
   const int t = blockIdx.x * 256 + threadIdx.x;
@@ -137,7 +157,9 @@ __global__ void __launch_bounds__(256) ce_chunk_sum_kernel(const float2* __restr
 }
 
 // acc[t, :] *= alpha[t] for the rows whose reference moved.  One wave per row.
-__global__ void __launch_bounds__(256) ce_rescale_rows_kernel(float* __restrict__ acc, const float* __restrict__ alpha, int T, int h) {
+__global__ void __launch_bounds__(256) ce_rescale_rows_kernel(float* __restrict__ acc, const float* __restrict__ alpha, int T, int h,
+                                                              const int* __restrict__ run_flag) {
+  if (run_flag && *run_flag == 0) return;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (t >= T) return;
   const float a = alpha[t];
@@ -180,20 +202,26 @@ __global__ void __launch_bounds__(256) ce_frozen_dx_kernel(float* __restrict__ a
 }  // namespace
 
 hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, float2* pmax, int nparts, int first, float* m,
-                             float* l, float* alpha, void* p) {
+                             float* l, float* alpha, void* p, const int* flag) {
   if (T == 0 || vc == 0) return hipSuccess;
   const int nblk = (vc + CE_PROB_ROWS - 1) / CE_PROB_ROWS;
   if (T % 4 || nblk > nparts) return hipErrorInvalidValue;   // one partial row per CE_PROB_ROWS vocabulary rows
-  RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float2*)pmax, nparts, T, first, m, l, alpha);
-  RP_LAUNCH(ce_chunk_prob_kernel, dim3((T / 4 + 255) / 256, nblk), dim3(256), 0, st, z, vc, T, (const float*)m, (bf16*)p, pmax);
+  RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float2*)pmax, nparts, T, first, m, l, alpha, flag);
+  RP_LAUNCH(ce_chunk_prob_kernel, dim3((T / 4 + 255) / 256, nblk), dim3(256), 0, st, z, vc, T, (const float*)m, (bf16*)p, pmax, flag);
   RP_LAUNCH(ce_chunk_sum_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (const float2*)pmax, nblk, T, l);
   return hipGetLastError();
 }
 
-hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int T, int h) {
+hipError_t k_ce_chunk_check(hipStream_t st, const float2* pmax, int nparts, int T, const float* m, int* flag) {
+  if (T == 0) return hipSuccess;
+  RP_LAUNCH(ce_chunk_check_kernel, dim3((T + 255) / 256, (nparts + 7) / 8), dim3(256), 0, st, pmax, nparts, T, m, flag);
+  return hipGetLastError();
+}
+
+hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int T, int h, const int* flag) {
   if (T == 0) return hipSuccess;
   if (h % 4) return hipErrorInvalidValue;
-  RP_LAUNCH(ce_rescale_rows_kernel, dim3((T + 3) / 4), dim3(256), 0, st, acc, alpha, T, h);
+  RP_LAUNCH(ce_rescale_rows_kernel, dim3((T + 3) / 4), dim3(256), 0, st, acc, alpha, T, h, flag);
   return hipGetLastError();
 }
 

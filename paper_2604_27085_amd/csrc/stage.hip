@@ -191,7 +191,7 @@ struct Exec {
     static const char* til[6] = {"", "256x256", "256x128", "128x128", "128x64", "256x128k2"};
     char nm[40];
     snprintf(nm, sizeof(nm), "gemm_%s_%s", til[gemm_pick_tile(g)], lay[layout]);
-    const double out_b = (g.epi == EPI_BF16 || g.epi == EPI_CE_DZ) ? 2.0
+    const double out_b = (g.epi == EPI_BF16 || g.epi == EPI_CE_DZ || g.epi == EPI_CE_P) ? 2.0
                          : g.epi == EPI_SWIGLU_BWD ? 4.0 : (g.epi == EPI_CE_STATS ? 0.0 : 4.0 * (1 + g.beta));
     mark(nm, 2.0 * g.M * (double)g.N * ((double)g.K + g.K2),
          2.0 * ((double)g.M * g.K + (double)g.N * g.K + (double)g.M * g.K2 + (double)g.N * g.K2) + out_b * g.M * (double)g.N +
@@ -773,20 +773,37 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
     // -> acc_t += p W_c;  finally lse_t = m_t + log l_t and dx_t = coef_t (acc_t / l_t - W[y_t]).
     float* const zc = X.at<float>(P.h_z);
     float* const acc = X.at<float>(P.h_dxacc);
+    int* const flag = X.at<int>(P.h_flag);
     RUN(X, "fill", 0, 4.0 * Td * D.h, k_fill_u32(X.st, acc, (long)T * D.h, 0u));
+    RUN(X, "fill", 0, 4.0, k_fill_u32(X.st, flag, 1, 0u));
     for (int v0 = 0, ci = 0; v0 < D.V; v0 += P.head_chunk, ++ci) {
       const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
+      const int nparts = gemm_ce_stats_partials(vc);
       const bf16_t* Wc = Wv + (size_t)v0 * D.h;
       GemmArgs g; gemm_zero_args(g);
-      g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h; g.epi = EPI_F32_COLMAX;
-      g.C = zc; g.ldc = T; g.labels = labels; g.zlab = X.at<float>(P.h_zlab); g.part = X.at<float2>(P.h_part); g.part_ld = T;
+      g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h;
+      g.ldc = T; g.labels = labels; g.zlab = X.at<float>(P.h_zlab); g.part = X.at<float2>(P.h_part); g.part_ld = T;
       g.row_offset = v0;
-      X.mark_gemm(GEMM_NT, g);
+      if (ci > 0) {
+        // the probabilities straight from the accumulators, against the reference as it stands; the chunk is redone
+        // below only if a token outgrew its reference by too much for that (the flag stays 0 otherwise)
+        GemmArgs f = g;
+        f.epi = EPI_CE_P; f.C = X.at<void>(P.h_dzt); f.lse = X.at<float>(P.h_m);
+        X.mark_gemm(GEMM_NT, f);
+        X.chk(gemm_launch(X.st, GEMM_NT, f), "lm head probabilities");
+        RUN(X, "ce_chunk_check", 0, 8.0 * nparts * Td, k_ce_chunk_check(X.st, X.at<float2>(P.h_part), nparts, T, X.at<float>(P.h_m), flag));
+        g.run_flag = flag;
+      }
+      g.epi = EPI_F32_COLMAX; g.C = zc;
+      if (ci == 0) X.mark_gemm(GEMM_NT, g); else X.mark("ce_slow_path", 0, 0);
       X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head logits");
-      RUN(X, "ce_chunk_update", 0, 6.0 * vc * Td,
-          k_ce_chunk_update(X.st, zc, vc, T, X.at<float2>(P.h_part), gemm_ce_stats_partials(vc), ci == 0, X.at<float>(P.h_m),
-                            X.at<float>(P.h_l), X.at<float>(P.h_alpha), X.at<void>(P.h_dzt)));
-      if (ci > 0) RUN(X, "ce_rescale", 0, 4.0 * Td, k_ce_rescale_rows(X.st, acc, X.at<float>(P.h_alpha), T, D.h));
+      RUN(X, ci == 0 ? "ce_chunk_update" : "ce_slow_path", 0, ci == 0 ? 6.0 * vc * Td : 8.0 * nparts * Td,
+          k_ce_chunk_update(X.st, zc, vc, T, X.at<float2>(P.h_part), nparts, ci == 0, X.at<float>(P.h_m),
+                            X.at<float>(P.h_l), X.at<float>(P.h_alpha), X.at<void>(P.h_dzt), ci == 0 ? nullptr : flag));
+      if (ci > 0) {
+        RUN(X, "ce_slow_path", 0, 0, k_ce_rescale_rows(X.st, acc, X.at<float>(P.h_alpha), T, D.h, flag));
+        RUN(X, "fill", 0, 4.0, k_fill_u32(X.st, flag, 1, 0u));   // every reader of the flag is behind it in the stream
+      }
       GemmArgs d; gemm_zero_args(d);   // acc[T, h] += p^T^T . W_c
       d.A = X.at<void>(P.h_dzt); d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = acc;
       d.ldc = D.h; d.beta = 1; d.epi = EPI_F32;
