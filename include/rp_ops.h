@@ -17,7 +17,9 @@ extern "C" {
  * (A2, B2, K2): optional second operand pair, same layout, appended to the reduction (LoRA up-projection).
  * K, K2 and all leading dimensions are multiples of 8; N (and M for layout 2) too when that operand is transposed.
  * tile 0 = automatic, 1..4 force 256x256, 256x128, 128x128, 128x64; 5 = 256x128 worked on by two wave groups that
- * split every K tile (for outputs too small to fill the chip with 256x256 tiles).
+ * split every K tile (for outputs too small to fill the chip with 256x256 tiles); 6 = 256x256 with B (and B2) given
+ * in fragment order (rp_op_gemm_arrange; ldb, ldb2 unused; layouts 0 and 1): that operand is streamed into registers
+ * without passing through LDS.
  * split_ws [dev, split_ws_bytes] or NULL: scratch for a reduction split.  An accumulating fp32 product (out_f32 1 with
  * beta) whose 256x256 tiles would leave most compute units idle is cut into up to 16 slices along K when the scratch
  * holds slices * M * N floats; the slices' partial products are added to C in slice order by a second kernel, so the
@@ -26,6 +28,13 @@ extern "C" {
 RP_API rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const void* B, void* C, int M, int N, int K,
                      long lda, long ldb, long ldc, float alpha, int beta, const void* A2, const void* B2, int K2, long lda2,
                      long ldb2, const void* R, long ldr, int tile, void* split_ws, size_t split_ws_bytes);
+
+/* The B operand of rp_op_gemm in the fragment order of the matrix instruction, for tile 6: B is [N, K] row-major
+ * (transposed 0: the operand of layout 0) or [K, N] row-major (transposed 1: layout 1), bf16, row stride ldb.
+ * out [dev, out_bytes]: ceil(N/64) * ceil(K/64) * 8192 bytes, columns and reduction indices past the end zero.
+ * The weights of the projections (App. B.2) are constant over a stage's micro-batches, so one arrangement per upload
+ * serves every call. */
+RP_API rp_status rp_op_gemm_arrange(void* stream, const void* B, long ldb, int N, int K, int transposed, void* out, size_t out_bytes);
 
 /* RMSNorm: y = x * rstd * g, rstd_t = (mean_j x_tj^2 + eps)^(-1/2); rstd fp32 [T] (may be NULL). */
 RP_API rp_status rp_op_rmsnorm_fwd(void* stream, const void* x, const void* g, void* y, float* rstd, int T, int h, float eps);

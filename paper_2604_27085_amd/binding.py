@@ -94,6 +94,7 @@ _SIGS = {
     "rp_trace_start": [_vp, _i],
     "rp_trace_stop": [_vp, C.POINTER(TraceRecord), _i, C.POINTER(_i)],
     "rp_op_gemm": [_vp, _i, _i, _vp, _vp, _vp, _i, _i, _i, _l, _l, _l, _f, _i, _vp, _vp, _i, _l, _l, _vp, _l, _i, _vp, _sz],
+    "rp_op_gemm_arrange": [_vp, _vp, _l, _i, _i, _i, _vp, _sz],
     "rp_op_rmsnorm_fwd": [_vp, _vp, _vp, _vp, _vp, _i, _i, _f],
     "rp_op_rmsnorm_bwd": [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i],
     "rp_op_rmsnorm_bwd_noalloc": [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i],
@@ -297,6 +298,10 @@ def rp_op_gemm(stream, layout, out_f32, A, B, Cm, M, N, K, lda, ldb, ldc, alpha=
     _check(lib.rp_op_gemm(stream, layout, out_f32, _ptr(A), _ptr(B), _ptr(Cm), M, N, K, lda, ldb, ldc, alpha, beta,
                           _ptr(A2), _ptr(B2), K2, lda2, ldb2, _ptr(R), ldr, tile, _ptr(split_ws),
                           split_ws.numel() * split_ws.element_size() if split_ws is not None else 0))
+
+
+def rp_op_gemm_arrange(stream, Bm, ldb, N, K, transposed, out):
+    _check(lib.rp_op_gemm_arrange(stream, _ptr(Bm), ldb, N, K, transposed, _ptr(out), out.numel() * out.element_size()))
 
 
 def rp_op_rmsnorm_fwd(stream, x, g, y, rstd, T_, h, eps):

@@ -110,7 +110,11 @@ struct Cfg {
 };
 
 // GATED: the conditional instance (a name of its own in profiles): returns at once unless *p.run_flag is set.
-template <int WGM, int WGN, int BK, bool TA, bool TB, int KG, bool GATED>
+// BD: the B operand does not pass through LDS.  p.B (and p.B2) point at copies in MFMA fragment order (gemm_arrange):
+// every wave streams the fragments of its 64 columns straight into registers, 1 KB per load instruction, through a ring
+// that holds one K tile and is refilled fragment by fragment right after a fragment's last MFMA -- a whole K tile of
+// latency per load.  Half of the LDS stores and a third of the LDS reads of the staged kernel go away.
+template <int WGM, int WGN, int BK, bool TA, bool TB, int KG, bool GATED, bool BD>
 __global__ void __launch_bounds__(WGM* WGN* KG * 64)
     __attribute__((amdgpu_waves_per_eu(Cfg<WGM, WGN, BK, TA, TB, KG>::WPS, Cfg<WGM, WGN, BK, TA, TB, KG>::WPS)))
     gemm_kernel(const GemmArgs p) {
@@ -175,9 +179,9 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   // every chunk rotates on its own: at its slot of K tile kt it is stored to LDS (it holds tile kt+1, loaded one
   // tile earlier) and immediately reloaded with tile kt+2, so global loads and LDS stores are spread evenly over
   // the MFMAs of a tile instead of arriving in bursts, and every load has a full tile of time to return.
-  constexpr int NLD = LA::NREG + LB::NREG;
+  static_assert(!BD || (KG == 1 && BK == 64), "the direct B path is built for one wave group and K tiles of 64");
+  constexpr int NLD = LA::NREG + (BD ? 0 : LB::NREG);
   static_assert(NLD % KSL == 0, "staging chunks do not divide over the steps of a K tile");
-  constexpr int PER = NLD / KSL;
   uint4 rg[NLD];
   struct Seg { bool second; int k0, Klim; };
   auto seg_of = [&](int kt_local) {
@@ -202,8 +206,24 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  // direct B path: fragment (ks, j) of K tile t of the wave's 64-column block blk lies at
+  // (((blk * tiles_in_segment + t) * KS + ks) * TN + j) KB of the arranged copy, 16 bytes per lane
+  [[maybe_unused]] uint4 bq[KS][TN];
+  [[maybe_unused]] const uint32_t bd_blk = (uint32_t)(n0 / WAVE_N + wn);
+  [[maybe_unused]] const uint32_t bd_nk2 = (uint32_t)((p.K2 + BK - 1) / BK);
+  [[maybe_unused]] auto bd_load = [&](int ks, int j, const Seg& sg) {
+    const uint32_t t = bd_blk * (sg.second ? bd_nk2 : (uint32_t)nk1) + (uint32_t)(sg.k0 / BK);
+    return buf_load16(sg.second ? rsB2 : rsB, ((t * KS + ks) * TN + j) * 1024u + (uint32_t)lane * 16u, 0u);
+  };
+
   if (nk > 0) {
     const Seg s0 = seg_of(0);
+    if constexpr (BD) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bq[ks][j] = bd_load(ks, j, s0);
+    }
 #pragma unroll
     for (int r = 0; r < NLD; ++r) load_chunk(r, s0);
 #pragma unroll
@@ -222,8 +242,10 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   auto load_frags = [&](int buf, const bf16* pa, const bf16* pb, int ks) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) af[buf][i] = read_frag<LDA, TA>(pa, i * 32, ks);
+    if constexpr (!BD) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[buf][j] = read_frag<LDB, TB>(pb, j * 32, ks);
+      for (int j = 0; j < TN; ++j) bfr[buf][j] = read_frag<LDB, TB>(pb, j * 32, ks);
+    }
   };
   // One K tile.  STORE: tile kt+1 exists (its chunks are in the staging registers); LOAD: tile kt+2 exists.
   // The tile is a flat sequence of S = KSL * NM slots, one MFMA each, followed by that slot's share of the memory
@@ -233,7 +255,7 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   //   - before slot S-4 the workgroup barrier: by then every wave has stored its chunks of tile kt+1 and has all its
   //     fragments of tile kt in registers, so the first fragments of tile kt+1 are read under the last four MFMAs
   //     and the next tile may overwrite this tile's buffer.
-  constexpr int NM = TM * TN, NF = TM + TN, S = KSL * NM, TAIL = 4;
+  constexpr int NM = TM * TN, NF = TM + (BD ? 0 : TN), S = KSL * NM, TAIL = 4;
   static_assert(NF <= NM && KSL % 2 == 0 && NLD <= S - TAIL, "slot plan does not fit");
   load_frags(0, sA0 + offA, sB0 + offB, ks0);
   auto tile = [&](int kt, auto store_tag, auto load_tag) {
@@ -243,21 +265,26 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
     bf16* const na = (kt & 1) ? sA0 : sA1;
     bf16* const nb = (kt & 1) ? sB0 : sB1;
     const Seg sg = seg_of(kt + 2);
+    [[maybe_unused]] const Seg sg1 = seg_of(kt + 1);
 #pragma unroll
     for (int sl = 0; sl < S; ++sl) {
       const int ks = sl / NM, I = sl % NM, cur = ks & 1;
       if (STORE && sl == S - TAIL) __syncthreads();
-      acc[I / TN][I % TN] = mfma32(af[cur][I / TN], bfr[cur][I % TN], acc[I / TN][I % TN]);
+      if constexpr (BD) acc[I / TN][I % TN] = mfma32(af[cur][I / TN], bq[ks][I % TN], acc[I / TN][I % TN]);
+      else acc[I / TN][I % TN] = mfma32(af[cur][I / TN], bfr[cur][I % TN], acc[I / TN][I % TN]);
       if (ks + 1 < KSL && I < NF) {
         if (I < TM) af[cur ^ 1][I] = read_frag<LDA, TA>(pa, I * 32, ks0 + ks + 1);
-        else bfr[cur ^ 1][I - TM] = read_frag<LDB, TB>(pb, (I - TM) * 32, ks0 + ks + 1);
+        else if constexpr (!BD) bfr[cur ^ 1][I - TM] = read_frag<LDB, TB>(pb, (I - TM) * 32, ks0 + ks + 1);
       }
       if (STORE && sl >= S - TAIL) {   // first step of tile kt+1, from the other buffer, into the idle fragment set
 #pragma unroll
         for (int f = ((sl - (S - TAIL)) * NF) / TAIL; f < ((sl - (S - TAIL) + 1) * NF) / TAIL; ++f) {
           if (f < TM) af[0][f] = read_frag<LDA, TA>(na + offA, f * 32, ks0);
-          else bfr[0][f - TM] = read_frag<LDB, TB>(nb + offB, (f - TM) * 32, ks0);
+          else if constexpr (!BD) bfr[0][f - TM] = read_frag<LDB, TB>(nb + offB, (f - TM) * 32, ks0);
         }
+      }
+      if constexpr (BD && STORE) {   // this was the last MFMA of the tile that reads fragment (ks, j): refill it for tile kt+1
+        if (I >= NM - TN) bq[ks][I - (NM - TN)] = bd_load(ks, I - (NM - TN), sg1);
       }
 #pragma unroll
       for (int q = 0; q < NLD; ++q)
@@ -304,11 +331,11 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   epilogue(p, Mlim, acc, smem, wmn, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
 }
 
-template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1, bool GATED = false>
+template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1, bool GATED = false, bool BD = false>
 hipError_t launch_one(hipStream_t st, const GemmArgs& a) {
   using C = Cfg<WGM, WGN, BK, TA, TB, KG>;
   static bool attr_done = false;
-  auto kern = gemm_kernel<WGM, WGN, BK, TA, TB, KG, GATED>;
+  auto kern = gemm_kernel<WGM, WGN, BK, TA, TB, KG, GATED, BD>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return e;
@@ -324,6 +351,10 @@ template <bool TA, bool TB>
 hipError_t launch_tile(hipStream_t st, const GemmArgs& a, int tile) {
   if (a.run_flag) {   // only the frozen head's conditional logits product: NT, 256x256 (checked by gemm_launch)
     if constexpr (!TA && !TB) return launch_one<2, 4, 64, false, false, 1, true>(st, a);
+    return hipErrorInvalidValue;
+  }
+  if (a.b_direct) {   // B in fragment order: its memory layout no longer matters, one instance serves NT and NN
+    if constexpr (!TA) return launch_one<2, 4, 64, false, false, 1, false, true>(st, a);
     return hipErrorInvalidValue;
   }
   switch (tile) {
@@ -358,6 +389,33 @@ __global__ void __launch_bounds__(256) splitk_merge_kernel(const float* __restri
       *dst = acc;
     }
   }
+}
+
+// One 16-byte chunk of the fragment order per thread (see gemm_arranged_bytes).
+__global__ void __launch_bounds__(256) gemm_arrange_kernel(const bf16* __restrict__ B, long ldb, int N, int K, int transposed,
+                                                           uint4* __restrict__ out, long chunks, int nkt) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= chunks) return;
+  const int lane = (int)(idx & 63);
+  const long f = idx >> 6;
+  const int j = (int)(f & 1), ks = (int)((f >> 1) & 3);
+  const long t = f >> 3;
+  const int kt = (int)(t % nkt);
+  const int blk = (int)(t / nkt);
+  const int n = blk * 64 + j * 32 + (lane & 31), k = kt * 64 + ks * 16 + (lane >> 5) * 8;
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (n < N && k < K) {   // K is a multiple of 8: the eight indices are in range together
+    if (!transposed) {
+      v = *reinterpret_cast<const uint4*>(B + (long)n * ldb + k);
+    } else {
+      const unsigned short* src = reinterpret_cast<const unsigned short*>(B) + (long)k * ldb + n;
+      unsigned short e[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) e[i] = src[(long)i * ldb];
+      v = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16), e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+    }
+  }
+  out[idx] = v;
 }
 
 // Picks the tile with the smallest modelled time: n = workgroups on the busiest CU, each costing its area divided by
@@ -399,7 +457,19 @@ void gemm_zero_args(GemmArgs& a) {
 
 int gemm_ce_stats_partials(int M) { return 2 * ((M + 255) / 256); }
 
+size_t gemm_arranged_bytes(int N, int K) { return (size_t)((N + 63) / 64) * (size_t)((K + 63) / 64) * 8192; }
+
+hipError_t gemm_arrange(hipStream_t st, const void* B, long ldb, int N, int K, int transposed, void* out) {
+  if (N <= 0 || K <= 0) return hipSuccess;
+  if (!B || !out || K % 8 || ldb % 8 || (transposed && N % 8)) return hipErrorInvalidValue;
+  const long chunks = (long)(gemm_arranged_bytes(N, K) / 16);
+  RP_LAUNCH(gemm_arrange_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, (const bf16*)B, ldb, N, K, transposed,
+            (uint4*)out, chunks, (K + 63) / 64);
+  return hipGetLastError();
+}
+
 int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
+  if (a.b_direct) return 1;
   if (a.epi == EPI_CE_STATS || a.epi == EPI_F32_COLMAX || a.epi == EPI_CE_P) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
   if (tile_hint) return tile_hint;
   // the eight-wave 256x128 tile is used for the plain epilogues
@@ -418,18 +488,25 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   if (a.epi == EPI_F32_COLMAX && (a.beta || !a.part || !a.labels || !a.zlab)) return hipErrorInvalidValue;
   if (a.run_flag && (a.epi != EPI_F32_COLMAX || layout != GEMM_NT)) return hipErrorInvalidValue;
   if (a.epi == EPI_CE_P && (!a.part || !a.labels || !a.zlab || !a.lse)) return hipErrorInvalidValue;
-  if (a.N % 8 || a.K % 8 || a.lda % 8 || a.ldb % 8) return hipErrorInvalidValue;
+  if (a.N % 8 || a.K % 8 || a.lda % 8 || (!a.b_direct && a.ldb % 8)) return hipErrorInvalidValue;
   if (a.epi != EPI_CE_STATS && a.ldc % (out_f32 ? 4 : 8)) return hipErrorInvalidValue;
   if (a.R && a.ldr % 4) return hipErrorInvalidValue;
   if (a.epi == EPI_SWIGLU_BWD && (!a.R || a.ldr % 8 || a.ldc % 8 || a.grp_tab)) return hipErrorInvalidValue;
   const bool ta = layout == GEMM_TN, tb = layout != GEMM_NT;
   if (ta && a.M % 8) return hipErrorInvalidValue;
   if (!a.A2 || !a.B2) a.K2 = 0;
-  if (a.K2 && (a.K2 % 8 || a.lda2 % 8 || a.ldb2 % 8)) return hipErrorInvalidValue;
+  if (a.K2 && (a.K2 % 8 || a.lda2 % 8 || (!a.b_direct && a.ldb2 % 8))) return hipErrorInvalidValue;
   a.bytesA = ta ? extent_bytes(a.K, a.M, a.lda) : extent_bytes(a.M, a.K, a.lda);
   a.bytesB = tb ? extent_bytes(a.K, a.N, a.ldb) : extent_bytes(a.N, a.K, a.ldb);
   a.bytesA2 = ta ? extent_bytes(a.K2, a.M, a.lda2) : extent_bytes(a.M, a.K2, a.lda2);
   a.bytesB2 = tb ? extent_bytes(a.K2, a.N, a.ldb2) : extent_bytes(a.N, a.K2, a.ldb2);
+  if (a.b_direct) {
+    if (ta || a.grp_tab || a.run_flag) return hipErrorInvalidValue;
+    const size_t b1 = gemm_arranged_bytes(a.N, a.K), b2 = a.K2 ? gemm_arranged_bytes(a.N, a.K2) : 0;
+    if (b1 >= ((size_t)1 << 31) || b2 >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    a.bytesB = (unsigned)b1;
+    a.bytesB2 = (unsigned)b2;
+  }
   // operands are addressed with 32-bit byte offsets
   if (a.bytesA == ~0u || a.bytesB == ~0u || a.bytesA2 == ~0u || a.bytesB2 == ~0u) return hipErrorInvalidValue;
   int tile = gemm_pick_tile(a, tile_hint);

@@ -55,6 +55,9 @@ struct GemmArgs {
   const int4* grp_tab; const int* grp_ntiles; int grp_max_tiles; long grp_strideB; const int* row_map;
   int row_map_rows;            // rows of the A buffer that row_map indexes
   const int* run_flag;         // optional [dev]: the kernel returns at once when *run_flag == 0 (conditional slow paths)
+  // B (and B2) are copies in MFMA fragment order made by gemm_arrange (ldb, ldb2 unused): the kernel streams them into
+  // registers without passing through LDS.  256x256 tile, NT or NN (the arrangement absorbs the difference), not grouped.
+  int b_direct;
   int splits;                  // reduction slices (grid.y), chosen by gemm_launch
   int part_row0;               // first partial row this launch writes (2 per M tile)
   // Reduction split (EPI_F32 with beta): with a scratch buffer of at least splits * M * N floats the slices write
@@ -76,3 +79,9 @@ void gemm_zero_args(GemmArgs& a);
 // Tile gemm_launch picks for these arguments: 1..4 = 256x256, 256x128, 128x128, 128x64 (8, 4, 2, 1 waves),
 // 5 = 256x128 with eight waves in two groups that split every K tile.
 int gemm_pick_tile(const GemmArgs& a, int tile_hint = 0);
+
+// Fragment order of a B operand for b_direct: blocks of 64 output columns x K tiles of 64, each 8 KB = 4 steps x 2
+// column halves x 64 lanes x 8 consecutive reduction indices; columns and reduction indices past the end are zero.
+// B is [N, K] row-major (transposed = 0: the NT operand) or [K, N] row-major (transposed = 1: the NN operand).
+size_t gemm_arranged_bytes(int N, int K);
+hipError_t gemm_arrange(hipStream_t st, const void* B, long ldb, int N, int K, int transposed, void* out);

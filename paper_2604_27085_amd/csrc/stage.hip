@@ -910,7 +910,7 @@ rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const
                      long ldb2, const void* R, long ldr, int tile, void* split_ws, size_t split_ws_bytes) {
   if (out_f32 < 0 || out_f32 > 3 || (out_f32 == 3 && !split_ws) || (split_ws && reinterpret_cast<uintptr_t>(split_ws) % 16))
     return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad out_f32 / split_ws");
-  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 5)
+  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 6)
     return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad arguments");
   if ((layout != GEMM_NT) && (N % 8 || (layout == GEMM_TN && M % 8))) return fail(nullptr, RP_EINVAL, "rp_op_gemm: transposed operands need multiples of 8");
   GemmArgs g; gemm_zero_args(g);
@@ -918,7 +918,15 @@ rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const
   g.A2 = A2; g.B2 = B2; g.K2 = (A2 && B2) ? K2 : 0; g.lda2 = lda2; g.ldb2 = ldb2; g.R = R; g.ldr = ldr;
   g.epi = out_f32 == 2 ? EPI_F32_ATOMIC : (out_f32 ? EPI_F32 : EPI_BF16);
   g.split_ws = static_cast<float*>(split_ws); g.split_ws_bytes = split_ws ? split_ws_bytes : 0; g.split_out_bf16 = out_f32 == 3;
+  if (tile == 6) { g.b_direct = 1; tile = 0; }   // B and B2 in fragment order (rp_op_gemm_arrange)
   hipError_t e = gemm_launch(reinterpret_cast<hipStream_t>(stream), layout, g, tile);
+  OP_RET(e);
+}
+
+rp_status rp_op_gemm_arrange(void* stream, const void* B, long ldb, int N, int K, int transposed, void* out, size_t out_bytes) {
+  if (!B || !out || N < 0 || K < 0 || K % 8 || ldb % 8 || (transposed && N % 8)) return fail(nullptr, RP_EINVAL, "rp_op_gemm_arrange: bad arguments");
+  if (out_bytes < gemm_arranged_bytes(N, K)) return fail(nullptr, RP_EINVAL, "rp_op_gemm_arrange: out holds %zu bytes, %zu needed", out_bytes, gemm_arranged_bytes(N, K));
+  hipError_t e = gemm_arrange(reinterpret_cast<hipStream_t>(stream), B, ldb, N, K, transposed, out);
   OP_RET(e);
 }
 

@@ -75,6 +75,53 @@ def test_gemm_layouts_ragged(rp, layout, tile):
     assert rel_l2(H.to_f32(Cm), -0.5 * ref) < 4e-3
 
 
+@pytest.mark.parametrize("layout", [0, 1])
+def test_gemm_b_operand_in_fragment_order(rp, layout):
+    """Tile 6: B (and the second pair's B) pre-arranged in the fragment order of the matrix instruction and streamed
+    into registers without LDS.  Against the fp64 product, and bit for bit against the staged 256x256 kernel (same
+    operand values, same order of multiply-adds).  Ragged everywhere: rows and columns against 256/64, K and K2 against
+    the K tile of 64; second operand pair, residual, fp32 accumulation."""
+    B, H = rp
+    rng = np.random.default_rng(300 + layout)
+    M, N, K, K2 = 584, 456, 712, 40
+    a, b = rnd(rng, (M, K)), rnd(rng, (N, K), 0.05)
+    u, bl = rnd(rng, (M, K2)), rnd(rng, (N, K2), 0.1)
+    res = rnd(rng, (M, N))
+    ref = a.astype(np.float64) @ b.T.astype(np.float64) + u.astype(np.float64) @ bl.T.astype(np.float64)
+    if layout == 0:
+        Bm, ldb, B2m, ldb2 = dev(H, b), K, dev(H, bl), K2
+    else:
+        Bm, ldb, B2m, ldb2 = dev(H, np.ascontiguousarray(b.T)), N, dev(H, np.ascontiguousarray(bl.T)), N
+    nblk = (N + 63) // 64
+    arr = torch.full((nblk * ((K + 63) // 64) * 4096,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    arr2 = torch.full((nblk * ((K2 + 63) // 64) * 4096,), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    B.rp_op_gemm_arrange(stream(), Bm, ldb, N, K, layout, arr)
+    B.rp_op_gemm_arrange(stream(), B2m, ldb2, N, K2, layout, arr2)
+    A, A2, R = dev(H, a), dev(H, u), dev(H, res)
+    outs = []
+    for tile, b1, b2, l1, l2 in ((1, Bm, B2m, ldb, ldb2), (6, arr, arr2, 0, 0)):
+        Cm = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+        B.rp_op_gemm(stream(), layout, 0, A, b1, Cm, M, N, K, K, l1, N, A2=A2, B2=b2, K2=K2, lda2=K2, ldb2=l2, R=R, ldr=N, tile=tile)
+        C32 = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda:0")
+        B.rp_op_gemm(stream(), layout, 1, A, b1, C32, M, N, K, K, l1, N, alpha=0.25, beta=1, A2=A2, B2=b2, K2=K2, lda2=K2, ldb2=l2, tile=tile)
+        Cp = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")     # no second pair
+        B.rp_op_gemm(stream(), layout, 0, A, b1, Cp, M, N, K, K, l1, N, tile=tile)
+        torch.cuda.synchronize()
+        outs.append((H.to_f32(Cm), C32.cpu().numpy(), H.to_f32(Cp)))
+    assert rel_l2(outs[1][0], ref + res) < 4e-3
+    assert rel_l2(outs[1][1], 0.25 * ref + 0.5) < 1e-5
+    assert rel_l2(outs[1][2], a.astype(np.float64) @ b.T.astype(np.float64)) < 4e-3
+    for got, want in zip(outs[1], outs[0]):
+        np.testing.assert_array_equal(got, want)
+    # the arrangement itself: zero padding and element order, from the definition
+    arr_h = H.to_f32(arr).reshape(nblk, (K + 63) // 64, 4, 2, 64, 8)
+    want = np.zeros((nblk * 64, ((K + 63) // 64) * 64), dtype=np.float32)
+    want[:N, :K] = b
+    want = want.reshape(nblk, 2, 32, (K + 63) // 64, 4, 2, 8)          # blk, j, lr, kt, ks, lk, e
+    want = want.transpose(0, 3, 4, 1, 5, 2, 6).reshape(nblk, (K + 63) // 64, 4, 2, 64, 8)   # lane = lk * 32 + lr
+    np.testing.assert_array_equal(arr_h, want)
+
+
 def test_gemm_second_pair_residual_and_atomic(rp):
     B, H = rp
     rng = np.random.default_rng(7)
