@@ -361,6 +361,35 @@ def measure(name, args, steps, warmup, full):
     return rec
 
 
+def gemm_probe(size, reps):
+    """The projection GEMM alone at M = N = K = size: the staged 256x256 kernel against the variant that streams a
+    pre-arranged B operand past LDS (tile 6), as NT and as NN.  One JSON line; for counter runs (--gemm-reps 3)."""
+    import torch
+    from paper_2604_27085_amd import binding as B
+    st = torch.cuda.current_stream().cuda_stream
+    M = N = K = size
+    a = (torch.randn(M, K, device="cuda") * 0.5).bfloat16()
+    c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    out = {"probe": "gemm", "M": M, "N": N, "K": K, "reps": reps}
+    for layout, lname in ((0, "NT"), (1, "NN")):
+        b = (torch.randn((N, K) if layout == 0 else (K, N), device="cuda") * 0.05).bfloat16()
+        ldb = K if layout == 0 else N
+        arr = torch.empty(((N + 63) // 64) * ((K + 63) // 64) * 4096, dtype=torch.bfloat16, device="cuda")
+        B.rp_op_gemm_arrange(st, b, ldb, N, K, layout, arr)
+        for tile, bb, l, tname in ((1, b, ldb, "staged"), (6, arr, 0, "b_direct")):
+            B.rp_op_gemm(st, layout, 0, a, bb, c, M, N, K, K, l, N, tile=tile)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                B.rp_op_gemm(st, layout, 0, a, bb, c, M, N, K, K, l, N, tile=tile)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / reps * 1e3
+            out["%s_%s" % (lname, tname)] = {"us": round(us, 1), "tflops": round(2.0 * M * N * K / us / 1e6, 1)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -374,6 +403,8 @@ def main():
     ap.add_argument("--round-streams", type=int, default=1, help="transfer streams per direction in the round leg (1 or 2)")
     ap.add_argument("--round-piece-mib", type=int, default=0, help="largest transfer piece in that leg (0 = the library's default)")
     ap.add_argument("--round-micro", type=int, default=4, help="micro-batches per round in the multi-stream leg")
+    ap.add_argument("--gemm-probe", type=int, default=0, help="only time the square GEMM of this size, staged against B-direct, and exit")
+    ap.add_argument("--gemm-reps", type=int, default=20)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures the one-GPU worker; a stage runs whole on one GPU and nothing here uses a "
@@ -381,6 +412,9 @@ def main():
         sys.exit(2)
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.gemm_probe:
+        gemm_probe(args.gemm_probe, args.gemm_reps)
+        return
 
     main_rec = measure(args.config, args, args.steps, args.warmup, True)
     others = {}
