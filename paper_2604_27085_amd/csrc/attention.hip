@@ -736,6 +736,216 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
   }
 }
 
+// The same products with two waves per SIMD.  A workgroup is eight waves: the 32 keys of key group w = wave / 2 are shared
+// by a pair of waves, and wave h = wave % 2 of the pair keeps the accumulators of one half of the head dimension only
+// (dK^T, dV^T rows [h*D/2, (h+1)*D/2): half the registers).  The scores need the whole head dimension, so the pair splits
+// them by queries instead: wave h recomputes S and dP for the 32 queries of half h of the tile, turns them into P and dS, and
+// hands both (already in the operand layout of the update products, identical in the two waves since they own the same
+// keys) to its partner through LDS.  Every wave then updates its half of the accumulators with its own 32 queries --
+// before the workgroup barrier that publishes the exchange -- and with the partner's 32 queries after it.  Same number of
+// MFMAs per workgroup as the one-wave-per-SIMD kernel, same LDS fragment traffic per CU, 8 KB of exchange per pair and tile.
+template <int D>
+__global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p) {
+  constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32, DH = DT / 2;
+  static_assert(DT % 2 == 0, "the head dimension is split over two waves");
+  using T64 = Tile64<D, 512>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);             // 2*64*LDK + 2 * 2*64*LDT elements, then the exchange
+  bf16* const Qs = smem;
+  bf16* const dOs = smem + 64 * LDK;
+  bf16* const Qt = smem + 2 * 64 * LDK;                             // Qt | dOt, two sets (tile parity)
+  constexpr int TSET = 2 * 64 * LDT;
+  uint4* const exch = reinterpret_cast<uint4*>(Qt + 2 * TSET);      // [8 waves][4 fragments][64 lanes]
+
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
+  const int w8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int w = w8 >> 1, h = w8 & 1;
+  const int nhb = p.a * p.batch;
+  int kvt, hb;                                 // launch order: see attn_bwd_dkv_fused_kernel
+  if (p.kblock) {
+    const int hp = nhb >> 3, per = hp * p.kblock;
+    const int s = (int)blockIdx.x >> 3, r = s % per;
+    hb = ((int)blockIdx.x & 7) * hp + r / p.kblock;
+    kvt = (s / per) * p.kblock + r % p.kblock;
+    if (kvt * 128 >= p.seq) return;
+  } else {
+    kvt = (int)blockIdx.x / nhb;
+    hb = (int)blockIdx.x % nhb;
+  }
+  const int hq = hb % p.a, b = hb / p.a;
+  const int grp = p.a / p.kh;
+  const int g = hq / grp;
+  const int kv0 = kvt * 128, kw0 = kv0 + 32 * w;
+  const long tok0 = (long)b * p.seq;
+  const bf16* kb = p.k + tok0 * p.ldk + g * D;
+  const bf16* vb = p.v + tok0 * p.ldv + g * D;
+  const int kpos = kw0 + lr;
+  const bool kok = kpos < p.seq;
+
+  uint4 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = make_uint4(0u, 0u, 0u, 0u);
+    vf[ks] = make_uint4(0u, 0u, 0u, 0u);
+    if (kok) {
+      kf[ks] = *reinterpret_cast<const uint4*>(kb + (long)kpos * p.ldk + 16 * ks + 8 * lk);
+      vf[ks] = *reinterpret_cast<const uint4*>(vb + (long)kpos * p.ldv + 16 * ks + 8 * lk);
+    }
+  }
+  f32x16 dkacc[DH], dvacc[DH];
+#pragma unroll
+  for (int dt = 0; dt < DH; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dkacc[dt][v] = 0.f; dvacc[dt][v] = 0.f; }
+
+  const int nQ = (p.seq + 63) / 64;
+  const int qt0 = kv0 / 64;
+  const int niter = nQ - qt0;
+
+  // this wave's 32 queries of a tile: rows 32*h .. 32*h + 31
+  const bf16* qfrag = Qs + (32 * h + lr) * LDK + 8 * lk;
+  const bf16* dofrag = dOs + (32 * h + lr) * LDK + 8 * lk;
+  const bf16* qx = Qs + (32 * h + lr) * LDK + D;
+  const bf16* dox = dOs + (32 * h + lr) * LDK + D;
+  // this wave's half of the head dimension: columns 32*DH*h .. of the transposed tiles
+  const bf16* qtfrag = Qt + tr_base<LDT>(lane) + 32 * DH * h;
+  const bf16* dotfrag = qtfrag + 64 * LDT;
+  const uint4 one_f = ones3(lk);
+  uint4* const ex_mine = exch + (w8 * 4) * 64 + lane;
+  const uint4* const ex_theirs = exch + ((w8 ^ 1) * 4) * 64 + lane;
+
+  uint4 qreg[T64::NREG], doreg[T64::NREG];
+  float st_reg = 0.f;
+  const rsrc_t rq = seq_rsrc(p.q + tok0 * p.ldq + hq * D, p.ldq, p.seq, D);
+  const rsrc_t rdo = seq_rsrc(p.dout + tok0 * p.lddo + hq * D, p.lddo, p.seq, D);
+  auto prefetch = [&](int it) {
+    const int q0 = (qt0 + it) * 64;
+    T64::load(qreg, rq, p.ldq, q0, tid);
+    T64::load(doreg, rdo, p.lddo, q0, tid);
+    if (tid < 128) {
+      const int qi = q0 + (tid & 63);
+      const long sidx = ((long)b * p.a + hq) * p.seq + (qi < p.seq ? qi : 0);
+      const float v = tid < 64 ? -p.lse_in[sidx] / p.scale : -p.delta[sidx];
+      st_reg = qi < p.seq ? v : (tid < 64 ? -3.0e4f : 0.f);
+    }
+  };
+  if (niter > 0) prefetch(0);
+
+#ifndef RP_PAIR_AHEAD
+#define RP_PAIR_AHEAD 2
+#endif
+#ifndef RP_PAIR_PRIO
+#define RP_PAIR_PRIO 1
+#endif
+  constexpr int AHEAD = RP_PAIR_AHEAD;     // two waves per SIMD cover each other's LDS latency: a short ring is enough
+  // the update products of one 32-query half t2 with the fragments pf (P) and df (dS): 4 * DH MFMAs
+  auto update_half = [&](int set, int t2, const uint4 (&pf)[2], const uint4 (&df)[2]) {
+    constexpr int NU = 4 * DH;
+    auto ufrag_at = [&](int n) {   // n = (g2 * DH + dt) * 2 + which
+      return read_frag_tr<LDT>(((n & 1) ? qtfrag : dotfrag) + set * TSET, 2 * t2 + n / (2 * DH), 32 * ((n >> 1) % DH));
+    };
+    uint4 uring[AHEAD];
+#pragma unroll
+    for (int n = 0; n < AHEAD; ++n) uring[n] = ufrag_at(n);
+    if (RP_PAIR_PRIO) MFMA_PHASE_BEGIN();
+#pragma unroll
+    for (int n = 0; n < NU; ++n) {
+      const uint4 a = uring[n % AHEAD];
+      if (n + AHEAD < NU) uring[n % AHEAD] = ufrag_at(n + AHEAD);
+      const int g2 = n / (2 * DH), dt = (n >> 1) % DH;
+      if (n & 1) dkacc[dt] = mfma32(a, df[g2], dkacc[dt]);
+      else dvacc[dt] = mfma32(a, pf[g2], dvacc[dt]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (RP_PAIR_PRIO) MFMA_PHASE_END();
+  };
+
+  // Two barriers per tile.  After the first one every wave is done with the previous tile's score phase and has
+  // published its fragments: the new tile is stored (the transposed tiles into the other set) and, meanwhile, the
+  // accumulators are updated with the partner's half of the PREVIOUS tile, whose transposed tiles are still in place.
+  auto partner_update = [&](int it_prev) {
+    const uint4 ppf[2] = {ex_theirs[0], ex_theirs[64]};
+    const uint4 pdf[2] = {ex_theirs[128], ex_theirs[192]};
+    update_half(it_prev & 1, h ^ 1, ppf, pdf);
+  };
+  for (int it = 0; it < niter; ++it) {
+    __syncthreads();
+    bf16* const qt_set = Qt + (it & 1) * TSET;
+    T64::template store<LDK>(qreg, Qs, tid);
+    T64::template store<LDT>(qreg, qt_set, tid);
+    T64::template store<LDK>(doreg, dOs, tid);
+    T64::template store<LDT>(doreg, qt_set + 64 * LDT, tid);
+    if (tid < 64) *reinterpret_cast<uint4*>(Qs + tid * LDK + D) = split3(st_reg);
+    else if (tid < 128) *reinterpret_cast<uint4*>(dOs + (tid - 64) * LDK + D) = split3(st_reg);
+    if (it > 0) partner_update(it - 1);
+    __syncthreads();
+    if (it + 1 < niter) prefetch(it + 1);
+    const int q0 = (qt0 + it) * 64;
+    const int qh0 = q0 + 32 * h;                                            // first query of this wave's half
+    const bool need_mask = (qh0 < kw0 + 31) || (kw0 + 32 > p.seq);          // wave-uniform
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 s = zero16, dp = zero16;
+    {
+      constexpr int NS = 2 * (KS + 1);
+      auto sfrag_at = [&](int n) {
+        const int ks = n >> 1;
+        const bf16* src = ks < KS ? ((n & 1) ? dofrag : qfrag) + 16 * ks : ((n & 1) ? dox : qx);
+        return *reinterpret_cast<const uint4*>(src);
+      };
+      uint4 ring[AHEAD];
+#pragma unroll
+      for (int n = 0; n < AHEAD; ++n) ring[n] = sfrag_at(n);
+      if (RP_PAIR_PRIO) MFMA_PHASE_BEGIN();
+#pragma unroll
+      for (int n = 0; n < NS; ++n) {
+        const uint4 a = ring[n % AHEAD];
+        if (n + AHEAD < NS) ring[n % AHEAD] = sfrag_at(n + AHEAD);
+        const int ks = n >> 1;
+        if (n & 1) dp = mfma32(a, ks < KS ? vf[ks] : one_f, dp);
+        else s = mfma32(a, ks < KS ? kf[ks] : one_f, s);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (RP_PAIR_PRIO) MFMA_PHASE_END();
+    }
+    // rows of the score tile are queries: q = qh0 + 8*(v/4) + 4*lk + v%4
+    if (need_mask) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int qpos = qh0 + 8 * (v >> 2) + 4 * lk + (v & 3);
+        float pr = fast_exp2(s[v] * p.scale_log2e);
+        pr = (kpos > qpos || !kok) ? 0.f : pr;
+        s[v] = pr;                         // P
+        dp[v] = pr * dp[v];                // dS
+      }
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float pr = fast_exp2(s[v] * p.scale_log2e);
+        s[v] = pr;
+        dp[v] = pr * dp[v];
+      }
+    }
+    const uint4 pfg[2] = {pack_frag(s, 0), pack_frag(s, 8)};
+    const uint4 dfg[2] = {pack_frag(dp, 0), pack_frag(dp, 8)};
+    // the partner read last tile's fragments before the barrier above: the slots are free
+    ex_mine[0] = pfg[0]; ex_mine[64] = pfg[1]; ex_mine[128] = dfg[0]; ex_mine[192] = dfg[1];
+    update_half(it & 1, h, pfg, dfg);
+  }
+  __syncthreads();
+  if (niter > 0) partner_update(niter - 1);
+  __syncthreads();
+  if (grp == 1) {
+    bf16* const stage = smem + w8 * 32 * (D / 2 + 8);
+    store_acc_T<D / 2>(dkacc, p.scale, stage, p.dk + tok0 * p.lddk + g * D + h * (D / 2), p.lddk, kw0, p.seq, lane);
+    store_acc_T<D / 2>(dvacc, 1.f, stage, p.dv + tok0 * p.lddv + g * D + h * (D / 2), p.lddv, kw0, p.seq, lane);
+  } else {
+    float* const stage = reinterpret_cast<float*>(smem) + w8 * 32 * (D / 2 + 4);
+    const long ldp = (long)p.a * D;
+    store_acc_T_f32<D / 2>(dkacc, p.scale, stage, p.dk_part + tok0 * ldp + hq * D + h * (D / 2), ldp, kw0, p.seq, lane);
+    store_acc_T_f32<D / 2>(dvacc, 1.f, stage, p.dv_part + tok0 * ldp + hq * D + h * (D / 2), ldp, kw0, p.seq, lane);
+  }
+}
+
 // dk[t, g, :] = sum over the query heads of group g of the fp32 partials, in head order; same for dv.
 template <int D>
 __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __restrict__ dk_part, const float* __restrict__ dv_part,
@@ -766,6 +976,7 @@ __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __res
 
 constexpr int dq_smem_bytes(int d) { return (2 * 64 * (d + 8) + 64 * (d + 32)) * 2; }
 constexpr int dkv_fused_smem_bytes(int d) { return (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
+constexpr int dkv_pair_smem_bytes(int d) { return (2 * 64 * (d + 8) + 4 * 64 * (d + 32)) * 2 + 8 * 4 * 64 * 16; }
 void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
   p.batch = batch; p.seq = seq; p.a = a; p.kh = kh;
   p.scale = 1.0f / sqrtf((float)d);
@@ -796,6 +1007,15 @@ hipError_t launch_dkv_fused(hipStream_t st, const AttnArgs& p, int grid) {
   hipError_t e = set_smem(attn_bwd_dkv_fused_kernel<D>, dkv_fused_smem_bytes(D), done);
   if (e != hipSuccess) return e;
   RP_LAUNCH((attn_bwd_dkv_fused_kernel<D>), dim3(grid), dim3(256), dkv_fused_smem_bytes(D), st, p);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_dkv_pair(hipStream_t st, const AttnArgs& p, int grid) {
+  static bool done = false;
+  hipError_t e = set_smem(attn_bwd_dkv_pair_kernel<D>, dkv_pair_smem_bytes(D), done);
+  if (e != hipSuccess) return e;
+  RP_LAUNCH((attn_bwd_dkv_pair_kernel<D>), dim3(grid), dim3(512), dkv_pair_smem_bytes(D), st, p);
   return hipGetLastError();
 }
 
@@ -872,6 +1092,10 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
       p.kblock = nkv >= 192 ? 32 : 16;
       nk = ((nkv + p.kblock - 1) / p.kblock) * p.kblock * nhb;
     }
+#ifndef RP_DKV_PAIR
+#define RP_DKV_PAIR 1
+#endif
+    if (d == 128 && RP_DKV_PAIR) return launch_dkv_pair<128>(st, p, nk);
     return d == 128 ? launch_dkv_fused<128>(st, p, nk) : launch_dkv_fused<64>(st, p, nk);
   } else {
     return d == 128 ? launch_dq<128, 1, 4>(st, p) : launch_dq<64, 1, 4>(st, p);
