@@ -187,11 +187,11 @@ RP_DEV void store_acc_T_f32(const f32x16 (&acc)[D / 32], float mul, float* stage
 
 // ================================================================================================ forward
 template <int D, int QT, int NW>
-__global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_fwd_kernel(const AttnArgs p) {
+__global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_fwd_kernel(const AttnArgs p) {
   constexpr int LDK = D + 8, LDV = D + 32, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
   using T64 = Tile64<D, NT>;
-  constexpr int MAIN = 64 * LDK + 64 * LDV, STG = NW * 32 * LDK;
-  __shared__ __attribute__((aligned(16))) bf16 smem[MAIN > STG ? MAIN : STG];
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];   // fwd_smem_bytes(D, NW)
+  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);
   bf16* const Ks = smem;
   bf16* const Vs = smem + 64 * LDK;
 
@@ -398,13 +398,11 @@ __global__ void __launch_bounds__(256) attn_delta_kernel(const bf16* __restrict_
 
 // ================================================================================================ dQ
 template <int D, int QT, int NW>
-__global__ void __launch_bounds__(NW * 64, QT == 1 ? 2 : 1) attn_bwd_dq_kernel(const AttnArgs p) {
+__global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_bwd_dq_kernel(const AttnArgs p) {
   constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
   using T64 = Tile64<D, NT>;
-  constexpr int MAIN = 2 * 64 * LDK + 64 * LDT, STG = NW * 32 * LDK;
-  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];   // dq_smem_bytes(D, NW)
   bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);
-  static_assert(MAIN >= STG, "staging does not fit");
   bf16* const Ks = smem;
   bf16* const Vs = smem + 64 * LDK;
   bf16* const Kt = smem + 2 * 64 * LDK;
@@ -974,7 +972,10 @@ __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __res
                                               pack_bf16x2(s1.z, s1.w));
 }
 
-constexpr int dq_smem_bytes(int d) { return (2 * 64 * (d + 8) + 64 * (d + 32)) * 2; }
+// operand tiles, or the epilogue's staging of every wave's 32 x d block, whichever is larger
+constexpr int max_i(int a, int b) { return a > b ? a : b; }
+constexpr int fwd_smem_bytes(int d, int nw) { return max_i(64 * (d + 8) + 64 * (d + 32), nw * 32 * (d + 8)) * 2; }
+constexpr int dq_smem_bytes(int d, int nw) { return max_i(2 * 64 * (d + 8) + 64 * (d + 32), nw * 32 * (d + 8)) * 2; }
 constexpr int dkv_fused_smem_bytes(int d) { return (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
 constexpr int dkv_pair_smem_bytes(int d) { return (2 * 64 * (d + 8) + 4 * 64 * (d + 32)) * 2 + 8 * 4 * 64 * 16; }
 void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
@@ -994,10 +995,13 @@ hipError_t set_smem(K kern, int bytes, bool& done) {
 template <int D, int QT, int NW>
 hipError_t launch_fwd(hipStream_t st, const AttnArgs& p) {
   constexpr int BQ = NW * 32 * QT;
+  static bool done = false;
+  hipError_t e = set_smem(attn_fwd_kernel<D, QT, NW>, fwd_smem_bytes(D, NW), done);
+  if (e != hipSuccess) return e;
   const int grid = ((p.seq + BQ - 1) / BQ) * p.a * p.batch;
   AttnArgs pf = p;
-  pf.fold = grid > 256 && grid <= 512;
-  RP_LAUNCH((attn_fwd_kernel<D, QT, NW>), dim3(grid), dim3(NW * 64), 0, st, pf);
+  pf.fold = NW <= 4 && grid > 256 && grid <= 512;
+  RP_LAUNCH((attn_fwd_kernel<D, QT, NW>), dim3(grid), dim3(NW * 64), fwd_smem_bytes(D, NW), st, pf);
   return hipGetLastError();
 }
 
@@ -1023,12 +1027,12 @@ template <int D, int QT, int NW>
 hipError_t launch_dq(hipStream_t st, const AttnArgs& p) {
   constexpr int BQ = NW * 32 * QT;
   static bool done = false;
-  hipError_t e = set_smem(attn_bwd_dq_kernel<D, QT, NW>, dq_smem_bytes(D), done);
+  hipError_t e = set_smem(attn_bwd_dq_kernel<D, QT, NW>, dq_smem_bytes(D, NW), done);
   if (e != hipSuccess) return e;
   const int grid = ((p.seq + BQ - 1) / BQ) * p.a * p.batch;
   AttnArgs pf = p;
-  pf.fold = grid > 256 && grid <= 512;
-  RP_LAUNCH((attn_bwd_dq_kernel<D, QT, NW>), dim3(grid), dim3(NW * 64), dq_smem_bytes(D), st, pf);
+  pf.fold = NW <= 4 && grid > 256 && grid <= 512;
+  RP_LAUNCH((attn_bwd_dq_kernel<D, QT, NW>), dim3(grid), dim3(NW * 64), dq_smem_bytes(D, NW), st, pf);
   return hipGetLastError();
 }
 
@@ -1043,6 +1047,12 @@ hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* 
   p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.ldo = ldo;
   fill_common(p, batch, seq, a, kh, d);
   // workgroup = 4 waves x 32 queries; 64 queries per wave halve the LDS reads per MFMA but spill at d = 128
+#ifndef RP_ATTN_NW8
+#define RP_ATTN_NW8 1
+#endif
+  // eight waves per workgroup (256 queries) store every K/V tile once for twice the products; enough workgroups needed
+  const bool big = RP_ATTN_NW8 && (long)((seq + 255) / 256) * a * batch >= 1024;
+  if (d == 128 && big) return launch_fwd<128, 1, 8>(st, p);
   if (d == 128) return launch_fwd<128, 1, 4>(st, p);
   if (d == 64) return launch_fwd<64, 1, 4>(st, p);
   return hipErrorInvalidValue;
@@ -1098,6 +1108,8 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
     if (d == 128 && RP_DKV_PAIR) return launch_dkv_pair<128>(st, p, nk);
     return d == 128 ? launch_dkv_fused<128>(st, p, nk) : launch_dkv_fused<64>(st, p, nk);
   } else {
+    const bool big = RP_ATTN_NW8 && (long)((seq + 255) / 256) * a * batch >= 1024;
+    if (d == 128 && big) return launch_dq<128, 1, 8>(st, p);
     return d == 128 ? launch_dq<128, 1, 4>(st, p) : launch_dq<64, 1, 4>(st, p);
   }
   return hipGetLastError();
