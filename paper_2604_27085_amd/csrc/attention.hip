@@ -192,6 +192,9 @@ __global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_fw
   using T64 = Tile64<D, NT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];   // fwd_smem_bytes(D, NW)
   bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);
+  // eight-wave workgroups have the CU to themselves: two sets of K/V tiles, one barrier per key tile
+  constexpr bool DB = NW >= 8;
+  constexpr int SET = 64 * LDK + 64 * LDV;
   bf16* const Ks = smem;
   bf16* const Vs = smem + 64 * LDK;
 
@@ -235,21 +238,43 @@ __global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_fw
       for (int v = 0; v < 16; ++v) oacc[t][dt][v] = 0.f;
   }
 
-  const bf16* kfrag = Ks + lr * LDK + 8 * lk;
-  const bf16* vfrag = Vs + tr_base<LDV>(lane);
+  const bf16* const kfrag0 = Ks + lr * LDK + 8 * lk;
+  const bf16* const vfrag0 = Vs + tr_base<LDV>(lane);
   uint4 kreg[T64::NREG], vreg[T64::NREG];
   T64::load(kreg, rk, p.ldk, 0, tid);
   T64::load(vreg, rv, p.ldv, 0, tid);
 
-  for (int j = 0; j < nkv; ++j) {
-    __syncthreads();
+  if constexpr (DB) {     // tile 0 into set 0, tile 1 on its way
     T64::template store<LDK>(kreg, Ks, tid);
     T64::template store<LDV>(vreg, Vs, tid);
-    __syncthreads();
-    if (j + 1 < nkv) {
-      T64::load(kreg, rk, p.ldk, (j + 1) * 64, tid);
-      T64::load(vreg, rv, p.ldv, (j + 1) * 64, tid);
+    if (nkv > 1) {
+      T64::load(kreg, rk, p.ldk, 64, tid);
+      T64::load(vreg, rv, p.ldv, 64, tid);
     }
+  }
+  for (int j = 0; j < nkv; ++j) {
+    __syncthreads();
+    if constexpr (DB) {
+      // everyone is done with tile j-1: its set takes tile j+1 (in registers since the last trip), tile j+2 sets out
+      if (j + 1 < nkv) {
+        T64::template store<LDK>(kreg, Ks + ((j + 1) & 1) * SET, tid);
+        T64::template store<LDV>(vreg, Vs + ((j + 1) & 1) * SET, tid);
+      }
+      if (j + 2 < nkv) {
+        T64::load(kreg, rk, p.ldk, (j + 2) * 64, tid);
+        T64::load(vreg, rv, p.ldv, (j + 2) * 64, tid);
+      }
+    } else {
+      T64::template store<LDK>(kreg, Ks, tid);
+      T64::template store<LDV>(vreg, Vs, tid);
+      __syncthreads();
+      if (j + 1 < nkv) {
+        T64::load(kreg, rk, p.ldk, (j + 1) * 64, tid);
+        T64::load(vreg, rv, p.ldv, (j + 1) * 64, tid);
+      }
+    }
+    const bf16* const kfrag = kfrag0 + (DB ? (j & 1) * SET : 0);
+    const bf16* const vfrag = vfrag0 + (DB ? (j & 1) * SET : 0);
     const int kv0 = j * 64;
     // Waves whose queries all precede this tile's keys (the last tile of the two upper waves) run it fully masked
     // rather than skip it: they would wait at the next barrier anyway, and a skipped update would make the compiler
@@ -453,23 +478,42 @@ __global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_bw
 #pragma unroll
       for (int v = 0; v < 16; ++v) dqacc[t][dt][v] = 0.f;
 
-  const bf16* kfrag = Ks + lr * LDK + 8 * lk;
-  const bf16* vfrag = Vs + lr * LDK + 8 * lk;
-  const bf16* ktfrag = Kt + tr_base<LDT>(lane);
+  const bf16* const kfrag0 = Ks + lr * LDK + 8 * lk;
+  const bf16* const vfrag0 = Vs + lr * LDK + 8 * lk;
+  const bf16* const ktfrag0 = Kt + tr_base<LDT>(lane);
   uint4 kreg[T64::NREG], vreg[T64::NREG];
   T64::load(kreg, rk, p.ldk, 0, tid);
   T64::load(vreg, rv, p.ldv, 0, tid);
+  // eight-wave workgroups have the CU to themselves: two sets of tiles, one barrier per key tile (see the forward kernel)
+  constexpr bool DB = NW >= 8;
+  constexpr int SET = 2 * 64 * LDK + 64 * LDT;
+  auto store_tiles = [&](int set) {
+    T64::template store<LDK>(kreg, Ks + set * SET, tid);
+    T64::template store<LDT>(kreg, Kt + set * SET, tid);
+    T64::template store<LDK>(vreg, Vs + set * SET, tid);
+  };
+  auto load_tiles = [&](int jj) {
+    T64::load(kreg, rk, p.ldk, jj * 64, tid);
+    T64::load(vreg, rv, p.ldv, jj * 64, tid);
+  };
+  if constexpr (DB) {
+    store_tiles(0);
+    if (nkv > 1) load_tiles(1);
+  }
 
   for (int j = 0; j < nkv; ++j) {
     __syncthreads();
-    T64::template store<LDK>(kreg, Ks, tid);
-    T64::template store<LDT>(kreg, Kt, tid);
-    T64::template store<LDK>(vreg, Vs, tid);
-    __syncthreads();
-    if (j + 1 < nkv) {
-      T64::load(kreg, rk, p.ldk, (j + 1) * 64, tid);
-      T64::load(vreg, rv, p.ldv, (j + 1) * 64, tid);
+    if constexpr (DB) {
+      if (j + 1 < nkv) store_tiles((j + 1) & 1);
+      if (j + 2 < nkv) load_tiles(j + 2);
+    } else {
+      store_tiles(0);
+      __syncthreads();
+      if (j + 1 < nkv) load_tiles(j + 1);
     }
+    const bf16* const kfrag = kfrag0 + (DB ? (j & 1) * SET : 0);
+    const bf16* const vfrag = vfrag0 + (DB ? (j & 1) * SET : 0);
+    const bf16* const ktfrag = ktfrag0 + (DB ? (j & 1) * SET : 0);
     const int kv0 = j * 64;
     {   // a wave whose queries all precede this tile's keys runs it fully masked (see the forward kernel)
       const bool need_mask = (kv0 + 63 > qw0) || (kv0 + 64 > p.seq);
@@ -974,8 +1018,8 @@ __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __res
 
 // operand tiles, or the epilogue's staging of every wave's 32 x d block, whichever is larger
 constexpr int max_i(int a, int b) { return a > b ? a : b; }
-constexpr int fwd_smem_bytes(int d, int nw) { return max_i(64 * (d + 8) + 64 * (d + 32), nw * 32 * (d + 8)) * 2; }
-constexpr int dq_smem_bytes(int d, int nw) { return max_i(2 * 64 * (d + 8) + 64 * (d + 32), nw * 32 * (d + 8)) * 2; }
+constexpr int fwd_smem_bytes(int d, int nw) { return max_i((nw >= 8 ? 2 : 1) * (64 * (d + 8) + 64 * (d + 32)), nw * 32 * (d + 8)) * 2; }
+constexpr int dq_smem_bytes(int d, int nw) { return max_i((nw >= 8 ? 2 : 1) * (2 * 64 * (d + 8) + 64 * (d + 32)), nw * 32 * (d + 8)) * 2; }
 constexpr int dkv_fused_smem_bytes(int d) { return (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
 constexpr int dkv_pair_smem_bytes(int d) { return (2 * 64 * (d + 8) + 4 * 64 * (d + 32)) * 2 + 8 * 4 * 64 * 16; }
 void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
