@@ -788,16 +788,16 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
 // MFMAs per workgroup as the one-wave-per-SIMD kernel, same LDS fragment traffic per CU, 8 KB of exchange per pair and tile.
 template <int D>
 __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p) {
-  constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32, DH = DT / 2;
+  // One LDS layout serves both kinds of fragment reads: a row stride of D + 24 elements is 12 banks past a multiple of
+  // 64, so the 16 rows of a plain 16-byte read phase start 12 banks apart (all 64 banks, 4 each) and the 4 rows of a
+  // transposing 8-byte read phase cover 8 banks each without meeting.  Every Q and dO tile is stored once.
+  constexpr int LDU = D + 24, KS = D / 16, DT = D / 32, DH = DT / 2;
   static_assert(DT % 2 == 0, "the head dimension is split over two waves");
   using T64 = Tile64<D, 512>;
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
-  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);             // 2*64*LDK + 2 * 2*64*LDT elements, then the exchange
-  bf16* const Qs = smem;
-  bf16* const dOs = smem + 64 * LDK;
-  bf16* const Qt = smem + 2 * 64 * LDK;                             // Qt | dOt, two sets (tile parity)
-  constexpr int TSET = 2 * 64 * LDT;
-  uint4* const exch = reinterpret_cast<uint4*>(Qt + 2 * TSET);      // [8 waves][4 fragments][64 lanes]
+  bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);             // two sets (tile parity) of Q | dO, then the exchange
+  constexpr int TSET = 2 * 64 * LDU;
+  uint4* const exch = reinterpret_cast<uint4*>(smem + 2 * TSET);    // [8 waves][4 fragments][64 lanes]
 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w8 = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -845,13 +845,13 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
   const int niter = nQ - qt0;
 
   // this wave's 32 queries of a tile: rows 32*h .. 32*h + 31
-  const bf16* qfrag = Qs + (32 * h + lr) * LDK + 8 * lk;
-  const bf16* dofrag = dOs + (32 * h + lr) * LDK + 8 * lk;
-  const bf16* qx = Qs + (32 * h + lr) * LDK + D;
-  const bf16* dox = dOs + (32 * h + lr) * LDK + D;
+  const bf16* qfrag = smem + (32 * h + lr) * LDU + 8 * lk;
+  const bf16* dofrag = qfrag + 64 * LDU;
+  const bf16* qx = smem + (32 * h + lr) * LDU + D;
+  const bf16* dox = qx + 64 * LDU;
   // this wave's half of the head dimension: columns 32*DH*h .. of the transposed tiles
-  const bf16* qtfrag = Qt + tr_base<LDT>(lane) + 32 * DH * h;
-  const bf16* dotfrag = qtfrag + 64 * LDT;
+  const bf16* qtfrag = smem + tr_base<LDU>(lane) + 32 * DH * h;
+  const bf16* dotfrag = qtfrag + 64 * LDU;
   const uint4 one_f = ones3(lk);
   uint4* const ex_mine = exch + (w8 * 4) * 64 + lane;
   const uint4* const ex_theirs = exch + ((w8 ^ 1) * 4) * 64 + lane;
@@ -884,7 +884,7 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
   auto update_half = [&](int set, int t2, const uint4 (&pf)[2], const uint4 (&df)[2]) {
     constexpr int NU = 4 * DH;
     auto ufrag_at = [&](int n) {   // n = (g2 * DH + dt) * 2 + which
-      return read_frag_tr<LDT>(((n & 1) ? qtfrag : dotfrag) + set * TSET, 2 * t2 + n / (2 * DH), 32 * ((n >> 1) % DH));
+      return read_frag_tr<LDU>(((n & 1) ? qtfrag : dotfrag) + set * TSET, 2 * t2 + n / (2 * DH), 32 * ((n >> 1) % DH));
     };
     uint4 uring[AHEAD];
 #pragma unroll
@@ -903,8 +903,8 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
   };
 
   // Two barriers per tile.  After the first one every wave is done with the previous tile's score phase and has
-  // published its fragments: the new tile is stored (the transposed tiles into the other set) and, meanwhile, the
-  // accumulators are updated with the partner's half of the PREVIOUS tile, whose transposed tiles are still in place.
+  // published its fragments: the new tile is stored (into the other set) and, meanwhile, the
+  // accumulators are updated with the partner's half of the PREVIOUS tile, whose set is still in place.
   auto partner_update = [&](int it_prev) {
     const uint4 ppf[2] = {ex_theirs[0], ex_theirs[64]};
     const uint4 pdf[2] = {ex_theirs[128], ex_theirs[192]};
@@ -912,13 +912,11 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
   };
   for (int it = 0; it < niter; ++it) {
     __syncthreads();
-    bf16* const qt_set = Qt + (it & 1) * TSET;
-    T64::template store<LDK>(qreg, Qs, tid);
-    T64::template store<LDT>(qreg, qt_set, tid);
-    T64::template store<LDK>(doreg, dOs, tid);
-    T64::template store<LDT>(doreg, qt_set + 64 * LDT, tid);
-    if (tid < 64) *reinterpret_cast<uint4*>(Qs + tid * LDK + D) = split3(st_reg);
-    else if (tid < 128) *reinterpret_cast<uint4*>(dOs + (tid - 64) * LDK + D) = split3(st_reg);
+    bf16* const q_set = smem + (it & 1) * TSET;
+    T64::template store<LDU>(qreg, q_set, tid);
+    T64::template store<LDU>(doreg, q_set + 64 * LDU, tid);
+    if (tid < 64) *reinterpret_cast<uint4*>(q_set + tid * LDU + D) = split3(st_reg);
+    else if (tid < 128) *reinterpret_cast<uint4*>(q_set + 64 * LDU + (tid - 64) * LDU + D) = split3(st_reg);
     if (it > 0) partner_update(it - 1);
     __syncthreads();
     if (it + 1 < niter) prefetch(it + 1);
@@ -932,7 +930,7 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
       auto sfrag_at = [&](int n) {
         const int ks = n >> 1;
         const bf16* src = ks < KS ? ((n & 1) ? dofrag : qfrag) + 16 * ks : ((n & 1) ? dox : qx);
-        return *reinterpret_cast<const uint4*>(src);
+        return *reinterpret_cast<const uint4*>(src + (it & 1) * TSET);
       };
       uint4 ring[AHEAD];
 #pragma unroll
@@ -1021,7 +1019,7 @@ constexpr int max_i(int a, int b) { return a > b ? a : b; }
 constexpr int fwd_smem_bytes(int d, int nw) { return max_i((nw >= 8 ? 2 : 1) * (64 * (d + 8) + 64 * (d + 32)), nw * 32 * (d + 8)) * 2; }
 constexpr int dq_smem_bytes(int d, int nw) { return max_i((nw >= 8 ? 2 : 1) * (2 * 64 * (d + 8) + 64 * (d + 32)), nw * 32 * (d + 8)) * 2; }
 constexpr int dkv_fused_smem_bytes(int d) { return (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
-constexpr int dkv_pair_smem_bytes(int d) { return (2 * 64 * (d + 8) + 4 * 64 * (d + 32)) * 2 + 8 * 4 * 64 * 16; }
+constexpr int dkv_pair_smem_bytes(int d) { return 2 * (2 * 64 * (d + 24)) * 2 + 8 * 4 * 64 * 16; }
 void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
   p.batch = batch; p.seq = seq; p.a = a; p.kh = kh;
   p.scale = 1.0f / sqrtf((float)d);
