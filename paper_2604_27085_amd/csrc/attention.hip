@@ -424,13 +424,14 @@ __global__ void __launch_bounds__(256) attn_delta_kernel(const bf16* __restrict_
 // ================================================================================================ dQ
 template <int D, int QT, int NW>
 __global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_bwd_dq_kernel(const AttnArgs p) {
-  constexpr int LDK = D + 8, LDT = D + 32, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
+  // K is read both ways (plain for S, transposing for dQ += dS K): its tile has the row stride d + 24 that keeps both
+  // kinds of reads free of bank conflicts (see attn_bwd_dkv_pair_kernel) and is stored once
+  constexpr int LDK = D + 8, LDU = D + 24, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
   using T64 = Tile64<D, NT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];   // dq_smem_bytes(D, NW)
   bf16* const smem = reinterpret_cast<bf16*>(dyn_smem);
   bf16* const Ks = smem;
-  bf16* const Vs = smem + 64 * LDK;
-  bf16* const Kt = smem + 2 * 64 * LDK;
+  bf16* const Vs = smem + 64 * LDU;
 
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lk = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -478,18 +479,17 @@ __global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_bw
 #pragma unroll
       for (int v = 0; v < 16; ++v) dqacc[t][dt][v] = 0.f;
 
-  const bf16* const kfrag0 = Ks + lr * LDK + 8 * lk;
+  const bf16* const kfrag0 = Ks + lr * LDU + 8 * lk;
   const bf16* const vfrag0 = Vs + lr * LDK + 8 * lk;
-  const bf16* const ktfrag0 = Kt + tr_base<LDT>(lane);
+  const bf16* const ktfrag0 = Ks + tr_base<LDU>(lane);
   uint4 kreg[T64::NREG], vreg[T64::NREG];
   T64::load(kreg, rk, p.ldk, 0, tid);
   T64::load(vreg, rv, p.ldv, 0, tid);
   // eight-wave workgroups have the CU to themselves: two sets of tiles, one barrier per key tile (see the forward kernel)
   constexpr bool DB = NW >= 8;
-  constexpr int SET = 2 * 64 * LDK + 64 * LDT;
+  constexpr int SET = 64 * LDU + 64 * LDK;
   auto store_tiles = [&](int set) {
-    T64::template store<LDK>(kreg, Ks + set * SET, tid);
-    T64::template store<LDT>(kreg, Kt + set * SET, tid);
+    T64::template store<LDU>(kreg, Ks + set * SET, tid);
     T64::template store<LDK>(vreg, Vs + set * SET, tid);
   };
   auto load_tiles = [&](int jj) {
@@ -524,7 +524,7 @@ __global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_bw
         f32x16 sT[QT], dpT[QT];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const uint4 ak = *reinterpret_cast<const uint4*>(kfrag + 32 * kt * LDK + 16 * ks);
+          const uint4 ak = *reinterpret_cast<const uint4*>(kfrag + 32 * kt * LDU + 16 * ks);
           const uint4 av = *reinterpret_cast<const uint4*>(vfrag + 32 * kt * LDK + 16 * ks);
 #pragma unroll
           for (int t = 0; t < QT; ++t) {
@@ -560,7 +560,7 @@ __global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_bw
           for (int g2 = 0; g2 < 2; ++g2)
 #pragma unroll
             for (int t = 0; t < QT; ++t) df[g2][t] = pack_frag(sT[t], 8 * g2);
-          auto ufrag_at = [&](int n) { return read_frag_tr<LDT>(ktfrag, 2 * kt + n / DT, 32 * (n % DT)); };
+          auto ufrag_at = [&](int n) { return read_frag_tr<LDU>(ktfrag, 2 * kt + n / DT, 32 * (n % DT)); };
           uint4 uring[AHEAD];
 #pragma unroll
           for (int n = 0; n < AHEAD; ++n) uring[n] = ufrag_at(n);
@@ -1017,7 +1017,7 @@ __global__ void __launch_bounds__(256) attn_dkv_reduce_kernel(const float* __res
 // operand tiles, or the epilogue's staging of every wave's 32 x d block, whichever is larger
 constexpr int max_i(int a, int b) { return a > b ? a : b; }
 constexpr int fwd_smem_bytes(int d, int nw) { return max_i((nw >= 8 ? 2 : 1) * (64 * (d + 8) + 64 * (d + 32)), nw * 32 * (d + 8)) * 2; }
-constexpr int dq_smem_bytes(int d, int nw) { return max_i((nw >= 8 ? 2 : 1) * (2 * 64 * (d + 8) + 64 * (d + 32)), nw * 32 * (d + 8)) * 2; }
+constexpr int dq_smem_bytes(int d, int nw) { return max_i((nw >= 8 ? 2 : 1) * (64 * (d + 24) + 64 * (d + 8)), nw * 32 * (d + 8)) * 2; }
 constexpr int dkv_fused_smem_bytes(int d) { return (2 * 64 * (d + 8) + 2 * 64 * (d + 32)) * 2; }
 constexpr int dkv_pair_smem_bytes(int d) { return 2 * (2 * 64 * (d + 24)) * 2 + 8 * 4 * 64 * 16; }
 void fill_common(AttnArgs& p, int batch, int seq, int a, int kh, int d) {
