@@ -45,7 +45,9 @@ struct TileLoader {
   int row0, ch;
 
   // row_map (only for operands whose rows are the tile rows): row gx is read from row row_map[gx] of the buffer.
-  RP_DEV void init(long ld, int x0, int Xdim, int tid, const int* row_map = nullptr) {
+  // fold_half (only !TR): the tile's rows are the two halves of a folded index range -- rows [0, BX/2) are x0/2 + row,
+  // rows [BX/2, BX) are fold_half + x0/2 + row - BX/2 (the gate and up rows of one SwiGLU column block).
+  RP_DEV void init(long ld, int x0, int Xdim, int tid, const int* row_map = nullptr, int fold_half = 0) {
     row0 = tid / S::CH;
     ch = tid % S::CH;
     kstep = TR ? (uint32_t)ld * 2u : 2u;
@@ -53,7 +55,7 @@ struct TileLoader {
     for (int it = 0; it < NREG; ++it) {
       const int row = row0 + it * RSTEP;
       if constexpr (!TR) {
-        const int gx = x0 + row;
+        const int gx = fold_half ? (x0 >> 1) + (row < BX / 2 ? row : fold_half + row - BX / 2) : x0 + row;
         const long src = (row_map && gx < Xdim) ? row_map[gx] : gx;
         voff[it] = gx < Xdim ? (uint32_t)(src * ld + ch * 8) * 2u : OOB;
       } else {
@@ -164,14 +166,15 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
   LA la, la2;
   LB lb, lb2;
   la.init(p.lda, m0, Mlim, tid, TA ? nullptr : p.row_map);
-  lb.init(p.ldb, n0, p.N, tid);
+  const int fold = (!TB && p.epi == EPI_SWIGLU_FWD) ? p.N >> 1 : 0;   // uniform
+  lb.init(p.ldb, n0, p.N, tid, nullptr, fold);
   const rsrc_t rsA = make_rsrc(p.A, p.bytesA), rsB = make_rsrc(Bbase, p.bytesB);
   rsrc_t rsA2 = rsA, rsB2 = rsB;
   la2 = la;
   lb2 = lb;
   if (p.K2 > 0) {
     la2.init(p.lda2, m0, p.M, tid);
-    lb2.init(p.ldb2, n0, p.N, tid);
+    lb2.init(p.ldb2, n0, p.N, tid, nullptr, fold);
     rsA2 = make_rsrc(p.A2, p.bytesA2);
     rsB2 = make_rsrc(p.B2, p.bytesB2);
   }
@@ -328,7 +331,9 @@ __global__ void __launch_bounds__(WGM* WGN* KG * 64)
     epilogue(p, Mlim, acc, smem, wave, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm, kg, kg + 1);
     return;
   }
-  epilogue(p, Mlim, acc, smem, wmn, lane, m0 + wm * WAVE_M, n0 + wn * WAVE_N, p.part_row0 + tile_m * WGM + wm);
+  // a folded tile's wave columns: waves 0, 1 of a row hold gate columns, waves 2, 3 the up columns that go with them
+  const int wcol = fold ? (n0 >> 1) + (wn & 1) * WAVE_N + (wn >> 1) * fold : n0 + wn * WAVE_N;
+  epilogue(p, Mlim, acc, smem, wmn, lane, m0 + wm * WAVE_M, wcol, p.part_row0 + tile_m * WGM + wm);
 }
 
 template <int WGM, int WGN, int BK, bool TA, bool TB, int KG = 1, bool GATED = false, bool BD = false>
@@ -470,7 +475,7 @@ hipError_t gemm_arrange(hipStream_t st, const void* B, long ldb, int N, int K, i
 
 int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
   if (a.b_direct) return 1;
-  if (a.epi == EPI_CE_STATS || a.epi == EPI_F32_COLMAX || a.epi == EPI_CE_P) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
+  if (a.epi == EPI_CE_STATS || a.epi == EPI_F32_COLMAX || a.epi == EPI_CE_P || a.epi == EPI_SWIGLU_FWD) return 1;   // the partial-row numbering assumes 256-row tiles of two wave rows
   if (tile_hint) return tile_hint;
   // the eight-wave 256x128 tile is used for the plain epilogues
   const bool plain = a.epi == EPI_BF16 || a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC;
@@ -491,6 +496,8 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   if (a.N % 8 || a.K % 8 || a.lda % 8 || (!a.b_direct && a.ldb % 8)) return hipErrorInvalidValue;
   if (a.epi != EPI_CE_STATS && a.ldc % (out_f32 ? 4 : 8)) return hipErrorInvalidValue;
   if (a.R && a.ldr % 4) return hipErrorInvalidValue;
+  if (a.epi == EPI_SWIGLU_FWD && (layout != GEMM_NT || !a.C2 || a.R || a.grp_tab || a.b_direct || a.N % 256 || a.ldc2 % 8 || a.alpha != 1.f))
+    return hipErrorInvalidValue;
   if (a.epi == EPI_SWIGLU_BWD && (!a.R || a.ldr % 8 || a.ldc % 8 || a.grp_tab)) return hipErrorInvalidValue;
   const bool ta = layout == GEMM_TN, tb = layout != GEMM_NT;
   if (ta && a.M % 8) return hipErrorInvalidValue;

@@ -24,7 +24,12 @@ enum {
   // rows = vocab, cols = tokens: C bf16 [rows, cols] = exp(min(acc - ref[col], CE_P_CLAMP)) against a per-token reference
   // exponent (p.lse holds ref), plus per-column partials (maximum of acc in .x, fp32 sum of the exponentials in .y, one
   // per 128 rows) and the label logit.  The frozen head's later vocabulary chunks: no logits go to memory.
-  EPI_CE_P = 7
+  EPI_CE_P = 7,
+  // NT, 256x256 tile, the N = 2m columns are gate | up of a SwiGLU MLP: an output tile takes 128 gate columns and the 128
+  // up columns that belong to them (B rows t*128.. and m + t*128..), C [M, 2m] bf16 is written as by EPI_BF16 (no
+  // residual) and C2 [M, m] bf16 = silu(gate) * up from the rounded values, as the separate SwiGLU kernel would compute
+  // it from C.  m must be a multiple of 128.
+  EPI_SWIGLU_FWD = 8
 };
 // exp argument beyond which EPI_CE_P saturates; a chunk whose maximum exceeds ref + CE_P_LIMIT is redone the slow way
 #define RP_CE_P_CLAMP 64.0f
@@ -54,6 +59,7 @@ struct GemmArgs {
   // 256x256 tiles, NT or NN, no second operand pair.
   const int4* grp_tab; const int* grp_ntiles; int grp_max_tiles; long grp_strideB; const int* row_map;
   int row_map_rows;            // rows of the A buffer that row_map indexes
+  void* C2; long ldc2;         // EPI_SWIGLU_FWD: the activation output
   const int* run_flag;         // optional [dev]: the kernel returns at once when *run_flag == 0 (conditional slow paths)
   // B (and B2) are copies in MFMA fragment order made by gemm_arrange (ldb, ldb2 unused): the kernel streams them into
   // registers without passing through LDS.  256x256 tile, NT or NN (the arrangement absorbs the difference), not grouped.

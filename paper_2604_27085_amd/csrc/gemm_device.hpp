@@ -136,7 +136,7 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
   unsigned char* const stg = smem + wave * STG_BYTES;
   const int rr = lane >> 3, cc = lane & 7;   // read-back: 8 rows per pass, 8 chunks of 16 bytes per row
 
-  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ || p.epi == EPI_SWIGLU_BWD || p.epi == EPI_CE_P) {
+  if ((p.epi == EPI_BF16 && !p.R) || p.epi == EPI_CE_DZ || p.epi == EPI_SWIGLU_BWD || p.epi == EPI_CE_P || p.epi == EPI_SWIGLU_FWD) {
     bf16* s16 = reinterpret_cast<bf16*>(stg);
     unsigned short* const h16 = reinterpret_cast<unsigned short*>(stg);
     // two rows of a column are converted by one instruction and go out as the halves of its result
@@ -309,6 +309,30 @@ RP_DEV void epilogue(const GemmArgs& p, int M, const f32x16 (&acc)[TM][TN], unsi
         const int row = t * 16 + (lane >> 2), grow = wrow0 + row;
         if (grow < M && gcol < p.N)
           *reinterpret_cast<uint4*>(Cp + (long)grow * p.ldc + gcol) = *reinterpret_cast<const uint4*>(s16 + row * STG_LD + lcol);
+      }
+    }
+    if (p.epi == EPI_SWIGLU_FWD) {
+      // silu(gate) * up from the staged (rounded) blocks: wave wn holds gate columns, wave wn + 2 of the same row the up
+      // columns that go with them; each of the two takes 64 of the 128 rows.  Same arithmetic as the SwiGLU kernel.
+      __syncthreads();
+      const int wn = wave & 3;
+      const bf16* const gs = reinterpret_cast<const bf16*>(smem + (wave & ~2) * STG_BYTES);
+      const bf16* const us = reinterpret_cast<const bf16*>(smem + (wave | 2) * STG_BYTES);
+      bf16* const Ap = reinterpret_cast<bf16*>(p.C2);
+      const int acol = (wn < 2 ? wcol0 : wcol0 - (p.N >> 1)) + cc * 8;     // gate column = activation column
+#pragma unroll
+      for (int t = 0; t < WAVE_M / 16; ++t) {
+        const int row = (wn >> 1) * (WAVE_M / 2) + t * 8 + rr, grow = wrow0 + row;
+        const uint4 gv = *reinterpret_cast<const uint4*>(gs + row * STG_LD + cc * 8);
+        const uint4 uv = *reinterpret_cast<const uint4*>(us + row * STG_LD + cc * 8);
+        const uint32_t gw[4] = {gv.x, gv.y, gv.z, gv.w}, uw[4] = {uv.x, uv.y, uv.z, uv.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float g0 = bf16_lo(gw[e]), g1 = bf16_hi(gw[e]);
+          o[e] = pack_bf16x2(g0 / (1.f + __expf(-g0)) * bf16_lo(uw[e]), g1 / (1.f + __expf(-g1)) * bf16_hi(uw[e]));
+        }
+        if (grow < M) *reinterpret_cast<uint4*>(Ap + (long)grow * p.ldc2 + acol) = make_uint4(o[0], o[1], o[2], o[3]);
       }
     }
   } else if (p.epi == EPI_BF16 || p.epi == EPI_F32 || p.epi == EPI_F32_COLMAX) {

@@ -192,7 +192,7 @@ struct Exec {
     char nm[40];
     snprintf(nm, sizeof(nm), "gemm_%s_%s", til[gemm_pick_tile(g)], lay[layout]);
     const double out_b = (g.epi == EPI_BF16 || g.epi == EPI_CE_DZ || g.epi == EPI_CE_P) ? 2.0
-                         : g.epi == EPI_SWIGLU_BWD ? 4.0 : (g.epi == EPI_CE_STATS ? 0.0 : 4.0 * (1 + g.beta));
+                         : g.epi == EPI_SWIGLU_BWD ? 4.0 : g.epi == EPI_SWIGLU_FWD ? 3.0 : (g.epi == EPI_CE_STATS ? 0.0 : 4.0 * (1 + g.beta));
     mark(nm, 2.0 * g.M * (double)g.N * ((double)g.K + g.K2),
          2.0 * ((double)g.M * g.K + (double)g.N * g.K + (double)g.M * g.K2 + (double)g.N * g.K2) + out_b * g.M * (double)g.N +
              (g.R ? (g.epi == EPI_SWIGLU_BWD ? 4.0 : 2.0) * g.M * (double)g.N : 0.0));
@@ -205,10 +205,10 @@ struct Exec {
   // C[M,N] (bf16) = alpha * A * op(B) (+ second pair) (+ R)
   void gemm_bf16(int layout, const void* A, long lda, const void* B, long ldb, void* C, long ldc, int M, int N, int K,
                  float alpha = 1.f, const void* A2 = nullptr, long lda2 = 0, const void* B2 = nullptr, long ldb2 = 0,
-                 int K2 = 0, const void* R = nullptr, long ldr = 0, int epi = EPI_BF16) {
+                 int K2 = 0, const void* R = nullptr, long ldr = 0, int epi = EPI_BF16, void* C2 = nullptr, long ldc2 = 0) {
     GemmArgs g; gemm_zero_args(g);
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
-    g.A2 = A2; g.lda2 = lda2; g.B2 = B2; g.ldb2 = ldb2; g.K2 = K2; g.R = R; g.ldr = ldr; g.epi = epi;
+    g.A2 = A2; g.lda2 = lda2; g.B2 = B2; g.ldb2 = ldb2; g.K2 = K2; g.R = R; g.ldr = ldr; g.epi = epi; g.C2 = C2; g.ldc2 = ldc2;
     mark_gemm(layout, g);
     chk(gemm_launch(st, layout, g), "gemm_bf16");
   }
@@ -301,15 +301,17 @@ const void* lora_b_matrix(const LayerW& W, const FusedLora& f, int N, size_t der
 hipError_t build_derived(const rp_ctx* ctx, hipStream_t st, char* slot, int l);
 
 // Y[T,N] = X W^T (+ LoRA) (+ R).  u_buf receives U = s * X A^T (kept for the backward).
+// act (optional, N = 2m, gate | up): the product's epilogue also writes silu(gate) * up [T, m] there.
 void linear_fwd(Exec& X, const LayerW& W, int w_id, const FusedLora& f, size_t bd_off, const void* x, int K, void* y,
-                int N, void* u_buf, const void* R) {
+                int N, void* u_buf, const void* R, void* act = nullptr) {
   const int nr = f.n * X.D.r;
   const void* Bm = nullptr;
   if (f.n) {
     Bm = lora_b_matrix(W, f, N, bd_off);
     X.gemm_skinny_bf16(GEMM_NT, x, K, W.t(f.a_id[0]), K, u_buf, (int)X.T, nr, K, X.ctx->cfg.lora_scale);
   }
-  X.gemm_bf16(GEMM_NT, x, K, W.t(w_id), K, y, N, (int)X.T, N, K, 1.f, f.n ? u_buf : nullptr, nr, Bm, nr, f.n ? nr : 0, R, N);
+  X.gemm_bf16(GEMM_NT, x, K, W.t(w_id), K, y, N, (int)X.T, N, K, 1.f, f.n ? u_buf : nullptr, nr, Bm, nr, f.n ? nr : 0, R, N,
+              act ? EPI_SWIGLU_FWD : EPI_BF16, act, N / 2);
 }
 
 // dX[T,K] = dY W (+ LoRA);  dW += dY^T X;  LoRA gradients.  u_buf = U saved by the forward, ud = scratch [T, n*r].
@@ -382,8 +384,14 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z, 
     RUN(X, "moe_combine", 0, 2.0 * Tkd * D.h + 4.0 * Td * D.h, k_moe_combine(X.st, f, slot_of, w, S(b.y), z, T, D.h, D.topk));
     return;
   }
-  linear_fwd(X, W, RP_T_WGU, fused_gu(D), X.ctx->dl.bd3, S(b.n2), D.h, S(b.gu), 2 * D.m, S(b.u3), nullptr);
-  RUN(X, "swiglu_fwd", 0, 6.0 * Td * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), T, D.m));
+  // SwiGLU rides in the gate/up product's epilogue when the column blocks pair up (m a multiple of 128): gate | up are
+  // still stored for the backward, the activation is not read back from them by a kernel of its own
+  if (D.m % 128 == 0) {
+    linear_fwd(X, W, RP_T_WGU, fused_gu(D), X.ctx->dl.bd3, S(b.n2), D.h, S(b.gu), 2 * D.m, S(b.u3), nullptr, S(b.act));
+  } else {
+    linear_fwd(X, W, RP_T_WGU, fused_gu(D), X.ctx->dl.bd3, S(b.n2), D.h, S(b.gu), 2 * D.m, S(b.u3), nullptr);
+    RUN(X, "swiglu_fwd", 0, 6.0 * Td * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), T, D.m));
+  }
   linear_fwd(X, W, RP_T_WD, fused_single(D.lora[6], RP_T_LA_DOWN, RP_T_LB_DOWN, D.h), 0, S(b.act), D.m, z, D.h, S(b.u4), S(b.y));
 }
 
