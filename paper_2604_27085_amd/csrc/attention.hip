@@ -873,13 +873,7 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
   };
   if (niter > 0) prefetch(0);
 
-#ifndef RP_PAIR_AHEAD
-#define RP_PAIR_AHEAD 2
-#endif
-#ifndef RP_PAIR_PRIO
-#define RP_PAIR_PRIO 1
-#endif
-  constexpr int AHEAD = RP_PAIR_AHEAD;     // two waves per SIMD cover each other's LDS latency: a short ring is enough
+  constexpr int AHEAD = 2;     // two waves per SIMD cover each other's LDS latency: a short ring is enough
   // the update products of one 32-query half t2 with the fragments pf (P) and df (dS): 4 * DH MFMAs
   auto update_half = [&](int set, int t2, const uint4 (&pf)[2], const uint4 (&df)[2]) {
     constexpr int NU = 4 * DH;
@@ -889,7 +883,7 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
     uint4 uring[AHEAD];
 #pragma unroll
     for (int n = 0; n < AHEAD; ++n) uring[n] = ufrag_at(n);
-    if (RP_PAIR_PRIO) MFMA_PHASE_BEGIN();
+    MFMA_PHASE_BEGIN();
 #pragma unroll
     for (int n = 0; n < NU; ++n) {
       const uint4 a = uring[n % AHEAD];
@@ -899,7 +893,7 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
       else dvacc[dt] = mfma32(a, pf[g2], dvacc[dt]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (RP_PAIR_PRIO) MFMA_PHASE_END();
+    MFMA_PHASE_END();
   };
 
   // Two barriers per tile.  After the first one every wave is done with the previous tile's score phase and has
@@ -935,7 +929,7 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
       uint4 ring[AHEAD];
 #pragma unroll
       for (int n = 0; n < AHEAD; ++n) ring[n] = sfrag_at(n);
-      if (RP_PAIR_PRIO) MFMA_PHASE_BEGIN();
+      MFMA_PHASE_BEGIN();
 #pragma unroll
       for (int n = 0; n < NS; ++n) {
         const uint4 a = ring[n % AHEAD];
@@ -945,7 +939,7 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
         else s = mfma32(a, ks < KS ? kf[ks] : one_f, s);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (RP_PAIR_PRIO) MFMA_PHASE_END();
+      MFMA_PHASE_END();
     }
     // rows of the score tile are queries: q = qh0 + 8*(v/4) + 4*lk + v%4
     if (need_mask) {
@@ -1089,11 +1083,8 @@ hipError_t k_attn_fwd(hipStream_t st, const void* q, const void* k, const void* 
   p.ldq = ldq; p.ldk = ldk; p.ldv = ldv; p.ldo = ldo;
   fill_common(p, batch, seq, a, kh, d);
   // workgroup = 4 waves x 32 queries; 64 queries per wave halve the LDS reads per MFMA but spill at d = 128
-#ifndef RP_ATTN_NW8
-#define RP_ATTN_NW8 1
-#endif
   // eight waves per workgroup (256 queries) store every K/V tile once for twice the products; enough workgroups needed
-  const bool big = RP_ATTN_NW8 && (long)((seq + 255) / 256) * a * batch >= 1024;
+  const bool big = (long)((seq + 255) / 256) * a * batch >= 1024;
   if (d == 128 && big) return launch_fwd<128, 1, 8>(st, p);
   if (d == 128) return launch_fwd<128, 1, 4>(st, p);
   if (d == 64) return launch_fwd<64, 1, 4>(st, p);
@@ -1144,13 +1135,10 @@ hipError_t k_attn_bwd(hipStream_t st, int part, const void* q, const void* k, co
       p.kblock = nkv >= 192 ? 32 : 16;
       nk = ((nkv + p.kblock - 1) / p.kblock) * p.kblock * nhb;
     }
-#ifndef RP_DKV_PAIR
-#define RP_DKV_PAIR 1
-#endif
-    if (d == 128 && RP_DKV_PAIR) return launch_dkv_pair<128>(st, p, nk);
-    return d == 128 ? launch_dkv_fused<128>(st, p, nk) : launch_dkv_fused<64>(st, p, nk);
+    if (d == 128) return launch_dkv_pair<128>(st, p, nk);
+    return launch_dkv_fused<64>(st, p, nk);   // d = 64: its registers already allow two waves per SIMD
   } else {
-    const bool big = RP_ATTN_NW8 && (long)((seq + 255) / 256) * a * batch >= 1024;
+    const bool big = (long)((seq + 255) / 256) * a * batch >= 1024;
     if (d == 128 && big) return launch_dq<128, 1, 8>(st, p);
     return d == 128 ? launch_dq<128, 1, 4>(st, p) : launch_dq<64, 1, 4>(st, p);
   }

@@ -496,7 +496,7 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   if (a.N % 8 || a.K % 8 || a.lda % 8 || (!a.b_direct && a.ldb % 8)) return hipErrorInvalidValue;
   if (a.epi != EPI_CE_STATS && a.ldc % (out_f32 ? 4 : 8)) return hipErrorInvalidValue;
   if (a.R && a.ldr % 4) return hipErrorInvalidValue;
-  if (a.epi == EPI_SWIGLU_FWD && (layout != GEMM_NT || !a.C2 || a.R || a.grp_tab || a.b_direct || a.N % 256 || a.ldc2 % 8 || a.alpha != 1.f))
+  if (a.epi == EPI_SWIGLU_FWD && (layout != GEMM_NT || !a.C2 || a.R || a.b_direct || a.N % 256 || a.ldc2 % 8 || a.alpha != 1.f))
     return hipErrorInvalidValue;
   if (a.epi == EPI_SWIGLU_BWD && (!a.R || a.ldr % 8 || a.ldc % 8 || a.grp_tab)) return hipErrorInvalidValue;
   const bool ta = layout == GEMM_TN, tb = layout != GEMM_NT;
@@ -518,7 +518,7 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   if (a.bytesA == ~0u || a.bytesB == ~0u || a.bytesA2 == ~0u || a.bytesB2 == ~0u) return hipErrorInvalidValue;
   int tile = gemm_pick_tile(a, tile_hint);
   if (a.grp_tab) {   // grouped: 256-row tiles as in the table, rows of A are tile rows, one operand pair
-    if (ta || a.K2 || !a.grp_ntiles || a.grp_max_tiles <= 0 || (a.epi != EPI_BF16 && a.epi != EPI_F32)) return hipErrorInvalidValue;
+    if (ta || a.K2 || !a.grp_ntiles || a.grp_max_tiles <= 0 || (a.epi != EPI_BF16 && a.epi != EPI_F32 && a.epi != EPI_SWIGLU_FWD)) return hipErrorInvalidValue;
     tile = 1;
     if (a.row_map) {
       a.bytesA = extent_bytes(a.row_map_rows, a.K, a.lda);

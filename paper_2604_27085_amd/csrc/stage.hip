@@ -226,10 +226,11 @@ struct Exec {
   // Grouped GEMM over expert-sorted slot rows: C[slot, N] = A[row_map ? row_map[slot] : slot, K] * op(B_e), B_e the
   // matrix of the expert that owns the slot.  set = the layer's saved internals (routing plan).
   void gemm_grouped(int layout, const char* set, const void* A, long lda, int a_rows, bool gather, const void* B, long ldb,
-                    long strideB, void* C, long ldc, int N, int K) {
+                    long strideB, void* C, long ldc, int N, int K, void* act = nullptr) {
     GemmArgs g; gemm_zero_args(g);
     const long Tk = T * D.topk;
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.M = (int)Tk; g.N = N; g.K = K; g.epi = EPI_BF16;
+    if (act) { g.epi = EPI_SWIGLU_FWD; g.C2 = act; g.ldc2 = N / 2; }   // gate | up columns: silu(gate) * up from the epilogue
     g.grp_tab = reinterpret_cast<const int4*>(set + P.lb.m_tab);
     g.grp_ntiles = reinterpret_cast<const int*>(set + P.lb.m_ntiles);
     g.grp_max_tiles = P.moe_max_tiles;
@@ -239,7 +240,7 @@ struct Exec {
       char nm[40];
       snprintf(nm, sizeof(nm), "gemm_grouped_%s", layout == GEMM_NT ? "NT" : "NN");
       // every expert's weights are read once; rows as in the dense case
-      mark(nm, 2.0 * Tk * (double)N * K, 2.0 * ((double)Tk * K + (double)D.E * N * K) + 2.0 * Tk * (double)N);
+      mark(nm, 2.0 * Tk * (double)N * K, 2.0 * ((double)Tk * K + (double)D.E * N * K) + (act ? 3.0 : 2.0) * Tk * (double)N);
     }
     chk(gemm_launch(st, layout, g), "gemm_grouped");
   }
@@ -378,8 +379,12 @@ void layer_forward(Exec& X, const LayerW& W, char* set, const void* x, void* z, 
     RUN(X, "moe_route", 0, 4.0 * Td * D.E + 8.0 * Tkd, k_moe_route(X.st, X.router, idx, w, T, D.E, D.topk));
     RUN(X, "moe_plan", 0, 16.0 * Tkd, k_moe_plan(X.st, idx, T, D.E, D.topk, (int*)S(b.m_cnt), (int*)S(b.m_seg), S(b.m_tab),
                                                      (int*)S(b.m_ntiles), slot_of, (int*)S(b.m_tok), (int*)S(b.m_hist)));
-    X.gemm_grouped(GEMM_NT, set, S(b.n2), D.h, T, true, W.t(RP_T_WGU), D.h, (long)2 * D.m * D.h, S(b.gu), 2 * D.m, 2 * D.m, D.h);
-    RUN(X, "swiglu_fwd", 0, 6.0 * Tkd * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), Tk, D.m));
+    if (D.m % 128 == 0) {   // SwiGLU in the epilogue, as in the dense layer
+      X.gemm_grouped(GEMM_NT, set, S(b.n2), D.h, T, true, W.t(RP_T_WGU), D.h, (long)2 * D.m * D.h, S(b.gu), 2 * D.m, 2 * D.m, D.h, S(b.act));
+    } else {
+      X.gemm_grouped(GEMM_NT, set, S(b.n2), D.h, T, true, W.t(RP_T_WGU), D.h, (long)2 * D.m * D.h, S(b.gu), 2 * D.m, 2 * D.m, D.h);
+      RUN(X, "swiglu_fwd", 0, 6.0 * Tkd * D.m, k_swiglu_fwd(X.st, S(b.gu), S(b.act), Tk, D.m));
+    }
     X.gemm_grouped(GEMM_NT, set, S(b.act), D.m, (int)Tk, false, W.t(RP_T_WD), D.m, (long)D.h * D.m, f, D.h, D.h, D.m);
     RUN(X, "moe_combine", 0, 2.0 * Tkd * D.h + 4.0 * Td * D.h, k_moe_combine(X.st, f, slot_of, w, S(b.y), z, T, D.h, D.topk));
     return;
