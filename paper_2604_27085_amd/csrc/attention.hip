@@ -8,17 +8,22 @@
 // that order.  An operand whose reduction index is contiguous in memory (K for Q.K^T, V for dO.V^T, Q and dO in the
 // score products of the dK/dV kernel) is read with plain 16-byte LDS loads from a [rows][D + 8] tile; an operand
 // whose reduction index is the row index of the tile (V for P.V, K for dS.K, Q and dO for dK/dV) is read with the
-// transposing LDS load from a [rows][D + 32] tile.  Tiles needed both ways are stored in LDS twice; nothing is
-// transposed in registers.  Global loads are 16-byte buffer loads whose descriptor ends with the sequence, so rows
-// past the end read as zero without a branch.
+// transposing LDS load from a [rows][D + 32] tile.  A tile needed both ways (K in the dQ kernel, Q and dO in the dK/dV
+// kernel at d = 128) has the row stride D + 24, which keeps both kinds of reads free of bank conflicts, and is stored
+// once; nothing is transposed in registers.  Global loads are 16-byte buffer loads whose descriptor ends with the
+// sequence, so rows past the end read as zero without a branch.
 //
-//   forward : workgroup = NW waves x 32*QT queries of one head, loop over 64-key tiles up to the diagonal
+//   forward : workgroup = NW waves x 32*QT queries of one head, loop over 64-key tiles up to the diagonal; NW = 8 (one
+//             workgroup per CU, two sets of K/V tiles, one barrier per tile) when the grid is large enough, else 4
 //   dQ      : same decomposition; recomputes S^T and dP^T, accumulates dQ^T
-//   dK, dV  : workgroup = 4 waves x 32 keys against ONE query head, loops over 64-query tiles from the diagonal on
-//             and accumulates dK^T, dV^T in registers.  With grouped queries every query head of a group writes an
-//             fp32 partial and a small kernel adds the group's partials in head order (no atomics, fixed order);
-//             one workgroup per query head rather than per kv head doubles the workgroup count, which is what lets
-//             the triangular work balance over the CUs.
+//   dK, dV  : workgroup = 128 keys against ONE query head, loops over 64-query tiles from the diagonal on and
+//             accumulates dK^T, dV^T in registers.  d = 128: eight waves, pairs of waves share 32 keys, split the
+//             accumulators over the head dimension and the score recomputation over the queries
+//             (attn_bwd_dkv_pair_kernel); d = 64: four waves x 32 keys (attn_bwd_dkv_fused_kernel).  With grouped queries
+//             every query head of a group writes an fp32 partial and a small kernel adds the group's partials in head
+//             order (no atomics, fixed order); one workgroup per query head rather than per kv head multiplies the
+//             workgroup count, which is what lets the triangular work balance over the CUs.
+// Launch orders keep an XCD (eight of them, each with its own L2) on few heads: see xcd_head() and the dK/dV kernels.
 #include "common.hpp"
 #include "kernels.hpp"
 #include <stdlib.h>

@@ -14,13 +14,14 @@
 // reloaded with the tile after next), so that global loads and LDS stores arrive evenly instead of in bursts that
 // stall MFMA issue behind a full memory queue, and every load has a whole tile of time to return; the workgroup
 // barrier sits before the last four MFMAs of a tile and the first fragments of the next tile are read under them.
-// Measured on MI355X the 256x256 tile asks L2 for one byte per 128 FLOP; the chip runs power-limited near 1.8 GHz
-// under this kernel.  Tried and dropped: direct HBM -> LDS loads with a four-deep ring, touching lines two tiles
+// Measured on MI355X the 256x256 tile asks L2 for one byte per 128 FLOP; the matrix pipe is busy 75-79 % of the kernel's
+// cycles and the chip runs power-limited near 1.65 GHz under it.  Tried and dropped: direct HBM -> LDS loads with a four-deep ring, touching lines two tiles
 // ahead to pull them into L2, touching the first lines of the workgroup's successor tile before the epilogue,
-// staggered K-loop starts, a reduction split merged through scratch memory, a 128x128 wave tile with one wave per
-// SIMD.  Outputs too small to fill the chip with 256x256 tiles use a 256x128 tile worked
+// staggered K-loop starts, a reduction split merged by the last workgroup to arrive, a 128x128 wave tile with one wave
+// per SIMD.  Outputs too small to fill the chip with 256x256 tiles use a 256x128 tile worked
 // on by two wave groups that split every K tile (merged through LDS); GEMMs that accumulate into an fp32 output and
-// would still leave CUs idle are split along the reduction and merged with fp32 atomics.
+// would still leave CUs idle are split along the reduction: the slices write partial products to scratch memory and a
+// second kernel adds them in slice order (reproducible run to run).  A variant keeps the B operand out of LDS (BD).
 //
 // Operands whose reduction index is not contiguous in memory (the weight in an activation-gradient GEMM, both operands
 // of a weight-gradient GEMM) keep their memory layout in LDS and are read with the transposing LDS load, so all
