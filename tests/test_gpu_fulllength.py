@@ -32,21 +32,25 @@ def rel(a, b):
     return pu.rel_l2(a, b)
 
 
-def run_attention(B, H, q, k, v, do, seq, a, kh):
-    """q, do: bf16 device [T, a*D]; k, v: [T, kh*D].  Returns o, lse, dq, dk, dv as float32 ndarrays."""
+def run_attention(B, H, q, k, v, do, seq, a, kh, batch=1):
+    """q, do: bf16 device [T, a*D]; k, v: [T, kh*D], T = batch * seq.  Returns o, lse, dq, dk, dv as float32 ndarrays
+    ([seq, heads, D] and lse [a, seq]; with batch > 1 a leading batch axis)."""
     dv_ = "cuda:0"
     o = torch.empty_like(q)
-    lse = torch.empty((1, a, seq), dtype=torch.float32, device=dv_)
-    B.rp_op_attn_fwd(stream(), q, k, v, o, lse, a * D, kh * D, kh * D, a * D, 1, seq, a, kh, D)
+    lse = torch.empty((batch, a, seq), dtype=torch.float32, device=dv_)
+    B.rp_op_attn_fwd(stream(), q, k, v, o, lse, a * D, kh * D, kh * D, a * D, batch, seq, a, kh, D)
     dq = torch.empty_like(q)
     dk, dvv = torch.empty_like(k), torch.empty_like(v)
-    delta = torch.empty((1, a, seq), dtype=torch.float32, device=dv_)
-    scratch = torch.empty((2, seq, a * D), dtype=torch.float32, device=dv_)
+    delta = torch.empty((batch, a, seq), dtype=torch.float32, device=dv_)
+    scratch = torch.empty((2, batch * seq, a * D), dtype=torch.float32, device=dv_)
     B.rp_op_attn_bwd(stream(), q, k, v, o, do, lse, delta, dq, dk, dvv, scratch, a * D, kh * D, kh * D, a * D, a * D, a * D,
-                     kh * D, kh * D, 1, seq, a, kh, D)
+                     kh * D, kh * D, batch, seq, a, kh, D)
     torch.cuda.synchronize()
-    f = lambda t, h: H.to_f32(t).reshape(seq, h, D)
-    return f(o, a), lse.cpu().numpy()[0], f(dq, a), f(dk, kh), f(dvv, kh)
+    if batch == 1:
+        f = lambda t, h: H.to_f32(t).reshape(seq, h, D)
+        return f(o, a), lse.cpu().numpy()[0], f(dq, a), f(dk, kh), f(dvv, kh)
+    f = lambda t, h: H.to_f32(t).reshape(batch, seq, h, D)
+    return f(o, a), lse.cpu().numpy(), f(dq, a), f(dk, kh), f(dvv, kh)
 
 
 @pytest.mark.timeout(600)
@@ -90,6 +94,47 @@ def test_zero_queries_give_running_means_at_full_length(rp, name, capsys):
             dp = v64[: t + 1, g] @ do[t, j].astype(np.float64) - mean_v[t, g] @ do[t, j].astype(np.float64)
             ref = (dp @ k64[: t + 1, g]) / ((t + 1) * np.sqrt(D))
             assert np.linalg.norm(dq[t, j] - ref) <= 1.5e-2 * np.linalg.norm(ref) + 5e-5, (t, j)      # t = 0: exactly zero
+
+
+@pytest.mark.timeout(600)
+def test_zero_queries_two_sequences_of_ragged_length(rp, capsys):
+    """The same closed forms for a batch of two sequences whose length (12424) is a multiple of none of the tile sizes:
+    98 key tiles of 128 put the dK/dV kernel on its XCD-aware launch order with a ragged last run (positions past the
+    last key tile exit), 16/4 heads x 2 sequences give every XCD four heads, and the forward and dQ kernels run their
+    256-query workgroups with a ragged last one.  Different values per sequence: a kernel that mixed the two up, or
+    dropped a tile of either, would miss the running means."""
+    B, H = rp
+    batch, seq, a, kh = 2, 12424, 16, 4
+    grp = a // kh
+    with capsys.disabled():
+        print("[batch 2] zero queries, seq %d, %d/%d heads" % (seq, a, kh), flush=True)
+    rng = np.random.default_rng(77)
+    k = synth.bf16_round(rng.standard_normal((batch, seq, kh, D), dtype=np.float32))
+    v = synth.bf16_round(rng.standard_normal((batch, seq, kh, D), dtype=np.float32))
+    do = synth.bf16_round(rng.standard_normal((batch, seq, a, D), dtype=np.float32))
+    qd = torch.zeros((batch * seq, a * D), dtype=torch.bfloat16, device="cuda:0")
+    dev = lambda t: H.bf16_tensor(t.reshape(batch * seq, -1), "cuda:0")
+    o, lse, dq, dk, dv = run_attention(B, H, qd, dev(k), dev(v), dev(do), seq, a, kh, batch)
+    cnt = np.arange(1, seq + 1, dtype=np.float64)
+    for b in range(batch):
+        mean_v = np.cumsum(v[b].astype(np.float64), axis=0) / cnt[:, None, None]
+        assert np.max(np.abs(lse[b] - np.log(cnt)[None, :])) < 2e-5
+        for j in range(a):
+            err = np.linalg.norm(o[b, :, j] - mean_v[:, j // grp], axis=1) / np.linalg.norm(mean_v[:, j // grp], axis=1)
+            assert rel(o[b, :, j], mean_v[:, j // grp]) < 4e-3 and err.max() < 2e-2, (b, j, int(err.argmax()), err.max())
+        w = do[b].astype(np.float64) / cnt[:, None, None]
+        dv_ref = np.cumsum(w[::-1], axis=0)[::-1].reshape(seq, kh, grp, D).sum(axis=2)
+        assert rel(dv[b], dv_ref) < 6e-3
+        err = np.linalg.norm((dv[b] - dv_ref).reshape(seq, -1), axis=1) / np.linalg.norm(dv_ref.reshape(seq, -1), axis=1)
+        assert err.max() < 3e-2, (b, int(err.argmax()), err.max())
+        assert np.max(np.abs(dk[b])) <= 1e-6 * np.max(np.abs(dv[b]))
+        k64, v64 = k[b].astype(np.float64), v[b].astype(np.float64)
+        for t in (0, 127, 128, 6000, seq - 129, seq - 9, seq - 1):
+            for j in (0, grp, a - 1):
+                g = j // grp
+                dp = v64[: t + 1, g] @ do[b, t, j].astype(np.float64) - mean_v[t, g] @ do[b, t, j].astype(np.float64)
+                ref = (dp @ k64[: t + 1, g]) / ((t + 1) * np.sqrt(D))
+                assert np.linalg.norm(dq[b, t, j] - ref) <= 1.5e-2 * np.linalg.norm(ref) + 5e-5, (b, t, j)
 
 
 @pytest.mark.timeout(600)
