@@ -82,9 +82,12 @@ typedef struct {
   int32_t head_chunk;  /* vocabulary rows per pass of the LM head (the logits of one pass are the largest buffer of its
                           workspace); 0 = automatic (32768, or 16384 for more than 4096 tokens), else a multiple of 256.
                           Enters rp_query_sizes like every other field. */
-  int32_t head_two_sweeps; /* 0: a frozen head (train_base = 0) makes one sweep over the vocabulary; 1: it runs the
-                          two-sweep schedule of a trainable head (statistics, then gradients) -- same results, for
-                          comparison runs */
+  int32_t head_two_sweeps; /* 0: the LM head makes one sweep over the vocabulary (a trainable head then keeps the
+                          bf16 probabilities of the whole vocabulary, 2 * vocab * tokens bytes, in its workspace and
+                          forms dW from them afterwards -- only while that is at most 4 GiB, else as 1);  1: the
+                          two-sweep schedule (softmax statistics, then the logits
+                          again for the gradients): no vocabulary-sized buffer, one more logit-sized product -- same
+                          results within bf16 noise */
 } rp_stage_cfg;
 
 /* Tensor ids inside one layer's chunk of the weight blob (and of the gradient blob). */
@@ -191,7 +194,8 @@ RP_API rp_status rp_stage_backward(rp_ctx* ctx, int slot_id, int phases, const v
 
 /* LM head fused with the mean cross-entropy, forward and backward in one call (the oversized last stage, Sec. 2.3;
  * returns a scalar loss, Sec. 4.1.1).  xf = rmsnorm(x; gf); Z = xf Wv^T is produced tile by tile and reduced on
- * the fly, never stored at [T, V];  loss = mean over rows with label != RP_IGNORE_INDEX of (logsumexp Z_t - Z[t, y_t]);
+ * the fly, never stored at [T, V] (fp32 logits exist for one vocabulary chunk at most; see cfg.head_two_sweeps for
+ * the bf16 probabilities a trainable head may keep);  loss = mean over rows with label != RP_IGNORE_INDEX of (logsumexp Z_t - Z[t, y_t]);
  * dZ = grad_scale (softmax - onehot) / N_valid.
  * x [dev] bf16 [T, h]; labels [dev] int32 [T]; loss_out [dev] one fp32; dx [dev] bf16 [T, h] overwritten;
  * grads [dev]: the stage's fp32 gradient blob (the one rp_stage_backward takes); its head chunk {gf [h], Wv [V, h]}

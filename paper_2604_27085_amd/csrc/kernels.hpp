@@ -81,6 +81,13 @@ hipError_t k_ce_chunk_check(hipStream_t st, const float2* pmax, int nparts, int 
 // acc[t, :] *= alpha[t] where alpha[t] != 1 (nothing when flag is given and *flag == 0).
 hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int T, int h, const int* flag);
 hipError_t k_ce_lse_from_ref(hipStream_t st, const float* m, const float* l, float* lse, int T);
+// One sweep with a trainable head (the probabilities of all chunks stay in memory, [V, T] bf16):
+// p[r, t] *= alpha[t] for r < rows (nothing when flag is given and *flag == 0);
+hipError_t k_ce_rescale_p(hipStream_t st, void* p, long rows, int T, const float* alpha, const int* flag);
+// p[labels[t], t] -= l[t] for tokens with coef != 0 and a label inside the vocabulary;
+hipError_t k_ce_patch_label(hipStream_t st, void* p, int T, int V, const int* labels, const float* l, const float* coef);
+// xs[t, :] = xf[t, :] * coef[t] / l[t] (bf16).
+hipError_t k_ce_scale_x(hipStream_t st, const void* xf, const float* coef, const float* l, void* xs, int T, int h);
 // acc[t, :] = coef[t] * (acc[t, :] / l[t] - W[labels[t], :]) (zero where coef is zero).
 hipError_t k_ce_frozen_dx(hipStream_t st, float* acc, const float* l, const float* coef, const int* labels, const void* W, int T, int h,
                           int V);

@@ -130,6 +130,8 @@ struct Plan {
   size_t fwd_bytes, bwd_bytes;
   // head
   size_t h_xf, h_rstd, h_part, h_zlab, h_lse, h_coef, h_dzt, h_dxacc, h_partials, head_bytes;
+  bool head_keep_p;      // trainable head in one sweep (see make_plan)
+  size_t h_pall, h_xs;   // then: the probabilities of the whole vocabulary [V, T] bf16, the scaled input
   size_t h_z, h_m, h_l, h_alpha, h_flag;   // frozen head: fp32 logits of one chunk, reference exponent, normaliser, rescale
                                            // factor, the flag that switches a chunk's slow path on
   int head_chunk, head_parts;
@@ -198,13 +200,19 @@ inline Plan make_plan(const rp_stage_cfg& c, int batch, int seq) {
     P.head_parts = 2 * ((D.V + 255) / 256);
     P.h_xf = take(T * D.h * 2); P.h_rstd = take(T * 4); P.h_part = take((size_t)P.head_parts * T * 8);
     P.h_zlab = take(T * 4); P.h_lse = take(T * 4); P.h_coef = take(T * 4);
-    P.h_dzt = take((size_t)P.head_chunk * T * 2); P.h_dxacc = take(T * D.h * 4);
+    // a trainable head in one sweep keeps every chunk's probabilities (h_pall, bf16 [V, T]) instead of one chunk's dZ^T:
+    // taken when that buffer stays within 4 GiB (1.2 GB at 151936 x 4096), else the two-sweep schedule
+    const bool keep_p = c.train_base && !c.head_two_sweeps && (size_t)D.V * T * 2 <= ((size_t)4 << 30);
+    P.head_keep_p = keep_p;
+    P.h_dzt = keep_p ? 0 : take((size_t)P.head_chunk * T * 2);
+    P.h_dxacc = take(T * D.h * 4);
     P.h_partials = take((size_t)RP_PARTIAL_BLOCKS * D.h * 4);
     P.h_split = take(RP_SPLITK_WS_BYTES);
-    if (!c.train_base) {
+    if (!c.train_base || keep_p) {
       P.h_z = take((size_t)P.head_chunk * T * 4);
       P.h_m = take(T * 4); P.h_l = take(T * 4); P.h_alpha = take(T * 4); P.h_flag = take(4);
     }
+    if (keep_p) { P.h_pall = take((size_t)D.V * T * 2); P.h_xs = take(T * D.h * 2); }
   }
   P.head_bytes = o;
   return P;

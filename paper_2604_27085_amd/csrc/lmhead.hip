@@ -168,6 +168,54 @@ __global__ void __launch_bounds__(256) ce_rescale_rows_kernel(float* __restrict_
   for (int c = lane; c < h / 4; c += 64) { float4 v = row[c]; v.x *= a; v.y *= a; v.z *= a; v.w *= a; row[c] = v; }
 }
 
+// One sweep with a trainable head: the probabilities of every chunk stay in memory ([V, T] bf16, against the reference
+// exponent), and the weight gradient is formed afterwards as  dW = P'^T^T xs,  P'[v, t] = p[v, t] - l_t [v = y_t],
+// xs_t = (coef_t / l_t) xf_t  (= sum_t coef_t (p_tv / l_t - [v = y_t]) xf_t).
+//
+// p[r, t] *= alpha[t] for the rows r < rows stored so far, where a token's reference moved (alpha != 1).  Grid-stride.
+__global__ void __launch_bounds__(256) ce_rescale_p_kernel(bf16* __restrict__ p, long rows, int T, const float* __restrict__ alpha,
+                                                           const int* __restrict__ run_flag) {
+  if (run_flag && *run_flag == 0) return;
+  const int t8 = T >> 3;
+  const long total = rows * t8;
+  for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
+    const int c = (int)(idx % t8);
+    const float4 a0 = *reinterpret_cast<const float4*>(alpha + c * 8), a1 = *reinterpret_cast<const float4*>(alpha + c * 8 + 4);
+    if (a0.x == 1.f && a0.y == 1.f && a0.z == 1.f && a0.w == 1.f && a1.x == 1.f && a1.y == 1.f && a1.z == 1.f && a1.w == 1.f) continue;
+    uint4* const q = reinterpret_cast<uint4*>(p) + idx;
+    const uint4 v = *q;
+    *q = make_uint4(pack_bf16x2(bf16_lo(v.x) * a0.x, bf16_hi(v.x) * a0.y), pack_bf16x2(bf16_lo(v.y) * a0.z, bf16_hi(v.y) * a0.w),
+                    pack_bf16x2(bf16_lo(v.z) * a1.x, bf16_hi(v.z) * a1.y), pack_bf16x2(bf16_lo(v.w) * a1.z, bf16_hi(v.w) * a1.w));
+  }
+}
+
+// p[y_t, t] -= l_t for every token whose label takes part in the loss (coef != 0) and lies inside the vocabulary.  One
+// element per token, all in different columns: no two threads touch the same one.
+__global__ void __launch_bounds__(256) ce_patch_label_kernel(bf16* __restrict__ p, int T, int V, const int* __restrict__ labels,
+                                                             const float* __restrict__ l, const float* __restrict__ coef) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int y = labels[t];
+  if (coef[t] == 0.f || y < 0 || y >= V) return;
+  bf16* const e = p + (long)y * T + t;
+  *e = (bf16)((float)*e - l[t]);
+}
+
+// xs[t, :] = xf[t, :] * coef[t] / l[t]  (bf16; zero rows for ignored tokens)
+__global__ void __launch_bounds__(256) ce_scale_x_kernel(const bf16* __restrict__ xf, const float* __restrict__ coef,
+                                                         const float* __restrict__ l, bf16* __restrict__ xs, int T, int h) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= T) return;
+  const float s = coef[t] == 0.f ? 0.f : coef[t] / l[t];
+  const uint4* src = reinterpret_cast<const uint4*>(xf + (long)t * h);
+  uint4* dst = reinterpret_cast<uint4*>(xs + (long)t * h);
+  for (int c = lane; c < h / 8; c += 64) {
+    const uint4 v = src[c];
+    dst[c] = make_uint4(pack_bf16x2(bf16_lo(v.x) * s, bf16_hi(v.x) * s), pack_bf16x2(bf16_lo(v.y) * s, bf16_hi(v.y) * s),
+                        pack_bf16x2(bf16_lo(v.z) * s, bf16_hi(v.z) * s), pack_bf16x2(bf16_lo(v.w) * s, bf16_hi(v.w) * s));
+  }
+}
+
 __global__ void __launch_bounds__(256) ce_lse_from_ref_kernel(const float* __restrict__ m, const float* __restrict__ l,
                                                               float* __restrict__ lse, int T) {
   const int t = blockIdx.x * 256 + threadIdx.x;
@@ -222,6 +270,26 @@ hipError_t k_ce_rescale_rows(hipStream_t st, float* acc, const float* alpha, int
   if (T == 0) return hipSuccess;
   if (h % 4) return hipErrorInvalidValue;
   RP_LAUNCH(ce_rescale_rows_kernel, dim3((T + 3) / 4), dim3(256), 0, st, acc, alpha, T, h, flag);
+  return hipGetLastError();
+}
+
+hipError_t k_ce_rescale_p(hipStream_t st, void* p, long rows, int T, const float* alpha, const int* flag) {
+  if (T == 0 || rows == 0) return hipSuccess;
+  if (T % 8) return hipErrorInvalidValue;
+  RP_LAUNCH(ce_rescale_p_kernel, dim3(2048), dim3(256), 0, st, (bf16*)p, rows, T, alpha, flag);
+  return hipGetLastError();
+}
+
+hipError_t k_ce_patch_label(hipStream_t st, void* p, int T, int V, const int* labels, const float* l, const float* coef) {
+  if (T == 0) return hipSuccess;
+  RP_LAUNCH(ce_patch_label_kernel, dim3((T + 255) / 256), dim3(256), 0, st, (bf16*)p, T, V, labels, l, coef);
+  return hipGetLastError();
+}
+
+hipError_t k_ce_scale_x(hipStream_t st, const void* xf, const float* coef, const float* l, void* xs, int T, int h) {
+  if (T == 0) return hipSuccess;
+  if (h % 8) return hipErrorInvalidValue;
+  RP_LAUNCH(ce_scale_x_kernel, dim3((T + 3) / 4), dim3(256), 0, st, (const bf16*)xf, coef, l, (bf16*)xs, T, h);
   return hipGetLastError();
 }
 

@@ -779,11 +779,16 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
   const double Td = (double)T;
   RUN(X, "rmsnorm_fwd", 0, 4.0 * Td * D.h, k_rmsnorm_fwd(X.st, x, W.t(RP_T_GF), X.at<void>(P.h_xf), X.at<float>(P.h_rstd), T, D.h, ctx->cfg.rms_eps));
   RUN(X, "fill", 0, 4.0 * Td, k_fill_u32(X.st, X.at<void>(P.h_zlab), T, 0u));
-  if (!train && !ctx->cfg.train_base && !ctx->cfg.head_two_sweeps) {
-    // Frozen head: without dW the softmax normaliser is only needed at the very end, so one sweep over the vocabulary
-    // suffices (two logit-sized products instead of three).  Per chunk: logits (fp32) -> p = exp(z - m_t) against a
-    // per-token reference exponent that moves (and rescales what has been accumulated) only when a chunk outgrows it
-    // -> acc_t += p W_c;  finally lse_t = m_t + log l_t and dx_t = coef_t (acc_t / l_t - W[y_t]).
+  if (!ctx->cfg.head_two_sweeps && (!ctx->cfg.train_base || P.head_keep_p)) {
+    // One sweep over the vocabulary: the softmax normaliser is only needed at the very end.  Per chunk: logits -> p =
+    // exp(z - m_t) against a per-token reference exponent that moves (and rescales what has been accumulated) only when
+    // a chunk outgrows it -> acc_t += p W_c;  finally lse_t = m_t + log l_t and dx_t = coef_t (acc_t / l_t - W[y_t]).
+    // Frozen head: two logit-sized products instead of three, one chunk of p in memory at a time.  Trainable head
+    // (keep_p): the p of every chunk stay in memory ([V, T] bf16) and the weight gradient follows from them afterwards,
+    // dW = P'^T^T xs with P'[v, t] = p[v, t] - l_t [v = y_t], xs_t = (coef_t / l_t) xf_t: three products instead of the
+    // four of the two-sweep schedule, which has to compute the logits twice.
+    const bool keep_p = P.head_keep_p;
+    bf16_t* const pall = keep_p ? X.at<bf16_t>(P.h_pall) : nullptr;
     float* const zc = X.at<float>(P.h_z);
     float* const acc = X.at<float>(P.h_dxacc);
     int* const flag = X.at<int>(P.h_flag);
@@ -793,6 +798,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
       const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
       const int nparts = gemm_ce_stats_partials(vc);
       const bf16_t* Wc = Wv + (size_t)v0 * D.h;
+      void* const pc = keep_p ? static_cast<void*>(pall + (size_t)v0 * T) : X.at<void>(P.h_dzt);   // this chunk's p [vc, T]
       GemmArgs g; gemm_zero_args(g);
       g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h;
       g.ldc = T; g.labels = labels; g.zlab = X.at<float>(P.h_zlab); g.part = X.at<float2>(P.h_part); g.part_ld = T;
@@ -801,7 +807,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
         // the probabilities straight from the accumulators, against the reference as it stands; the chunk is redone
         // below only if a token outgrew its reference by too much for that (the flag stays 0 otherwise)
         GemmArgs f = g;
-        f.epi = EPI_CE_P; f.C = X.at<void>(P.h_dzt); f.lse = X.at<float>(P.h_m);
+        f.epi = EPI_CE_P; f.C = pc; f.lse = X.at<float>(P.h_m);
         X.mark_gemm(GEMM_NT, f);
         X.chk(gemm_launch(X.st, GEMM_NT, f), "lm head probabilities");
         RUN(X, "ce_chunk_check", 0, 8.0 * nparts * Td, k_ce_chunk_check(X.st, X.at<float2>(P.h_part), nparts, T, X.at<float>(P.h_m), flag));
@@ -812,13 +818,14 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
       X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head logits");
       RUN(X, ci == 0 ? "ce_chunk_update" : "ce_slow_path", 0, ci == 0 ? 6.0 * vc * Td : 8.0 * nparts * Td,
           k_ce_chunk_update(X.st, zc, vc, T, X.at<float2>(P.h_part), nparts, ci == 0, X.at<float>(P.h_m),
-                            X.at<float>(P.h_l), X.at<float>(P.h_alpha), X.at<void>(P.h_dzt), ci == 0 ? nullptr : flag));
+                            X.at<float>(P.h_l), X.at<float>(P.h_alpha), pc, ci == 0 ? nullptr : flag));
       if (ci > 0) {
         RUN(X, "ce_slow_path", 0, 0, k_ce_rescale_rows(X.st, acc, X.at<float>(P.h_alpha), T, D.h, flag));
+        if (keep_p) RUN(X, "ce_slow_path", 0, 0, k_ce_rescale_p(X.st, pall, v0, T, X.at<float>(P.h_alpha), flag));
         RUN(X, "fill", 0, 4.0, k_fill_u32(X.st, flag, 1, 0u));   // every reader of the flag is behind it in the stream
       }
       GemmArgs d; gemm_zero_args(d);   // acc[T, h] += p^T^T . W_c
-      d.A = X.at<void>(P.h_dzt); d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = acc;
+      d.A = pc; d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = acc;
       d.ldc = D.h; d.beta = 1; d.epi = EPI_F32;
       X.give_split_ws(d);
       X.mark_gemm(GEMM_TN, d);
@@ -827,10 +834,25 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
     RUN(X, "ce_lse", 0, 12.0 * Td, k_ce_lse_from_ref(X.st, X.at<float>(P.h_m), X.at<float>(P.h_l), X.at<float>(P.h_lse), T));
     RUN(X, "ce_finalize", 0, 16.0 * Td,
         k_ce_finalize(X.st, X.at<float>(P.h_lse), X.at<float>(P.h_zlab), labels, grad_scale, X.at<float>(P.h_coef), loss_out, T));
+    if (train && G.t(RP_T_WV)) {
+      RUN(X, "ce_patch_label", 0, 16.0 * Td, k_ce_patch_label(X.st, pall, T, D.V, labels, X.at<float>(P.h_l), X.at<float>(P.h_coef)));
+      RUN(X, "ce_scale_x", 0, 4.0 * Td * D.h,
+          k_ce_scale_x(X.st, X.at<void>(P.h_xf), X.at<float>(P.h_coef), X.at<float>(P.h_l), X.at<void>(P.h_xs), T, D.h));
+      for (int v0 = 0; v0 < D.V; v0 += P.head_chunk) {
+        const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
+        GemmArgs w; gemm_zero_args(w);  // dW_c[vc, h] += P'_c . xs
+        w.A = pall + (size_t)v0 * T; w.lda = T; w.B = X.at<void>(P.h_xs); w.ldb = D.h; w.M = vc; w.N = D.h; w.K = T;
+        w.C = G.t(RP_T_WV) + (size_t)v0 * D.h; w.ldc = D.h; w.beta = 1; w.epi = EPI_F32;
+        X.give_split_ws(w);
+        X.mark_gemm(GEMM_NN, w);
+        X.chk(gemm_launch(X.st, GEMM_NN, w), "lm head dW");
+      }
+    }
     RUN(X, "ce_frozen_dx", 0, 8.0 * Td * D.h + 2.0 * Td * D.h,
         k_ce_frozen_dx(X.st, acc, X.at<float>(P.h_l), X.at<float>(P.h_coef), labels, Wv, T, D.h, D.V));
     RUN(X, "rmsnorm_bwd", 0, 8.0 * Td * D.h,
-        k_rmsnorm_bwd(X.st, acc, 1, x, W.t(RP_T_GF), X.at<float>(P.h_rstd), nullptr, dx, nullptr, X.at<float>(P.h_partials), T, D.h));
+        k_rmsnorm_bwd(X.st, acc, 1, x, W.t(RP_T_GF), X.at<float>(P.h_rstd), nullptr, dx, train ? G.t(RP_T_GF) : nullptr,
+                      X.at<float>(P.h_partials), T, D.h));
     return finish_call(ctx, sl, X);
   }
   {  // sweep 1: logits tile by tile, reduced to per-token (max, sum exp) partials; nothing of size T x V is stored

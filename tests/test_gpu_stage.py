@@ -387,6 +387,38 @@ def test_frozen_head_reference_moves_between_chunks(hz):
     assert ref["loss"] > 20.0        # the loss is dominated by the large logits: the rescale path was exercised
 
 
+def test_trainable_head_in_one_sweep_when_the_reference_moves_between_chunks(hz):
+    """Trainable head, one sweep: the probabilities of every chunk stay in memory against the reference exponent and the
+    weight gradient is formed from them afterwards.  As above, later chunks outgrow the earlier ones -- the second by
+    less than the limit (probabilities of order e^44 are stored as they are), the third by more (the reference moves:
+    the accumulated input gradient, the normaliser AND the probabilities already stored are rescaled).  dW rows of all
+    three chunks, the final norm's gain gradient, dx and the loss against the oracle; labels in every chunk, some
+    ignored; and the two-sweep schedule (cfg.head_two_sweeps) gives the same within the bf16 noise."""
+    c = dict(n_layers=0, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=256, vocab=40008, n_experts=0, top_k=0,
+             lora_rank=0, lora=(), train_base=1, batch=1, seq=72, x_from="normal", head_chunk=16384)
+    wl = synth.make_workload(c, 82, gains_random=True)
+    Wv = wl["head"]["Wv"]
+    Wv[16384:32768] *= 12.0
+    Wv[32768:] *= 40.0
+    wl["head"]["Wv"] = synth.bf16_round(Wv)
+    wl["labels"][::7] = -100
+    wl["labels"][1::9] = 40007       # last row of the ragged last chunk
+    wl["labels"][2::9] = 3           # first chunk
+    wl["labels"][3::9] = 20000       # second chunk
+    ref = pu.oracle_chain(c, wl, grad_scale=32.0)
+    got = pu.gpu_chain(c, wl, hz, grad_scale=32.0)
+    errs = pu.compare_chain(ref, got, c)
+    assert {"loss", "head_dx", "head.Wv", "head.gf"} <= set(errs), sorted(errs)
+    assert ref["loss"] > 20.0
+    # rows of the first chunk receive gradient only through probabilities that were rescaled twice; they must not be lost
+    gw, rw = got["head_grads"]["Wv"], ref["head_grads"]["Wv"]
+    for lo, hi in ((0, 16384), (16384, 32768), (32768, 40008)):
+        assert pu.rel_l2(gw[lo:hi], rw[lo:hi]) < 2e-2, (lo, hi)
+    two = pu.gpu_chain(dict(c, head_two_sweeps=1), wl, hz, grad_scale=32.0)
+    assert pu.rel_l2(two["head_grads"]["Wv"], gw) < 1e-2 and pu.rel_l2(two["head_dx"], got["head_dx"]) < 1e-2
+    assert abs(two["loss"] - got["loss"]) <= 1e-5 * abs(got["loss"])
+
+
 def test_frozen_head_single_ragged_chunk(hz):
     """Frozen head whose vocabulary fits one chunk and is not a multiple of any tile; ragged token count."""
     c = dict(n_layers=0, hidden=128, n_q_heads=2, n_kv_heads=1, head_dim=64, ffn=256, vocab=1000, n_experts=0, top_k=0,
