@@ -76,6 +76,8 @@ hipError_t k_ce_lse(hipStream_t st, const float2* part, int P, long part_ld, flo
 // already there are then added to l as they are).
 hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, float2* pmax, int nparts, int first, float* m,
                              float* l, float* alpha, void* p, const int* flag);
+// m[t] = max over the partial rows' .x, l[t] = 0, alpha[t] = 1: the reference exponents a sweep starts from.
+hipError_t k_ce_ref_init(hipStream_t st, const float2* pmax, int nparts, int T, float* m, float* l, float* alpha);
 // *flag = 1 when some token's maximum over the chunk (pmax .x) lies more than RP_CE_P_LIMIT above its reference m.
 hipError_t k_ce_chunk_check(hipStream_t st, const float2* pmax, int nparts, int T, const float* m, int* flag);
 // acc[t, :] *= alpha[t] where alpha[t] != 1 (nothing when flag is given and *flag == 0).

@@ -260,6 +260,12 @@ hipError_t k_ce_chunk_update(hipStream_t st, const float* z, int vc, int T, floa
   return hipGetLastError();
 }
 
+hipError_t k_ce_ref_init(hipStream_t st, const float2* pmax, int nparts, int T, float* m, float* l, float* alpha) {
+  if (T == 0) return hipSuccess;
+  RP_LAUNCH(ce_chunk_ref_kernel, dim3((T + 255) / 256), dim3(256), 0, st, pmax, nparts, T, 1, m, l, alpha, (const int*)nullptr);
+  return hipGetLastError();
+}
+
 hipError_t k_ce_chunk_check(hipStream_t st, const float2* pmax, int nparts, int T, const float* m, int* flag) {
   if (T == 0) return hipSuccess;
   RP_LAUNCH(ce_chunk_check_kernel, dim3((T + 255) / 256, (nparts + 7) / 8), dim3(256), 0, st, pmax, nparts, T, m, flag);

@@ -794,7 +794,20 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
     int* const flag = X.at<int>(P.h_flag);
     RUN(X, "fill", 0, 4.0 * Td * D.h, k_fill_u32(X.st, acc, (long)T * D.h, 0u));
     RUN(X, "fill", 0, 4.0, k_fill_u32(X.st, flag, 1, 0u));
-    for (int v0 = 0, ci = 0; v0 < D.V; v0 += P.head_chunk, ++ci) {
+    {
+      // The reference exponents the sweep starts from: every token's largest logit over the first 256 vocabulary rows.
+      // Any reference within e^60 of the row's true maximum serves (bf16 keeps its relative precision over that range),
+      // so this small product lets every chunk, the first one included, take the path without fp32 logits.
+      const int r0 = D.V < 256 ? D.V : 256;
+      GemmArgs g; gemm_zero_args(g);
+      g.A = Wv; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = r0; g.N = T; g.K = D.h; g.epi = EPI_F32_COLMAX;
+      g.C = zc; g.ldc = T; g.labels = labels; g.zlab = X.at<float>(P.h_zlab); g.part = X.at<float2>(P.h_part); g.part_ld = T;
+      X.mark_gemm(GEMM_NT, g);
+      X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head reference");
+      RUN(X, "ce_ref_init", 0, 28.0 * Td,
+          k_ce_ref_init(X.st, X.at<float2>(P.h_part), gemm_ce_stats_partials(r0), T, X.at<float>(P.h_m), X.at<float>(P.h_l), X.at<float>(P.h_alpha)));
+    }
+    for (int v0 = 0; v0 < D.V; v0 += P.head_chunk) {
       const int vc = (D.V - v0 < P.head_chunk) ? (D.V - v0) : P.head_chunk;
       const int nparts = gemm_ce_stats_partials(vc);
       const bf16_t* Wc = Wv + (size_t)v0 * D.h;
@@ -803,7 +816,7 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
       g.A = Wc; g.lda = D.h; g.B = X.at<void>(P.h_xf); g.ldb = D.h; g.M = vc; g.N = T; g.K = D.h;
       g.ldc = T; g.labels = labels; g.zlab = X.at<float>(P.h_zlab); g.part = X.at<float2>(P.h_part); g.part_ld = T;
       g.row_offset = v0;
-      if (ci > 0) {
+      {
         // the probabilities straight from the accumulators, against the reference as it stands; the chunk is redone
         // below only if a token outgrew its reference by too much for that (the flag stays 0 otherwise)
         GemmArgs f = g;
@@ -811,19 +824,17 @@ rp_status rp_lmhead_ce_fwd_bwd(rp_ctx* ctx, int slot_id, const void* x, const in
         X.mark_gemm(GEMM_NT, f);
         X.chk(gemm_launch(X.st, GEMM_NT, f), "lm head probabilities");
         RUN(X, "ce_chunk_check", 0, 8.0 * nparts * Td, k_ce_chunk_check(X.st, X.at<float2>(P.h_part), nparts, T, X.at<float>(P.h_m), flag));
-        g.run_flag = flag;
       }
-      g.epi = EPI_F32_COLMAX; g.C = zc;
-      if (ci == 0) X.mark_gemm(GEMM_NT, g); else X.mark("ce_slow_path", 0, 0);
+      // the slow path, behind the flag: fp32 logits, reference move with rescale of what has been accumulated, p again
+      g.run_flag = flag; g.epi = EPI_F32_COLMAX; g.C = zc;
+      X.mark("ce_slow_path", 0, 0);
       X.chk(gemm_launch(X.st, GEMM_NT, g), "lm head logits");
-      RUN(X, ci == 0 ? "ce_chunk_update" : "ce_slow_path", 0, ci == 0 ? 6.0 * vc * Td : 8.0 * nparts * Td,
-          k_ce_chunk_update(X.st, zc, vc, T, X.at<float2>(P.h_part), nparts, ci == 0, X.at<float>(P.h_m),
-                            X.at<float>(P.h_l), X.at<float>(P.h_alpha), pc, ci == 0 ? nullptr : flag));
-      if (ci > 0) {
-        RUN(X, "ce_slow_path", 0, 0, k_ce_rescale_rows(X.st, acc, X.at<float>(P.h_alpha), T, D.h, flag));
-        if (keep_p) RUN(X, "ce_slow_path", 0, 0, k_ce_rescale_p(X.st, pall, v0, T, X.at<float>(P.h_alpha), flag));
-        RUN(X, "fill", 0, 4.0, k_fill_u32(X.st, flag, 1, 0u));   // every reader of the flag is behind it in the stream
-      }
+      RUN(X, "ce_slow_path", 0, 8.0 * nparts * Td,
+          k_ce_chunk_update(X.st, zc, vc, T, X.at<float2>(P.h_part), nparts, 0, X.at<float>(P.h_m), X.at<float>(P.h_l),
+                            X.at<float>(P.h_alpha), pc, flag));
+      RUN(X, "ce_slow_path", 0, 0, k_ce_rescale_rows(X.st, acc, X.at<float>(P.h_alpha), T, D.h, flag));
+      if (keep_p && v0 > 0) RUN(X, "ce_slow_path", 0, 0, k_ce_rescale_p(X.st, pall, v0, T, X.at<float>(P.h_alpha), flag));
+      RUN(X, "fill", 0, 4.0, k_fill_u32(X.st, flag, 1, 0u));   // every reader of the flag is behind it in the stream
       GemmArgs d; gemm_zero_args(d);   // acc[T, h] += p^T^T . W_c
       d.A = pc; d.lda = T; d.B = Wc; d.ldb = D.h; d.M = T; d.N = D.h; d.K = vc; d.C = acc;
       d.ldc = D.h; d.beta = 1; d.epi = EPI_F32;
