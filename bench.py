@@ -390,6 +390,41 @@ def gemm_probe(size, reps):
     print(json.dumps(out))
 
 
+def attn_probe(name, reps):
+    """Attention alone at the shape of a workload (sequence, heads, head_dim 128): forward, then the backward (delta, dK/dV,
+    its reduce, dQ) through the op-level entry points.  One JSON line; for counter runs (--attn-reps 2)."""
+    import torch
+    import synth
+    from paper_2604_27085_amd import binding as B
+    c = synth.CONFIGS[name]
+    seq, a, kh, d, batch = c["seq"], c["n_q_heads"], c["n_kv_heads"], c["head_dim"], c["batch"]
+    T = batch * seq
+    st = torch.cuda.current_stream().cuda_stream
+    mk = lambda h: torch.randn(T, h * d, device="cuda").bfloat16()
+    q, k, v, do = mk(a), mk(kh), mk(kh), mk(a)
+    o, dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    lse = torch.empty((batch, a, seq), dtype=torch.float32, device="cuda")
+    delta = torch.empty_like(lse)
+    scratch = torch.empty((2, T, a * d), dtype=torch.float32, device="cuda")
+    fwd = lambda: B.rp_op_attn_fwd(st, q, k, v, o, lse, a * d, kh * d, kh * d, a * d, batch, seq, a, kh, d)
+    bwd = lambda: B.rp_op_attn_bwd(st, q, k, v, o, do, lse, delta, dq, dk, dv, scratch, a * d, kh * d, kh * d, a * d, a * d,
+                                   a * d, kh * d, kh * d, batch, seq, a, kh, d)
+    unit = batch * float(seq) * seq * a * d          # FLOPs of one causal s x s x d product over all heads
+    out = {"probe": "attention", "workload": name, "seq": seq, "heads": [a, kh], "head_dim": d, "reps": reps}
+    for nm, fn, units in (("forward", fwd, 2.0), ("backward", bwd, 5.0)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        out[nm] = {"us": round(us, 1), "algorithmic_tflops": round(units * unit / us / 1e6, 1)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -405,6 +440,8 @@ def main():
     ap.add_argument("--round-micro", type=int, default=4, help="micro-batches per round in the multi-stream leg")
     ap.add_argument("--gemm-probe", type=int, default=0, help="only time the square GEMM of this size, staged against B-direct, and exit")
     ap.add_argument("--gemm-reps", type=int, default=20)
+    ap.add_argument("--attn-probe", default="", help="only time the attention kernels at this workload's shape (C2 .. C5) and exit")
+    ap.add_argument("--attn-reps", type=int, default=5)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures the one-GPU worker; a stage runs whole on one GPU and nothing here uses a "
@@ -414,6 +451,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.gemm_probe:
         gemm_probe(args.gemm_probe, args.gemm_reps)
+        return
+    if args.attn_probe:
+        attn_probe(args.attn_probe, args.attn_reps)
         return
 
     main_rec = measure(args.config, args, args.steps, args.warmup, True)

@@ -9,8 +9,8 @@
 // score products of the dK/dV kernel) is read with plain 16-byte LDS loads from a [rows][D + 8] tile; an operand
 // whose reduction index is the row index of the tile (V for P.V, K for dS.K, Q and dO for dK/dV) is read with the
 // transposing LDS load from a [rows][D + 32] tile.  A tile needed both ways (K in the dQ kernel, Q and dO in the dK/dV
-// kernel at d = 128) has the row stride D + 24, which keeps both kinds of reads free of bank conflicts, and is stored
-// once; nothing is transposed in registers.  Global loads are 16-byte buffer loads whose descriptor ends with the
+// kernel at d = 128) has the row stride D + 24, which serves both kinds of reads (the transposing ones with some bank
+// conflicts), and is stored once; nothing is transposed in registers.  Global loads are 16-byte buffer loads whose descriptor ends with the
 // sequence, so rows past the end read as zero without a branch.
 //
 //   forward : workgroup = NW waves x 32*QT queries of one head, loop over 64-key tiles up to the diagonal; NW = 8 (one
@@ -429,8 +429,8 @@ __global__ void __launch_bounds__(256) attn_delta_kernel(const bf16* __restrict_
 // ================================================================================================ dQ
 template <int D, int QT, int NW>
 __global__ void __launch_bounds__(NW * 64, (QT == 1 && NW <= 4) ? 2 : 1) attn_bwd_dq_kernel(const AttnArgs p) {
-  // K is read both ways (plain for S, transposing for dQ += dS K): its tile has the row stride d + 24 that keeps both
-  // kinds of reads free of bank conflicts (see attn_bwd_dkv_pair_kernel) and is stored once
+  // K is read both ways (plain for S, transposing for dQ += dS K): its tile has the row stride d + 24 that serves both
+  // (see attn_bwd_dkv_pair_kernel) and is stored once
   constexpr int LDK = D + 8, LDU = D + 24, KS = D / 16, DT = D / 32, NT = NW * 64, BQ = NW * 32 * QT;
   using T64 = Tile64<D, NT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];   // dq_smem_bytes(D, NW)
@@ -793,9 +793,13 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_fused_kernel(const AttnArgs 
 // MFMAs per workgroup as the one-wave-per-SIMD kernel, same LDS fragment traffic per CU, 8 KB of exchange per pair and tile.
 template <int D>
 __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p) {
-  // One LDS layout serves both kinds of fragment reads: a row stride of D + 24 elements is 12 banks past a multiple of
-  // 64, so the 16 rows of a plain 16-byte read phase start 12 banks apart (all 64 banks, 4 each) and the 4 rows of a
-  // transposing 8-byte read phase cover 8 banks each without meeting.  Every Q and dO tile is stored once.
+  // One LDS layout serves both kinds of fragment reads, so that every Q and dO tile is stored once: a row stride of
+  // D + 24 elements is 12 banks past a multiple of 64, which keeps the 16 rows of a plain 16-byte read phase on distinct
+  // banks; the transposing 8-byte reads (32 lanes a phase: 4 rows x 64 bytes) overlap on a quarter of their banks
+  // (SQ_LDS_BANK_CONFLICT: 22 % of the LDS-active cycles).  Measured cheaper than storing the tiles twice (-3 %); a
+  // layout with the transposing stride D + 32 and the 16-byte chunks of a row permuted (c ^ (row / 4 & 3)) removes the
+  // conflicts altogether (LDS-active cycles -20 %) and is not faster: the two workgroup barriers per tile, which
+  // re-align the waves of a SIMD every time, bound this kernel, not the LDS.
   constexpr int LDU = D + 24, KS = D / 16, DT = D / 32, DH = DT / 2;
   static_assert(DT % 2 == 0, "the head dimension is split over two waves");
   using T64 = Tile64<D, 512>;
