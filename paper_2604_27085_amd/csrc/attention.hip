@@ -798,8 +798,8 @@ __global__ void __launch_bounds__(512) attn_bwd_dkv_pair_kernel(const AttnArgs p
   // banks; the transposing 8-byte reads (32 lanes a phase: 4 rows x 64 bytes) overlap on a quarter of their banks
   // (SQ_LDS_BANK_CONFLICT: 22 % of the LDS-active cycles).  Measured cheaper than storing the tiles twice (-3 %); a
   // layout with the transposing stride D + 32 and the 16-byte chunks of a row permuted (c ^ (row / 4 & 3)) removes the
-  // conflicts altogether (LDS-active cycles -20 %) and is not faster: the two workgroup barriers per tile, which
-  // re-align the waves of a SIMD every time, bound this kernel, not the LDS.
+  // conflicts altogether (LDS-active cycles -20 %) and is not faster; neither is a variant with one workgroup barrier
+  // per tile and a flag handshake inside the pair.  No unit is more than half busy: the waves wait on their own chain.
   constexpr int LDU = D + 24, KS = D / 16, DT = D / 32, DH = DT / 2;
   static_assert(DT % 2 == 0, "the head dimension is split over two waves");
   using T64 = Tile64<D, 512>;
