@@ -428,10 +428,14 @@ __global__ void __launch_bounds__(256) gemm_arrange_kernel(const bf16* __restric
 // a relative efficiency that was measured with one workgroup per CU and with the CU fully occupied.
 // atomic_nk: K tiles of 64 when the output accumulates in fp32, so that an under-filled 256x256 launch can be split
 // along the reduction (merged by atomic adds, which only pays off for long reductions); else 0.
-int choose_tile(int M, int N, bool plain_epilogue, int atomic_nk) {
+// k_tiles: K tiles of 64 in the reduction.  The two-group tile pays a fixed accumulator exchange per output tile, so its
+// efficiency against the 256x256 tile grows with the length of the reduction: measured 0.75-0.84 at K = 2048, 0.94 at
+// K = 4096, 1.0 at K = 12288 -- modelled as 0.75 at 32 K tiles rising to 0.85 at 96.
+int choose_tile(int M, int N, bool plain_epilogue, int atomic_nk, int k_tiles) {
   static const int bm[5] = {256, 256, 128, 128, 256}, bn[5] = {256, 128, 128, 64, 128};
   static const int per_cu[5] = {1, 2, 3, 5, 1};
-  static const double eff_full[5] = {1.0, 0.7, 0.6, 0.4, 0.75}, eff_single[5] = {1.0, 0.375, 0.25, 0.15, 0.75};
+  const double k2 = 0.75 + 0.1 * (k_tiles <= 32 ? 0.0 : k_tiles >= 96 ? 1.0 : (k_tiles - 32) / 64.0);
+  const double eff_full[5] = {1.0, 0.7, 0.6, 0.4, k2}, eff_single[5] = {1.0, 0.375, 0.25, 0.15, k2};
   int best = 1;
   double best_cost = 1e300;
   for (int t = 0; t < (plain_epilogue ? 5 : 4); ++t) {
@@ -482,7 +486,7 @@ int gemm_pick_tile(const GemmArgs& a, int tile_hint) {
   const bool plain = a.epi == EPI_BF16 || a.epi == EPI_F32 || a.epi == EPI_F32_ATOMIC;
   const bool can_split = a.epi == EPI_F32 && (a.beta || a.split_out_bf16) && a.split_ws;
   const int atomic_nk = can_split ? (a.K + 63) / 64 + (a.K2 + 63) / 64 : 0;
-  return choose_tile(a.M, a.N, plain, atomic_nk);
+  return choose_tile(a.M, a.N, plain, atomic_nk, (a.K + 63) / 64 + (a.K2 + 63) / 64);
 }
 
 hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int tile_hint) {
