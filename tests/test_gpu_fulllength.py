@@ -32,7 +32,7 @@ def rel(a, b):
     return pu.rel_l2(a, b)
 
 
-def run_attention(B, H, q, k, v, do, seq, a, kh, batch=1):
+def run_attention(B, H, q, k, v, do, seq, a, kh, batch=1, D=D):
     """q, do: bf16 device [T, a*D]; k, v: [T, kh*D], T = batch * seq.  Returns o, lse, dq, dk, dv as float32 ndarrays
     ([seq, heads, D] and lse [a, seq]; with batch > 1 a leading batch axis)."""
     dv_ = "cuda:0"
@@ -135,6 +135,44 @@ def test_zero_queries_two_sequences_of_ragged_length(rp, capsys):
                 dp = v64[: t + 1, g] @ do[b, t, j].astype(np.float64) - mean_v[t, g] @ do[b, t, j].astype(np.float64)
                 ref = (dp @ k64[: t + 1, g]) / ((t + 1) * np.sqrt(D))
                 assert np.linalg.norm(dq[b, t, j] - ref) <= 1.5e-2 * np.linalg.norm(ref) + 5e-5, (b, t, j)
+
+
+@pytest.mark.timeout(600)
+def test_zero_queries_head_dim_64_at_ragged_length(rp, capsys):
+    """Head dimension 64 (the GPT-OSS shape) at 12424 tokens with 32/8 heads: long enough for the XCD-aware order of the
+    dK/dV kernel (98 key tiles, ragged last run) and for thousands of workgroups per launch, which the short kernel tests
+    do not reach at this head dimension.  Same closed forms as above."""
+    B, H = rp
+    seq, a, kh, d = 12424, 32, 8, 64
+    grp = a // kh
+    with capsys.disabled():
+        print("[d = 64] zero queries, seq %d, %d/%d heads" % (seq, a, kh), flush=True)
+    rng = np.random.default_rng(64)
+    k = synth.bf16_round(rng.standard_normal((seq, kh, d), dtype=np.float32))
+    v = synth.bf16_round(rng.standard_normal((seq, kh, d), dtype=np.float32))
+    do = synth.bf16_round(rng.standard_normal((seq, a, d), dtype=np.float32))
+    qd = torch.zeros((seq, a * d), dtype=torch.bfloat16, device="cuda:0")
+    dev = lambda t: H.bf16_tensor(t.reshape(seq, -1), "cuda:0")
+    o, lse, dq, dk, dv = run_attention(B, H, qd, dev(k), dev(v), dev(do), seq, a, kh, 1, d)
+    cnt = np.arange(1, seq + 1, dtype=np.float64)
+    mean_v = np.cumsum(v.astype(np.float64), axis=0) / cnt[:, None, None]
+    assert np.max(np.abs(lse - np.log(cnt)[None, :])) < 2e-5
+    for j in range(a):
+        err = np.linalg.norm(o[:, j] - mean_v[:, j // grp], axis=1) / np.linalg.norm(mean_v[:, j // grp], axis=1)
+        assert rel(o[:, j], mean_v[:, j // grp]) < 4e-3 and err.max() < 2e-2, (j, int(err.argmax()), err.max())
+    w = do.astype(np.float64) / cnt[:, None, None]
+    dv_ref = np.cumsum(w[::-1], axis=0)[::-1].reshape(seq, kh, grp, d).sum(axis=2)
+    assert rel(dv, dv_ref) < 6e-3
+    err = np.linalg.norm((dv - dv_ref).reshape(seq, -1), axis=1) / np.linalg.norm(dv_ref.reshape(seq, -1), axis=1)
+    assert err.max() < 3e-2, (int(err.argmax()), err.max())
+    assert np.max(np.abs(dk)) <= 1e-6 * np.max(np.abs(dv))
+    k64, v64 = k.astype(np.float64), v.astype(np.float64)
+    for t in (0, 63, 64, 255, 256, 6000, seq - 129, seq - 9, seq - 1):
+        for j in (0, grp, a - 1):
+            g = j // grp
+            dp = v64[: t + 1, g] @ do[t, j].astype(np.float64) - mean_v[t, g] @ do[t, j].astype(np.float64)
+            ref = (dp @ k64[: t + 1, g]) / ((t + 1) * np.sqrt(d))
+            assert np.linalg.norm(dq[t, j] - ref) <= 1.5e-2 * np.linalg.norm(ref) + 5e-5, (t, j)
 
 
 @pytest.mark.timeout(600)
