@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librp.so")
-SOURCES = ["gemm.hip", "elementwise.hip", "attention.hip", "lmhead.hip", "moe.hip", "transfers.hip", "partition.hip", "stage.hip"]
+SOURCES = ["gemm.hip", "gemm_dtl.hip", "elementwise.hip", "attention.hip", "lmhead.hip", "moe.hip", "transfers.hip", "partition.hip", "stage.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Xclang", "-target-feature",
          "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # attention: the score tiles go from the MFMA straight into the softmax arithmetic; keeping MFMA results in ordinary

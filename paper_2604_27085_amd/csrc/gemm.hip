@@ -521,7 +521,7 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   }
   // operands are addressed with 32-bit byte offsets
   if (a.bytesA == ~0u || a.bytesB == ~0u || a.bytesA2 == ~0u || a.bytesB2 == ~0u) return hipErrorInvalidValue;
-  int tile = gemm_pick_tile(a, tile_hint);
+  int tile = gemm_pick_tile(a, tile_hint == 7 ? 1 : tile_hint);
   if (a.grp_tab) {   // grouped: 256-row tiles as in the table, rows of A are tile rows, one operand pair
     if (ta || a.K2 || !a.grp_ntiles || a.grp_max_tiles <= 0 || (a.epi != EPI_BF16 && a.epi != EPI_F32 && a.epi != EPI_SWIGLU_FWD)) return hipErrorInvalidValue;
     tile = 1;
@@ -560,8 +560,11 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
     a.C = a.split_ws; a.ldc = a.N; a.beta = 0; a.c_slice_stride = (long)a.M * a.N;
   }
   hipError_t e;
+  // NT products on 256x256 tiles run the four-wave kernel that loads its operands straight into LDS (gemm_dtl.hip),
+  // unless the staged eight-wave kernel is asked for by name (hint 1) or the variant has no counterpart there
+  const bool dtl = layout == GEMM_NT && tile == 1 && tile_hint != 1 && !a.run_flag && !a.b_direct;
   switch (layout) {
-    case GEMM_NT: e = launch_tile<false, false>(st, a, tile); break;
+    case GEMM_NT: e = dtl ? gemm_dtl_launch(st, a) : launch_tile<false, false>(st, a, tile); break;
     case GEMM_NN: e = launch_tile<false, true>(st, a, tile); break;
     default: e = launch_tile<true, true>(st, a, tile); break;
   }

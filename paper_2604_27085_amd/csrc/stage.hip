@@ -956,7 +956,7 @@ rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const
                      long ldb2, const void* R, long ldr, int tile, void* split_ws, size_t split_ws_bytes) {
   if (out_f32 < 0 || out_f32 > 3 || (out_f32 == 3 && !split_ws) || (split_ws && reinterpret_cast<uintptr_t>(split_ws) % 16))
     return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad out_f32 / split_ws");
-  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 6)
+  if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 7)
     return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad arguments");
   if ((layout != GEMM_NT) && (N % 8 || (layout == GEMM_TN && M % 8))) return fail(nullptr, RP_EINVAL, "rp_op_gemm: transposed operands need multiples of 8");
   GemmArgs g; gemm_zero_args(g);
