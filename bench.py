@@ -362,8 +362,10 @@ def measure(name, args, steps, warmup, full):
 
 
 def gemm_probe(size, reps):
-    """The projection GEMM alone at M = N = K = size: the staged 256x256 kernel against the variant that streams a
-    pre-arranged B operand past LDS (tile 6), as NT and as NN.  One JSON line; for counter runs (--gemm-reps 3)."""
+    """The projection GEMM alone at M = N = K = size: as NT the four-wave kernel that loads its operands straight into LDS
+    (tile 7, what the stage runs), as NT and NN the staged eight-wave 256x256 kernel (tile 1) and the variant that
+    streams a pre-arranged B operand past LDS (tile 6); for context the library product (torch.matmul) on the same
+    box.  One JSON line; for counter runs (--gemm-reps 3)."""
     import torch
     from paper_2604_27085_amd import binding as B
     st = torch.cuda.current_stream().cuda_stream
@@ -371,22 +373,30 @@ def gemm_probe(size, reps):
     a = (torch.randn(M, K, device="cuda") * 0.5).bfloat16()
     c = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
     out = {"probe": "gemm", "M": M, "N": N, "K": K, "reps": reps}
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        return {"us": round(us, 1), "tflops": round(2.0 * M * N * K / us / 1e6, 1)}
+
     for layout, lname in ((0, "NT"), (1, "NN")):
         b = (torch.randn((N, K) if layout == 0 else (K, N), device="cuda") * 0.05).bfloat16()
         ldb = K if layout == 0 else N
         arr = torch.empty(((N + 63) // 64) * ((K + 63) // 64) * 4096, dtype=torch.bfloat16, device="cuda")
         B.rp_op_gemm_arrange(st, b, ldb, N, K, layout, arr)
-        for tile, bb, l, tname in ((1, b, ldb, "staged"), (6, arr, 0, "b_direct")):
-            B.rp_op_gemm(st, layout, 0, a, bb, c, M, N, K, K, l, N, tile=tile)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                B.rp_op_gemm(st, layout, 0, a, bb, c, M, N, K, K, l, N, tile=tile)
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) / reps * 1e3
-            out["%s_%s" % (lname, tname)] = {"us": round(us, 1), "tflops": round(2.0 * M * N * K / us / 1e6, 1)}
+        variants = [(1, b, ldb, "staged"), (6, arr, 0, "b_direct")]
+        if layout == 0:
+            variants.insert(0, (7, b, ldb, "lds_direct"))
+        for tile, bb, l, tname in variants:
+            out["%s_%s" % (lname, tname)] = timed(lambda: B.rp_op_gemm(st, layout, 0, a, bb, c, M, N, K, K, l, N, tile=tile))
+        out["%s_library" % lname] = timed(lambda: torch.matmul(a, b.t() if layout == 0 else b, out=c))
     print(json.dumps(out))
 
 
