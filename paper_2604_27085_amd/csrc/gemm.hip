@@ -15,10 +15,13 @@
 // stall MFMA issue behind a full memory queue, and every load has a whole tile of time to return; the workgroup
 // barrier sits before the last four MFMAs of a tile and the first fragments of the next tile are read under them.
 // Measured on MI355X the 256x256 tile asks L2 for one byte per 128 FLOP; the matrix pipe is busy 75-79 % of the kernel's
-// cycles and the chip runs power-limited near 1.65 GHz under it.  Tried and dropped: direct HBM -> LDS loads with a four-deep ring, touching lines two tiles
+// cycles and the chip runs power-limited near 1.65 GHz under it.  Tried and dropped here: touching lines two tiles
 // ahead to pull them into L2, touching the first lines of the workgroup's successor tile before the epilogue,
-// staggered K-loop starts, a reduction split merged by the last workgroup to arrive, a 128x128 wave tile with one wave
-// per SIMD.  Outputs too small to fill the chip with 256x256 tiles use a 256x128 tile worked
+// staggered K-loop starts, a reduction split merged by the last workgroup to arrive.  The NT product on 256x256 tiles
+// has a faster kernel of its own (gemm_dtl.hip: four waves of 128x128, one per SIMD, operands loaded straight into
+// LDS); this file keeps every other tile and layout, and the eight-wave 256x256 NT instance as the reference it is
+// tested against bit for bit.
+// Outputs too small to fill the chip with 256x256 tiles use a 256x128 tile worked
 // on by two wave groups that split every K tile (merged through LDS); GEMMs that accumulate into an fp32 output and
 // would still leave CUs idle are split along the reduction: the slices write partial products to scratch memory and a
 // second kernel adds them in slice order (reproducible run to run).  A variant keeps the B operand out of LDS (BD).
