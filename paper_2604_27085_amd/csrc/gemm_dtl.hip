@@ -75,6 +75,9 @@ RP_DEV i32x4 raw_rsrc(const void* base, uint32_t bytes) {
   return r;
 }
 
+// TB: the B operand is [K, N] (reduction index strided, the NN product); its units keep that layout and its fragments
+// are read with the transposing LDS load.
+template <bool TB>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) gemm_dtl_kernel(const GemmArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -105,12 +108,30 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   const int nk = (nk_all - kt0) < per_split ? (nk_all - kt0 > 0 ? nk_all - kt0 : 0) : per_split;
 
   // a folded tile (SwiGLU forward): every wave's block is 64 gate columns and the 64 up columns that go with them
-  const int fold = (p.epi == EPI_SWIGLU_FWD) ? p.N >> 1 : 0;   // uniform
+  const int fold = (!TB && p.epi == EPI_SWIGLU_FWD) ? p.N >> 1 : 0;   // uniform
 
-  // Load instruction i (0..7 per operand) of this wave fills the 1 KB block 8*wave + i of a unit: operand rows
-  // 8*(8*wave + i) .. + 7, lane l -> row + (l >> 3), chunk position l & 7, i.e. data chunk (l & 7) ^ ((row >> 1) & 7).
+  // Load instruction i (0..7 per operand) of this wave fills the 1 KB block 8*wave + i of a unit.
+  //   reduction-contiguous operand: operand rows 8*(8*wave + i) .. + 7, lane l -> row + (l >> 3), chunk position l & 7,
+  //     i.e. data chunk (l & 7) ^ ((row >> 1) & 7);
+  //   TB: the unit is [64 reduction rows][256 columns] (512-byte rows, eight 64-byte segments = MFMA tile columns each);
+  //     reduction rows 2*(8*wave + i), + 1, lane l -> row + (l >> 5), chunk position l & 31, whose segment (l & 31) >> 2
+  //     holds data segment ((l & 31) >> 2) ^ (row & 3): the four reduction rows a transposing read touches at once
+  //     lie in four different quarters of the banks.
   uint32_t voA[8], voB[8];
   int lch[2];     // the lane's data chunk in even / odd instructions (rows 8 apart flip bit 2 of the swizzle)
+  auto b_offset = [&](int i, long ldb) -> uint32_t {   // byte offset of the lane's chunk of load i of a B unit at reduction offset 0
+    if constexpr (!TB) {
+      const int r = 8 * (8 * wave + i) + (lane >> 3);
+      const int ch = (lane & 7) ^ ((r >> 1) & 7);
+      const int gn = fold ? (n0 >> 1) + (r >> 7) * 64 + (r & 63) + ((r >> 6) & 1) * fold : n0 + r;
+      return gn < p.N ? (uint32_t)((long)gn * ldb + ch * 8) * 2u : OOB;
+    } else {
+      const int kr = 2 * (8 * wave + i) + (lane >> 5);
+      const int pos = lane & 31;
+      const int gn = n0 + (((pos >> 2) ^ (kr & 3)) * 32) + (pos & 3) * 8;
+      return gn < p.N ? (uint32_t)((long)kr * ldb + gn) * 2u : OOB;
+    }
+  };
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int r = 8 * (8 * wave + i) + (lane >> 3);
@@ -119,8 +140,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int gm = m0 + r;
     const long srcm = (p.row_map && gm < Mlim) ? p.row_map[gm] : gm;
     voA[i] = gm < Mlim ? (uint32_t)(srcm * p.lda + ch * 8) * 2u : OOB;
-    const int gn = fold ? (n0 >> 1) + (r >> 7) * 64 + (r & 63) + ((r >> 6) & 1) * fold : n0 + r;
-    voB[i] = gn < p.N ? (uint32_t)((long)gn * p.ldb + ch * 8) * 2u : OOB;
+    voB[i] = b_offset(i, p.ldb);
   }
   const i32x4 rsA = raw_rsrc(p.A, p.bytesA), rsB = raw_rsrc(Bbase, p.bytesB);
   i32x4 rsA2 = rsA, rsB2 = rsB;
@@ -140,7 +160,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   for (int i = 0; i < 8; ++i) { vcA[i] = voA[i]; vcB[i] = voB[i]; }
   int ld_kt = kt0, ld_k0 = kt0 * BK, ld_Klim = p.K;
   bool ld_second = false, ld_live = true;
-  uint32_t ld_soff = 0;
+  uint32_t ld_soff = 0, ld_soffB = 0;
+  uint32_t ld_kstepB = TB ? (uint32_t)p.ldb * 2u : 2u;   // bytes per reduction index in the B operand
   uint32_t ld_ring = 0;          // byte offset of the ring slot of the tile's B unit; its A unit is the next slot
   uint32_t ld_ldsB = 0, ld_ldsA = 0;
   // before the loads of local tile s = 0, 1, 2, ..., in three parts (for slots of their own in the K loop); tiles past
@@ -155,13 +176,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       rcA = rsA2;
       rcB = rsB2;
       if (p.K2 > 0) {   // the offsets of the second pair are worked out here rather than kept in registers through the loop
+        if constexpr (TB) ld_kstepB = (uint32_t)p.ldb2 * 2u;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int r = 8 * (8 * wave + i) + (lane >> 3);
           const int ch = (lane & 7) ^ ((r >> 1) & 7);
-          const int gn = fold ? (n0 >> 1) + (r >> 7) * 64 + (r & 63) + ((r >> 6) & 1) * fold : n0 + r;
           vcA[i] = (m0 + r) < p.M ? (uint32_t)((long)(m0 + r) * p.lda2 + ch * 8) * 2u : OOB;
-          vcB[i] = gn < p.N ? (uint32_t)((long)gn * p.ldb2 + ch * 8) * 2u : OOB;
+          vcB[i] = b_offset(i, p.ldb2);
         }
       }
       // Whatever the compiler reloads from scratch memory on this path counts in vmcnt like the loads above; left
@@ -170,6 +191,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       __builtin_amdgcn_s_waitcnt(0x0f70);
     }
     ld_soff = s < nk ? (uint32_t)ld_k0 * 2u : OOB;   // (from s, not from the flag: the scalar offset has to stay provably wave-uniform)
+    ld_soffB = s < nk ? (uint32_t)ld_k0 * ld_kstepB : OOB;
     ++ld_kt;
   };
   auto setup_mask = [&]() {
@@ -179,7 +201,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       // (the next tile belongs to the other pair, whose offsets are worked out afresh, or lies past the end)
       const uint32_t mk0 = (ld_k0 + lch[0] * 8 < ld_Klim) ? 0u : OOB, mk1 = (ld_k0 + lch[1] * 8 < ld_Klim) ? 0u : OOB;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { vcA[i] |= (i & 1) ? mk1 : mk0; vcB[i] |= (i & 1) ? mk1 : mk0; }
+      for (int i = 0; i < 8; ++i) {
+        vcA[i] |= (i & 1) ? mk1 : mk0;
+        if constexpr (!TB) vcB[i] |= (i & 1) ? mk1 : mk0;
+        else vcB[i] |= (ld_k0 + 2 * (8 * wave + i) + (lane >> 5) < ld_Klim) ? 0u : OOB;
+      }
       __builtin_amdgcn_s_waitcnt(0x0f70);   // as at the end of the pair switch
     }
     ld_k0 += BK;
@@ -193,7 +219,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   auto tile_setup = [&](int s) { setup_pair(s); setup_mask(); setup_lds(); };
   auto issue_b = [&](auto itag) __attribute__((always_inline)) {
     constexpr int i = decltype(itag)::value;
-    load_to_lds<i * 1024>(ld_ldsB, vcB[i], rcB, ld_soff);
+    load_to_lds<i * 1024>(ld_ldsB, vcB[i], rcB, ld_soffB);
   };
   auto issue_a = [&](auto itag) __attribute__((always_inline)) {
     constexpr int i = decltype(itag)::value;
@@ -223,6 +249,24 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   uint4 af[2][4], bfr[2][4];
   auto read_a = [&](int set, uint32_t off, int i) { af[set][i] = *reinterpret_cast<const uint4*>(smem + off + i * 4096); };
   auto read_b = [&](int set, uint32_t off, int j) { bfr[set][j] = *reinterpret_cast<const uint4*>(smem + off + j * 4096); };
+  // TB: a fragment of B is two transposing reads (reduction rows +0..3 and +4..7 of the lane's half of the 16-deep step).
+  // fkBt[j]: byte offset of the lane's first read of step 0 for MFMA tile column j of the wave: reduction row
+  // 8*lk + (l%16)/4, the tile column's segment moved by the row's swizzle, columns 16*((l/16)%2) + 4*(l%4) of the tile.
+  [[maybe_unused]] uint32_t fkBt[4];
+  if constexpr (TB) {
+    const int l16 = lane & 15, g16 = lane >> 4, c2 = l16 >> 2;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      fkBt[j] = (uint32_t)((8 * lk + c2) * 512 + (((wn * 4 + j) ^ c2) * 64) + 32 * (g16 & 1) + 8 * (l16 & 3));
+  }
+  [[maybe_unused]] auto read_bt = [&](int set, uint32_t off, int j, int half) {   // off includes the step: + ks * 8192
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(smem + off + half * 2048));
+    const uint2 u = __builtin_bit_cast(uint2, v);
+    if (half == 0) { bfr[set][j].x = u.x; bfr[set][j].y = u.y; }
+    else { bfr[set][j].z = u.x; bfr[set][j].w = u.y; }
+  };
 
   // prologue: tiles 0 and 1 set out (in the order of the K loop: B, then A); tile 0 has landed everywhere after the barrier
 #pragma unroll
@@ -231,13 +275,16 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     issue_b(IC<0>{}); issue_b(IC<1>{}); issue_b(IC<2>{}); issue_b(IC<3>{}); issue_b(IC<4>{}); issue_b(IC<5>{}); issue_b(IC<6>{}); issue_b(IC<7>{});
     issue_a(IC<0>{}); issue_a(IC<1>{}); issue_a(IC<2>{}); issue_a(IC<3>{}); issue_a(IC<4>{}); issue_a(IC<5>{}); issue_a(IC<6>{}); issue_a(IC<7>{});
   }
-  tile_setup(2);
+  if constexpr (!TB) tile_setup(2);   // (the TB loop sets the state of tile t+2 up in its first slots)
   __builtin_amdgcn_s_waitcnt(0x0f70 | (16 & 15) | ((16 >> 4) << 14));   // vmcnt(16)
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 4; ++i) read_a(0, UNIT_BYTES + fkA[0], i);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) read_b(0, fkB[0], j);
+  for (int j = 0; j < 4; ++j) {
+    if constexpr (!TB) read_b(0, fkB[0], j);
+    else { read_bt(0, fkBt[j], j, 0); read_bt(0, fkBt[j], j, 1); }
+  }
 
   // Slot plan of tile t (64 slots of one MFMA; 16-deep step ks = slots 16 ks .. 16 ks + 15, fragment set ks & 1).  A slot
   // holds at most one memory instruction: with one wave per SIMD whatever a slot issues beside its MFMA has to fit into
@@ -292,11 +339,70 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       curA = nA;
     }
   };
+  // The same for TB.  A step reads twelve fragments' worth of instructions (four for A, two each for the four of B), so
+  // only four slots of a step are left for loads and none are empty:
+  //   slots 16 ks + 0..3, 4..11  the fragment reads of A and B of step ks + 1 (of step 0 of tile t+1 for ks = 3)
+  //   slots 1, 2                 the state of the loads of tile t+2
+  //   slots 12..15, 28..31       the loads of B of tile t+2
+  //   slot  46                   vmcnt(8); barrier
+  //   slots 47, 53, 55, 57, 60..63  the loads of A of tile t+2
+  [[maybe_unused]] auto main_loop_tb = [&]() __attribute__((always_inline)) {
+    constexpr int BARB = 46;
+    uint32_t ring = 0;
+    uint32_t curA = UNIT_BYTES, nA = 0;
+    uint32_t fa = curA + fkA[1];
+    uint32_t fbj[4], nfbj[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { fbj[j] = fkBt[j]; nfbj[j] = 0; }
+    for (int t = 0; t < nk; ++t) {
+      auto slot = [&](auto sltag) __attribute__((always_inline)) {
+        constexpr int sl = decltype(sltag)::value;
+        constexpr int ks = sl >> 4, I = sl & 15, i = I >> 2, jj = I & 3, set = ks & 1;
+        if constexpr (sl == BARB) {
+          __builtin_amdgcn_s_waitcnt(0x0f70 | 8);
+          __syncthreads();
+        }
+        if constexpr (I == 0 && ks < 3) __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+        acc[jj >> 1][i][jj & 1] = mfma32(af[set][i], bfr[set][jj], acc[jj >> 1][i][jj & 1]);
+        if constexpr (I < 4) read_a(set ^ 1, fa, I);
+        if constexpr (I >= 4 && I < 12) {
+          constexpr int j = (I - 4) >> 1, half = (I - 4) & 1;
+          if constexpr (ks < 3) read_bt(set ^ 1, fbj[j] + (ks + 1) * 8192, j, half);
+          else read_bt(0, nfbj[j], j, half);
+        }
+        if constexpr (sl == 1) setup_pair(t + 2);
+        if constexpr (sl == 2) { setup_mask(); setup_lds(); }
+        if constexpr (sl == 13) fa = curA + fkA[2];
+        if constexpr (sl == 14) ring = ring + 2 * UNIT_BYTES >= (uint32_t)DTL_SMEM ? ring + 2 * UNIT_BYTES - DTL_SMEM : ring + 2 * UNIT_BYTES;
+        if constexpr (sl == 15) nA = ring + UNIT_BYTES == (uint32_t)DTL_SMEM ? 0u : ring + UNIT_BYTES;
+        if constexpr (sl == 29) fa = curA + fkA[3];
+        if constexpr (sl == 44) { nfbj[0] = ring + fkBt[0]; nfbj[1] = ring + fkBt[1]; }
+        if constexpr (sl == 45) { nfbj[2] = ring + fkBt[2]; nfbj[3] = ring + fkBt[3]; fa = nA + fkA[0]; }
+        if constexpr (sl == 59) fa = nA + fkA[1];
+        if constexpr (sl >= 12 && sl < 16) issue_b(IC<(sl - 12)>{});
+        if constexpr (sl >= 28 && sl < 32) issue_b(IC<(sl - 28 + 4)>{});
+        if constexpr (sl == 47) issue_a(IC<0>{});
+        if constexpr (sl == 53) issue_a(IC<1>{});
+        if constexpr (sl == 55) issue_a(IC<2>{});
+        if constexpr (sl == 57) issue_a(IC<3>{});
+        if constexpr (sl >= 60) issue_a(IC<(sl >= 60 ? sl - 60 + 4 : 0)>{});
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      for_seq(slot, std::make_integer_sequence<int, 64>{});
+      curA = nA;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) fbj[j] = nfbj[j];
+    }
+  };
+  if constexpr (TB) {
+    main_loop_tb();
+  } else {
   switch (wave) {
     case 0: main_loop(std::integral_constant<int, 0>{}); break;
     case 1: main_loop(std::integral_constant<int, 1>{}); break;
     case 2: main_loop(std::integral_constant<int, 2>{}); break;
     default: main_loop(std::integral_constant<int, 3>{}); break;
+  }
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the empty loads past the end write LDS too
   __syncthreads();                      // every wave is done with the operand stages: the epilogue reuses the LDS
@@ -350,16 +456,21 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 
 }  // namespace
 
-hipError_t gemm_dtl_launch(hipStream_t st, const GemmArgs& a) {
+template <bool TB>
+static hipError_t dtl_launch_one(hipStream_t st, const GemmArgs& a) {
   static bool attr_done = false;
+  auto kern = gemm_dtl_kernel<TB>;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_dtl_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, DTL_SMEM);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DTL_SMEM);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   int tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256);
   if (a.grp_tab) tiles = a.grp_max_tiles * ((a.N + 255) / 256);
-  RP_LAUNCH(gemm_dtl_kernel, dim3(tiles, a.splits > 0 ? a.splits : 1), dim3(256), DTL_SMEM, st, a);
+  RP_LAUNCH(kern, dim3(tiles, a.splits > 0 ? a.splits : 1), dim3(256), DTL_SMEM, st, a);
   return hipGetLastError();
 }
 
+hipError_t gemm_dtl_launch(hipStream_t st, const GemmArgs& a, bool b_transposed) {
+  return b_transposed ? dtl_launch_one<true>(st, a) : dtl_launch_one<false>(st, a);
+}
