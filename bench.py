@@ -362,10 +362,10 @@ def measure(name, args, steps, warmup, full):
 
 
 def gemm_probe(size, reps):
-    """The projection GEMM alone at M = N = K = size: as NT the four-wave kernel that loads its operands straight into LDS
-    (tile 7, what the stage runs), as NT and NN the staged eight-wave 256x256 kernel (tile 1) and the variant that
-    streams a pre-arranged B operand past LDS (tile 6); for context the library product (torch.matmul) on the same
-    box.  One JSON line; for counter runs (--gemm-reps 3)."""
+    """The projection GEMM alone at M = N = K = size, as NT and as NN: the four-wave kernel that loads its operands straight
+    into LDS (tile 7, what the stage runs for long reductions), the staged eight-wave 256x256 kernel (tile 1) and the
+    variant that streams a pre-arranged B operand past LDS (tile 6); for context the library product (torch.matmul) on
+    the same box.  One JSON line; for counter runs (--gemm-reps 3)."""
     import torch
     from paper_2604_27085_amd import binding as B
     st = torch.cuda.current_stream().cuda_stream
@@ -375,7 +375,8 @@ def gemm_probe(size, reps):
     out = {"probe": "gemm", "M": M, "N": N, "K": K, "reps": reps}
 
     def timed(fn):
-        fn()
+        for _ in range(reps):     # untimed: the clock of a chip that was idle takes tens of milliseconds to settle
+            fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -391,9 +392,7 @@ def gemm_probe(size, reps):
         ldb = K if layout == 0 else N
         arr = torch.empty(((N + 63) // 64) * ((K + 63) // 64) * 4096, dtype=torch.bfloat16, device="cuda")
         B.rp_op_gemm_arrange(st, b, ldb, N, K, layout, arr)
-        variants = [(1, b, ldb, "staged"), (6, arr, 0, "b_direct")]
-        if layout == 0:
-            variants.insert(0, (7, b, ldb, "lds_direct"))
+        variants = [(7, b, ldb, "lds_direct"), (1, b, ldb, "staged"), (6, arr, 0, "b_direct")]
         for tile, bb, l, tname in variants:
             out["%s_%s" % (lname, tname)] = timed(lambda: B.rp_op_gemm(st, layout, 0, a, bb, c, M, N, K, K, l, N, tile=tile))
         out["%s_library" % lname] = timed(lambda: torch.matmul(a, b.t() if layout == 0 else b, out=c))
