@@ -563,16 +563,20 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
     a.C = a.split_ws; a.ldc = a.N; a.beta = 0; a.c_slice_stride = (long)a.M * a.N;
   }
   hipError_t e;
-  // NT and NN products on 256x256 tiles run the four-wave kernel that loads its operands straight into LDS
-  // (gemm_dtl.hip) when the reduction is at least 48 K tiles long -- its per-tile fixed cost (four waves doing the
-  // epilogue in two halves, a deeper prologue) is higher, and at K = 2048 with a cross-entropy or SwiGLU epilogue the
-  // eight-wave kernel is 9 % faster -- unless a kernel is asked for by name (hint 1: eight waves, hint 7: four) or the
-  // variant has no counterpart there.
-  const bool dtl = layout != GEMM_TN && tile == 1 && tile_hint != 1 && !a.run_flag && !a.b_direct && (tile_hint == 7 || a.K + a.K2 >= 3072);
-  switch (layout) {
-    case GEMM_NT: e = dtl ? gemm_dtl_launch(st, a, false) : launch_tile<false, false>(st, a, tile); break;
-    case GEMM_NN: e = dtl ? gemm_dtl_launch(st, a, true) : launch_tile<false, true>(st, a, tile); break;
-    default: e = launch_tile<true, true>(st, a, tile); break;
+  // Products on 256x256 tiles run the four-wave kernel that loads its operands straight into LDS (gemm_dtl.hip) when
+  // the reduction is at least 48 K tiles long -- its per-tile fixed cost (four waves doing the epilogue in two halves, a
+  // deeper prologue) is higher, and at K = 2048 with a cross-entropy or SwiGLU epilogue the eight-wave kernel is 9 %
+  // faster -- unless a kernel is asked for by name (hint 1: eight waves, hint 7: four) or the variant has no
+  // counterpart there.
+  const bool dtl = tile == 1 && tile_hint != 1 && !a.run_flag && !a.b_direct && (tile_hint == 7 || a.K + a.K2 >= 3072);
+  if (dtl) {
+    e = gemm_dtl_launch(st, a, layout);
+  } else {
+    switch (layout) {
+      case GEMM_NT: e = launch_tile<false, false>(st, a, tile); break;
+      case GEMM_NN: e = launch_tile<false, true>(st, a, tile); break;
+      default: e = launch_tile<true, true>(st, a, tile); break;
+    }
   }
   if (e != hipSuccess || !merged) return e;
   const long quads = (long)a.M * (a.N / 4);

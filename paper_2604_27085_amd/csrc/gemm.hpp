@@ -84,7 +84,7 @@ int gemm_ce_stats_partials(int M);
 void gemm_zero_args(GemmArgs& a);
 // The 256x256 NT (b_transposed false) or NN (true) product with operands loaded straight into LDS and four waves of
 // 128x128 (gemm_dtl.hip); arguments as prepared by gemm_launch (extents, slices).
-hipError_t gemm_dtl_launch(hipStream_t st, const GemmArgs& a, bool b_transposed);
+hipError_t gemm_dtl_launch(hipStream_t st, const GemmArgs& a, int layout);
 // Tile gemm_launch picks for these arguments: 1..4 = 256x256, 256x128, 128x128, 128x64 (8, 4, 2, 1 waves),
 // 5 = 256x128 with eight waves in two groups that split every K tile.  (An NT or NN product on tile 1 with a long
 // enough reduction runs gemm_dtl_launch unless tile_hint is 1; hint 7 asks for it by name.)

@@ -80,9 +80,10 @@ RP_DEV i32x4 raw_rsrc(const void* base, uint32_t bytes) {
 }
 
 // TB: the B operand is [K, N] (reduction index strided, the NN product); its units keep that layout and its fragments
-// are read with the transposing LDS load.
-template <bool TB>
+// are read with the transposing LDS load.  TA (with TB: the TN product): the same for A, which is [K, M].
+template <bool TA, bool TB>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) gemm_dtl_kernel(const GemmArgs p) {
+  static_assert(!TA || TB, "A transposed alone is not a layout of this library");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -136,14 +137,27 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       return gn < p.N ? (uint32_t)((long)kr * ldb + gn) * 2u : OOB;
     }
   };
+  auto a_offset = [&](int i, long lda, bool first) -> uint32_t {   // the same for A (rows of a transposed A are not mapped)
+    if constexpr (!TA) {
+      const int r = 8 * (8 * wave + i) + (lane >> 3);
+      const int ch = (lane & 7) ^ ((r >> 1) & 7);
+      const int gm = m0 + r;
+      if (!first) return gm < p.M ? (uint32_t)((long)gm * lda + ch * 8) * 2u : OOB;
+      const long srcm = (p.row_map && gm < Mlim) ? p.row_map[gm] : gm;
+      return gm < Mlim ? (uint32_t)(srcm * lda + ch * 8) * 2u : OOB;
+    } else {
+      const int kr = 2 * (8 * wave + i) + (lane >> 5);
+      const int pos = lane & 31;
+      const int gm = m0 + (((pos >> 2) ^ (kr & 3)) * 32) + (pos & 3) * 8;
+      return gm < (first ? Mlim : p.M) ? (uint32_t)((long)kr * lda + gm) * 2u : OOB;
+    }
+  };
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int r = 8 * (8 * wave + i) + (lane >> 3);
     const int ch = (lane & 7) ^ ((r >> 1) & 7);
     lch[i & 1] = ch;
-    const int gm = m0 + r;
-    const long srcm = (p.row_map && gm < Mlim) ? p.row_map[gm] : gm;
-    voA[i] = gm < Mlim ? (uint32_t)(srcm * p.lda + ch * 8) * 2u : OOB;
+    voA[i] = a_offset(i, p.lda, true);
     voB[i] = b_offset(i, p.ldb);
   }
   const i32x4 rsA = raw_rsrc(p.A, p.bytesA), rsB = raw_rsrc(Bbase, p.bytesB);
@@ -165,6 +179,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   int ld_kt = kt0, ld_k0 = kt0 * BK, ld_Klim = p.K;
   bool ld_second = false, ld_live = true;
   uint32_t ld_soff = 0, ld_soffB = 0;
+  uint32_t ld_kstepA = TA ? (uint32_t)p.lda * 2u : 2u;
   uint32_t ld_kstepB = TB ? (uint32_t)p.ldb * 2u : 2u;   // bytes per reduction index in the B operand
   uint32_t ld_ring = 0;          // byte offset of the ring slot of the tile's B unit; its A unit is the next slot
   uint32_t ld_ldsB = 0, ld_ldsA = 0;
@@ -181,11 +196,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       rcB = rsB2;
       if (p.K2 > 0) {   // the offsets of the second pair are worked out here rather than kept in registers through the loop
         if constexpr (TB) ld_kstepB = (uint32_t)p.ldb2 * 2u;
+        if constexpr (TA) ld_kstepA = (uint32_t)p.lda2 * 2u;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const int r = 8 * (8 * wave + i) + (lane >> 3);
-          const int ch = (lane & 7) ^ ((r >> 1) & 7);
-          vcA[i] = (m0 + r) < p.M ? (uint32_t)((long)(m0 + r) * p.lda2 + ch * 8) * 2u : OOB;
+          vcA[i] = a_offset(i, p.lda2, false);
           vcB[i] = b_offset(i, p.ldb2);
         }
       }
@@ -194,7 +208,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       // pipeline every tile.
       __builtin_amdgcn_s_waitcnt(0x0f70);
     }
-    ld_soff = s < nk ? (uint32_t)ld_k0 * 2u : OOB;   // (from s, not from the flag: the scalar offset has to stay provably wave-uniform)
+    ld_soff = s < nk ? (uint32_t)ld_k0 * ld_kstepA : OOB;   // (from s, not from the flag: the scalar offset has to stay provably wave-uniform)
     ld_soffB = s < nk ? (uint32_t)ld_k0 * ld_kstepB : OOB;
     ++ld_kt;
   };
@@ -206,9 +220,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       const uint32_t mk0 = (ld_k0 + lch[0] * 8 < ld_Klim) ? 0u : OOB, mk1 = (ld_k0 + lch[1] * 8 < ld_Klim) ? 0u : OOB;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        vcA[i] |= (i & 1) ? mk1 : mk0;
-        if constexpr (!TB) vcB[i] |= (i & 1) ? mk1 : mk0;
-        else vcB[i] |= (ld_k0 + 2 * (8 * wave + i) + (lane >> 5) < ld_Klim) ? 0u : OOB;
+        const uint32_t mkr = (ld_k0 + 2 * (8 * wave + i) + (lane >> 5) < ld_Klim) ? 0u : OOB;   // row-wise, for [K, X] units
+        vcA[i] |= TA ? mkr : ((i & 1) ? mk1 : mk0);
+        vcB[i] |= TB ? mkr : ((i & 1) ? mk1 : mk0);
       }
       __builtin_amdgcn_s_waitcnt(0x0f70);   // as at the end of the pair switch
     }
@@ -263,6 +277,21 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     for (int j = 0; j < 4; ++j)
       fkBt[j] = (uint32_t)((8 * lk + c2) * 512 + (((wn * 4 + j) ^ c2) * 64) + 32 * (g16 & 1) + 8 * (l16 & 3));
   }
+  [[maybe_unused]] uint32_t fkAt[4];
+  if constexpr (TA) {
+    const int l16 = lane & 15, g16 = lane >> 4, c2 = l16 >> 2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      fkAt[i] = (uint32_t)((8 * lk + c2) * 512 + (((wm * 4 + i) ^ c2) * 64) + 32 * (g16 & 1) + 8 * (l16 & 3));
+  }
+  [[maybe_unused]] auto read_at = [&](int set, uint32_t off, int i, int half) {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(smem + off + half * 2048));
+    const uint2 u = __builtin_bit_cast(uint2, v);
+    if (half == 0) { af[set][i].x = u.x; af[set][i].y = u.y; }
+    else { af[set][i].z = u.x; af[set][i].w = u.y; }
+  };
   [[maybe_unused]] auto read_bt = [&](int set, uint32_t off, int j, int half) {   // off includes the step: + ks * 8192
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4* lds_ptr;
@@ -279,11 +308,14 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     issue_b(IC<0>{}); issue_b(IC<1>{}); issue_b(IC<2>{}); issue_b(IC<3>{}); issue_b(IC<4>{}); issue_b(IC<5>{}); issue_b(IC<6>{}); issue_b(IC<7>{});
     issue_a(IC<0>{}); issue_a(IC<1>{}); issue_a(IC<2>{}); issue_a(IC<3>{}); issue_a(IC<4>{}); issue_a(IC<5>{}); issue_a(IC<6>{}); issue_a(IC<7>{});
   }
-  if constexpr (!TB) tile_setup(2);   // (the TB loop sets the state of tile t+2 up in its first slots)
+  if constexpr (!TB) tile_setup(2);   // (the loops for transposed operands set the state of tile t+2 up in their first slots)
   __builtin_amdgcn_s_waitcnt(0x0f70 | (16 & 15) | ((16 >> 4) << 14));   // vmcnt(16)
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 4; ++i) read_a(0, UNIT_BYTES + fkA[0], i);
+  for (int i = 0; i < 4; ++i) {
+    if constexpr (!TA) read_a(0, UNIT_BYTES + fkA[0], i);
+    else { read_at(0, UNIT_BYTES + fkAt[i], i, 0); read_at(0, UNIT_BYTES + fkAt[i], i, 1); }
+  }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     if constexpr (!TB) read_b(0, fkB[0], j);
@@ -398,7 +430,66 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       for (int j = 0; j < 4; ++j) fbj[j] = nfbj[j];
     }
   };
-  if constexpr (TB) {
+  // TN: sixteen transposing reads per step, one per slot (two per slot in step 2, so that the tile's last read is
+  // five slots old at the barrier), the loads on top of them:
+  //   slots 1, 2                    the state of the loads of tile t+2
+  //   slots 3, 7, .., 31            the loads of B of tile t+2
+  //   slots 32..39                  the reads of step 3, two per slot;  40..43 the read offsets of tile t+1
+  //   slot  44                      vmcnt(8); barrier
+  //   slots 45, 46, 47, 51, 55, 59, 62, 63   the loads of A of tile t+2
+  //   slots 48..63                  the reads of step 0 of tile t+1
+  [[maybe_unused]] auto main_loop_tn = [&]() __attribute__((always_inline)) {
+    constexpr int BARB = 44;
+    uint32_t ring = 0, nA = 0;
+    uint32_t faj[4], fbj[4], nfaj[4], nfbj[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { faj[j] = UNIT_BYTES + fkAt[j]; fbj[j] = fkBt[j]; nfaj[j] = 0; nfbj[j] = 0; }
+    for (int t = 0; t < nk; ++t) {
+      auto slot = [&](auto sltag) __attribute__((always_inline)) {
+        constexpr int sl = decltype(sltag)::value;
+        constexpr int ks = sl >> 4, I = sl & 15, i = I >> 2, jj = I & 3, set = ks & 1;
+        if constexpr (sl == BARB) {
+          __builtin_amdgcn_s_waitcnt(0x0f70 | 8);
+          __syncthreads();
+        }
+        if constexpr (I == 0 && ks < 3) __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+        acc[jj >> 1][i][jj & 1] = mfma32(af[set][i], bfr[set][jj], acc[jj >> 1][i][jj & 1]);
+        if constexpr (ks < 2 || ks == 3) {   // one read per slot: A fragments in slots 0..7, B in 8..15
+          constexpr int f = (I & 7) >> 1, half = I & 1;
+          if constexpr (ks < 2) {
+            if constexpr (I < 8) read_at(set ^ 1, faj[f] + (ks + 1) * 8192, f, half);
+            else read_bt(set ^ 1, fbj[f] + (ks + 1) * 8192, f, half);
+          } else {
+            if constexpr (I < 8) read_at(0, nfaj[f], f, half);
+            else read_bt(0, nfbj[f], f, half);
+          }
+        } else if constexpr (I < 8) {        // step 2: the reads of step 3, two per slot
+          constexpr int f = I >> 1, half = I & 1;
+          read_at(set ^ 1, faj[f] + 3 * 8192, f, half);
+          read_bt(set ^ 1, fbj[f] + 3 * 8192, f, half);
+        }
+        if constexpr (sl == 1) setup_pair(t + 2);
+        if constexpr (sl == 2) { setup_mask(); setup_lds(); }
+        if constexpr (sl == 13) ring = ring + 2 * UNIT_BYTES >= (uint32_t)DTL_SMEM ? ring + 2 * UNIT_BYTES - DTL_SMEM : ring + 2 * UNIT_BYTES;
+        if constexpr (sl == 14) nA = ring + UNIT_BYTES == (uint32_t)DTL_SMEM ? 0u : ring + UNIT_BYTES;
+        if constexpr (sl >= 40 && sl < 44) { nfaj[sl - 40] = nA + fkAt[sl - 40]; nfbj[sl - 40] = ring + fkBt[sl - 40]; }
+        if constexpr (sl < 32 && (sl & 3) == 3) issue_b(IC<(sl >> 2)>{});
+        if constexpr (sl >= 45 && sl < 48) issue_a(IC<(sl - 45)>{});
+        if constexpr (sl == 51) issue_a(IC<3>{});
+        if constexpr (sl == 55) issue_a(IC<4>{});
+        if constexpr (sl == 59) issue_a(IC<5>{});
+        if constexpr (sl == 62) issue_a(IC<6>{});
+        if constexpr (sl == 63) issue_a(IC<7>{});
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      for_seq(slot, std::make_integer_sequence<int, 64>{});
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { faj[j] = nfaj[j]; fbj[j] = nfbj[j]; }
+    }
+  };
+  if constexpr (TA) {
+    main_loop_tn();
+  } else if constexpr (TB) {
     main_loop_tb();
   } else {
   switch (wave) {
@@ -460,10 +551,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 
 }  // namespace
 
-template <bool TB>
+template <bool TA, bool TB>
 static hipError_t dtl_launch_one(hipStream_t st, const GemmArgs& a) {
   static bool attr_done = false;
-  auto kern = gemm_dtl_kernel<TB>;
+  auto kern = gemm_dtl_kernel<TA, TB>;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DTL_SMEM);
     if (e != hipSuccess) return e;
@@ -475,6 +566,10 @@ static hipError_t dtl_launch_one(hipStream_t st, const GemmArgs& a) {
   return hipGetLastError();
 }
 
-hipError_t gemm_dtl_launch(hipStream_t st, const GemmArgs& a, bool b_transposed) {
-  return b_transposed ? dtl_launch_one<true>(st, a) : dtl_launch_one<false>(st, a);
+hipError_t gemm_dtl_launch(hipStream_t st, const GemmArgs& a, int layout) {
+  switch (layout) {
+    case GEMM_NT: return dtl_launch_one<false, false>(st, a);
+    case GEMM_NN: return dtl_launch_one<false, true>(st, a);
+    default: return dtl_launch_one<true, true>(st, a);
+  }
 }

@@ -959,7 +959,6 @@ rp_status rp_op_gemm(void* stream, int layout, int out_f32, const void* A, const
   if (!A || !B || !C || M < 0 || N < 0 || K < 0 || K % 8 || K2 % 8 || lda % 8 || ldb % 8 || layout < 0 || layout > 2 || tile < 0 || tile > 7)
     return fail(nullptr, RP_EINVAL, "rp_op_gemm: bad arguments");
   if ((layout != GEMM_NT) && (N % 8 || (layout == GEMM_TN && M % 8))) return fail(nullptr, RP_EINVAL, "rp_op_gemm: transposed operands need multiples of 8");
-  if (tile == 7 && layout == GEMM_TN) return fail(nullptr, RP_EINVAL, "rp_op_gemm: tile 7 exists for layouts 0 and 1 only");
   GemmArgs g; gemm_zero_args(g);
   g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.alpha = alpha; g.beta = beta;
   g.A2 = A2; g.B2 = B2; g.K2 = (A2 && B2) ? K2 : 0; g.lda2 = lda2; g.ldb2 = ldb2; g.R = R; g.ldr = ldr;

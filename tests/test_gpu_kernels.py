@@ -75,10 +75,10 @@ def test_gemm_layouts_ragged(rp, layout, tile):
     assert rel_l2(H.to_f32(Cm), -0.5 * ref) < 4e-3
 
 
-@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("layout", [0, 1, 2])
 @pytest.mark.parametrize("shape", [(584, 456, 712, 40), (256, 256, 64, 0), (1, 8, 8, 16), (700, 1032, 2056, 0), (300, 520, 0, 24)])
 def test_gemm_operands_loaded_straight_into_lds(rp, shape, layout):
-    """Tile 7 (what tile 0 picks for layouts 0 and 1 on 256x256 tiles): four waves of 128x128, operands fetched from memory
+    """Tile 7 (what tile 0 picks on 256x256 tiles when the reduction is long): four waves of 128x128, operands fetched from memory
     straight into a ring of LDS units, reduction tails and tiles past the end read through out-of-range offsets.
     Against the fp64 product, and bit for bit against the staged eight-wave kernel (tile 1: same matrix instruction,
     same order of the reduction).  Ragged rows and columns against 256/128/64, K and K2 against the K tile of 64 (the
@@ -91,21 +91,29 @@ def test_gemm_operands_loaded_straight_into_lds(rp, shape, layout):
     u, bl = rnd(rng, (M, max(K2, 8))), rnd(rng, (N, max(K2, 8)), 0.1)
     res = rnd(rng, (M, N))
     ref = a[:, :K].astype(np.float64) @ b[:, :K].T.astype(np.float64) + u[:, :K2].astype(np.float64) @ bl[:, :K2].T.astype(np.float64)
-    A, A2, R = dev(H, a), dev(H, u), dev(H, res)
+    if layout == 2:      # A [K, M]: rows of A have to come in multiples of 8
+        M = (M + 7) // 8 * 8
+        a, u, res = rnd(rng, (M, max(K, 8))), rnd(rng, (M, max(K2, 8))), rnd(rng, (M, N))
+        ref = a[:, :K].astype(np.float64) @ b[:, :K].T.astype(np.float64) + u[:, :K2].astype(np.float64) @ bl[:, :K2].T.astype(np.float64)
+        A, A2, R = dev(H, np.ascontiguousarray(a.T)), dev(H, np.ascontiguousarray(u.T)), dev(H, res)
+        lda, lda2 = M, M
+    else:
+        A, A2, R = dev(H, a), dev(H, u), dev(H, res)
+        lda, lda2 = max(K, 8), max(K2, 8)
     if layout == 0:      # B [N, K], reduction index contiguous
         Bm, ldb, B2m, ldb2 = dev(H, b), max(K, 8), dev(H, bl), max(K2, 8)
     else:                # B [K, N]: read with the transposing LDS load
         Bm, ldb, B2m, ldb2 = dev(H, np.ascontiguousarray(b.T)), N, dev(H, np.ascontiguousarray(bl.T)), N
-    kw = dict(A2=A2, B2=B2m, K2=K2, lda2=max(K2, 8), ldb2=ldb2) if K2 else {}
+    kw = dict(A2=A2, B2=B2m, K2=K2, lda2=lda2, ldb2=ldb2) if K2 else {}
     ws = torch.empty(16 * M * N, dtype=torch.float32, device="cuda:0")
     outs = []
     for tile in (1, 7):
         Cm = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
-        B.rp_op_gemm(stream(), layout, 0, A, Bm, Cm, M, N, K, max(K, 8), ldb, N, R=R, ldr=N, tile=tile, **kw)
+        B.rp_op_gemm(stream(), layout, 0, A, Bm, Cm, M, N, K, lda, ldb, N, R=R, ldr=N, tile=tile, **kw)
         C32 = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda:0")
-        B.rp_op_gemm(stream(), layout, 1, A, Bm, C32, M, N, K, max(K, 8), ldb, N, alpha=0.25, beta=1, tile=tile, **kw)
+        B.rp_op_gemm(stream(), layout, 1, A, Bm, C32, M, N, K, lda, ldb, N, alpha=0.25, beta=1, tile=tile, **kw)
         Cs = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda:0")     # with scratch: may be cut along the reduction
-        B.rp_op_gemm(stream(), layout, 1, A, Bm, Cs, M, N, K, max(K, 8), ldb, N, beta=1, tile=tile, split_ws=ws, **kw)
+        B.rp_op_gemm(stream(), layout, 1, A, Bm, Cs, M, N, K, lda, ldb, N, beta=1, tile=tile, split_ws=ws, **kw)
         torch.cuda.synchronize()
         outs.append((H.to_f32(Cm), C32.cpu().numpy(), Cs.cpu().numpy()))
     scale = max(np.sqrt(np.mean(ref ** 2)), 1e-3)
