@@ -82,12 +82,12 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a, int tile_h
 // Number of partial rows an EPI_CE_STATS launch with M vocab rows writes for tile choice made by gemm_launch.
 int gemm_ce_stats_partials(int M);
 void gemm_zero_args(GemmArgs& a);
-// The 256x256 NT (b_transposed false) or NN (true) product with operands loaded straight into LDS and four waves of
+// The 256x256 product (layout GEMM_NT, GEMM_NN or GEMM_TN) with operands loaded straight into LDS and four waves of
 // 128x128 (gemm_dtl.hip); arguments as prepared by gemm_launch (extents, slices).
 hipError_t gemm_dtl_launch(hipStream_t st, const GemmArgs& a, int layout);
 // Tile gemm_launch picks for these arguments: 1..4 = 256x256, 256x128, 128x128, 128x64 (8, 4, 2, 1 waves),
-// 5 = 256x128 with eight waves in two groups that split every K tile.  (An NT or NN product on tile 1 with a long
-// enough reduction runs gemm_dtl_launch unless tile_hint is 1; hint 7 asks for it by name.)
+// 5 = 256x128 with eight waves in two groups that split every K tile.  (A product on tile 1 with a long enough
+// reduction and an output that is not skinny runs gemm_dtl_launch unless tile_hint is 1; hint 7 asks for it by name.)
 int gemm_pick_tile(const GemmArgs& a, int tile_hint = 0);
 
 // Fragment order of a B operand for b_direct: blocks of 64 output columns x K tiles of 64, each 8 KB = 4 steps x 2
