@@ -1,5 +1,5 @@
-// bf16 GEMM C = A * B^T (NT: both operands reduction-contiguous) or C = A * B (NN: B is [K, N]), 256x256 output tile,
-// operands loaded from HBM straight into LDS (no staging registers, no LDS store instructions) and four waves of 128x128
+// bf16 GEMM C = A * B^T (NT: both operands reduction-contiguous), C = A * B (NN: B is [K, N]) or C = A^T * B (TN: A is
+// [K, M] as well), 256x256 output tile, operands loaded from HBM straight into LDS (no staging registers, no LDS store instructions) and four waves of 128x128
 // each -- one wave per SIMD, 256 accumulator registers per lane (the AGPR half of the register file).
 //
 // Against the eight-wave kernel of gemm.hip a K tile of the same output tile costs a third fewer fragment reads (every
@@ -8,7 +8,7 @@
 // the SIMD -- so the loop is laid out slot by slot (one MFMA plus at most one memory instruction, which has to issue
 // within the 32 cycles the MFMA runs), every fragment is read a 16-deep step ahead and every load one to two K tiles
 // ahead.  Measured on MI355X (8192^3, same box): 1.38-1.42 PFLOP/s against 1.29-1.31 for the eight-wave kernel as NT,
-// 1.43 against 1.31 as NN; matrix pipe busy 85 % of the kernel's cycles against 77-78 %.
+// 1.43 against 1.31 as NN, 1.30 against 1.20 as TN; matrix pipe busy 85 % of the kernel's cycles against 77-78 %.
 //
 //   LDS       a ring of five 32 KB units; a unit is one operand of one K tile of 64: 256 rows of 128 bytes -- a load
 //             fetches whole 128-byte lines (rows of 64 bytes, as a K tile of 32 would have, double the requests to L2:
@@ -31,10 +31,11 @@
 //   NN        B's units keep the operand's [K, N] layout (64 rows of 512 bytes; the 64-byte segment of MFMA tile column
 //             s of row k at segment s ^ (k & 3)), its fragments are two transposing reads (ds_read_b64_tr_b16) each:
 //             twelve read instructions and four loads per 16-slot step, a slot plan of its own.
+//   TN        the same for A: sixteen reads per step, one per slot, the loads on top of them.
 // Second operand pair, row map, grouped mode, reduction slices and every epilogue of gemm_device.hpp (applied to the
 // two 128x64 halves of a wave's block in turn) as in gemm.hip; results are bit-identical to its 256x256 tile (same
-// MFMA, same order of the reduction).  gemm_launch picks this kernel for reductions of 48 K tiles or more: its fixed
-// cost per output tile is higher than the eight-wave kernel's.
+// MFMA, same order of the reduction).  gemm_launch picks this kernel for reductions of 48 K tiles or more and outputs
+// that are not skinny: its fixed cost per output tile is higher than the eight-wave kernel's.
 #include "gemm_device.hpp"
 #include <type_traits>
 #include <utility>
