@@ -20,7 +20,7 @@ extern "C" {
  * split every K tile (for outputs too small to fill the chip with 256x256 tiles); 6 = 256x256 with B (and B2) given
  * in fragment order (rp_op_gemm_arrange; ldb, ldb2 unused; layouts 0 and 1): that operand is streamed into registers
  * without passing through LDS; 7 = 256x256 by four waves of 128x128 whose operands are loaded from memory straight
- * into LDS (what "automatic" picks whenever it picks 256x256 tiles, K + K2 >= 3072 and M, N > 64 -- 1 always names
+ * into LDS (what "automatic" picks whenever it picks 256x256 tiles, K + K2 >= 2560 and M, N > 64 -- 1 always names
  * the eight-wave kernel that stages its operands through registers; the two give bit-identical results).
  * split_ws [dev, split_ws_bytes] or NULL: scratch for a reduction split.  An accumulating fp32 product (out_f32 1 with
  * beta) whose 256x256 tiles would leave most compute units idle is cut into up to 16 slices along K when the scratch

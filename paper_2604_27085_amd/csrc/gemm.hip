@@ -564,12 +564,12 @@ hipError_t gemm_launch(hipStream_t st, int layout, const GemmArgs& a_in, int til
   }
   hipError_t e;
   // Products on 256x256 tiles run the four-wave kernel that loads its operands straight into LDS (gemm_dtl.hip) when
-  // the reduction is at least 48 K tiles long -- its per-tile fixed cost (four waves doing the epilogue in two halves, a
+  // the reduction is at least 40 K tiles long -- its per-tile fixed cost (four waves doing the epilogue in two halves, a
   // deeper prologue) is higher, and at K = 2048 with a cross-entropy or SwiGLU epilogue the eight-wave kernel is 9 %
   // faster -- unless a kernel is asked for by name (hint 1: eight waves, hint 7: four) or the variant has no
   // counterpart there.
   // Skinny outputs (the LoRA products, bound by reading the other operand once) stay on the eight-wave kernel too: +14 %.
-  const bool dtl = tile == 1 && tile_hint != 1 && !a.run_flag && !a.b_direct && (tile_hint == 7 || (a.K + a.K2 >= 3072 && a.M > 64 && a.N > 64));
+  const bool dtl = tile == 1 && tile_hint != 1 && !a.run_flag && !a.b_direct && (tile_hint == 7 || (a.K + a.K2 >= 2560 && a.M > 64 && a.N > 64));
   if (dtl) {
     e = gemm_dtl_launch(st, a, layout);
   } else {

@@ -34,7 +34,7 @@
 //   TN        the same for A: sixteen reads per step, one per slot, the loads on top of them.
 // Second operand pair, row map, grouped mode, reduction slices and every epilogue of gemm_device.hpp (applied to the
 // two 128x64 halves of a wave's block in turn) as in gemm.hip; results are bit-identical to its 256x256 tile (same
-// MFMA, same order of the reduction).  gemm_launch picks this kernel for reductions of 48 K tiles or more and outputs
+// MFMA, same order of the reduction).  gemm_launch picks this kernel for reductions of 40 K tiles or more and outputs
 // that are not skinny: its fixed cost per output tile is higher than the eight-wave kernel's.
 #include "gemm_device.hpp"
 #include <type_traits>
