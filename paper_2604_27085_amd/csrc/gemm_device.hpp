@@ -63,12 +63,11 @@ RP_DEV int frag_base(int lane, int x_wave) {
   return TR ? (8 * lk + (l16 >> 2)) * LDROW + x_wave + 16 * (g16 & 1) + 4 * (l16 & 3) : (x_wave + lr) * LDROW + lk * 8;
 }
 
-// Workgroup -> output tile: XCD-aware remap (consecutive logical ids share an XCD's L2), then groups of 8 tile rows
+// Workgroup -> output tile: XCD-aware remap (consecutive logical ids share an XCD's L2), then groups of GM tile rows
 // sweep the tile columns.
-RP_DEV void tile_of_block(int M, int N, int BM, int BN, int& tile_m, int& tile_n) {
+RP_DEV void tile_of_block(int M, int N, int BM, int BN, int& tile_m, int& tile_n, int GM = 8) {
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const int pid = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  constexpr int GM = 8;
   const int group = pid / (GM * tiles_n);
   const int first_m = group * GM;
   const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;

@@ -103,7 +103,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     Mlim = g.y + g.z;
     Bbase += (long)g.x * p.grp_strideB;
   } else {
-    tile_of_block(p.M, p.N, 256, 256, tile_m, tile_n);
+    // narrow outputs (up to 24 tile columns) sweep their columns in groups of 4 tile rows, wide ones of 8: measured
+    // +2-3 % at N = 5120, -1.5-2 % at N >= 10240 for groups of 4
+    tile_of_block(p.M, p.N, 256, 256, tile_m, tile_n, (p.N + 255) / 256 <= 24 ? 4 : 8);
     m0 = tile_m * 256;
   }
   const int n0 = tile_n * 256;
